@@ -1,0 +1,319 @@
+"""Pins of the CPU oracle's verify-logits path (no GPU).
+
+The paper fixes the verify logits only through their definition: scoring the draft window in
+one call must give what K+1 ordinary single-token decodes give (section "Speculative Sampling
+Results").  The oracle *is* that sequential loop, so it is pinned here against things other
+than itself: a whole-sequence causal evaluation written with library primitives, closed forms
+of each building block, and invariants that a dropped term, a wrong index or a transposed
+operand would break.
+"""
+import math
+
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from paper_2411_00853_amd import workload as wl
+
+SMALL = wl.ModelShape(n_layers=2, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ffn=96,
+                      vocab=97, dtype="fp32")
+SMALL_BF16 = wl.ModelShape(n_layers=3, d_model=128, n_q_heads=8, n_kv_heads=2, head_dim=32, d_ffn=160,
+                           vocab=211, dtype="bf16")
+
+
+def _weights(shape, seed=7, std=0.08):
+    # larger std than the benchmark's 0.02 so that attention and FFN terms are not negligible
+    return wl.make_weights(shape, seed, "cpu", std=std)
+
+
+def textbook_causal_logits(shape, w, tokens):
+    """Whole-sequence causal transformer in fp64 from library primitives (embedding, rms_norm,
+    matmul, complex multiplication for the rotary embedding, scaled_dot_product_attention with a
+    causal mask, silu).  Returns [T, vocab]."""
+    f64 = torch.float64
+    T = len(tokens)
+    hd, Hq, Hkv = shape.head_dim, shape.n_q_heads, shape.n_kv_heads
+    x = F.embedding(torch.tensor(tokens), w["tok_embed"].to(f64))
+    pos = torch.arange(T, dtype=f64)
+    inv_freq = shape.rope_theta ** (-torch.arange(0, hd, 2, dtype=f64) / hd)
+    rot = torch.polar(torch.ones(T, hd // 2, dtype=f64), pos[:, None] * inv_freq[None, :])  # e^{i m theta}
+
+    def rope(t):  # t [T, H, hd]; dimension i pairs with i + hd/2
+        z = torch.complex(t[..., : hd // 2], t[..., hd // 2:]) * rot[:, None, :]
+        return torch.cat([z.real, z.imag], dim=-1)
+
+    for lw in w["layers"]:
+        h = F.rms_norm(x, (shape.d_model,), lw["attn_norm"].to(f64), eps=shape.rms_eps)
+        qkv = h @ lw["w_qkv"].to(f64).T
+        q, k, v = torch.split(qkv, [Hq * hd, Hkv * hd, Hkv * hd], dim=-1)
+        q = rope(q.view(T, Hq, hd)).transpose(0, 1)
+        k = rope(k.view(T, Hkv, hd)).transpose(0, 1)
+        v = v.view(T, Hkv, hd).transpose(0, 1)
+        if shape.dtype == "bf16":  # keys and values live in the cache in its storage type
+            k, v = k.to(torch.bfloat16).to(f64), v.to(torch.bfloat16).to(f64)
+        k = k.repeat_interleave(Hq // Hkv, dim=0)
+        v = v.repeat_interleave(Hq // Hkv, dim=0)
+        o = F.scaled_dot_product_attention(q[None], k[None], v[None], is_causal=True)[0]
+        x = x + o.transpose(0, 1).reshape(T, Hq * hd) @ lw["w_o"].to(f64).T
+        h = F.rms_norm(x, (shape.d_model,), lw["ffn_norm"].to(f64), eps=shape.rms_eps)
+        gu = h @ lw["w_gate_up"].to(f64).T
+        x = x + (F.silu(gu[:, : shape.d_ffn]) * gu[:, shape.d_ffn:]) @ lw["w_down"].to(f64).T
+    h = F.rms_norm(x, (shape.d_model,), w["final_norm"].to(f64), eps=shape.rms_eps)
+    return h @ w["lm_head"].to(f64).T
+
+
+@pytest.mark.parametrize("shape,tol", [(SMALL, 2e-5), (SMALL_BF16, 2e-2)])
+def test_sequential_decode_equals_textbook_causal_prefill(shape, tol):
+    # With an empty cache the window is a plain causal prefill.  For bf16 the textbook side rounds
+    # k,v once from fp64 while the oracle rounds fp32 values, so a few cache entries may differ by
+    # one bf16 ulp: hence the loose second tolerance (a structural mistake moves logits by O(1)).
+    w = _weights(shape)
+    tokens = [3, 17, 5, 96, 0, 41, 17, 8, 2]
+    m = oracle.Model(shape, w, max_kv_len=16)
+    cache = m.new_cache(float("nan"))
+    got = m.verify_sequential(cache, 0, tokens).double()
+    want = textbook_causal_logits(shape, w, tokens)
+    assert want.abs().max() > 0.5  # the comparison is not between near-zero numbers
+    assert (got - want).abs().max().item() < tol
+
+
+def test_gains_and_eps_matter_and_match_textbook():
+    # non-trivial gains: the unit gains of the benchmark weights would hide a dropped gain
+    shape = SMALL
+    w = _weights(shape)
+    g = torch.Generator().manual_seed(1)
+    w["final_norm"] = torch.rand(shape.d_model, generator=g) + 0.5
+    for lw in w["layers"]:
+        lw["attn_norm"] = torch.rand(shape.d_model, generator=g) + 0.5
+        lw["ffn_norm"] = torch.rand(shape.d_model, generator=g) + 0.5
+    tokens = [1, 2, 3, 4, 5]
+    m = oracle.Model(shape, w, max_kv_len=8)
+    got = m.verify_sequential(m.new_cache(), 0, tokens).double()
+    want = textbook_causal_logits(shape, w, tokens)
+    assert (got - want).abs().max().item() < 2e-5
+
+
+def _prefill(m, cache, tokens):
+    for i, t in enumerate(tokens):
+        m.decode_one(cache, i, int(t))
+
+
+@pytest.mark.parametrize("shape", [SMALL, SMALL_BF16, wl.TINY])
+def test_rows_at_once_is_bit_identical_to_one_token_at_a_time(shape):
+    w = _weights(shape, std=0.05)
+    T = 24
+    m = oracle.Model(shape, w, max_kv_len=T)
+    rng = wl.Rng(5, "cpu")
+    seqs = []
+    for s, (n, k) in enumerate([(9, 4), (0, 2), (13, 0), (5, 10)]):
+        prompt = rng.randint(100 + s, (n,), shape.vocab).tolist()
+        window = rng.randint(200 + s, (k + 1,), shape.vocab).tolist()
+        c = m.new_cache()
+        _prefill(m, c, prompt)
+        seqs.append((c, n, window))
+    want = torch.cat([m.verify_sequential(c.clone(), n, win) for c, n, win in seqs])
+    caches = [c.clone() for c, _, _ in seqs]
+    got = m.verify_rows(caches, [n for _, n, _ in seqs], [win for _, _, win in seqs])
+    assert torch.equal(got, want)
+    # the caches end up identical too (window keys/values appended at n .. n+K)
+    for (c, n, win), c2 in zip(seqs, caches):
+        c1 = c.clone()
+        m.verify_sequential(c1, n, win)
+        assert torch.equal(c1.view(torch.uint8), c2.view(torch.uint8))
+
+
+def test_zero_lookahead_is_one_ordinary_decode():
+    shape = SMALL
+    w = _weights(shape)
+    m = oracle.Model(shape, w, max_kv_len=8)
+    c = m.new_cache()
+    _prefill(m, c, [4, 9, 2])
+    a = m.decode_one(c.clone(), 3, 11)
+    b = m.verify_rows([c.clone()], [3], [[11]])[0]
+    assert torch.equal(a, b)
+
+
+def test_slots_beyond_the_window_are_never_read():
+    shape = SMALL_BF16
+    w = _weights(shape)
+    m = oracle.Model(shape, w, max_kv_len=16)
+    clean = m.new_cache(0.0)
+    _prefill(m, clean, [1, 2, 3, 4, 5])
+    poisoned = clean.clone()
+    poisoned[:, :, :, 5:, :] = float("nan")
+    win = [7, 8, 9]
+    a = m.verify_rows([clean], [5], [win])
+    b = m.verify_rows([poisoned], [5], [win])
+    assert torch.isfinite(b).all() and torch.equal(a, b)
+    # rolling back (dropping the window) and repeating the step reproduces the same bits
+    poisoned[:, :, :, 5 + 1:, :] = float("nan")  # keep t0's slot, drop the drafts: kv_len = n + 0 + 1
+    c = m.verify_rows([poisoned], [5], [win])
+    assert torch.equal(a, c)
+
+
+def test_gqa_equals_mha_with_replicated_kv_heads():
+    gqa = SMALL
+    g = gqa.n_q_heads // gqa.n_kv_heads
+    mha = wl.ModelShape(gqa.n_layers, gqa.d_model, gqa.n_q_heads, gqa.n_q_heads, gqa.head_dim, gqa.d_ffn,
+                        gqa.vocab, dtype="fp32")
+    w = _weights(gqa)
+    w2 = {k: v for k, v in w.items() if k != "layers"}
+    w2["layers"] = []
+    hd = gqa.head_dim
+    for lw in w["layers"]:
+        q, k, v = torch.split(lw["w_qkv"], [gqa.d_q, gqa.d_kv, gqa.d_kv], dim=0)
+        rep = lambda t: t.view(gqa.n_kv_heads, hd, -1).repeat_interleave(g, dim=0).reshape(-1, t.shape[1])
+        lw2 = dict(lw)
+        lw2["w_qkv"] = torch.cat([q, rep(k), rep(v)], dim=0).contiguous()
+        w2["layers"].append(lw2)
+    toks = [5, 6, 7, 8, 9, 10]
+    a = oracle.Model(gqa, w, 8)
+    b = oracle.Model(mha, w2, 8)
+    la = a.verify_sequential(a.new_cache(), 0, toks)
+    lb = b.verify_sequential(b.new_cache(), 0, toks)
+    assert torch.equal(la, lb)
+
+
+def test_ffn_unit_and_head_permutations_leave_logits_unchanged_and_vocab_permutation_permutes_them():
+    shape = wl.ModelShape(2, 64, 4, 4, 16, 96, 97, dtype="fp32")
+    w = _weights(shape)
+    toks = [1, 50, 3, 77]
+    base = oracle.Model(shape, w, 8)
+    ref = base.verify_sequential(base.new_cache(), 0, toks)
+    g = torch.Generator().manual_seed(3)
+    pf = torch.randperm(shape.d_ffn, generator=g)
+    ph = torch.randperm(shape.n_q_heads, generator=g)
+    pv = torch.randperm(shape.vocab, generator=g)
+    hd, H = shape.head_dim, shape.n_q_heads
+    w2 = {"tok_embed": w["tok_embed"], "final_norm": w["final_norm"],
+          "lm_head": w["lm_head"][pv].contiguous(), "layers": []}
+    for lw in w["layers"]:
+        gate, up = lw["w_gate_up"][: shape.d_ffn], lw["w_gate_up"][shape.d_ffn:]
+        qkv = lw["w_qkv"].view(3, H, hd, shape.d_model)[:, ph].reshape(3 * H * hd, shape.d_model)
+        wo = lw["w_o"].view(shape.d_model, H, hd)[:, ph].reshape(shape.d_model, H * hd)
+        w2["layers"].append({
+            "attn_norm": lw["attn_norm"], "ffn_norm": lw["ffn_norm"],
+            "w_qkv": qkv.contiguous(), "w_o": wo.contiguous(),
+            "w_gate_up": torch.cat([gate[pf], up[pf]]).contiguous(),
+            "w_down": lw["w_down"][:, pf].contiguous()})
+    m2 = oracle.Model(shape, w2, 8)
+    got = m2.verify_sequential(m2.new_cache(), 0, toks)
+    assert (got - ref[:, pv]).abs().max().item() < 1e-5
+    assert (ref.max() - ref.min()) > 0.5
+
+
+# ------------------------------------------------------------------ building blocks, closed forms
+
+def test_rmsnorm_closed_forms():
+    d, eps = 48, 1e-5
+    gain = torch.linspace(0.5, 2.0, d)
+    x = torch.full((d,), 3.0)
+    out = oracle.rmsnorm(x, gain, eps)
+    want = 3.0 / math.sqrt(9.0 + eps) * gain.double()
+    assert (out.double() - want).abs().max() < 1e-6
+    # scale invariance up to eps and sign: rmsnorm(-c x) = -rmsnorm(x) for large c
+    x = torch.randn(d, generator=torch.Generator().manual_seed(0))
+    a = oracle.rmsnorm(x * 1000, gain, eps)
+    b = oracle.rmsnorm(x * -4000, gain, eps)
+    assert (a + b).abs().max() < 1e-5
+    # a unit vector scaled so mean square is 1 passes through (eps aside)
+    e = torch.zeros(d)
+    e[5] = math.sqrt(d)
+    out = oracle.rmsnorm(e, torch.ones(d), 0.0)
+    assert abs(out[5].item() - math.sqrt(d)) < 1e-5 and out.abs().sum().item() == pytest.approx(math.sqrt(d), abs=1e-5)
+
+
+def test_rope_closed_forms():
+    # head_dim 2: one pair rotated by pos * theta^0 = pos radians
+    v = oracle.rope(torch.tensor([1.0, 0.0]), 10000.0, 3)
+    assert v[0].item() == pytest.approx(math.cos(3.0), abs=1e-7)
+    assert v[1].item() == pytest.approx(math.sin(3.0), abs=1e-7)
+    # head_dim 4: second pair (dims 1 and 3) turns at theta^(-2/4)
+    v = oracle.rope(torch.tensor([0.0, 1.0, 0.0, 0.0]), 100.0, 5)
+    ang = 5 * 100.0 ** (-0.5)
+    assert v.tolist() == pytest.approx([0.0, math.cos(ang), 0.0, math.sin(ang)], abs=1e-7)
+    g = torch.Generator().manual_seed(2)
+    q, k = torch.randn(64, generator=g), torch.randn(64, generator=g)
+    assert torch.equal(oracle.rope(q, 10000.0, 0), q)                       # position 0 is the identity
+    assert oracle.rope(q, 10000.0, 977).norm().item() == pytest.approx(q.norm().item(), rel=1e-6)
+    # scores depend on the position difference only
+    d1 = torch.dot(oracle.rope(q, 1e4, 40).double(), oracle.rope(k, 1e4, 33).double())
+    d2 = torch.dot(oracle.rope(q, 1e4, 3040).double(), oracle.rope(k, 1e4, 3033).double())
+    d3 = torch.dot(oracle.rope(q, 1e4, 7).double(), k.double())
+    assert d1.item() == pytest.approx(d2.item(), abs=1e-4) and d1.item() == pytest.approx(d3.item(), abs=1e-4)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_linear_is_a_matrix_vector_product(dtype):
+    g = torch.Generator().manual_seed(4)
+    W = torch.randn(37, 53, generator=g).to(dtype)
+    x = torch.randn(53, generator=g)
+    y = oracle.linear(W, x)
+    want = W.double() @ x.double()      # library matmul; [out, in] layout: a transposed read fails here
+    assert (y.double() - want).abs().max() < 1e-5
+    eye = torch.eye(16).to(dtype)
+    xs = torch.randn(16, generator=g)
+    assert torch.equal(oracle.linear(eye, xs), xs)
+
+
+def test_attend_closed_forms():
+    shape = wl.ModelShape(1, 8, 2, 2, 4, 8, 11, dtype="fp32")
+    m = oracle.Model(shape, _weights(shape), max_kv_len=6)
+    c = m.new_cache()
+    g = torch.Generator().manual_seed(6)
+    c[0, 1] = torch.randn(2, 6, 4, generator=g)          # values
+    c[0, 0, 1] = torch.ones(6, 4) * 0.3                   # head 1: all keys equal -> uniform average
+    q = torch.randn(4, generator=g)
+    out = m.attend(c, 0, 1, 5, q)
+    assert (out - c[0, 1, 1, :5].mean(0)).abs().max() < 1e-6
+    # one key far more aligned than the rest picks out its value
+    c[0, 0, 0] = 0.0
+    c[0, 0, 0, 2] = torch.tensor([50.0, 0, 0, 0])
+    out = m.attend(c, 0, 0, 6, torch.tensor([10.0, 0, 0, 0]))
+    assert (out - c[0, 1, 0, 2]).abs().max() < 1e-6
+    # general case against the library softmax; also checks the 1/sqrt(hd) scale
+    c[0, 0, 0] = torch.randn(6, 4, generator=g)
+    out = m.attend(c, 0, 0, 4, q)
+    s = (c[0, 0, 0, :4].double() @ q.double()) / 2.0
+    want = torch.softmax(s, 0) @ c[0, 1, 0, :4].double()
+    assert (out.double() - want).abs().max() < 1e-6
+
+
+def test_bf16_rounding_matches_library_conversion():
+    g = torch.Generator().manual_seed(8)
+    xs = torch.cat([torch.randn(4000, generator=g) * 3,
+                    torch.tensor([1.00390625, 1.01171875, -1.00390625, 0.0, 65504.0, 1e-40, 3.0e38])])
+    want = xs.to(torch.bfloat16).float()
+    got = torch.tensor([oracle.round_bf16(float(v)) for v in xs])
+    assert torch.equal(got, want)
+
+
+def test_first_layer_cache_entry_is_the_rounded_value_projection():
+    shape = SMALL_BF16
+    w = _weights(shape)
+    m = oracle.Model(shape, w, 4)
+    c = m.new_cache()
+    tok = 19
+    m.decode_one(c, 0, tok)
+    x = w["tok_embed"][tok].double()
+    h = F.rms_norm(x, (shape.d_model,), w["layers"][0]["attn_norm"].double(), eps=shape.rms_eps)
+    v = (w["layers"][0]["w_qkv"].double() @ h)[shape.d_q + shape.d_kv:].view(shape.n_kv_heads, shape.head_dim)
+    got = c[0, 1, :, 0, :].double()
+    # position 0: no rotation; equal up to one bf16 ulp where fp32 and fp64 round differently
+    assert ((got - v).abs() <= v.abs() * 2.0 ** -8 + 1e-30).all()
+    k = (w["layers"][0]["w_qkv"].double() @ h)[shape.d_q: shape.d_q + shape.d_kv].view(shape.n_kv_heads, -1)
+    assert ((c[0, 0, :, 0, :].double() - k).abs() <= k.abs() * 2.0 ** -8 + 1e-30).all()
+
+
+def test_zeroed_output_projections_reduce_to_embedding_times_head():
+    shape = SMALL
+    w = _weights(shape)
+    for lw in w["layers"]:
+        lw["w_o"] = torch.zeros_like(lw["w_o"])
+        lw["w_down"] = torch.zeros_like(lw["w_down"])
+    m = oracle.Model(shape, w, 4)
+    got = m.decode_one(m.new_cache(), 0, 33).double()
+    x = w["tok_embed"][33].double()
+    want = w["lm_head"].double() @ F.rms_norm(x, (shape.d_model,), w["final_norm"].double(), eps=shape.rms_eps)
+    assert (got - want).abs().max() < 1e-6
