@@ -1,0 +1,44 @@
+/*
+ * spec_kernels.h -- single-kernel entry points of the verify-step library, exported so that each
+ * building block of spec_verify_step can be tested against the CPU oracle and profiled on its
+ * own.  Same conventions as spec_verify.h: plain device pointers, asynchronous on the given
+ * stream, negative spec_status on failure.  Not needed by an application.
+ */
+#ifndef SPEC_KERNELS_H
+#define SPEC_KERNELS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* dst[i] = src[i] for n_bytes (multiple of 16; both device, 16-byte aligned).  A plain streaming
+ * copy of known size: the yardstick that HBM byte counters and achieved bandwidth are scaled by. */
+int spec_k_copy(const void* src, void* dst, size_t n_bytes, void* stream);
+
+/* sum of n_bytes of device memory read as fp32 -> out[0] per workgroup slot (read-only stream). */
+int spec_k_read(const void* src, size_t n_bytes, float* out, void* stream);
+
+/* D = A * B for one 16x16x32 bf16 MFMA tile, operands and result in plain row-major device arrays
+ * (A bf16[16][32], B bf16[32][16], D fp32[16][16]).  Checks the register layout the GEMM and
+ * attention kernels assume for the matrix instruction. */
+int spec_k_mfma_tile(const void* a_bf16, const void* b_bf16, float* d, void* stream);
+
+/* Y[M][N] = X[M][K] * W^T for a packed bf16 W (see spec_pack_weight): the decoder's skinny GEMM
+ * including the reduction of its K-range partial sums.  X, Y fp32 row-major.  split_x != 0 feeds
+ * each activation as a bf16 head plus a bf16 remainder (two matrix instructions per tile) so that
+ * activation rounding stays near fp32 level.  workspace: device scratch of at least
+ * spec_k_gemm_workspace_bytes(M, N, K). */
+size_t spec_k_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
+int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, int32_t M, int32_t N, int32_t K,
+                     int32_t split_x, void* workspace, void* stream);
+
+/* Same product for a plain fp32 W[N][K]. */
+int spec_k_gemm_f32(const float* x, const float* w, float* y, int32_t M, int32_t N, int32_t K, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

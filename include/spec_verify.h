@@ -1,0 +1,179 @@
+/*
+ * spec_verify.h -- C ABI of the speculative-sampling verify step for AMD MI355X (gfx950).
+ *
+ * One call, spec_verify_step, does what the paper's section "Speculative Sampling Results"
+ * describes after the draft model has proposed its tokens: the target decoder scores the whole
+ * draft window in a single pass over its KV cache, the target and draft probabilities of each
+ * proposed token are compared, a prefix of the proposals is kept, the first rejected position is
+ * resampled from a combination of the two distributions, and one more token is sampled from the
+ * target when every proposal was kept.  The formulas are those of the works the paper cites for
+ * the method: keep proposal x with probability min(1, p(x)/q(x)); resample from
+ * normalize(max(0, p - q)).
+ *
+ * Conventions common to all entry points
+ *  - Every function returns SPEC_OK (0) or a negative spec_status.  Nothing throws or aborts
+ *    across this boundary.  spec_last_error() returns a thread-local message for the last failure.
+ *  - "device" pointers are HIP device memory on the GPU that was current at spec_verify_init;
+ *    "host" pointers are ordinary process memory.  The caller owns every buffer it passes
+ *    (weights, KV cache, kv_len, step inputs and outputs) and the stream; the library owns only
+ *    the handle and the workspace inside it, released by spec_verify_destroy.  The library never
+ *    frees, reallocates or keeps host pointers beyond the call.
+ *  - Work is enqueued on the given hipStream_t (passed as void*; NULL = the default stream) and
+ *    is NOT synchronised: outputs are valid once the caller has synchronised the stream.
+ *    Calls on one handle must not overlap in time (they share its workspace).
+ *  - Host-checkable arguments are validated before anything is launched.  Conditions that depend
+ *    on device data (kv_len + K + 1 > max_kv_len, token id >= vocab, rollback beyond the current
+ *    length) make the affected sequence a no-op (its n_accepted is written as -1), raise a flag
+ *    in the handle and are reported by spec_verify_poll.
+ */
+#ifndef SPEC_VERIFY_H
+#define SPEC_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPEC_OK = 0,
+    SPEC_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, temperature <= 0, ... */
+    SPEC_ERR_SHAPE = -2,         /* model shape the kernels do not support (see spec_model_cfg) */
+    SPEC_ERR_KV_OVERFLOW = -3,   /* a sequence would outgrow max_kv_len (reported by poll) */
+    SPEC_ERR_ALLOC = -4,         /* workspace allocation failed */
+    SPEC_ERR_DEVICE = -5,        /* a HIP call failed; message holds hipGetErrorString */
+    SPEC_ERR_TOKEN_RANGE = -6,   /* a token id outside [0, vocab) (reported by poll) */
+    SPEC_ERR_ROLLBACK = -7       /* rollback to a length above the current one (reported by poll) */
+} spec_status;
+
+typedef struct spec_handle spec_handle;   /* opaque */
+
+#define SPEC_DTYPE_FP32 0   /* weights, embedding and KV cache in fp32 (small configurations) */
+#define SPEC_DTYPE_BF16 1   /* weights, embedding and KV cache in bf16; fp32 accumulation */
+#define SPEC_MAX_BATCH 256
+#define SPEC_MAX_LOOKAHEAD 15
+
+/* Decoder-only transformer: pre-norm residual blocks, RMSNorm, rotary position embedding with
+ * dimension i paired with i + head_dim/2 and angle pos * rope_theta^(-2i/head_dim), grouped-query
+ * attention with score scale 1/sqrt(head_dim), SwiGLU feed-forward, untied LM head, no biases.
+ * Requirements: n_q_heads % n_kv_heads == 0; head_dim in {64, 128} for bf16 (any even value for
+ * fp32); d_model, n_q_heads*head_dim and d_ffn multiples of 32 for bf16;
+ * 1 <= max_batch <= SPEC_MAX_BATCH; 0 <= max_lookahead <= SPEC_MAX_LOOKAHEAD. */
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t max_batch;       /* sequences per step, and number of KV-cache slots */
+    int32_t max_kv_len;      /* positions a slot can hold, window tokens included */
+    int32_t max_lookahead;   /* largest K of any sequence */
+    int32_t dtype;           /* SPEC_DTYPE_* */
+    float rms_eps, rope_theta;
+} spec_model_cfg;
+
+/* Target weights, all device pointers.
+ * Norm gains: fp32[d_model].  tok_embed: dtype[vocab][d_model], rows contiguous.
+ * Projection matrices are logically [out_features][in_features] with
+ *   w_qkv     out = all query heads, then all key heads, then all value heads; in = d_model
+ *   w_o       out = d_model; in = n_q_heads*head_dim
+ *   w_gate_up out = d_ffn gate rows then d_ffn up rows; in = d_model
+ *   w_down    out = d_model; in = d_ffn
+ *   lm_head   out = vocab; in = d_model
+ * fp32: stored exactly so, rows contiguous.
+ * bf16: stored in the streaming tile order produced by spec_pack_weight (below), which lets a
+ *       64-lane wavefront fetch each 16x32 MFMA operand tile as one contiguous 1 KiB read. */
+typedef struct {
+    const float* attn_norm;
+    const void* w_qkv;
+    const void* w_o;
+    const float* ffn_norm;
+    const void* w_gate_up;
+    const void* w_down;
+} spec_layer_weights;
+
+typedef struct {
+    const void* tok_embed;
+    const float* final_norm;
+    const void* lm_head;
+    const spec_layer_weights* layers;   /* host array of n_layers entries (copied at init) */
+} spec_weights;
+
+/* Size in bytes of the packed form of a bf16 [n_out][n_in] matrix (n_out padded to 16). */
+size_t spec_packed_weight_bytes(int32_t n_out, int32_t n_in);
+
+/* Repack a row-major bf16 [n_out][n_in] device matrix into the streaming tile order.
+ * Tile (j, kb) covers output features 16j..16j+15 and input features 32kb..32kb+31 and occupies
+ * 512 consecutive elements at ((j*(n_in/32) + kb)*512); inside a tile, element (lane, e) with
+ * lane in [0,64), e in [0,8) holds W[16j + lane%16][32kb + 8*(lane/16) + e].  Rows beyond n_out
+ * are zero.  With interleave_halves != 0 (used for w_gate_up) tile index j takes its 16 rows from
+ * the first half of the matrix when j is even (rows 16*(j/2)..) and from the second half when j
+ * is odd, so a gate tile and the matching up tile are neighbours; n_out/2 must be a multiple of 16.
+ * n_in must be a multiple of 32.  src and dst must not overlap. */
+int spec_pack_weight(const void* src_row_major, void* dst_packed, int32_t n_out, int32_t n_in,
+                     int32_t interleave_halves, void* stream);
+
+/* Bytes the caller must provide for the KV cache of cfg (all layers, max_batch slots). */
+size_t spec_kv_cache_bytes(const spec_model_cfg* cfg);
+
+/* Create a handle.  weights and kv_cache may both be NULL for a sampler-only handle (every step
+ * must then supply target_logits_in).  kv_cache: device buffer of at least spec_kv_cache_bytes;
+ * its internal tile order is private -- fill and read it with spec_kv_import / spec_kv_export.
+ * kv_len: device int32[max_batch], number of valid cached positions per slot; read and updated
+ * by the step and by rollback.  Allocates the workspace; does not touch the caller's buffers. */
+int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* weights, void* kv_cache,
+                     size_t kv_cache_bytes, int32_t* kv_len, spec_handle** out);
+
+void spec_verify_destroy(spec_handle* h);
+
+/* Inputs of one step.  B = batch; Kmax = cfg.max_lookahead; V = cfg.vocab.
+ * Sequence b scores the window [last_token[b], draft_tokens[b][0..K_b-1]] at positions
+ * n_b .. n_b+K_b where n_b = kv_len[seq_slot[b]].  Target row j of a sequence gives the
+ * distribution of the token following window token j, so row i tests draft i and row K_b is the
+ * distribution of the extra token. */
+typedef struct {
+    int32_t batch;                 /* 1 .. max_batch */
+    const int32_t* lookahead;      /* HOST int32[B]: K_b in 0 .. Kmax */
+    const int32_t* seq_slot;       /* device int32[B]: distinct cache slots in [0, max_batch) */
+    const int32_t* last_token;     /* device int32[B] */
+    const int32_t* draft_tokens;   /* device int32[B][Kmax] (entries >= K_b ignored) */
+    const float* draft_logits;     /* device fp32[B][Kmax][V]; q_i = softmax(draft_logits[b][i]/T) */
+    const float* uniforms;         /* device fp32[B][Kmax+1] in [0,1): [b][i], i < K_b decides draft
+                                      i (kept iff u*q(x) < p(x)); [b][K_b] drives the final draw */
+    float temperature;             /* > 0; applied to target and draft logits alike */
+    const float* target_logits_in; /* optional device fp32[M][V], M = sum(K_b+1), rows ordered by
+                                      (sequence, window offset): if non-NULL the decoder pass is
+                                      skipped and only the sampling part runs */
+    int32_t auto_rollback;         /* 0: leave kv_len[slot] = n_b+K_b+1 (whole window appended);
+                                      1: write kv_len[slot] = n_b + n_accepted + 1 */
+} spec_step_args;
+
+typedef struct {
+    int32_t* n_accepted;           /* device int32[B]: number of drafts kept (-1: sequence skipped) */
+    int32_t* out_tokens;           /* device int32[B][Kmax+1]: kept drafts, final token, then -1 */
+    float* logits_out;             /* optional device fp32[M][V]: target logits of the window */
+} spec_step_out;
+
+/* The verify step.  The final token is drawn by inverse CDF in ascending token id: the first id
+ * whose inclusive prefix sum of r exceeds u*sum(r), with r = max(0, p_a - q_a) at the first
+ * rejected position a, or r = p_K when all K drafts were kept. */
+int spec_verify_step(spec_handle* h, const spec_step_args* args, const spec_step_out* out, void* stream);
+
+/* Set kv_len[seq_slot[i]] = new_len[i] for i < n (host arrays, n <= SPEC_MAX_BATCH).  The cache is
+ * contiguous per slot, so dropping rejected positions moves no data; stale entries are never read
+ * and are overwritten by the next append.  new_len must satisfy 0 <= new_len <= kv_len[slot]. */
+int spec_kv_rollback(spec_handle* h, const int32_t* seq_slot, const int32_t* new_len, int32_t n,
+                     void* stream);
+
+/* Copy positions [pos0, pos0+n_pos) of one slot between the cache and a plain device tensor
+ * dtype[n_layers][2 (k,v)][n_kv_heads][n_pos][head_dim].  Does not change kv_len. */
+int spec_kv_import(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, const void* src, void* stream);
+int spec_kv_export(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, void* dst, void* stream);
+
+/* Synchronise the stream and return the first device-side error raised since the last poll
+ * (SPEC_OK if none); clears the flag. */
+int spec_verify_poll(spec_handle* h, void* stream);
+
+const char* spec_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

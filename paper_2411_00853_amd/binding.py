@@ -1,0 +1,259 @@
+"""ctypes binding of libspecverify.so: the same entry points as include/spec_verify.h and
+include/spec_kernels.h, taking torch tensors where the C side takes device pointers.  Argument
+marshalling only -- no arithmetic of the method happens here, and there is no fallback: if the
+HIP library is missing or fails to load, every call raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+from . import build as _build
+
+SPEC_DTYPE_FP32, SPEC_DTYPE_BF16 = 0, 1
+SPEC_MAX_BATCH, SPEC_MAX_LOOKAHEAD = 256, 15
+SPEC_OK = 0
+
+
+class SpecError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"spec status {status}: {msg}")
+        self.status = status
+
+
+class spec_model_cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn",
+                                         "vocab", "max_batch", "max_kv_len", "max_lookahead", "dtype")] + \
+               [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class spec_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("attn_norm", "w_qkv", "w_o", "ffn_norm", "w_gate_up", "w_down")]
+
+
+class spec_weights(C.Structure):
+    _fields_ = [("tok_embed", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p),
+                ("layers", C.POINTER(spec_layer_weights))]
+
+
+class spec_step_args(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("lookahead", C.POINTER(C.c_int32)), ("seq_slot", C.c_void_p),
+                ("last_token", C.c_void_p), ("draft_tokens", C.c_void_p), ("draft_logits", C.c_void_p),
+                ("uniforms", C.c_void_p), ("temperature", C.c_float), ("target_logits_in", C.c_void_p),
+                ("auto_rollback", C.c_int32)]
+
+
+class spec_step_out(C.Structure):
+    _fields_ = [("n_accepted", C.c_void_p), ("out_tokens", C.c_void_p), ("logits_out", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library (building it first only if it was never built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build_library()
+        L = C.CDLL(_build.LIB)
+        L.spec_last_error.restype = C.c_char_p
+        L.spec_packed_weight_bytes.restype = C.c_size_t
+        L.spec_packed_weight_bytes.argtypes = [C.c_int32, C.c_int32]
+        L.spec_kv_cache_bytes.restype = C.c_size_t
+        L.spec_kv_cache_bytes.argtypes = [C.POINTER(spec_model_cfg)]
+        L.spec_k_gemm_workspace_bytes.restype = C.c_size_t
+        L.spec_k_gemm_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.spec_verify_destroy.restype = None
+        L.spec_verify_destroy.argtypes = [C.c_void_p]
+        L.spec_verify_init.argtypes = [C.POINTER(spec_model_cfg), C.POINTER(spec_weights), C.c_void_p, C.c_size_t,
+                                       C.c_void_p, C.POINTER(C.c_void_p)]
+        L.spec_verify_step.argtypes = [C.c_void_p, C.POINTER(spec_step_args), C.POINTER(spec_step_out), C.c_void_p]
+        L.spec_kv_rollback.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.c_void_p]
+        L.spec_kv_import.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.spec_kv_export.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.spec_verify_poll.argtypes = [C.c_void_p, C.c_void_p]
+        L.spec_pack_weight.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        L.spec_k_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.spec_k_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.spec_k_mfma_tile.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.spec_k_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                       C.c_void_p, C.c_void_p]
+        L.spec_k_gemm_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().spec_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != SPEC_OK:
+        raise SpecError(rc, last_error())
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    """Device pointer of a contiguous CUDA tensor (None passes NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def make_cfg(shape, max_batch: int, max_kv_len: int, max_lookahead: int) -> spec_model_cfg:
+    """spec_model_cfg from a workload.ModelShape-like object."""
+    return spec_model_cfg(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                          shape.d_ffn, shape.vocab, max_batch, max_kv_len, max_lookahead,
+                          SPEC_DTYPE_BF16 if shape.dtype == "bf16" else SPEC_DTYPE_FP32, shape.rms_eps, shape.rope_theta)
+
+
+def sampler_cfg(vocab: int, max_batch: int, max_lookahead: int) -> spec_model_cfg:
+    return spec_model_cfg(0, 0, 0, 0, 0, 0, vocab, max_batch, 0, max_lookahead, 0, 0.0, 0.0)
+
+
+def spec_packed_weight_bytes(n_out: int, n_in: int) -> int:
+    return int(lib().spec_packed_weight_bytes(n_out, n_in))
+
+
+def spec_pack_weight(src: torch.Tensor, interleave_halves: bool = False, stream=None) -> torch.Tensor:
+    """Row-major bf16 [n_out][n_in] device matrix -> new device buffer in streaming tile order."""
+    n_out, n_in = src.shape
+    nbytes = spec_packed_weight_bytes(n_out, n_in)
+    if nbytes == 0:
+        raise SpecError(-2, "matrix shape cannot be packed (n_in must be a multiple of 32)")
+    dst = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=src.device)
+    _check(lib().spec_pack_weight(_ptr(src, torch.bfloat16), _ptr(dst), n_out, n_in, int(interleave_halves),
+                                  _stream(stream)))
+    return dst
+
+
+def spec_kv_cache_bytes(cfg: spec_model_cfg) -> int:
+    return int(lib().spec_kv_cache_bytes(C.byref(cfg)))
+
+
+class Handle:
+    """Owns a spec_handle* and keeps the caller-owned tensors it points into alive."""
+
+    def __init__(self, ptr, cfg, keep):
+        self.ptr, self.cfg, self._keep = ptr, cfg, keep
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def close(self):
+        if getattr(self, "ptr", None):
+            lib().spec_verify_destroy(self.ptr)
+            self.ptr = None
+
+
+def spec_verify_init(cfg: spec_model_cfg, weights: Optional[dict], kv_cache: Optional[torch.Tensor],
+                     kv_len: Optional[torch.Tensor]) -> Handle:
+    """weights: {"tok_embed", "final_norm", "lm_head", "layers": [{"attn_norm", "w_qkv", "w_o", "ffn_norm",
+    "w_gate_up", "w_down"}]} of device tensors already in the layout the header prescribes (bf16
+    projection matrices packed with spec_pack_weight), or None for a sampler-only handle."""
+    out = C.c_void_p()
+    keep = [weights, kv_cache, kv_len]
+    wp = None
+    if weights is not None:
+        L = cfg.n_layers
+        arr = (spec_layer_weights * L)()
+        for l, lw in enumerate(weights["layers"]):
+            arr[l] = spec_layer_weights(_ptr(lw["attn_norm"], torch.float32), _ptr(lw["w_qkv"]), _ptr(lw["w_o"]),
+                                        _ptr(lw["ffn_norm"], torch.float32), _ptr(lw["w_gate_up"]), _ptr(lw["w_down"]))
+        w = spec_weights(_ptr(weights["tok_embed"]), _ptr(weights["final_norm"], torch.float32),
+                         _ptr(weights["lm_head"]), C.cast(arr, C.POINTER(spec_layer_weights)))
+        keep.append(arr)
+        wp = C.byref(w)
+    nbytes = kv_cache.numel() * kv_cache.element_size() if kv_cache is not None else 0
+    _check(lib().spec_verify_init(C.byref(cfg), wp, _ptr(kv_cache), nbytes, _ptr(kv_len, torch.int32), C.byref(out)))
+    return Handle(out.value, cfg, keep)
+
+
+def spec_verify_destroy(h: Handle):
+    h.close()
+
+
+def spec_verify_step(h: Handle, lookahead: Sequence[int], uniforms: torch.Tensor, temperature: float,
+                     n_accepted: torch.Tensor, out_tokens: torch.Tensor, seq_slot: Optional[torch.Tensor] = None,
+                     last_token: Optional[torch.Tensor] = None, draft_tokens: Optional[torch.Tensor] = None,
+                     draft_logits: Optional[torch.Tensor] = None, target_logits_in: Optional[torch.Tensor] = None,
+                     logits_out: Optional[torch.Tensor] = None, auto_rollback: bool = True, stream=None):
+    B = len(lookahead)
+    ks = (C.c_int32 * B)(*[int(k) for k in lookahead])
+    args = spec_step_args(B, ks, _ptr(seq_slot, torch.int32), _ptr(last_token, torch.int32),
+                          _ptr(draft_tokens, torch.int32), _ptr(draft_logits, torch.float32),
+                          _ptr(uniforms, torch.float32), float(temperature), _ptr(target_logits_in, torch.float32),
+                          int(auto_rollback))
+    out = spec_step_out(_ptr(n_accepted, torch.int32), _ptr(out_tokens, torch.int32), _ptr(logits_out, torch.float32))
+    _check(lib().spec_verify_step(h.ptr, C.byref(args), C.byref(out), _stream(stream)))
+
+
+def spec_kv_rollback(h: Handle, seq_slot: Sequence[int], new_len: Sequence[int], stream=None):
+    n = len(seq_slot)
+    a = (C.c_int32 * max(n, 1))(*[int(v) for v in seq_slot])
+    b = (C.c_int32 * max(n, 1))(*[int(v) for v in new_len])
+    _check(lib().spec_kv_rollback(h.ptr, a, b, n, _stream(stream)))
+
+
+def spec_kv_import(h: Handle, slot: int, pos0: int, src: torch.Tensor, stream=None):
+    """src: device tensor [n_layers][2][n_kv_heads][n_pos][head_dim] in the cache's storage dtype."""
+    _check(lib().spec_kv_import(h.ptr, slot, pos0, src.shape[3], _ptr(src), _stream(stream)))
+
+
+def spec_kv_export(h: Handle, slot: int, pos0: int, dst: torch.Tensor, stream=None):
+    _check(lib().spec_kv_export(h.ptr, slot, pos0, dst.shape[3], _ptr(dst), _stream(stream)))
+
+
+def spec_verify_poll(h: Handle, stream=None):
+    _check(lib().spec_verify_poll(h.ptr, _stream(stream)))
+
+
+# ---- single-kernel entry points (include/spec_kernels.h) -----------------------------------------
+
+def spec_k_copy(src: torch.Tensor, dst: torch.Tensor, stream=None):
+    _check(lib().spec_k_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream(stream)))
+
+
+def spec_k_read(src: torch.Tensor, out: torch.Tensor, stream=None):
+    _check(lib().spec_k_read(_ptr(src), src.numel() * src.element_size(), _ptr(out, torch.float32), _stream(stream)))
+
+
+def spec_k_mfma_tile(a: torch.Tensor, b: torch.Tensor, d: torch.Tensor, stream=None):
+    _check(lib().spec_k_mfma_tile(_ptr(a, torch.bfloat16), _ptr(b, torch.bfloat16), _ptr(d, torch.float32),
+                                  _stream(stream)))
+
+
+def spec_k_gemm_bf16(x: torch.Tensor, w_packed: torch.Tensor, n_out: int, split_x: bool = True,
+                     workspace: Optional[torch.Tensor] = None, y: Optional[torch.Tensor] = None, stream=None):
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, n_out), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        nb = int(lib().spec_k_gemm_workspace_bytes(M, n_out, K))
+        workspace = torch.empty(max(nb // 4, 4), dtype=torch.float32, device=x.device)
+    _check(lib().spec_k_gemm_bf16(_ptr(x, torch.float32), _ptr(w_packed), _ptr(y), M, n_out, K, int(split_x),
+                                  _ptr(workspace), _stream(stream)))
+    return y
+
+
+def spec_k_gemm_f32(x: torch.Tensor, w: torch.Tensor, stream=None):
+    M, K = x.shape
+    N = w.shape[0]
+    y = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    _check(lib().spec_k_gemm_f32(_ptr(x, torch.float32), _ptr(w, torch.float32), _ptr(y), M, N, K, _stream(stream)))
+    return y

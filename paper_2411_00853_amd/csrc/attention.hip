@@ -1,0 +1,384 @@
+// Windowed-causal attention of the verify step: the K+1 query tokens of a sequence (times the
+// query heads that share a kv head) attend over the sequence's cached positions plus the window
+// tokens up to and including themselves.  All queries of a (sequence, kv head) share ONE streamed
+// pass over that head's keys and values -- this is why scoring K drafts costs about as much as one
+// token (the paper's observation behind speculative sampling) -- so the kernel is bound by reading
+// the cache from HBM once, and is organised around that stream:
+//
+//  * The cache is stored in operand order (cache_layout.h): every 16-byte lane load of a key or
+//    value operand is part of a contiguous 1 KiB wavefront read, and a 32-position block (keys then
+//    values) is one contiguous 64*hd*2-byte run.  The next block is in flight while the current
+//    one is processed (two register buffers per wavefront).
+//  * Scores are computed transposed (S^T = K * Q^T) so that the exponentiated scores leave the
+//    matrix instruction in exactly the register order the second product (O^T = V^T * P^T) wants:
+//    no LDS round trip, no cross-lane movement except the 2-step maximum over a query's 4 lanes.
+//  * Online softmax in fp32 (base 2), one running maximum and sum per query, per wavefront.
+//  * The position range is cut into chunks across wavefronts to fill the machine; chunk results
+//    (unnormalised output, maximum, sum) are merged by a second small kernel in a fixed order.
+//  * Queries and probabilities enter the bf16 matrix instruction as head + remainder pairs; at a
+//    handful of query rows the matrix cores are far from busy, and this keeps the only bf16
+//    rounding in the path the one that the cache's storage type imposes.
+#include "cache_layout.h"
+#include "common.h"
+
+namespace specv {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+    uint4 u;
+    bf16x8 v;
+    uint16_t h[8];
+};
+
+__device__ __forceinline__ void split_frag(const float (&x)[8], Frag& hi, Frag& lo)
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const __bf16 hb = static_cast<__bf16>(x[e]);
+        hi.v[e] = hb;
+        lo.v[e] = static_cast<__bf16>(x[e] - static_cast<float>(hb));
+    }
+}
+
+template <int HD, int RT>
+__global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadPack ks, CacheGeom g, int n_q_heads,
+                                                        int layer, const uint4* __restrict__ cache,
+                                                        const float* __restrict__ q, int chunk_keys, int max_chunks,
+                                                        int r_cap, float scale_log2e, float* __restrict__ part_o,
+                                                        float* __restrict__ part_ml)
+{
+    constexpr int STEPS = HD / 32;     // 32-dim steps of the score product
+    constexpr int DT = HD / 16;        // 16-dim tiles of the output
+    constexpr int BLK_U4 = 8 * HD;     // uint4 per 32-position block (keys then values)
+    const int lane = threadIdx.x, c16 = lane & 15, gq = lane >> 4;
+    const int item = blockIdx.x;
+    const int chunk = item % max_chunks;
+    const int hkv = (item / max_chunks) % g.n_kv_heads;
+    const int b = item / (max_chunks * g.n_kv_heads);
+    if (!t.seq_ok[b]) return;
+    const int K = ks.k[b];
+    const int n = t.seq_n[b];
+    const int total = n + K + 1;
+    const int key0 = chunk * chunk_keys;
+    if (key0 >= total) return;
+    const int key1 = min(key0 + chunk_keys, total);
+    const int group = n_q_heads / g.n_kv_heads;
+    const int rows = (K + 1) * group;
+    const int dq = n_q_heads * HD;
+    const int row0 = t.seq_row0[b];
+
+    // queries, pre-scaled by log2(e)/sqrt(hd), as bf16 head + remainder operand fragments
+    Frag qh[RT][STEPS], ql[RT][STEPS];
+    int limit[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int r = rt * 16 + c16;
+        const bool real = r < rows;
+        const int j = real ? r / group : 0, hl = real ? r % group : 0;
+        limit[rt] = real ? n + j : -1;   // last visible position of this query
+        const float* src = q + (size_t)(row0 + j) * dq + (hkv * group + hl) * HD + 8 * gq;
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = real ? src[32 * s + e] * scale_log2e : 0.f;
+            split_frag(x, qh[rt][s], ql[rt][s]);
+        }
+    }
+
+    floatx4 acc[RT][DT];
+    float m_run[RT], l_run[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        m_run[rt] = -INFINITY;
+        l_run[rt] = 0.f;
+#pragma unroll
+        for (int d = 0; d < DT; ++d) acc[rt][d] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const uint4* head = cache + cache_head_base(g, layer, t.seq_slot[b], hkv) / 8;
+    const int blk0 = key0 >> 5, blk1 = (key1 + 31) >> 5;
+
+    uint4 ka[2][STEPS], va[DT], kb[2][STEPS], vb[DT];
+    auto load_block = [&](int blk, uint4(&kk)[2][STEPS], uint4(&vv)[DT]) {
+        if (blk < blk1) {
+            const uint4* p = head + (size_t)blk * BLK_U4 + lane;
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s) kk[sub][s] = p[sub * (2 * HD) + s * 64];
+#pragma unroll
+            for (int d = 0; d < DT; ++d) vv[d] = p[4 * HD + d * 64];
+        }
+    };
+    auto process = [&](int blk, const uint4(&kk)[2][STEPS], uint4(&vv)[DT]) {
+        const int kbase = blk * 32;
+        const bool tail = kbase + 32 > n;   // block reaches the window or the end: mask per element
+        if (tail) {
+            // values of positions that do not exist yet may hold anything: zero them
+#pragma unroll
+            for (int d = 0; d < DT; ++d) {
+                Frag f;
+                f.u = vv[d];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int key = kbase + (e < 4 ? 4 * gq + e : 16 + 4 * gq + e - 4);
+                    if (key >= total) f.h[e] = 0;
+                }
+                vv[d] = f.u;
+            }
+        }
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            floatx4 st[2];
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                st[sub] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s) {
+                    Frag kf;
+                    kf.u = kk[sub][s];
+                    st[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qh[rt][s].v, st[sub], 0, 0, 0);
+                    st[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, ql[rt][s].v, st[sub], 0, 0, 0);
+                }
+            }
+            float sv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sv[e] = st[e >> 2][e & 3];
+            if (tail) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int key = kbase + (e < 4 ? 4 * gq + e : 16 + 4 * gq + e - 4);
+                    if (key > limit[rt]) sv[e] = -INFINITY;
+                }
+            }
+            float mx = sv[0];
+#pragma unroll
+            for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[rt], mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = exp2f(m_run[rt] - m_use);
+            m_run[rt] = m_new;
+            float ps = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                sv[e] = exp2f(sv[e] - m_use);
+                ps += sv[e];
+            }
+            l_run[rt] = l_run[rt] * alpha + ps;
+            Frag ph, pl;
+            split_frag(sv, ph, pl);
+#pragma unroll
+            for (int d = 0; d < DT; ++d) {
+                Frag vf;
+                vf.u = vv[d];
+                floatx4 a = acc[rt][d];
+                a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
+                a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, ph.v, a, 0, 0, 0);
+                a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pl.v, a, 0, 0, 0);
+                acc[rt][d] = a;
+            }
+        }
+    };
+
+    load_block(blk0, ka, va);
+    for (int blk = blk0; blk < blk1; blk += 2) {
+        load_block(blk + 1, kb, vb);
+        process(blk, ka, va);
+        if (blk + 1 < blk1) {
+            load_block(blk + 2, ka, va);
+            process(blk + 1, kb, vb);
+        }
+    }
+
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        float l = l_run[rt];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const int r = rt * 16 + c16;
+        if (r < rows) {
+            float* o = part_o + ((size_t)item * r_cap + r) * HD + 4 * gq;
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+                *reinterpret_cast<float4*>(o + 16 * d) = make_float4(acc[rt][d][0], acc[rt][d][1], acc[rt][d][2], acc[rt][d][3]);
+            if (gq == 0) {
+                part_ml[((size_t)item * r_cap + r) * 2 + 0] = m_run[rt];
+                part_ml[((size_t)item * r_cap + r) * 2 + 1] = l;
+            }
+        }
+    }
+}
+
+// out[m][hq][:] = sum_c w_c o_c / sum_c w_c l_c with w_c = 2^(m_c - max m), chunks in index order
+__global__ void attn_merge_kernel(StepTables t, LookaheadPack ks, int n_kv_heads, int n_q_heads, int hd, int chunk_keys,
+                                  int max_chunks, int r_cap, const float* __restrict__ part_o,
+                                  const float* __restrict__ part_ml, float* __restrict__ out)
+{
+    const int m = blockIdx.x, hq = blockIdx.y, dim = threadIdx.x;
+    const int b = t.row_seq[m];
+    float* dst = out + ((size_t)m * n_q_heads + hq) * hd + dim;
+    if (!t.seq_ok[b]) {
+        *dst = 0.f;
+        return;
+    }
+    const int group = n_q_heads / n_kv_heads;
+    const int j = m - t.seq_row0[b];
+    const int r = j * group + hq % group;
+    const int total = t.seq_n[b] + ks.k[b] + 1;
+    const int n_chunks = (total + chunk_keys - 1) / chunk_keys;
+    const size_t item0 = ((size_t)b * n_kv_heads + hq / group) * max_chunks;
+    float mx = -INFINITY;
+    for (int c = 0; c < n_chunks; ++c) mx = fmaxf(mx, part_ml[((item0 + c) * r_cap + r) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int c = 0; c < n_chunks; ++c) {
+        const size_t idx = (item0 + c) * r_cap + r;
+        const float mc = part_ml[idx * 2];
+        if (mc == -INFINITY) continue;   // chunk entirely after this query's position
+        const float w = exp2f(mc - mx);
+        den += w * part_ml[idx * 2 + 1];
+        num += w * part_o[idx * hd + dim];
+    }
+    *dst = num / den;
+}
+
+// Plain fp32 attention for fp32 caches: one workgroup per (row, query head).
+__global__ void __launch_bounds__(256) attn_f32_kernel(StepTables t, CacheGeom g, int n_q_heads, int layer,
+                                                       const float* __restrict__ cache, const float* __restrict__ q,
+                                                       float scale, float* __restrict__ out)
+{
+    extern __shared__ float sh[];   // [hd] query, [n_keys] scores
+    __shared__ float red[4];
+    const int m = blockIdx.x, hq = blockIdx.y;
+    const int hd = g.head_dim;
+    const int pos = t.row_pos[m];
+    float* dst = out + ((size_t)m * n_q_heads + hq) * hd;
+    if (pos < 0) {
+        for (int i = threadIdx.x; i < hd; i += 256) dst[i] = 0.f;
+        return;
+    }
+    const int n_keys = pos + 1;
+    const int slot = t.seq_slot[t.row_seq[m]];
+    const int hkv = hq / (n_q_heads / g.n_kv_heads);
+    const float* kbase = cache + cache_head_base(g, layer, slot, hkv) + plain_offset(g, 0, 0, 0);
+    const float* vbase = cache + cache_head_base(g, layer, slot, hkv) + plain_offset(g, 1, 0, 0);
+    float* qs = sh;
+    float* sc = sh + hd;
+    for (int i = threadIdx.x; i < hd; i += 256) qs[i] = q[((size_t)m * n_q_heads + hq) * hd + i];
+    __syncthreads();
+    float mx = -INFINITY;
+    for (int k = threadIdx.x; k < n_keys; k += 256) {
+        float a = 0.f;
+        for (int e = 0; e < hd; ++e) a = fmaf(qs[e], kbase[(size_t)k * hd + e], a);
+        a *= scale;
+        sc[k] = a;
+        mx = fmaxf(mx, a);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float z = 0.f;
+    for (int k = threadIdx.x; k < n_keys; k += 256) {
+        const float p = expf(sc[k] - mx);
+        sc[k] = p;
+        z += p;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) z += __shfl_xor(z, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = z;
+    __syncthreads();
+    z = (red[0] + red[1]) + (red[2] + red[3]);
+    for (int e = threadIdx.x; e < hd; e += 256) {
+        float a = 0.f;
+        for (int k = 0; k < n_keys; ++k) a = fmaf(sc[k], vbase[(size_t)k * hd + e], a);
+        dst[e] = a / z;
+    }
+}
+
+}  // namespace
+
+AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count)
+{
+    // aim for ~8 wavefronts per compute unit when every sequence is at max length
+    AttnPlan p{};
+    const long want_items = 8L * cu_count;
+    long per = (long)batch * n_kv_heads;
+    long chunks = (want_items + per - 1) / per;
+    long keys = chunks > 0 ? (max_kv_len + chunks - 1) / chunks : max_kv_len;
+    int ck = 32;
+    while (ck < keys && ck < 1024) ck <<= 1;
+    p.chunk_keys = ck;
+    p.max_chunks = (max_kv_len + ck - 1) / ck;
+    return p;
+}
+
+size_t attn_partial_floats(const AttnPlan& p, int max_batch, int n_kv_heads, int group, int max_window, int hd)
+{
+    return (size_t)max_batch * n_kv_heads * p.max_chunks * group * max_window * hd;
+}
+
+template <int HD>
+static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, const LookaheadPack& ks,
+                         const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
+                         const AttnPlan& p, int r_cap, float sl2, float* part_o, float* part_ml)
+{
+#define SPECV_ATTN(RT)                                                                                           \
+    hipLaunchKernelGGL((attn_chunk_kernel<HD, RT>), grid, dim3(64), 0, s, t, ks, g, n_q_heads, layer,            \
+                       (const uint4*)cache, q, p.chunk_keys, p.max_chunks, r_cap, sl2, part_o, part_ml)
+    switch (rt) {
+    case 1: SPECV_ATTN(1); break;
+    case 2: SPECV_ATTN(2); break;
+    case 3: SPECV_ATTN(3); break;
+    case 4: SPECV_ATTN(4); break;
+    default: return fail(SPEC_ERR_SHAPE, "attention supports at most 64 query rows per kv head");
+    }
+#undef SPECV_ATTN
+    SPECV_LAUNCH_CHECK("attn_chunk_kernel");
+    return SPEC_OK;
+}
+
+int launch_attention(const AttnPlan& p, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,
+                     int n_q_heads, int layer, const void* cache, const float* q, float* part_o, float* part_ml,
+                     float* out, int max_window, hipStream_t s)
+{
+    const int hd = g.head_dim;
+    const float scale = 1.0f / sqrtf((float)hd);
+    if (g.dtype != SPEC_DTYPE_BF16) {
+        // scores for one row live in LDS: positions * 4 bytes
+        const size_t lds = (size_t)(hd + g.t_pad) * sizeof(float);
+        if (lds > 60 * 1024) return fail(SPEC_ERR_SHAPE, "fp32 attention supports max_kv_len up to ~15000");
+        hipLaunchKernelGGL(attn_f32_kernel, dim3(M, n_q_heads), dim3(256), lds, s, t, g, n_q_heads, layer,
+                           (const float*)cache, q, scale, out);
+        SPECV_LAUNCH_CHECK("attn_f32_kernel");
+        return SPEC_OK;
+    }
+    const int group = n_q_heads / g.n_kv_heads;
+    const int r_cap = group * max_window;
+    int kmax = 0;
+    for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
+    const int rt = ((kmax + 1) * group + 15) / 16;
+    const dim3 grid((unsigned)B * g.n_kv_heads * p.max_chunks);
+    const float sl2 = scale * 1.4426950408889634f;
+    int rc;
+    if (hd == 128)
+        rc = launch_chunks<128>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml);
+    else if (hd == 64)
+        rc = launch_chunks<64>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml);
+    else
+        return fail(SPEC_ERR_SHAPE, "bf16 attention needs head_dim 64 or 128");
+    if (rc) return rc;
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(M, n_q_heads), dim3(hd), 0, s, t, ks, g.n_kv_heads, n_q_heads, hd,
+                       p.chunk_keys, p.max_chunks, r_cap, part_o, part_ml, out);
+    SPECV_LAUNCH_CHECK("attn_merge_kernel");
+    return SPEC_OK;
+}
+
+}  // namespace specv

@@ -1,0 +1,149 @@
+// The decoder pass of the verify step: the order in which the kernels run for one window.
+// Per layer: RMSNorm -> QKV projection -> rotary + KV append -> windowed-causal attention ->
+// output projection (+residual) -> RMSNorm -> gate/up projection -> SiLU gating -> down projection
+// (+residual); then the final norm and the LM head.  Every reduction of GEMM K-range partial sums
+// is folded into the kernel that consumes the GEMM's result.
+#include <cmath>
+#include <vector>
+
+#include "handle.h"
+
+namespace specv {
+
+namespace {
+struct Dims {
+    int d, dq, dkv, nqkv, F, V;
+};
+Dims dims_of(const spec_model_cfg& c)
+{
+    Dims z;
+    z.d = c.d_model;
+    z.dq = c.n_q_heads * c.head_dim;
+    z.dkv = c.n_kv_heads * c.head_dim;
+    z.nqkv = z.dq + 2 * z.dkv;
+    z.F = c.d_ffn;
+    z.V = c.vocab;
+    return z;
+}
+}  // namespace
+
+int forward_init(spec_handle* h, int max_rows)
+{
+    const spec_model_cfg& c = h->cfg;
+    const Dims z = dims_of(c);
+    h->max_rows = max_rows;
+    h->geom = make_cache_geom(c);
+    if (c.dtype == SPEC_DTYPE_BF16 && max_rows > 352)
+        return fail(SPEC_ERR_SHAPE, "max_batch*(max_lookahead+1) = %d rows exceeds the 352 the bf16 GEMM supports",
+                    max_rows);
+    int rc = SPEC_OK;
+    Arena& a = h->arena;
+    auto A = [&](float** p, size_t count) {
+        if (rc == SPEC_OK) rc = a.alloc(reinterpret_cast<void**>(p), count * sizeof(float));
+    };
+    A(&h->x, (size_t)max_rows * z.d);
+    A(&h->hn, (size_t)max_rows * z.d);
+    A(&h->q, (size_t)max_rows * z.dq);
+    A(&h->att, (size_t)max_rows * z.dq);
+    A(&h->act, (size_t)max_rows * z.F);
+    A(&h->logits, (size_t)max_rows * z.V);
+    A(&h->cos_sin, (size_t)c.max_kv_len * c.head_dim);
+    size_t part = 0;
+    if (c.dtype == SPEC_DTYPE_BF16) {
+        // partial-sum space for the largest GEMM at any row count
+        const int Ns[G_COUNT] = {z.nqkv, z.d, 2 * z.F, z.d, z.V};
+        const int Ks[G_COUNT] = {z.d, z.dq, z.d, z.F, z.d};
+        for (int M = 16; M <= (max_rows + 15) / 16 * 16 && M <= 352; M += 16)
+            for (int i = 0; i < G_COUNT; ++i) {
+                const int rows = M < max_rows ? M : max_rows;
+                const size_t e = gemm_partial_elems(plan_gemm(rows, Ns[i], Ks[i], h->cu_count), rows);
+                if (e > part) part = e;
+            }
+        h->attn_plan = plan_attention(c.max_kv_len, c.max_batch, c.n_kv_heads, h->cu_count);
+        const int group = c.n_q_heads / c.n_kv_heads;
+        const size_t po = attn_partial_floats(h->attn_plan, c.max_batch, c.n_kv_heads, group, c.max_lookahead + 1,
+                                              c.head_dim);
+        A(&h->attn_part_o, po);
+        A(&h->attn_part_ml, po / c.head_dim * 2);
+    } else {
+        // fp32 path: GEMM results are written whole; one buffer wide enough for any of them
+        part = (size_t)max_rows * (size_t)std::max(std::max(z.nqkv, 2 * z.F), z.d);
+    }
+    A(&h->partial, part);
+    if (rc) return rc;
+
+    // rotary table in fp64 on the host: cos, sin of pos * theta^(-2i/hd)
+    const int half = c.head_dim / 2;
+    std::vector<float> tab((size_t)c.max_kv_len * c.head_dim);
+    for (int pos = 0; pos < c.max_kv_len; ++pos)
+        for (int i = 0; i < half; ++i) {
+            const double ang = (double)pos * std::pow((double)c.rope_theta, -2.0 * i / (double)c.head_dim);
+            tab[((size_t)pos * half + i) * 2 + 0] = (float)std::cos(ang);
+            tab[((size_t)pos * half + i) * 2 + 1] = (float)std::sin(ang);
+        }
+    SPECV_HIP(hipMemcpy(h->cos_sin, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice));
+    return SPEC_OK;
+}
+
+int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s)
+{
+    const spec_model_cfg& c = h->cfg;
+    const Dims z = dims_of(c);
+    const bool bf16 = c.dtype == SPEC_DTYPE_BF16;
+    const StepTables& t = h->tables;
+    int rc;
+#define RUN(expr)            \
+    do {                     \
+        rc = (expr);         \
+        if (rc) return rc;   \
+    } while (0)
+
+    // A GEMM leaves either K-range partial sums (bf16) or the whole result (fp32) in h->partial;
+    // the consumer is told how many ranges to add and the row stride.
+    struct Out {
+        int n_split;
+        size_t stride;
+        int ld;
+    };
+    auto gemm = [&](const float* xin, const void* w, int N, int K, Out* o) -> int {
+        if (bf16) {
+            const GemmPlan p = plan_gemm(M, N, K, h->cu_count);
+            o->n_split = p.n_split;
+            o->ld = p.n_pad;
+            o->stride = (size_t)M * p.n_pad;
+            return launch_gemm_bf16(p, xin, w, M, N, K, h->split_act, h->partial, s);
+        }
+        o->n_split = 1;
+        o->ld = N;
+        o->stride = 0;
+        return launch_gemm_f32(xin, (const float*)w, M, N, K, h->partial, s);
+    };
+
+    RUN(launch_embed_rmsnorm(c.dtype, h->tok_embed, t.row_tok, h->layers[0].attn_norm, c.rms_eps, M, z.d, h->x, h->hn, s));
+    Out o;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const spec_layer_weights& w = h->layers[l];
+        RUN(gemm(h->hn, w.w_qkv, z.nqkv, z.d, &o));
+        RUN(launch_rope_append(h->partial, o.n_split, o.stride, o.ld, t, M, h->geom, c.n_q_heads, l, h->cos_sin,
+                               h->kv_cache, h->q, s));
+        RUN(launch_attention(h->attn_plan, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache, h->q, h->attn_part_o,
+                             h->attn_part_ml, h->att, c.max_lookahead + 1, s));
+        RUN(gemm(h->att, w.w_o, z.d, z.dq, &o));
+        RUN(launch_resid_rmsnorm(h->partial, o.n_split, o.stride, o.ld, w.ffn_norm, c.rms_eps, M, z.d, h->x, h->hn, s));
+        RUN(gemm(h->hn, w.w_gate_up, 2 * z.F, z.d, &o));
+        RUN(launch_silu_mul(h->partial, o.n_split, o.stride, o.ld, M, z.F, bf16, h->act, s));
+        RUN(gemm(h->act, w.w_down, z.d, z.F, &o));
+        const float* next_gain = (l + 1 < c.n_layers) ? h->layers[l + 1].attn_norm : h->final_norm;
+        RUN(launch_resid_rmsnorm(h->partial, o.n_split, o.stride, o.ld, next_gain, c.rms_eps, M, z.d, h->x, h->hn, s));
+    }
+    if (bf16) {
+        RUN(gemm(h->hn, h->lm_head, z.V, z.d, &o));
+        RUN(launch_reduce_splits(h->partial, o.n_split, o.stride, M, z.V, o.ld, logits_out, s));
+    } else {
+        RUN(launch_gemm_f32(h->hn, (const float*)h->lm_head, M, z.V, z.d, logits_out, s));
+    }
+#undef RUN
+    return SPEC_OK;
+}
+
+}  // namespace specv

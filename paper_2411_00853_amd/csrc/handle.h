@@ -1,0 +1,57 @@
+// The opaque handle behind spec_verify.h and the decoder-pass entry points it drives.
+#pragma once
+
+#include <vector>
+
+#include "common.h"
+
+namespace specv {
+
+struct Arena {
+    std::vector<void*> blocks;
+    size_t total = 0;
+    int alloc(void** out, size_t bytes);
+    void release();
+};
+
+enum GemmId { G_QKV = 0, G_O, G_GATE_UP, G_DOWN, G_LM_HEAD, G_COUNT };
+
+}  // namespace specv
+
+struct spec_handle {
+    spec_model_cfg cfg;
+    bool has_model = false;
+    int device = 0;
+    int cu_count = 256;
+    void* kv_cache = nullptr;
+    int32_t* kv_len = nullptr;
+    int32_t* flag = nullptr;
+    specv::Arena arena;
+    specv::StepTables tables{};
+    specv::SamplerWorkspace sampler{};
+
+    // decoder pass
+    std::vector<spec_layer_weights> layers;
+    const void* tok_embed = nullptr;
+    const float* final_norm = nullptr;
+    const void* lm_head = nullptr;
+    specv::CacheGeom geom{};
+    specv::AttnPlan attn_plan{};
+    bool split_act = true;     // feed activations to the matrix cores as bf16 head + remainder
+    float* x = nullptr;        // [rows][d_model] residual stream
+    float* hn = nullptr;       // [rows][d_model] normalised activations
+    float* q = nullptr;        // [rows][n_q_heads*head_dim] rotated queries
+    float* att = nullptr;      // [rows][n_q_heads*head_dim] attention output
+    float* act = nullptr;      // [rows][d_ffn]
+    float* partial = nullptr;  // K-range partial sums of the current GEMM
+    float* logits = nullptr;   // [rows][vocab] when the caller gives no logits_out
+    float* cos_sin = nullptr;  // rotary table
+    float* attn_part_o = nullptr;
+    float* attn_part_ml = nullptr;
+    int max_rows = 0;
+};
+
+namespace specv {
+int forward_init(spec_handle* h, int max_rows);
+int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s);
+}  // namespace specv

@@ -1,0 +1,461 @@
+// Rejection-sampling part of the verify step: softmax statistics of every target and draft row,
+// the accept scan, the residual / extra-token draw and the KV length update.
+//
+// The procedure is the one the paper describes in its section "Speculative Sampling Results"
+// (compare the two models' probabilities of each proposed token, keep a prefix, resample the
+// first rejected token from a combination of the distributions, draw one more token from the
+// target if nothing was rejected), with the cited works' formulas: keep x iff u*q(x) < p(x),
+// resample from max(0, p - q).
+//
+// The vocabulary-wide work is pure streaming, so it is laid out for HBM: every logit is read once
+// by the statistics pass (float4 per lane, 32 values per lane in flight); only the one or two
+// rows that the final draw needs are read again.  Sums are kept in fp64 and every reduction has a
+// fixed order (no floating-point atomics), so results are reproducible bit for bit.
+#include "common.h"
+
+namespace specv {
+
+namespace {
+
+constexpr int TPB = 256;
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row bookkeeping.  One workgroup; thread b owns sequence b.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(TPB) prepare_kernel(StepTables t, LookaheadPack ks, int B, int Kmax, int V,
+                                                      int max_batch, int max_kv_len, int has_cache,
+                                                      const int32_t* __restrict__ seq_slot,
+                                                      const int32_t* __restrict__ last_token,
+                                                      const int32_t* __restrict__ draft_tokens,
+                                                      const int32_t* __restrict__ kv_len, int32_t* flag)
+{
+    __shared__ int row0[SPEC_MAX_BATCH + 1];
+    const int b = threadIdx.x;
+    if (b == 0) {
+        int r = 0, st = 0;
+        for (int i = 0; i < B; ++i) {
+            row0[i] = r;
+            t.seq_row0[i] = r;
+            t.seq_stat0[i] = st;
+            r += ks.k[i] + 1;
+            st += 2 * ks.k[i] + 1;
+        }
+        row0[B] = r;
+        t.seq_row0[B] = r;
+        t.seq_stat0[B] = st;
+    }
+    __syncthreads();
+    if (b >= B) return;
+    const int K = ks.k[b];
+    int ok = 1, err = 0;
+    int slot = b, n = 0;
+    if (has_cache) {
+        slot = seq_slot[b];
+        if (slot < 0 || slot >= max_batch) {
+            ok = 0;
+            err = SPEC_ERR_INVALID_ARG;
+            slot = 0;
+        } else {
+            // two sequences of one step must not share a slot
+            for (int i = 0; i < b; ++i)
+                if (seq_slot[i] == slot) { ok = 0; err = SPEC_ERR_INVALID_ARG; }
+            n = kv_len[slot];
+            if (n < 0 || n + K + 1 > max_kv_len) { ok = 0; err = SPEC_ERR_KV_OVERFLOW; }
+        }
+    }
+    int t0 = last_token ? last_token[b] : 0;
+    if (t0 < 0 || t0 >= V) { ok = 0; err = SPEC_ERR_TOKEN_RANGE; }
+    for (int i = 0; i < K; ++i) {
+        int x = draft_tokens[b * Kmax + i];
+        if (x < 0 || x >= V) { ok = 0; err = SPEC_ERR_TOKEN_RANGE; }
+    }
+    if (!ok) atomicCAS(flag, 0, err);
+    t.seq_n[b] = ok ? n : 0;
+    t.seq_ok[b] = ok;
+    t.seq_slot[b] = slot;
+    for (int j = 0; j <= K; ++j) {
+        int r = row0[b] + j;
+        t.row_seq[r] = b;
+        t.row_pos[r] = ok ? n + j : -1;
+        int tok = (j == 0) ? t0 : draft_tokens[b * Kmax + j - 1];
+        t.row_tok[r] = ok ? tok : 0;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 1: per (row, chunk) maximum and sum of exp((l - max)/T).
+// Statistics rows of sequence b: K_b+1 target rows, then K_b draft rows.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ const float* stat_row_ptr(const StepTables& t, const LookaheadPack& ks, int b, int local,
+                                                     int Kmax, int V, const float* target, const float* draft)
+{
+    const int K = ks.k[b];
+    if (local <= K) return target + (size_t)(t.seq_row0[b] + local) * V;
+    return draft + ((size_t)b * Kmax + (local - K - 1)) * V;
+}
+
+template <bool VEC4>
+__global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack ks, int B, int Kmax, int V,
+                                                    int n_chunks, const float* __restrict__ target,
+                                                    const float* __restrict__ draft, float inv_T,
+                                                    float* __restrict__ part_max, double* __restrict__ part_sum)
+{
+    __shared__ float smax[TPB / 64];
+    __shared__ double ssum[TPB / 64];
+    const int srow = blockIdx.x / n_chunks;
+    const int chunk = blockIdx.x % n_chunks;
+    // find the sequence of this statistics row (B <= 256: a short scan of the prefix array)
+    int b = 0;
+    while (b + 1 < B && t.seq_stat0[b + 1] <= srow) ++b;
+    const float* row = stat_row_ptr(t, ks, b, srow - t.seq_stat0[b], Kmax, V, target, draft);
+    const int base = chunk * STAT_CHUNK;
+    const int lim = min(STAT_CHUNK, V - base);
+
+    constexpr int PER = STAT_CHUNK / TPB;   // 32 values per lane
+    float v[PER];
+    if constexpr (VEC4) {
+        const float4* p4 = reinterpret_cast<const float4*>(row + base);
+#pragma unroll
+        for (int i = 0; i < PER / 4; ++i) {
+            int idx = i * TPB + threadIdx.x;
+            float4 x = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (idx * 4 < lim) x = p4[idx];   // lim is a multiple of 4 when VEC4
+            v[4 * i + 0] = x.x; v[4 * i + 1] = x.y; v[4 * i + 2] = x.z; v[4 * i + 3] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            int idx = i * TPB + threadIdx.x;
+            v[i] = idx < lim ? row[base + idx] : -INFINITY;
+        }
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) m = fmaxf(m, v[i]);
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) smax[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(smax[0], smax[1]), fmaxf(smax[2], smax[3]));
+    const float mm = (m == -INFINITY) ? 0.f : m;   // a chunk of -inf logits contributes nothing
+
+    double acc = 0.0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) acc += (double)__expf((v[i] - mm) * inv_T);   // exp(-inf) = 0 for padding
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) ssum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        part_max[(size_t)srow * n_chunks + chunk] = m;
+        part_sum[(size_t)srow * n_chunks + chunk] = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+    }
+}
+
+// Combine the chunk statistics of one row: max of maxima, sums rescaled to it.
+__device__ __forceinline__ void combine_row(const float* pm, const double* ps, int n_chunks, double inv_T, float* m_out,
+                                            double* z_out)
+{
+    float m = -INFINITY;
+    for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, pm[c]);
+    double z = 0.0;
+    for (int c = 0; c < n_chunks; ++c) z += ps[c] * exp((double)(pm[c] - m) * inv_T);
+    *m_out = m;
+    *z_out = z;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 2: accept scan (every workgroup of a sequence repeats it: a handful of scalars) and the
+// mass of the final-draw distribution inside this workgroup's chunk of the vocabulary.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(TPB) accept_mass_kernel(StepTables t, LookaheadPack ks, int Kmax, int V,
+                                                          int n_stat_chunks, int n_res_chunks,
+                                                          const float* __restrict__ target,
+                                                          const float* __restrict__ draft,
+                                                          const int32_t* __restrict__ draft_tokens,
+                                                          const float* __restrict__ uniforms, float inv_T_f,
+                                                          const float* __restrict__ part_max,
+                                                          const double* __restrict__ part_sum, SamplerWorkspace w)
+{
+    __shared__ float row_m[2 * SPEC_MAX_LOOKAHEAD + 2];
+    __shared__ double row_z[2 * SPEC_MAX_LOOKAHEAD + 2];
+    __shared__ int s_a;
+    __shared__ double ssum[TPB / 64];
+    const int b = blockIdx.y;
+    const int chunk = blockIdx.x;
+    const int K = ks.k[b];
+    const double inv_T = (double)inv_T_f;
+    const int st0 = t.seq_stat0[b];
+    if ((int)threadIdx.x < 2 * K + 1)
+        combine_row(part_max + (size_t)(st0 + threadIdx.x) * n_stat_chunks,
+                    part_sum + (size_t)(st0 + threadIdx.x) * n_stat_chunks, n_stat_chunks, inv_T,
+                    &row_m[threadIdx.x], &row_z[threadIdx.x]);
+    __syncthreads();
+    const float* trow0 = target + (size_t)t.seq_row0[b] * V;
+    const float* drow0 = draft + (size_t)b * Kmax * V;
+    if (threadIdx.x == 0) {
+        int a = K;
+        for (int i = 0; i < K; ++i) {
+            const int x = draft_tokens[b * Kmax + i];
+            const bool xin = x >= 0 && x < V;   // out-of-range ids were flagged by prepare; stay in bounds
+            const float lp = xin ? trow0[(size_t)i * V + x] : 0.f;
+            const float lq = xin ? drow0[(size_t)i * V + x] : 0.f;
+            const double ep = exp((double)(lp - row_m[i]) * inv_T);
+            const double eq = exp((double)(lq - row_m[K + 1 + i]) * inv_T);
+            // keep iff u * q(x) < p(x)  <=>  u * eq * Zp < ep * Zq
+            const double u = (double)uniforms[b * (Kmax + 1) + i];
+            if (!(u * eq * row_z[i] < ep * row_z[K + 1 + i])) { a = i; break; }
+        }
+        s_a = a;
+    }
+    __syncthreads();
+    const int a = s_a;
+    const bool residual = a < K;
+    const float* prow = trow0 + (size_t)a * V;            // a == K: the extra-token row
+    const float* qrow = drow0 + (size_t)(residual ? a : 0) * V;
+    const float mp = row_m[a];
+    const double izp = 1.0 / row_z[a];
+    const float mq = residual ? row_m[K + 1 + a] : 0.f;
+    const double izq = residual ? 1.0 / row_z[K + 1 + a] : 0.0;
+
+    const int base = chunk * RES_CHUNK;
+    const int lim = min(RES_CHUNK, V - base);
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < lim; i += TPB) {
+        double pv = (double)__expf((prow[base + i] - mp) * inv_T_f) * izp;
+        if (residual) {
+            double qv = (double)__expf((qrow[base + i] - mq) * inv_T_f) * izq;
+            pv = pv > qv ? pv - qv : 0.0;
+        }
+        acc += pv;
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) ssum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        w.chunk_mass[(size_t)b * n_res_chunks + chunk] = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+        if (chunk == 0) {
+            w.accepted[b] = a;
+            w.row_max[2 * b] = mp;
+            w.row_max[2 * b + 1] = mq;
+            w.row_inv_z[2 * b] = izp;
+            w.row_inv_z[2 * b + 1] = izq;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 3: locate u*S among the chunk masses, scan that chunk in ascending token id, emit.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, LookaheadPack ks, int Kmax, int V,
+                                                         int n_res_chunks, const float* __restrict__ target,
+                                                         const float* __restrict__ draft,
+                                                         const int32_t* __restrict__ draft_tokens,
+                                                         const float* __restrict__ uniforms, float inv_T_f,
+                                                         SamplerWorkspace w, int auto_rollback, int32_t* kv_len,
+                                                         int32_t* __restrict__ n_accepted,
+                                                         int32_t* __restrict__ out_tokens)
+{
+    __shared__ double r[RES_CHUNK];
+    __shared__ double wave_tot[TPB / 64];
+    __shared__ int s_chunk, s_tok;
+    __shared__ double s_before, s_target;
+    const int b = blockIdx.x;
+    const int K = ks.k[b];
+    if (!t.seq_ok[b]) {
+        if (threadIdx.x == 0) n_accepted[b] = -1;
+        for (int i = threadIdx.x; i <= Kmax; i += TPB) out_tokens[b * (Kmax + 1) + i] = -1;
+        return;
+    }
+    const int a = w.accepted[b];
+    bool residual = a < K;
+    const double* mass = w.chunk_mass + (size_t)b * n_res_chunks;
+    if (threadIdx.x == 0) {
+        double S = 0.0;
+        for (int c = 0; c < n_res_chunks; ++c) S += mass[c];
+        // S > 0 always holds for the extra-token row; for a residual it holds in exact arithmetic
+        // (a rejection means p(x) < q(x), so p exceeds q elsewhere).  S <= 0 falls back to p_a below.
+        s_before = S;
+        s_chunk = -1;
+        if (S > 0.0) {
+            const double target_mass = (double)uniforms[b * (Kmax + 1) + K] * S;
+            double c0 = 0.0;
+            int pick = -1, last_pos = -1;
+            double last_before = 0.0;
+            for (int c = 0; c < n_res_chunks; ++c) {
+                if (mass[c] > 0.0) { last_pos = c; last_before = c0; }
+                if (c0 + mass[c] > target_mass) { pick = c; break; }
+                c0 += mass[c];
+            }
+            if (pick < 0) { pick = last_pos; c0 = last_before; }
+            s_chunk = pick;
+            s_before = c0;
+            s_target = target_mass;
+        }
+    }
+    __syncthreads();
+    const float* prow = target + (size_t)(t.seq_row0[b] + a) * V;
+    const float* qrow = draft + ((size_t)b * Kmax + (residual ? a : 0)) * V;
+    const float mp = w.row_max[2 * b], mq = w.row_max[2 * b + 1];
+    const double izp = w.row_inv_z[2 * b], izq = w.row_inv_z[2 * b + 1];
+    int c_lo = s_chunk, c_hi = s_chunk + 1;
+    double before = s_before, target_mass = s_target;
+    if (s_chunk < 0) {   // degenerate residual: draw from p_a over the whole vocabulary, chunk by chunk
+        residual = false;
+        c_lo = 0;
+        c_hi = n_res_chunks;
+        before = 0.0;
+        target_mass = (double)uniforms[b * (Kmax + 1) + K];   // p_a sums to 1
+    }
+    if (threadIdx.x == 0) s_tok = -1;
+    int last_positive = -1;
+    constexpr int PER = RES_CHUNK / TPB;   // 16 consecutive ids per lane
+    for (int c = c_lo; c < c_hi; ++c) {
+        const int base = c * RES_CHUNK;
+        const int lim = min(RES_CHUNK, V - base);
+        __syncthreads();
+        for (int i = threadIdx.x; i < RES_CHUNK; i += TPB) {
+            double pv = 0.0;
+            if (i < lim) {
+                pv = (double)__expf((prow[base + i] - mp) * inv_T_f) * izp;
+                if (residual) {
+                    double qv = (double)__expf((qrow[base + i] - mq) * inv_T_f) * izq;
+                    pv = pv > qv ? pv - qv : 0.0;
+                }
+            }
+            r[i] = pv;
+        }
+        __syncthreads();
+        // lane-local sums of 16 consecutive ids, then an inclusive scan over the 256 lanes
+        double loc = 0.0;
+        int my_last = -1;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            double x = r[threadIdx.x * PER + i];
+            loc += x;
+            if (x > 0.0) my_last = base + threadIdx.x * PER + i;
+        }
+        double inc = loc;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            double up = __shfl_up(inc, o);
+            if ((int)(threadIdx.x & 63) >= o) inc += up;
+        }
+        if ((threadIdx.x & 63) == 63) wave_tot[threadIdx.x >> 6] = inc;
+        __syncthreads();
+        double off = before;
+        for (int wv = 0; wv < (int)(threadIdx.x >> 6); ++wv) off += wave_tot[wv];
+        inc += off;
+        const double exc = inc - loc;
+        // the lane whose range [exc, inc) the target mass falls in walks its ids
+        if (inc > target_mass && !(exc > target_mass)) {
+            double cdf = exc;
+            int tok = -1;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                cdf += r[threadIdx.x * PER + i];
+                if (tok < 0 && cdf > target_mass) tok = base + threadIdx.x * PER + i;
+            }
+            if (tok < 0) tok = my_last;   // rounding between the lane sum and the running sum
+            if (tok >= 0) atomicMax(&s_tok, tok);
+        }
+        // remember the last id with positive mass in case rounding leaves no crossing at all
+        int wl = my_last;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) wl = max(wl, __shfl_xor(wl, o));
+        last_positive = max(last_positive, wl);
+        __syncthreads();
+        if (s_tok >= 0) break;
+        before += (wave_tot[0] + wave_tot[1]) + (wave_tot[2] + wave_tot[3]);
+    }
+    __syncthreads();
+    // cross-wave maximum of last_positive through LDS (reuse wave_tot storage as ints is not safe; use r)
+    int* scratch = reinterpret_cast<int*>(r);
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = last_positive;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int y = s_tok;
+        if (y < 0) y = max(max(scratch[0], scratch[1]), max(scratch[2], scratch[3]));
+        if (y < 0) y = 0;
+        n_accepted[b] = a;
+        int32_t* o = out_tokens + b * (Kmax + 1);
+        for (int i = 0; i < a; ++i) o[i] = draft_tokens[b * Kmax + i];
+        o[a] = y;
+        for (int i = a + 1; i <= Kmax; ++i) o[i] = -1;
+        if (kv_len) kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : K) + 1;
+    }
+}
+
+// kv_len[slot] = len where 0 <= len <= kv_len[slot]; anything else leaves the slot alone and flags.
+__global__ void __launch_bounds__(TPB) rollback_kernel(RollbackPack p, int n, int max_batch, int32_t* kv_len,
+                                                       int32_t* flag)
+{
+    const int i = threadIdx.x;
+    if (i >= n) return;
+    const int slot = p.slot[i], len = p.len[i];
+    if (slot < 0 || slot >= max_batch) { atomicCAS(flag, 0, (int)SPEC_ERR_INVALID_ARG); return; }
+    if (len < 0 || len > kv_len[slot]) { atomicCAS(flag, 0, (int)SPEC_ERR_ROLLBACK); return; }
+    kv_len[slot] = len;
+}
+
+}  // namespace
+
+int launch_prepare(const StepTables& t, const LookaheadPack& ks, int B, int Kmax, int V, int max_batch,
+                   int max_kv_len, bool has_cache, const int32_t* seq_slot, const int32_t* last_token,
+                   const int32_t* draft_tokens, const int32_t* kv_len, int32_t* flag, hipStream_t s)
+{
+    hipLaunchKernelGGL(prepare_kernel, dim3(1), dim3(TPB), 0, s, t, ks, B, Kmax, V, max_batch, max_kv_len,
+                       has_cache ? 1 : 0, seq_slot, last_token, draft_tokens, kv_len, flag);
+    SPECV_LAUNCH_CHECK("prepare_kernel");
+    return SPEC_OK;
+}
+
+int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len, int32_t* flag, hipStream_t s)
+{
+    hipLaunchKernelGGL(rollback_kernel, dim3(1), dim3(TPB), 0, s, p, n, max_batch, kv_len, flag);
+    SPECV_LAUNCH_CHECK("rollback_kernel");
+    return SPEC_OK;
+}
+
+int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax,
+                   int V, int n_stat_rows, const float* target_logits, const float* draft_logits,
+                   const int32_t* draft_tokens, const float* uniforms, float temperature, int auto_rollback,
+                   int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens, hipStream_t s)
+{
+    const int n_stat_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
+    const int n_res_chunks = (V + RES_CHUNK - 1) / RES_CHUNK;
+    const float inv_T = 1.0f / temperature;
+    const bool vec4 = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(target_logits) & 15) == 0)
+                      && ((reinterpret_cast<uintptr_t>(draft_logits) & 15) == 0);
+    dim3 g1((unsigned)n_stat_rows * n_stat_chunks);
+    if (vec4)
+        hipLaunchKernelGGL(stats_kernel<true>, g1, dim3(TPB), 0, s, t, ks, B, Kmax, V, n_stat_chunks,
+                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum);
+    else
+        hipLaunchKernelGGL(stats_kernel<false>, g1, dim3(TPB), 0, s, t, ks, B, Kmax, V, n_stat_chunks,
+                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum);
+    SPECV_LAUNCH_CHECK("stats_kernel");
+    hipLaunchKernelGGL(accept_mass_kernel, dim3(n_res_chunks, B), dim3(TPB), 0, s, t, ks, Kmax, V, n_stat_chunks,
+                       n_res_chunks, target_logits, draft_logits, draft_tokens, uniforms, inv_T, w.part_max,
+                       w.part_sum, w);
+    SPECV_LAUNCH_CHECK("accept_mass_kernel");
+    hipLaunchKernelGGL(final_draw_kernel, dim3(B), dim3(TPB), 0, s, t, ks, Kmax, V, n_res_chunks, target_logits,
+                       draft_logits, draft_tokens, uniforms, inv_T, w, auto_rollback, kv_len, n_accepted,
+                       out_tokens);
+    SPECV_LAUNCH_CHECK("final_draw_kernel");
+    return SPEC_OK;
+}
+
+}  // namespace specv

@@ -1,0 +1,291 @@
+// C ABI of the verify step: handle, argument checks, workspace, and the order of kernel launches.
+// Every step of the path runs in the kernels of this library; this file only validates, sizes and
+// enqueues.
+#include "common.h"
+#include "handle.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+namespace specv {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int fail(int status, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int Arena::alloc(void** out, size_t bytes)
+{
+    *out = nullptr;
+    if (bytes == 0) bytes = 16;
+    void* p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(SPEC_ERR_ALLOC, "workspace allocation of %zu bytes failed", bytes);
+    }
+    blocks.push_back(p);
+    total += bytes;
+    *out = p;
+    return SPEC_OK;
+}
+
+void Arena::release()
+{
+    for (void* p : blocks) (void)hipFree(p);
+    blocks.clear();
+    total = 0;
+}
+
+static int check_cfg(const spec_model_cfg* c, bool has_model)
+{
+    if (!c) return fail(SPEC_ERR_INVALID_ARG, "cfg is NULL");
+    if (c->vocab <= 0) return fail(SPEC_ERR_INVALID_ARG, "vocab must be positive");
+    if (c->max_batch < 1 || c->max_batch > SPEC_MAX_BATCH)
+        return fail(SPEC_ERR_INVALID_ARG, "max_batch must be in 1..%d", SPEC_MAX_BATCH);
+    if (c->max_lookahead < 0 || c->max_lookahead > SPEC_MAX_LOOKAHEAD)
+        return fail(SPEC_ERR_INVALID_ARG, "max_lookahead must be in 0..%d", SPEC_MAX_LOOKAHEAD);
+    if (!has_model) return SPEC_OK;
+    if (c->dtype != SPEC_DTYPE_FP32 && c->dtype != SPEC_DTYPE_BF16)
+        return fail(SPEC_ERR_INVALID_ARG, "dtype must be SPEC_DTYPE_FP32 or SPEC_DTYPE_BF16");
+    if (c->n_layers <= 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0
+        || c->d_ffn <= 0 || c->max_kv_len <= 0)
+        return fail(SPEC_ERR_INVALID_ARG, "model dimensions must be positive");
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f))
+        return fail(SPEC_ERR_INVALID_ARG, "rms_eps must be >= 0 and rope_theta > 0");
+    if (c->n_q_heads % c->n_kv_heads) return fail(SPEC_ERR_SHAPE, "n_q_heads must be a multiple of n_kv_heads");
+    if (c->head_dim & 1) return fail(SPEC_ERR_SHAPE, "head_dim must be even");
+    if (c->max_kv_len < c->max_lookahead + 1)
+        return fail(SPEC_ERR_SHAPE, "max_kv_len must hold at least one window");
+    if (c->dtype == SPEC_DTYPE_BF16) {
+        if (c->head_dim != 64 && c->head_dim != 128) return fail(SPEC_ERR_SHAPE, "bf16 needs head_dim 64 or 128");
+        if (c->d_model % 32 || (c->n_q_heads * c->head_dim) % 32 || c->d_ffn % 32)
+            return fail(SPEC_ERR_SHAPE, "bf16 needs d_model, n_q_heads*head_dim and d_ffn multiples of 32");
+        if ((c->n_q_heads / c->n_kv_heads) * (c->max_lookahead + 1) > 64)
+            return fail(SPEC_ERR_SHAPE, "query heads per kv head times window length must not exceed 64");
+    } else {
+        if (c->head_dim > 256) return fail(SPEC_ERR_SHAPE, "fp32 needs head_dim <= 256");
+    }
+    return SPEC_OK;
+}
+
+}  // namespace specv
+
+using namespace specv;
+
+extern "C" const char* spec_last_error(void) { return g_err; }
+
+extern "C" size_t spec_kv_cache_bytes(const spec_model_cfg* c)
+{
+    if (check_cfg(c, true) != SPEC_OK) return 0;
+    CacheGeom g = make_cache_geom(*c);
+    return g.layer_stride * (size_t)c->n_layers * (c->dtype == SPEC_DTYPE_BF16 ? 2 : 4);
+}
+
+extern "C" int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* weights, void* kv_cache,
+                                size_t kv_cache_bytes, int32_t* kv_len, spec_handle** out)
+{
+    if (!out) return fail(SPEC_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    const bool has_model = weights != nullptr;
+    int rc = check_cfg(cfg, has_model);
+    if (rc) return rc;
+    if (has_model) {
+        if (!kv_cache || !kv_len) return fail(SPEC_ERR_INVALID_ARG, "a handle with weights needs kv_cache and kv_len");
+        if (!weights->tok_embed || !weights->final_norm || !weights->lm_head || !weights->layers)
+            return fail(SPEC_ERR_INVALID_ARG, "weights has a NULL member");
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            const spec_layer_weights& w = weights->layers[l];
+            if (!w.attn_norm || !w.w_qkv || !w.w_o || !w.ffn_norm || !w.w_gate_up || !w.w_down)
+                return fail(SPEC_ERR_INVALID_ARG, "layer %d has a NULL weight", l);
+        }
+        const size_t need = spec_kv_cache_bytes(cfg);
+        if (kv_cache_bytes < need)
+            return fail(SPEC_ERR_INVALID_ARG, "kv_cache_bytes %zu is below the required %zu", kv_cache_bytes, need);
+    } else if (kv_cache) {
+        return fail(SPEC_ERR_INVALID_ARG, "kv_cache given without weights");
+    }
+
+    spec_handle* h = new (std::nothrow) spec_handle();
+    if (!h) return fail(SPEC_ERR_ALLOC, "out of host memory");
+    h->cfg = *cfg;
+    h->has_model = has_model;
+    h->kv_cache = kv_cache;
+    h->kv_len = kv_len;
+    hipError_t e = hipGetDevice(&h->device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, h->device);
+    if (e != hipSuccess) {
+        delete h;
+        return fail(SPEC_ERR_DEVICE, "no usable HIP device: %s", hipGetErrorString(e));
+    }
+    h->cu_count = prop.multiProcessorCount;
+
+    const int B = cfg->max_batch, Kmax = cfg->max_lookahead, V = cfg->vocab;
+    const int max_rows = B * (Kmax + 1);
+    const int max_stat = B * (2 * Kmax + 1);
+    const int n_stat_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
+    const int n_res_chunks = (V + RES_CHUNK - 1) / RES_CHUNK;
+    Arena& a = h->arena;
+    rc = SPEC_OK;
+    auto A = [&](auto** p, size_t count) {
+        if (rc == SPEC_OK) rc = a.alloc(reinterpret_cast<void**>(p), count * sizeof(**p));
+    };
+    A(&h->flag, 4);
+    A(&h->tables.seq_row0, B + 1);
+    A(&h->tables.seq_stat0, B + 1);
+    A(&h->tables.seq_n, B);
+    A(&h->tables.seq_ok, B);
+    A(&h->tables.seq_slot, B);
+    A(&h->tables.row_seq, max_rows);
+    A(&h->tables.row_pos, max_rows);
+    A(&h->tables.row_tok, max_rows);
+    A(&h->sampler.part_max, (size_t)max_stat * n_stat_chunks);
+    A(&h->sampler.part_sum, (size_t)max_stat * n_stat_chunks);
+    A(&h->sampler.chunk_mass, (size_t)B * n_res_chunks);
+    A(&h->sampler.accepted, B);
+    A(&h->sampler.row_inv_z, 2 * (size_t)B);
+    A(&h->sampler.row_max, 2 * (size_t)B);
+    if (rc == SPEC_OK && hipMemset(h->flag, 0, 16) != hipSuccess) rc = fail(SPEC_ERR_DEVICE, "hipMemset failed");
+    if (rc == SPEC_OK && has_model) {
+        h->layers.assign(weights->layers, weights->layers + cfg->n_layers);
+        h->tok_embed = weights->tok_embed;
+        h->final_norm = weights->final_norm;
+        h->lm_head = weights->lm_head;
+        rc = forward_init(h, max_rows);
+    }
+    if (rc != SPEC_OK) {
+        a.release();
+        delete h;
+        return rc;
+    }
+    *out = h;
+    return SPEC_OK;
+}
+
+extern "C" void spec_verify_destroy(spec_handle* h)
+{
+    if (!h) return;
+    h->arena.release();
+    delete h;
+}
+
+extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, const spec_step_out* out, void* stream)
+{
+    if (!h || !args || !out) return fail(SPEC_ERR_INVALID_ARG, "NULL handle, args or out");
+    const spec_model_cfg& c = h->cfg;
+    const int B = args->batch, Kmax = c.max_lookahead;
+    if (B < 1 || B > c.max_batch) return fail(SPEC_ERR_INVALID_ARG, "batch %d outside 1..%d", B, c.max_batch);
+    if (!args->lookahead) return fail(SPEC_ERR_INVALID_ARG, "lookahead is NULL");
+    if (!(args->temperature > 0.f)) return fail(SPEC_ERR_INVALID_ARG, "temperature must be > 0");
+    if (!args->uniforms) return fail(SPEC_ERR_INVALID_ARG, "uniforms is NULL");
+    if (!out->n_accepted || !out->out_tokens) return fail(SPEC_ERR_INVALID_ARG, "n_accepted or out_tokens is NULL");
+    LookaheadPack ks;
+    memset(&ks, 0, sizeof(ks));
+    int M = 0, n_stat = 0, any_draft = 0;
+    for (int b = 0; b < B; ++b) {
+        const int k = args->lookahead[b];
+        if (k < 0 || k > Kmax) return fail(SPEC_ERR_INVALID_ARG, "lookahead[%d] = %d outside 0..%d", b, k, Kmax);
+        ks.k[b] = (uint8_t)k;
+        M += k + 1;
+        n_stat += 2 * k + 1;
+        any_draft |= k;
+    }
+    if (any_draft && (!args->draft_tokens || !args->draft_logits))
+        return fail(SPEC_ERR_INVALID_ARG, "draft_tokens or draft_logits is NULL");
+    const bool run_model = args->target_logits_in == nullptr;
+    if (run_model) {
+        if (!h->has_model) return fail(SPEC_ERR_INVALID_ARG, "sampler-only handle needs target_logits_in");
+        if (!args->seq_slot || !args->last_token) return fail(SPEC_ERR_INVALID_ARG, "seq_slot or last_token is NULL");
+    }
+    hipStream_t s = (hipStream_t)stream;
+    // draft_tokens may be NULL when every K_b is 0; the kernels then never read it
+    int rc = launch_prepare(h->tables, ks, B, Kmax, c.vocab, c.max_batch, c.max_kv_len, run_model, args->seq_slot,
+                            run_model ? args->last_token : nullptr, args->draft_tokens, h->kv_len, h->flag, s);
+    if (rc) return rc;
+    const float* logits = args->target_logits_in;
+    if (run_model) {
+        float* dst = out->logits_out ? out->logits_out : h->logits;
+        rc = forward_run(h, ks, B, M, dst, s);
+        if (rc) return rc;
+        logits = dst;
+    } else if (out->logits_out) {
+        SPECV_HIP(hipMemcpyAsync(out->logits_out, logits, (size_t)M * c.vocab * sizeof(float),
+                                 hipMemcpyDeviceToDevice, s));
+    }
+    return launch_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, n_stat, logits, args->draft_logits,
+                          args->draft_tokens, args->uniforms, args->temperature, args->auto_rollback,
+                          run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, s);
+}
+
+extern "C" int spec_kv_rollback(spec_handle* h, const int32_t* seq_slot, const int32_t* new_len, int32_t n,
+                                void* stream)
+{
+    if (!h || !seq_slot || !new_len) return fail(SPEC_ERR_INVALID_ARG, "NULL handle or array");
+    if (!h->has_model) return fail(SPEC_ERR_INVALID_ARG, "sampler-only handle has no KV cache");
+    if (n < 0 || n > SPEC_MAX_BATCH) return fail(SPEC_ERR_INVALID_ARG, "n outside 0..%d", SPEC_MAX_BATCH);
+    if (n == 0) return SPEC_OK;
+    RollbackPack p;
+    memset(&p, 0, sizeof(p));
+    for (int i = 0; i < n; ++i) {
+        if (seq_slot[i] < 0 || seq_slot[i] >= h->cfg.max_batch)
+            return fail(SPEC_ERR_INVALID_ARG, "seq_slot[%d] = %d outside 0..%d", i, seq_slot[i], h->cfg.max_batch - 1);
+        if (new_len[i] < 0 || new_len[i] > h->cfg.max_kv_len)
+            return fail(SPEC_ERR_INVALID_ARG, "new_len[%d] = %d outside 0..%d", i, new_len[i], h->cfg.max_kv_len);
+        for (int j = 0; j < i; ++j)
+            if (seq_slot[j] == seq_slot[i]) return fail(SPEC_ERR_INVALID_ARG, "seq_slot[%d] repeats a slot", i);
+        p.slot[i] = seq_slot[i];
+        p.len[i] = new_len[i];
+    }
+    return launch_rollback(p, n, h->cfg.max_batch, h->kv_len, h->flag, (hipStream_t)stream);
+}
+
+static int kv_copy_common(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, void* plain, bool to_cache,
+                          void* stream)
+{
+    if (!h || !plain) return fail(SPEC_ERR_INVALID_ARG, "NULL handle or tensor");
+    if (!h->has_model) return fail(SPEC_ERR_INVALID_ARG, "sampler-only handle has no KV cache");
+    if (slot < 0 || slot >= h->cfg.max_batch) return fail(SPEC_ERR_INVALID_ARG, "slot outside 0..%d", h->cfg.max_batch - 1);
+    if (pos0 < 0 || n_pos < 0 || pos0 + n_pos > h->cfg.max_kv_len)
+        return fail(SPEC_ERR_INVALID_ARG, "positions [%d, %d) outside the slot", pos0, pos0 + n_pos);
+    if (n_pos == 0) return SPEC_OK;
+    return launch_kv_copy(h->geom, h->kv_cache, slot, pos0, n_pos, plain, to_cache, (hipStream_t)stream);
+}
+
+extern "C" int spec_kv_import(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, const void* src, void* stream)
+{
+    return kv_copy_common(h, slot, pos0, n_pos, const_cast<void*>(src), true, stream);
+}
+
+extern "C" int spec_kv_export(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, void* dst, void* stream)
+{
+    return kv_copy_common(h, slot, pos0, n_pos, dst, false, stream);
+}
+
+extern "C" int spec_verify_poll(spec_handle* h, void* stream)
+{
+    if (!h) return fail(SPEC_ERR_INVALID_ARG, "NULL handle");
+    int32_t v = 0;
+    SPECV_HIP(hipStreamSynchronize((hipStream_t)stream));
+    SPECV_HIP(hipMemcpy(&v, h->flag, 4, hipMemcpyDeviceToHost));
+    if (v != 0) {
+        SPECV_HIP(hipMemset(h->flag, 0, 4));
+        return fail(v, "a sequence was skipped on the device (status %d)", v);
+    }
+    return SPEC_OK;
+}

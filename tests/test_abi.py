@@ -1,0 +1,61 @@
+"""The C-ABI library loads and exports every function the headers declare; host-only entry points
+and argument checks behave as documented.  No kernel is launched here (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = set()
+    for hdr in os.listdir(os.path.join(ROOT, "include")):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(spec_\w+)\s*\(", text))
+    return sorted(names)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2411_00853_amd import binding
+    return binding.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"spec_verify_init", "spec_verify_step", "spec_kv_rollback", "spec_verify_destroy",
+            "spec_last_error"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
+
+
+def test_host_only_size_helpers(lib):
+    from paper_2411_00853_amd import binding as sv
+    from paper_2411_00853_amd import workload as wl
+    assert sv.spec_packed_weight_bytes(4096, 4096) == 4096 * 4096 * 2
+    assert sv.spec_packed_weight_bytes(100, 64) == 112 * 64 * 2        # rows padded to 16
+    assert sv.spec_packed_weight_bytes(64, 100) == 0                   # n_in must be a multiple of 32
+    cfg = sv.make_cfg(wl.SEVEN_B, 8, 2048 + 6, 5)
+    # 32 layers x 8 slots x 32 heads x 2080 (padded) positions x 128 dims x (k,v) x 2 bytes
+    assert sv.spec_kv_cache_bytes(cfg) == 32 * 8 * 32 * 2080 * 128 * 2 * 2
+    tiny = sv.make_cfg(wl.TINY, 1, 133, 4)
+    assert sv.spec_kv_cache_bytes(tiny) == 2 * 1 * 4 * 133 * 64 * 2 * 4
+
+
+def test_bad_configurations_are_rejected_before_any_device_work(lib):
+    from paper_2411_00853_amd import binding as sv
+    from paper_2411_00853_amd import workload as wl
+    out = C.c_void_p()
+    assert lib.spec_verify_init(None, None, None, 0, None, C.byref(out)) == -1
+    assert b"cfg" in lib.spec_last_error()
+    bad = sv.make_cfg(wl.SEVEN_B, 300, 2054, 5)                       # max_batch above the limit
+    assert lib.spec_verify_init(C.byref(bad), None, None, 0, None, C.byref(out)) == -1
+    bad = sv.make_cfg(wl.SEVEN_B, 8, 2054, 16)                        # lookahead above the limit
+    assert lib.spec_verify_init(C.byref(bad), None, None, 0, None, C.byref(out)) == -1
+    odd = sv.make_cfg(wl.ModelShape(1, 64, 3, 2, 64, 64, 100), 1, 64, 2)   # 3 q heads over 2 kv heads
+    assert sv.spec_kv_cache_bytes(odd) == 0
+    assert lib.spec_verify_step(None, None, None, None) == -1
+    assert lib.spec_kv_rollback(None, None, None, 0, None) == -1
