@@ -38,6 +38,26 @@ int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, int32_t M, 
 /* Same product for a plain fp32 W[N][K]. */
 int spec_k_gemm_f32(const float* x, const float* w, float* y, int32_t M, int32_t N, int32_t K, void* stream);
 
+/* Per-kernel-class timing of spec_verify_step with HIP events recorded on the launch stream.
+ * Between profile_begin and profile_end every kernel (or short group of kernels) of a step is
+ * bracketed by two events; profile_end synchronises the stream, adds the elapsed times per class
+ * into ms[SPEC_PROF_COUNT] and the number of bracketed launches into launches[SPEC_PROF_COUNT]
+ * (host arrays), and switches timing off again.  Event recording costs a little time per launch,
+ * so profiled steps are slower than plain ones; kernel durations themselves are unaffected. */
+enum {
+    SPEC_PROF_GEMM = 0,          /* projection GEMMs (QKV, O, gate/up, down, LM head) */
+    SPEC_PROF_ATTENTION = 1,     /* windowed-causal attention, position-chunk pass */
+    SPEC_PROF_ATTN_MERGE = 2,    /* merge of the chunk results */
+    SPEC_PROF_GLUE = 3,          /* embedding, norms, rotary + KV append, SiLU gating, partial sums */
+    SPEC_PROF_SAMPLER_STATS = 4, /* softmax statistics over all target and draft rows */
+    SPEC_PROF_SAMPLER_DRAW = 5,  /* accept scan, residual mass, final draw, KV length update */
+    SPEC_PROF_PREPARE = 6,       /* row bookkeeping */
+    SPEC_PROF_COUNT = 7
+};
+struct spec_handle;
+int spec_verify_profile_begin(struct spec_handle* h);
+int spec_verify_profile_end(struct spec_handle* h, void* stream, double* ms, int32_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

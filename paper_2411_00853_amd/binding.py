@@ -82,6 +82,8 @@ def lib():
         L.spec_k_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                        C.c_void_p, C.c_void_p]
         L.spec_k_gemm_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        L.spec_verify_profile_begin.argtypes = [C.c_void_p]
+        L.spec_verify_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -257,3 +259,19 @@ def spec_k_gemm_f32(x: torch.Tensor, w: torch.Tensor, stream=None):
     y = torch.empty((M, N), dtype=torch.float32, device=x.device)
     _check(lib().spec_k_gemm_f32(_ptr(x, torch.float32), _ptr(w, torch.float32), _ptr(y), M, N, K, _stream(stream)))
     return y
+
+
+PROF_CLASSES = ("gemm", "attention", "attn_merge", "glue", "sampler_stats", "sampler_draw", "prepare")
+
+
+def spec_verify_profile_begin(h: Handle):
+    _check(lib().spec_verify_profile_begin(h.ptr))
+
+
+def spec_verify_profile_end(h: Handle, stream=None):
+    """Returns {class name: (total ms, bracketed launches)} since spec_verify_profile_begin."""
+    n = len(PROF_CLASSES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int32 * n)()
+    _check(lib().spec_verify_profile_end(h.ptr, _stream(stream), ms, cnt))
+    return {PROF_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}

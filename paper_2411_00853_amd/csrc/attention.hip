@@ -307,22 +307,31 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(StepTables t, CacheGeom g
 
 AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count)
 {
-    // aim for ~8 wavefronts per compute unit when every sequence is at max length
+    // One wavefront per (sequence, kv head, position chunk); the kernel's register footprint lets
+    // four wavefronts live on a compute unit, so aim for about two rounds of them when every
+    // sequence is at full length.  Chunks are whole 32-position cache blocks.
     AttnPlan p{};
     const long want_items = 8L * cu_count;
-    long per = (long)batch * n_kv_heads;
-    long chunks = (want_items + per - 1) / per;
-    long keys = chunks > 0 ? (max_kv_len + chunks - 1) / chunks : max_kv_len;
-    int ck = 32;
-    while (ck < keys && ck < 1024) ck <<= 1;
-    p.chunk_keys = ck;
-    p.max_chunks = (max_kv_len + ck - 1) / ck;
+    const long per = (long)batch * n_kv_heads;
+    long chunks = want_items / per;
+    if (chunks < 1) chunks = 1;
+    long keys = (max_kv_len + chunks - 1) / chunks;
+    keys = (keys + 31) / 32 * 32;
+    p.chunk_keys = (int)keys;
+    p.max_chunks = (max_kv_len + p.chunk_keys - 1) / p.chunk_keys;
     return p;
 }
 
-size_t attn_partial_floats(const AttnPlan& p, int max_batch, int n_kv_heads, int group, int max_window, int hd)
+size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
+                           int cu_count)
 {
-    return (size_t)max_batch * n_kv_heads * p.max_chunks * group * max_window * hd;
+    size_t worst = 0;
+    for (int b = 1; b <= max_batch; ++b) {
+        const AttnPlan p = plan_attention(max_kv_len, b, n_kv_heads, cu_count);
+        const size_t e = (size_t)b * n_kv_heads * p.max_chunks * group * max_window * hd;
+        if (e > worst) worst = e;
+    }
+    return worst;
 }
 
 template <int HD>
@@ -345,9 +354,9 @@ static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, 
     return SPEC_OK;
 }
 
-int launch_attention(const AttnPlan& p, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,
+int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,
                      int n_q_heads, int layer, const void* cache, const float* q, float* part_o, float* part_ml,
-                     float* out, int max_window, hipStream_t s)
+                     float* out, int max_window, Profiler* prof, hipStream_t s)
 {
     const int hd = g.head_dim;
     const float scale = 1.0f / sqrtf((float)hd);
@@ -355,11 +364,14 @@ int launch_attention(const AttnPlan& p, const StepTables& t, const LookaheadPack
         // scores for one row live in LDS: positions * 4 bytes
         const size_t lds = (size_t)(hd + g.t_pad) * sizeof(float);
         if (lds > 60 * 1024) return fail(SPEC_ERR_SHAPE, "fp32 attention supports max_kv_len up to ~15000");
+        ProfScope ps(prof, SPEC_PROF_ATTENTION, s);
         hipLaunchKernelGGL(attn_f32_kernel, dim3(M, n_q_heads), dim3(256), lds, s, t, g, n_q_heads, layer,
                            (const float*)cache, q, scale, out);
         SPECV_LAUNCH_CHECK("attn_f32_kernel");
         return SPEC_OK;
     }
+    (void)p_unused;
+    const AttnPlan p = plan_attention(max_kv_len, B, g.n_kv_heads, cu_count);
     const int group = n_q_heads / g.n_kv_heads;
     const int r_cap = group * max_window;
     int kmax = 0;
@@ -368,13 +380,17 @@ int launch_attention(const AttnPlan& p, const StepTables& t, const LookaheadPack
     const dim3 grid((unsigned)B * g.n_kv_heads * p.max_chunks);
     const float sl2 = scale * 1.4426950408889634f;
     int rc;
-    if (hd == 128)
-        rc = launch_chunks<128>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml);
-    else if (hd == 64)
-        rc = launch_chunks<64>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml);
-    else
-        return fail(SPEC_ERR_SHAPE, "bf16 attention needs head_dim 64 or 128");
+    {
+        ProfScope ps(prof, SPEC_PROF_ATTENTION, s);
+        if (hd == 128)
+            rc = launch_chunks<128>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml);
+        else if (hd == 64)
+            rc = launch_chunks<64>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml);
+        else
+            return fail(SPEC_ERR_SHAPE, "bf16 attention needs head_dim 64 or 128");
+    }
     if (rc) return rc;
+    ProfScope ps(prof, SPEC_PROF_ATTN_MERGE, s);
     hipLaunchKernelGGL(attn_merge_kernel, dim3(M, n_q_heads), dim3(hd), 0, s, t, ks, g.n_kv_heads, n_q_heads, hd,
                        p.chunk_keys, p.max_chunks, r_cap, part_o, part_ml, out);
     SPECV_LAUNCH_CHECK("attn_merge_kernel");

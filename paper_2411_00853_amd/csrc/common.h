@@ -28,8 +28,31 @@ int fail(int status, const char* fmt, ...);
             return ::specv::fail(SPEC_ERR_DEVICE, "launch of %s failed: %s", name, hipGetErrorString(e_)); \
     } while (0)
 
-// ---- device-side error flag codes (stored in the handle's flag word) --------------------------
-enum : int { FLAG_NONE = 0 };
+// ---- optional per-kernel-class timing with HIP events on the launch stream ----------------------
+// Classes follow SPEC_PROF_* in spec_kernels.h.  Off by default: then begin/end do nothing.
+struct Profiler {
+    bool on = false;
+    struct Rec {
+        hipEvent_t start, stop;
+        int cls;
+    };
+    Rec* recs = nullptr;
+    int cap = 0, used = 0;
+    void begin(int cls, hipStream_t s);
+    void end(hipStream_t s);
+};
+struct ProfScope {
+    Profiler* p;
+    hipStream_t s;
+    ProfScope(Profiler* p_, int cls, hipStream_t s_) : p(p_), s(s_)
+    {
+        if (p && p->on) p->begin(cls, s);
+    }
+    ~ProfScope()
+    {
+        if (p && p->on) p->end(s);
+    }
+};
 
 // ---- per-step row bookkeeping built on the device by the prepare kernel ------------------------
 struct LookaheadPack {
@@ -67,7 +90,7 @@ int launch_prepare(const StepTables& t, const LookaheadPack& ks, int B, int Kmax
 int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax,
                    int V, int n_stat_rows, const float* target_logits, const float* draft_logits,
                    const int32_t* draft_tokens, const float* uniforms, float temperature, int auto_rollback,
-                   int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens, hipStream_t s);
+                   int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens, Profiler* prof, hipStream_t s);
 
 struct RollbackPack {
     int32_t slot[SPEC_MAX_BATCH];
@@ -127,9 +150,10 @@ struct AttnPlan {
     int max_chunks;   // chunks per (sequence, kv head) at max_kv_len
 };
 AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count);
-size_t attn_partial_floats(const AttnPlan& p, int max_batch, int n_kv_heads, int group, int max_window, int hd);
-int launch_attention(const AttnPlan& p, const StepTables& t, const LookaheadPack& ks, int B, int M,
+size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
+                           int cu_count);
+int launch_attention(const AttnPlan& p, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M,
                      const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
-                     float* part_o, float* part_ml, float* out, int max_window, hipStream_t s);
+                     float* part_o, float* part_ml, float* out, int max_window, Profiler* prof, hipStream_t s);
 
 }  // namespace specv

@@ -61,8 +61,8 @@ int forward_init(spec_handle* h, int max_rows)
             }
         h->attn_plan = plan_attention(c.max_kv_len, c.max_batch, c.n_kv_heads, h->cu_count);
         const int group = c.n_q_heads / c.n_kv_heads;
-        const size_t po = attn_partial_floats(h->attn_plan, c.max_batch, c.n_kv_heads, group, c.max_lookahead + 1,
-                                              c.head_dim);
+        const size_t po = attn_partial_floats(c.max_kv_len, c.max_batch, c.n_kv_heads, group, c.max_lookahead + 1,
+                                              c.head_dim, h->cu_count);
         A(&h->attn_part_o, po);
         A(&h->attn_part_ml, po / c.head_dim * 2);
     } else {
@@ -92,10 +92,13 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
     const bool bf16 = c.dtype == SPEC_DTYPE_BF16;
     const StepTables& t = h->tables;
     int rc;
-#define RUN(expr)            \
-    do {                     \
-        rc = (expr);         \
-        if (rc) return rc;   \
+#define RUN(cls, expr)                          \
+    do {                                        \
+        {                                       \
+            ProfScope ps_(&h->prof, cls, s);    \
+            rc = (expr);                        \
+        }                                       \
+        if (rc) return rc;                      \
     } while (0)
 
     // A GEMM leaves either K-range partial sums (bf16) or the whole result (fp32) in h->partial;
@@ -119,28 +122,29 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
         return launch_gemm_f32(xin, (const float*)w, M, N, K, h->partial, s);
     };
 
-    RUN(launch_embed_rmsnorm(c.dtype, h->tok_embed, t.row_tok, h->layers[0].attn_norm, c.rms_eps, M, z.d, h->x, h->hn, s));
+    RUN(SPEC_PROF_GLUE, launch_embed_rmsnorm(c.dtype, h->tok_embed, t.row_tok, h->layers[0].attn_norm, c.rms_eps, M, z.d, h->x, h->hn, s));
     Out o;
     for (int l = 0; l < c.n_layers; ++l) {
         const spec_layer_weights& w = h->layers[l];
-        RUN(gemm(h->hn, w.w_qkv, z.nqkv, z.d, &o));
-        RUN(launch_rope_append(h->partial, o.n_split, o.stride, o.ld, t, M, h->geom, c.n_q_heads, l, h->cos_sin,
+        RUN(SPEC_PROF_GEMM, gemm(h->hn, w.w_qkv, z.nqkv, z.d, &o));
+        RUN(SPEC_PROF_GLUE, launch_rope_append(h->partial, o.n_split, o.stride, o.ld, t, M, h->geom, c.n_q_heads, l, h->cos_sin,
                                h->kv_cache, h->q, s));
-        RUN(launch_attention(h->attn_plan, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache, h->q, h->attn_part_o,
-                             h->attn_part_ml, h->att, c.max_lookahead + 1, s));
-        RUN(gemm(h->att, w.w_o, z.d, z.dq, &o));
-        RUN(launch_resid_rmsnorm(h->partial, o.n_split, o.stride, o.ld, w.ffn_norm, c.rms_eps, M, z.d, h->x, h->hn, s));
-        RUN(gemm(h->hn, w.w_gate_up, 2 * z.F, z.d, &o));
-        RUN(launch_silu_mul(h->partial, o.n_split, o.stride, o.ld, M, z.F, bf16, h->act, s));
-        RUN(gemm(h->act, w.w_down, z.d, z.F, &o));
+        rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache, h->q, h->attn_part_o,
+                              h->attn_part_ml, h->att, c.max_lookahead + 1, &h->prof, s);
+        if (rc) return rc;
+        RUN(SPEC_PROF_GEMM, gemm(h->att, w.w_o, z.d, z.dq, &o));
+        RUN(SPEC_PROF_GLUE, launch_resid_rmsnorm(h->partial, o.n_split, o.stride, o.ld, w.ffn_norm, c.rms_eps, M, z.d, h->x, h->hn, s));
+        RUN(SPEC_PROF_GEMM, gemm(h->hn, w.w_gate_up, 2 * z.F, z.d, &o));
+        RUN(SPEC_PROF_GLUE, launch_silu_mul(h->partial, o.n_split, o.stride, o.ld, M, z.F, bf16, h->act, s));
+        RUN(SPEC_PROF_GEMM, gemm(h->act, w.w_down, z.d, z.F, &o));
         const float* next_gain = (l + 1 < c.n_layers) ? h->layers[l + 1].attn_norm : h->final_norm;
-        RUN(launch_resid_rmsnorm(h->partial, o.n_split, o.stride, o.ld, next_gain, c.rms_eps, M, z.d, h->x, h->hn, s));
+        RUN(SPEC_PROF_GLUE, launch_resid_rmsnorm(h->partial, o.n_split, o.stride, o.ld, next_gain, c.rms_eps, M, z.d, h->x, h->hn, s));
     }
     if (bf16) {
-        RUN(gemm(h->hn, h->lm_head, z.V, z.d, &o));
-        RUN(launch_reduce_splits(h->partial, o.n_split, o.stride, M, z.V, o.ld, logits_out, s));
+        RUN(SPEC_PROF_GEMM, gemm(h->hn, h->lm_head, z.V, z.d, &o));
+        RUN(SPEC_PROF_GLUE, launch_reduce_splits(h->partial, o.n_split, o.stride, M, z.V, o.ld, logits_out, s));
     } else {
-        RUN(launch_gemm_f32(h->hn, (const float*)h->lm_head, M, z.V, z.d, logits_out, s));
+        RUN(SPEC_PROF_GEMM, launch_gemm_f32(h->hn, (const float*)h->lm_head, M, z.V, z.d, logits_out, s));
     }
 #undef RUN
     return SPEC_OK;

@@ -29,6 +29,7 @@ struct spec_handle {
     specv::Arena arena;
     specv::StepTables tables{};
     specv::SamplerWorkspace sampler{};
+    specv::Profiler prof;
 
     // decoder pass
     std::vector<spec_layer_weights> layers;

@@ -432,7 +432,7 @@ int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len
 int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax,
                    int V, int n_stat_rows, const float* target_logits, const float* draft_logits,
                    const int32_t* draft_tokens, const float* uniforms, float temperature, int auto_rollback,
-                   int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens, hipStream_t s)
+                   int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens, Profiler* prof, hipStream_t s)
 {
     const int n_stat_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
     const int n_res_chunks = (V + RES_CHUNK - 1) / RES_CHUNK;
@@ -440,6 +440,8 @@ int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const Lookahe
     const bool vec4 = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(target_logits) & 15) == 0)
                       && ((reinterpret_cast<uintptr_t>(draft_logits) & 15) == 0);
     dim3 g1((unsigned)n_stat_rows * n_stat_chunks);
+    {
+    ProfScope ps(prof, SPEC_PROF_SAMPLER_STATS, s);
     if (vec4)
         hipLaunchKernelGGL(stats_kernel<true>, g1, dim3(TPB), 0, s, t, ks, B, Kmax, V, n_stat_chunks,
                            target_logits, draft_logits, inv_T, w.part_max, w.part_sum);
@@ -447,6 +449,8 @@ int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const Lookahe
         hipLaunchKernelGGL(stats_kernel<false>, g1, dim3(TPB), 0, s, t, ks, B, Kmax, V, n_stat_chunks,
                            target_logits, draft_logits, inv_T, w.part_max, w.part_sum);
     SPECV_LAUNCH_CHECK("stats_kernel");
+    }
+    ProfScope ps(prof, SPEC_PROF_SAMPLER_DRAW, s);
     hipLaunchKernelGGL(accept_mass_kernel, dim3(n_res_chunks, B), dim3(TPB), 0, s, t, ks, Kmax, V, n_stat_chunks,
                        n_res_chunks, target_logits, draft_logits, draft_tokens, uniforms, inv_T, w.part_max,
                        w.part_sum, w);

@@ -6,6 +6,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -50,6 +51,28 @@ void Arena::release()
     for (void* p : blocks) (void)hipFree(p);
     blocks.clear();
     total = 0;
+}
+
+void Profiler::begin(int cls, hipStream_t s)
+{
+    if (used == cap) {
+        const int ncap = cap ? cap * 2 : 1024;
+        Rec* n = static_cast<Rec*>(realloc(recs, sizeof(Rec) * ncap));
+        if (!n) return;
+        recs = n;
+        for (int i = cap; i < ncap; ++i) {
+            (void)hipEventCreate(&recs[i].start);
+            (void)hipEventCreate(&recs[i].stop);
+        }
+        cap = ncap;
+    }
+    recs[used].cls = cls;
+    (void)hipEventRecord(recs[used].start, s);
+}
+
+void Profiler::end(hipStream_t s)
+{
+    if (used < cap) (void)hipEventRecord(recs[used++].stop, s);
 }
 
 static int check_cfg(const spec_model_cfg* c, bool has_model)
@@ -178,9 +201,41 @@ extern "C" int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* w
     return SPEC_OK;
 }
 
+extern "C" int spec_verify_profile_begin(spec_handle* h)
+{
+    if (!h) return fail(SPEC_ERR_INVALID_ARG, "NULL handle");
+    h->prof.used = 0;
+    h->prof.on = true;
+    return SPEC_OK;
+}
+
+extern "C" int spec_verify_profile_end(spec_handle* h, void* stream, double* ms, int32_t* launches)
+{
+    if (!h || !ms || !launches) return fail(SPEC_ERR_INVALID_ARG, "NULL argument");
+    h->prof.on = false;
+    SPECV_HIP(hipStreamSynchronize((hipStream_t)stream));
+    for (int i = 0; i < SPEC_PROF_COUNT; ++i) {
+        ms[i] = 0.0;
+        launches[i] = 0;
+    }
+    for (int i = 0; i < h->prof.used; ++i) {
+        float t = 0.f;
+        SPECV_HIP(hipEventElapsedTime(&t, h->prof.recs[i].start, h->prof.recs[i].stop));
+        ms[h->prof.recs[i].cls] += t;
+        launches[h->prof.recs[i].cls] += 1;
+    }
+    h->prof.used = 0;
+    return SPEC_OK;
+}
+
 extern "C" void spec_verify_destroy(spec_handle* h)
 {
     if (!h) return;
+    for (int i = 0; i < h->prof.cap; ++i) {
+        (void)hipEventDestroy(h->prof.recs[i].start);
+        (void)hipEventDestroy(h->prof.recs[i].stop);
+    }
+    free(h->prof.recs);
     h->arena.release();
     delete h;
 }
@@ -215,8 +270,12 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     }
     hipStream_t s = (hipStream_t)stream;
     // draft_tokens may be NULL when every K_b is 0; the kernels then never read it
-    int rc = launch_prepare(h->tables, ks, B, Kmax, c.vocab, c.max_batch, c.max_kv_len, run_model, args->seq_slot,
+    int rc;
+    {
+        ProfScope ps(&h->prof, SPEC_PROF_PREPARE, s);
+        rc = launch_prepare(h->tables, ks, B, Kmax, c.vocab, c.max_batch, c.max_kv_len, run_model, args->seq_slot,
                             run_model ? args->last_token : nullptr, args->draft_tokens, h->kv_len, h->flag, s);
+    }
     if (rc) return rc;
     const float* logits = args->target_logits_in;
     if (run_model) {
@@ -230,7 +289,7 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     }
     return launch_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, n_stat, logits, args->draft_logits,
                           args->draft_tokens, args->uniforms, args->temperature, args->auto_rollback,
-                          run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, s);
+                          run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, &h->prof, s);
 }
 
 extern "C" int spec_kv_rollback(spec_handle* h, const int32_t* seq_slot, const int32_t* new_len, int32_t n,

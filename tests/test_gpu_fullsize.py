@@ -1,0 +1,192 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+1B-shape and 7B-shape: every window row's logits against the oracle (<= 3e-2), tokens on identical
+logits under the margin rules.  Dynamic lookahead (32 ragged sequences): a sample of sequences
+through the oracle (shortest and longest cache, smallest and largest lookahead), plus properties
+that hold at any size for all of them.  Sampler stress: every sequence against the oracle.
+Weights are made on the GPU by the seeded generator and copied to the host for the oracle; KV
+contents are synthetic N(0,1) (stated in the workload recipe)."""
+import sys
+import time
+
+import pytest
+import torch
+
+import oracle
+from paper_2411_00853_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class BigWeights:
+    """Generator-made weights of one shape on both sides (made on the GPU, copied to the host)."""
+
+    def __init__(self, shape, seed):
+        from paper_2411_00853_amd import binding as sv
+        t = time.time()
+        self.shape = shape
+        raw = wl.make_weights(shape, seed, "cuda")
+        self.cpu = {"tok_embed": raw["tok_embed"].cpu(), "final_norm": raw["final_norm"].cpu(),
+                    "lm_head": raw["lm_head"].cpu(), "layers": [{k: v.cpu() for k, v in lw.items()} for lw in raw["layers"]]}
+        pk = sv.spec_pack_weight
+        self.dev = {"tok_embed": raw["tok_embed"], "final_norm": raw["final_norm"], "lm_head": pk(raw["lm_head"]),
+                    "layers": [{"attn_norm": lw["attn_norm"], "ffn_norm": lw["ffn_norm"], "w_qkv": pk(lw["w_qkv"]),
+                                "w_o": pk(lw["w_o"]), "w_gate_up": pk(lw["w_gate_up"], True),
+                                "w_down": pk(lw["w_down"])} for lw in raw["layers"]]}
+        torch.cuda.synchronize()
+        say(f"  [weights] generated, packed and copied to the host in {time.time() - t:.1f}s")
+
+
+class BigRig:
+    def __init__(self, weights, n_slots, max_kv_len, Kmax):
+        from paper_2411_00853_amd import binding as sv
+        shape = weights.shape
+        self.sv, self.shape, self.Kmax, self.max_kv_len = sv, shape, Kmax, max_kv_len
+        self.om = oracle.Model(shape, weights.cpu, max_kv_len)
+        self.cfg = sv.make_cfg(shape, n_slots, max_kv_len, Kmax)
+        self.kv = torch.empty(sv.spec_kv_cache_bytes(self.cfg), dtype=torch.uint8, device="cuda")
+        self.kv_len = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
+        self.h = sv.spec_verify_init(self.cfg, weights.dev, self.kv, self.kv_len)
+
+    def fill_slot(self, w, slot, n, seq_index, keep_cpu):
+        """Synthetic N(0,1) cache for one slot; returns the oracle-side cache if asked."""
+        s = self.shape
+        rng = wl.Rng(w.seed, "cuda")
+        plain = torch.empty((s.n_layers, 2, s.n_kv_heads, n, s.head_dim), dtype=s.torch_dtype, device="cuda")
+        for l in range(s.n_layers):
+            plain[l] = rng.normal(wl.S_KV + seq_index * 4096 + l, (2, s.n_kv_heads, n, s.head_dim), 1.0, s.torch_dtype)
+        self.sv.spec_kv_import(self.h, slot, 0, plain)
+        self.kv_len[slot] = n
+        if not keep_cpu:
+            return None
+        c = torch.zeros((s.n_layers, 2, s.n_kv_heads, self.max_kv_len, s.head_dim), dtype=s.torch_dtype)
+        c[:, :, :, :n] = plain.cpu()
+        return c
+
+    def close(self):
+        self.h.close()
+
+
+def _run_and_check(rig, w, check_seqs, label):
+    """One step of workload w; sequences in check_seqs are verified against the oracle."""
+    from helpers import SamplerCheck
+    sv, shape = rig.sv, w.shape
+    B, Kmax, V = w.batch, w.max_lookahead, shape.vocab
+    look = list(w.lookahead)
+    caches = {}
+    for b in range(B):
+        caches[b] = rig.fill_slot(w, b, w.kv_lens[b], b, b in check_seqs)
+    t0, _ = wl.make_context(w, "cuda")
+    toks, dl = wl.make_free_drafts(w, "cuda")
+    us = wl.make_uniforms(w, "cuda")
+    M = w.rows
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ot = torch.zeros((B, Kmax + 1), dtype=torch.int32, device="cuda")
+    lo = torch.zeros((M, V), dtype=torch.float32, device="cuda")
+    slots = torch.arange(B, dtype=torch.int32, device="cuda")
+    sv.spec_verify_step(rig.h, look, us, w.temperature, na, ot, seq_slot=slots, last_token=t0, draft_tokens=toks,
+                        draft_logits=dl, logits_out=lo, auto_rollback=True)
+    torch.cuda.synchronize()
+    sv.spec_verify_poll(rig.h)
+    na_c, ot_c, lo_c = na.cpu(), ot.cpu(), lo.cpu()
+    t0_c, toks_c, dl_c, us_c = t0.cpu(), toks.cpu(), dl.cpu(), us.cpu()
+    # properties that hold for every sequence at any size
+    kl = rig.kv_len.cpu().tolist()
+    row0 = [0]
+    for k in look:
+        row0.append(row0[-1] + k + 1)
+    for b in range(B):
+        a = int(na_c[b])
+        assert 0 <= a <= look[b] and kl[b] == w.kv_lens[b] + a + 1
+        assert ot_c[b, :a].tolist() == toks_c[b, :a].tolist() and 0 <= int(ot_c[b, a]) < V
+        assert (ot_c[b, a + 1:] == -1).all()
+    assert torch.isfinite(lo_c).all()
+    # the oracle on the chosen sequences
+    seqs = sorted(check_seqs)
+    t = time.time()
+    want = rig.om.verify_rows([caches[b] for b in seqs], [w.kv_lens[b] for b in seqs],
+                              [[int(t0_c[b])] + toks_c[b, :look[b]].tolist() for b in seqs])
+    say(f"  [{label}] oracle: {want.shape[0]} rows in {time.time() - t:.1f}s")
+    worst, r = 0.0, 0
+    for b in seqs:
+        got = lo_c[row0[b]:row0[b + 1]]
+        worst = max(worst, (got - want[r:r + look[b] + 1]).abs().max().item())
+        r += look[b] + 1
+    say(f"  [{label}] logits max-abs error {worst:.3e} (logit std {want.std().item():.3f})")
+    assert worst <= 3e-2
+    # token parity on identical logits: replay the sampler on the oracle's logits for those sequences
+    sub_look = [look[b] for b in seqs]
+    Bs = len(seqs)
+    na2 = torch.zeros(Bs, dtype=torch.int32, device="cuda")
+    ot2 = torch.zeros((Bs, Kmax + 1), dtype=torch.int32, device="cuda")
+    idx = torch.tensor(seqs, device="cuda")
+    sv.spec_verify_step(rig.h, sub_look, us[idx].contiguous(), w.temperature, na2, ot2,
+                        draft_tokens=toks[idx].contiguous(), draft_logits=dl[idx].contiguous(),
+                        target_logits_in=want.cuda())
+    torch.cuda.synchronize()
+    chk = SamplerCheck()
+    r = 0
+    for i, b in enumerate(seqs):
+        chk.compare(want[r:r + look[b] + 1], dl_c[b], toks_c[b, :look[b]].tolist(), us_c[b, :look[b] + 1].tolist(),
+                    w.temperature, int(na2[i]), ot2[i].cpu().tolist(), Kmax)
+        r += look[b] + 1
+    say(f"  [{label}] sampler: exact accept {chk.exact_accept}, margin {chk.margin_accept}; "
+        f"exact token {chk.exact_token}, margin {chk.margin_token}; accepted {na_c.tolist()}")
+    return worst, chk
+
+
+def test_1b_shape_full():
+    w = wl.workload_1b()
+    rig = BigRig(BigWeights(w.shape, w.seed), w.batch, w.max_kv_len, w.max_lookahead)
+    try:
+        _run_and_check(rig, w, {0}, "1b")
+    finally:
+        rig.close()
+
+
+@pytest.fixture(scope="module")
+def weights7b():
+    return BigWeights(wl.SEVEN_B, wl.workload_7b().seed)
+
+
+def test_7b_shape_full_all_rows(weights7b):
+    # exactly the handle bench.py builds: 8 slots, 2054 positions, lookahead 5
+    w = wl.workload_7b()
+    rig = BigRig(weights7b, w.batch, w.max_kv_len, w.max_lookahead)
+    try:
+        _run_and_check(rig, w, set(range(8)), "7b")
+    finally:
+        rig.close()
+
+
+def test_dynamic_lookahead_sampled_sequences(weights7b):
+    # same target weights as the 7B-shape case; 32 ragged sequences
+    w = wl.workload_dyn()
+    n, k = w.kv_lens, w.lookahead
+    pick = {min(range(32), key=lambda b: n[b]), max(range(32), key=lambda b: n[b]),
+            min(range(32), key=lambda b: k[b]), max(range(32), key=lambda b: k[b])}
+    say(f"  [dyn] rows {w.rows}, checking sequences {sorted(pick)}: n={[n[b] for b in sorted(pick)]} "
+        f"K={[k[b] for b in sorted(pick)]}")
+    rig = BigRig(weights7b, w.batch, w.max_kv_len, w.max_lookahead)
+    try:
+        _run_and_check(rig, w, pick, "dyn")
+    finally:
+        rig.close()
+
+
+def test_sampler_stress_full():
+    from helpers import check_sampler_against_oracle, run_sampler_gpu
+    t = time.time()
+    s = wl.make_stress(device="cuda")      # 64 x (8+1) x 128256 target rows, 64 x 8 draft rows
+    tl, dl, toks, us = s.target_logits.cpu(), s.draft_logits.cpu(), s.draft_tokens.cpu(), s.uniforms.cpu()
+    say(f"  [stress] inputs in {time.time() - t:.1f}s")
+    na, ot = run_sampler_gpu(tl, dl, toks, us, s.lookahead, s.temperature, 8)
+    t = time.time()
+    chk = check_sampler_against_oracle(tl, dl, toks, us, s.lookahead, s.temperature, 8, na, ot)
+    say(f"  [stress] oracle {time.time() - t:.1f}s; exact accept {chk.exact_accept}, margin {chk.margin_accept}; "
+        f"exact token {chk.exact_token}, margin {chk.margin_token}; mean accepted {na.float().mean().item():.2f}")
+    assert chk.exact_accept >= 60 and chk.exact_token >= 50
