@@ -35,6 +35,10 @@ size_t spec_k_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
 int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, int32_t M, int32_t N, int32_t K,
                      int32_t split_x, void* workspace, void* stream);
 
+/* Tuning knob: number of workgroups a GEMM launch aims for when it cuts K into ranges
+ * (0 = default, two per compute unit).  Process-wide; affects launches made after the call. */
+void spec_k_set_gemm_wg_target(int32_t workgroups);
+
 /* Same product for a plain fp32 W[N][K]. */
 int spec_k_gemm_f32(const float* x, const float* w, float* y, int32_t M, int32_t N, int32_t K, void* stream);
 

@@ -82,6 +82,8 @@ def lib():
         L.spec_k_gemm_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                        C.c_void_p, C.c_void_p]
         L.spec_k_gemm_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        L.spec_k_set_gemm_wg_target.restype = None
+        L.spec_k_set_gemm_wg_target.argtypes = [C.c_int32]
         L.spec_verify_profile_begin.argtypes = [C.c_void_p]
         L.spec_verify_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
         _lib = L
@@ -251,6 +253,10 @@ def spec_k_gemm_bf16(x: torch.Tensor, w_packed: torch.Tensor, n_out: int, split_
     _check(lib().spec_k_gemm_bf16(_ptr(x, torch.float32), _ptr(w_packed), _ptr(y), M, n_out, K, int(split_x),
                                   _ptr(workspace), _stream(stream)))
     return y
+
+
+def spec_k_set_gemm_wg_target(workgroups: int):
+    lib().spec_k_set_gemm_wg_target(int(workgroups))
 
 
 def spec_k_gemm_f32(x: torch.Tensor, w: torch.Tensor, stream=None):

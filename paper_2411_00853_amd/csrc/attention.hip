@@ -20,18 +20,10 @@
 //    rounding in the path the one that the cache's storage type imposes.
 #include "cache_layout.h"
 #include "common.h"
+#include "frag.h"
 
 namespace specv {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-union Frag {
-    uint4 u;
-    bf16x8 v;
-    uint16_t h[8];
-};
 
 __device__ __forceinline__ void split_frag(const float (&x)[8], Frag& hi, Frag& lo)
 {
@@ -79,12 +71,12 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
         const bool real = r < rows;
         const int j = real ? r / group : 0, hl = real ? r % group : 0;
         limit[rt] = real ? n + j : -1;   // last visible position of this query
-        const float* src = q + (size_t)(row0 + j) * dq + (hkv * group + hl) * HD + 8 * gq;
+        const float4* src = reinterpret_cast<const float4*>(q + (size_t)(row0 + j) * dq + (hkv * group + hl) * HD + 8 * gq);
+        const float sc = real ? scale_log2e : 0.f;   // rows past the window contribute zeros
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            float x[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = real ? src[32 * s + e] * scale_log2e : 0.f;
+            const float4 a = src[8 * s], b = src[8 * s + 1];
+            const float x[8] = {a.x * sc, a.y * sc, a.z * sc, a.w * sc, b.x * sc, b.y * sc, b.z * sc, b.w * sc};
             split_frag(x, qh[rt][s], ql[rt][s]);
         }
     }
@@ -103,20 +95,20 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
     const int blk0 = key0 >> 5, blk1 = (key1 + 31) >> 5;
 
     uint4 ka[2][STEPS], va[DT], kb[2][STEPS], vb[DT];
+    // unconditional loads (a block index past the chunk re-reads the chunk's last block): with no
+    // branch around them the compiler counts outstanding loads exactly and the prefetch stays in flight
     auto load_block = [&](int blk, uint4(&kk)[2][STEPS], uint4(&vv)[DT]) {
-        if (blk < blk1) {
-            const uint4* p = head + (size_t)blk * BLK_U4 + lane;
+        const uint4* p = head + (size_t)min(blk, blk1 - 1) * BLK_U4 + lane;
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-                for (int s = 0; s < STEPS; ++s) kk[sub][s] = p[sub * (2 * HD) + s * 64];
+            for (int s = 0; s < STEPS; ++s) kk[sub][s] = p[sub * (2 * HD) + s * 64];
 #pragma unroll
-            for (int d = 0; d < DT; ++d) vv[d] = p[4 * HD + d * 64];
-        }
+        for (int d = 0; d < DT; ++d) vv[d] = p[4 * HD + d * 64];
     };
     auto process = [&](int blk, const uint4(&kk)[2][STEPS], uint4(&vv)[DT]) {
         const int kbase = blk * 32;
-        const bool tail = kbase + 32 > n;   // block reaches the window or the end: mask per element
+        const bool tail = kbase + 32 > n || kbase >= key1;   // reaches the window / the end: mask per element
         if (tail) {
             // values of positions that do not exist yet may hold anything: zero them
 #pragma unroll
@@ -152,7 +144,7 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int key = kbase + (e < 4 ? 4 * gq + e : 16 + 4 * gq + e - 4);
-                    if (key > limit[rt]) sv[e] = -INFINITY;
+                    if (key > limit[rt] || kbase >= key1) sv[e] = -INFINITY;
                 }
             }
             float mx = sv[0];
@@ -186,14 +178,15 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
         }
     };
 
+    // Two blocks per trip, no branch inside: a block index past the chunk holds only positions
+    // >= total, which the tail masking turns into zero weight, so an odd block count just ends with
+    // one idle half trip.
     load_block(blk0, ka, va);
     for (int blk = blk0; blk < blk1; blk += 2) {
         load_block(blk + 1, kb, vb);
         process(blk, ka, va);
-        if (blk + 1 < blk1) {
-            load_block(blk + 2, ka, va);
-            process(blk + 1, kb, vb);
-        }
+        load_block(blk + 2, ka, va);
+        process(blk + 1, kb, vb);
     }
 
 #pragma unroll
@@ -215,36 +208,47 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
     }
 }
 
-// out[m][hq][:] = sum_c w_c o_c / sum_c w_c l_c with w_c = 2^(m_c - max m), chunks in index order
-__global__ void attn_merge_kernel(StepTables t, LookaheadPack ks, int n_kv_heads, int n_q_heads, int hd, int chunk_keys,
-                                  int max_chunks, int r_cap, const float* __restrict__ part_o,
-                                  const float* __restrict__ part_ml, float* __restrict__ out)
+// out[m][hq][:] = sum_c w_c o_c / sum_c w_c l_c with w_c = 2^(m_c - max m), chunks in index order.
+// One thread per 8 consecutive dims of a (row, query head); the result goes out as the output
+// projection's operand fragments.
+__global__ void __launch_bounds__(64) attn_merge_kernel(StepTables t, LookaheadPack ks, int n_kv_heads, int n_q_heads,
+                                                        int hd, int chunk_keys, int max_chunks, int r_cap,
+                                                        const float* __restrict__ part_o,
+                                                        const float* __restrict__ part_ml, XOut xo)
 {
-    const int m = blockIdx.x, hq = blockIdx.y, dim = threadIdx.x;
+    const int per_head = hd / 8;
+    const int m = blockIdx.x;
+    const int unit = blockIdx.y * 64 + threadIdx.x;       // 8-dim unit within the row
+    const int hq = unit / per_head, d8 = unit % per_head;
+    if (hq >= n_q_heads) return;
     const int b = t.row_seq[m];
-    float* dst = out + ((size_t)m * n_q_heads + hq) * hd + dim;
-    if (!t.seq_ok[b]) {
-        *dst = 0.f;
-        return;
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (t.seq_ok[b]) {
+        const int group = n_q_heads / n_kv_heads;
+        const int j = m - t.seq_row0[b];
+        const int r = j * group + hq % group;
+        const int total = t.seq_n[b] + ks.k[b] + 1;
+        const int n_chunks = (total + chunk_keys - 1) / chunk_keys;
+        const size_t item0 = ((size_t)b * n_kv_heads + hq / group) * max_chunks;
+        float mx = -INFINITY;
+        for (int c = 0; c < n_chunks; ++c) mx = fmaxf(mx, part_ml[((item0 + c) * r_cap + r) * 2]);
+        float den = 0.f;
+        for (int c = 0; c < n_chunks; ++c) {
+            const size_t idx = (item0 + c) * r_cap + r;
+            const float mc = part_ml[idx * 2];
+            if (mc == -INFINITY) continue;   // chunk entirely after this query's position
+            const float w = exp2f(mc - mx);
+            den += w * part_ml[idx * 2 + 1];
+            const float4 a = *reinterpret_cast<const float4*>(part_o + idx * hd + d8 * 8);
+            const float4 bq = *reinterpret_cast<const float4*>(part_o + idx * hd + d8 * 8 + 4);
+            v[0] += w * a.x; v[1] += w * a.y; v[2] += w * a.z; v[3] += w * a.w;
+            v[4] += w * bq.x; v[5] += w * bq.y; v[6] += w * bq.z; v[7] += w * bq.w;
+        }
+        const float inv = 1.0f / den;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= inv;
     }
-    const int group = n_q_heads / n_kv_heads;
-    const int j = m - t.seq_row0[b];
-    const int r = j * group + hq % group;
-    const int total = t.seq_n[b] + ks.k[b] + 1;
-    const int n_chunks = (total + chunk_keys - 1) / chunk_keys;
-    const size_t item0 = ((size_t)b * n_kv_heads + hq / group) * max_chunks;
-    float mx = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) mx = fmaxf(mx, part_ml[((item0 + c) * r_cap + r) * 2]);
-    float num = 0.f, den = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-        const size_t idx = (item0 + c) * r_cap + r;
-        const float mc = part_ml[idx * 2];
-        if (mc == -INFINITY) continue;   // chunk entirely after this query's position
-        const float w = exp2f(mc - mx);
-        den += w * part_ml[idx * 2 + 1];
-        num += w * part_o[idx * hd + dim];
-    }
-    *dst = num / den;
+    store_x_unit(static_cast<uint4*>(xo.frags), xo.mt, xo.planes, m, unit, v);
 }
 
 // Plain fp32 attention for fp32 caches: one workgroup per (row, query head).
@@ -356,7 +360,7 @@ static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, 
 
 int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,
                      int n_q_heads, int layer, const void* cache, const float* q, float* part_o, float* part_ml,
-                     float* out, int max_window, Profiler* prof, hipStream_t s)
+                     const XOut& xo, int max_window, Profiler* prof, hipStream_t s)
 {
     const int hd = g.head_dim;
     const float scale = 1.0f / sqrtf((float)hd);
@@ -366,7 +370,7 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
         if (lds > 60 * 1024) return fail(SPEC_ERR_SHAPE, "fp32 attention supports max_kv_len up to ~15000");
         ProfScope ps(prof, SPEC_PROF_ATTENTION, s);
         hipLaunchKernelGGL(attn_f32_kernel, dim3(M, n_q_heads), dim3(256), lds, s, t, g, n_q_heads, layer,
-                           (const float*)cache, q, scale, out);
+                           (const float*)cache, q, scale, xo.plain);
         SPECV_LAUNCH_CHECK("attn_f32_kernel");
         return SPEC_OK;
     }
@@ -391,8 +395,8 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
     }
     if (rc) return rc;
     ProfScope ps(prof, SPEC_PROF_ATTN_MERGE, s);
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(M, n_q_heads), dim3(hd), 0, s, t, ks, g.n_kv_heads, n_q_heads, hd,
-                       p.chunk_keys, p.max_chunks, r_cap, part_o, part_ml, out);
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(M, (n_q_heads * hd / 8 + 63) / 64), dim3(64), 0, s, t, ks, g.n_kv_heads,
+                       n_q_heads, hd, p.chunk_keys, p.max_chunks, r_cap, part_o, part_ml, xo);
     SPECV_LAUNCH_CHECK("attn_merge_kernel");
     return SPEC_OK;
 }

@@ -115,18 +115,39 @@ struct CacheGeom {
 };
 CacheGeom make_cache_geom(const spec_model_cfg& c);
 
-int launch_embed_rmsnorm(int dtype, const void* tok_embed, const int32_t* row_tok, const float* gain, float eps,
-                         int M, int d, float* x, float* h, hipStream_t s);
-// `partial` is [n_split][M][ld]; consumers add the ranges in index order.
-int launch_resid_rmsnorm(const float* partial, int n_split, size_t split_stride, int ld, const float* gain, float eps,
-                         int M, int d, float* x, float* h, hipStream_t s);
-int launch_silu_mul(const float* partial, int n_split, size_t split_stride, int ld, int M, int F, bool interleaved,
-                    float* act, hipStream_t s);
-int launch_rope_append(const float* partial, int n_split, size_t split_stride, int ld, const StepTables& t, int M,
-                       const CacheGeom& g, int n_q_heads, int layer, const float* cos_sin, void* cache,
-                       float* q_out, hipStream_t s);
-int launch_reduce_splits(const float* partial, int n_split, size_t split_stride, int M, int N, int ld, float* out,
+// Row-wise sums of squares travel as SSQ_CHUNK-column partial sums ([M][n_ssq]).  RMSNorm is split
+// in two: the producer of a GEMM's input multiplies by the gain; the row's 1/rms factors out of the
+// dot product and is applied by the consumer of the GEMM's output (NormScale).
+constexpr int SSQ_CHUNK = 1024;
+inline int ssq_chunks(int d) { return (d + SSQ_CHUNK - 1) / SSQ_CHUNK; }
+struct NormScale {
+    const float* ssq;   // NULL: no scaling
+    int n_ssq;
+    int d;              // row length the mean is taken over
+    float eps;
+};
+// Where a producer puts a GEMM operand: fragment buffer (bf16 path) and/or plain fp32 rows.
+struct XOut {
+    void* frags;        // NULL on the fp32 path
+    int mt, planes;
+    float* plain;       // NULL on the bf16 path
+};
+int launch_embed(int dtype, const void* tok_embed, const int32_t* row_tok, int M, int d, float* x, float* ssq,
+                 const float* gain, const XOut& xo, hipStream_t s);
+// x[m] += sum of the n_split partial ranges ([n_split][M][ld], added in index order); ssq updated;
+// x * gain written as the next GEMM's operand
+int launch_resid(const float* partial, int n_split, size_t split_stride, int ld, int M, int d, float* x, float* ssq,
+                 const float* gain, const XOut& xo, hipStream_t s);
+// h = x * inv_rms * gain (only the fp32 path materialises normalised activations)
+int launch_rmsnorm_apply(const float* x, const float* ssq, const float* gain, float eps, int M, int d, float* h,
                          hipStream_t s);
+int launch_silu_mul(const float* partial, int n_split, size_t split_stride, int ld, int M, int F, bool interleaved,
+                    const NormScale& ns, const XOut& xo, hipStream_t s);
+int launch_rope_append(const float* partial, int n_split, size_t split_stride, int ld, const StepTables& t, int M,
+                       const CacheGeom& g, int n_q_heads, int layer, const float* cos_sin, const NormScale& ns,
+                       void* cache, float* q_out, hipStream_t s);
+int launch_reduce_splits(const float* partial, int n_split, size_t split_stride, int M, int N, int ld,
+                         const float* ssq, int n_ssq, int d, float eps, float* out, hipStream_t s);
 int launch_kv_copy(const CacheGeom& g, void* cache, int slot, int pos0, int n_pos, void* plain, bool to_cache,
                    hipStream_t s);
 
@@ -137,12 +158,18 @@ struct GemmPlan {
     int n_pad;        // N rounded up to 16
     int mt;           // 16-row tiles
     int nt;           // 16-column tiles per wavefront
+    int planes;       // 2: bf16 head + remainder; 1: bf16 head only
     int kb_per_split; // 32-wide K blocks per range
 };
-GemmPlan plan_gemm(int M, int N, int K, int cu_count);
+GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x);
+int gemm_row_tiles(int M);   // row tiles (mt) of the variant that serves M rows; 0 if none
 size_t gemm_partial_elems(const GemmPlan& p, int M);
-int launch_gemm_bf16(const GemmPlan& p, const float* x, const void* w_packed, int M, int N, int K,
-                     bool split_x, float* partial, hipStream_t s);
+// x_frags: X as operand fragments (frag.h) with p.mt row tiles and p.planes planes
+int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packed, int M, int N, int K,
+                     float* partial, hipStream_t s);
+int launch_pack_x(const float* x, const float* gain, int M, int K, int mt_count, int planes, void* x_frags,
+                  hipStream_t s);
+void set_gemm_wg_target(int workgroups);
 int launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* y, hipStream_t s);
 
 struct AttnPlan {
@@ -154,6 +181,6 @@ size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int gr
                            int cu_count);
 int launch_attention(const AttnPlan& p, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M,
                      const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
-                     float* part_o, float* part_ml, float* out, int max_window, Profiler* prof, hipStream_t s);
+                     float* part_o, float* part_ml, const XOut& xo, int max_window, Profiler* prof, hipStream_t s);
 
 }  // namespace specv

@@ -3,6 +3,7 @@
 // pass: embedding + RMSNorm, residual add + RMSNorm, SiLU gating, rotary embedding + KV append.
 #include "cache_layout.h"
 #include "common.h"
+#include "frag.h"
 
 namespace specv {
 namespace {
@@ -27,126 +28,181 @@ __device__ __forceinline__ float sum_splits(const float* p, int n_split, size_t 
     return v;
 }
 
-// x[m] = E[token_m];  h[m] = x / sqrt(mean(x^2) + eps) * gain
-template <typename T>
-__global__ void __launch_bounds__(TPB) embed_rmsnorm_kernel(const T* __restrict__ E, const int32_t* __restrict__ row_tok,
-                                                            const float* __restrict__ gain, float eps, int d,
-                                                            float* __restrict__ x, float* __restrict__ h)
+__device__ __forceinline__ float4 sum_splits4(const float* p, int n_split, size_t stride)
 {
-    __shared__ double sh[4];
-    const int m = blockIdx.x;
-    const T* e = E + (size_t)row_tok[m] * d;
-    double ss = 0.0;
-    for (int i = threadIdx.x; i < d; i += TPB) {
-        const float v = static_cast<float>(e[i]);
-        x[(size_t)m * d + i] = v;
-        ss += (double)v * v;
+    float4 v = *reinterpret_cast<const float4*>(p);
+    for (int s = 1; s < n_split; ++s) {
+        const float4 w = *reinterpret_cast<const float4*>(p + (size_t)s * stride);
+        v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
     }
-    ss = block_sum(ss, sh);
-    const float inv = (float)(1.0 / sqrt(ss / d + (double)eps));
-    for (int i = threadIdx.x; i < d; i += TPB) h[(size_t)m * d + i] = x[(size_t)m * d + i] * inv * gain[i];
+    return v;
 }
 
-// x[m] += sum of partial ranges;  h[m] = rmsnorm(x[m]) * gain
-__global__ void __launch_bounds__(TPB) resid_rmsnorm_kernel(const float* __restrict__ partial, int n_split,
-                                                            size_t split_stride, int ld, const float* __restrict__ gain,
-                                                            float eps, int d, float* __restrict__ x,
+// Emit 8 consecutive values of a row as the next GEMM's operand: x * gain, as fragments (bf16 path)
+// and/or plain fp32 (fp32 path, where the normalisation is applied separately).
+__device__ __forceinline__ void emit_operand(const XOut& xo, int m, int k8, int d, const float (&v)[8],
+                                             const float* __restrict__ gain)
+{
+    if (xo.frags) {
+        float g[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[e] = v[e] * (gain ? gain[k8 * 8 + e] : 1.f);
+        store_x_unit(static_cast<uint4*>(xo.frags), xo.mt, xo.planes, m, k8, g);
+    }
+    if (xo.plain) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xo.plain[(size_t)m * d + k8 * 8 + e] = v[e];
+    }
+}
+
+constexpr int UNIT_TPB = SSQ_CHUNK / 8;   // one thread per 8 columns of a chunk
+
+// One workgroup per (row, SSQ_CHUNK columns): x = E[token] (or x += partial sums); ssq[m][chunk] =
+// sum x^2 over the chunk; x * gain goes out as the next GEMM's operand.  d is a multiple of 8.
+template <typename T, bool EMBED>
+__global__ void __launch_bounds__(UNIT_TPB) resid_kernel(const T* __restrict__ E, const int32_t* __restrict__ row_tok,
+                                                         const float* __restrict__ partial, int n_split,
+                                                         size_t split_stride, int ld, int d, float* __restrict__ x,
+                                                         float* __restrict__ ssq, const float* __restrict__ gain,
+                                                         XOut xo)
+{
+    __shared__ double sh[2];
+    const int m = blockIdx.x, chunk = blockIdx.y;
+    const int k8 = chunk * UNIT_TPB + threadIdx.x;
+    double ss = 0.0;
+    if (k8 * 8 < d) {
+        float v[8];
+        float* xp = x + (size_t)m * d + k8 * 8;
+        if constexpr (EMBED) {
+            const T* e = E + (size_t)row_tok[m] * d + k8 * 8;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = static_cast<float>(e[i]);
+        } else {
+            const float4 a = *reinterpret_cast<const float4*>(xp), b = *reinterpret_cast<const float4*>(xp + 4);
+            const float* pp = partial + (size_t)m * ld + k8 * 8;
+            const float4 pa = sum_splits4(pp, n_split, split_stride), pb = sum_splits4(pp + 4, n_split, split_stride);
+            v[0] = a.x + pa.x; v[1] = a.y + pa.y; v[2] = a.z + pa.z; v[3] = a.w + pa.w;
+            v[4] = b.x + pb.x; v[5] = b.y + pb.y; v[6] = b.z + pb.z; v[7] = b.w + pb.w;
+        }
+        *reinterpret_cast<float4*>(xp) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(xp + 4) = make_float4(v[4], v[5], v[6], v[7]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ss += (double)v[i] * v[i];
+        emit_operand(xo, m, k8, d, v, gain);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) ssq[(size_t)m * gridDim.y + chunk] = (float)(sh[0] + sh[1]);
+}
+
+// h = x / sqrt(mean(x^2) + eps) * gain from the partial sums of squares
+__global__ void __launch_bounds__(TPB) rmsnorm_apply_kernel(const float* __restrict__ x, const float* __restrict__ ssq,
+                                                            int n_ssq, const float* __restrict__ gain, float eps, int d,
                                                             float* __restrict__ h)
 {
-    __shared__ double sh[4];
     const int m = blockIdx.x;
-    double ss = 0.0;
-    for (int i = threadIdx.x; i < d; i += TPB) {
-        const float v = x[(size_t)m * d + i] + sum_splits(partial + (size_t)m * ld + i, n_split, split_stride);
-        x[(size_t)m * d + i] = v;
-        ss += (double)v * v;
-    }
-    ss = block_sum(ss, sh);
-    const float inv = (float)(1.0 / sqrt(ss / d + (double)eps));
+    float ss = 0.f;
+    for (int i = 0; i < n_ssq; ++i) ss += ssq[(size_t)m * n_ssq + i];
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     for (int i = threadIdx.x; i < d; i += TPB) h[(size_t)m * d + i] = x[(size_t)m * d + i] * inv * gain[i];
 }
 
-// act[m][f] = silu(gate) * up.  Interleaved: the GEMM's columns come in 16-wide tiles alternating
-// gate and up (see spec_pack_weight); otherwise gate columns [0,F) then up columns [F,2F).
+// act[m][f] = silu(gate) * up for 8 consecutive f per thread, gate and up first scaled by the row's
+// 1/rms (the FFN norm's scale, see NormScale).  Interleaved: the GEMM's columns come in 16-wide
+// tiles alternating gate and up (see spec_pack_weight); otherwise gate columns [0,F) then up
+// columns [F,2F).  The result goes out as the down projection's operand.  F is a multiple of 8.
 __global__ void __launch_bounds__(TPB) silu_mul_kernel(const float* __restrict__ partial, int n_split, size_t split_stride,
-                                                       int ld, int M, int F, int interleaved, float* __restrict__ act)
+                                                       int ld, int M, int F, int interleaved, NormScale ns, XOut xo)
 {
-    const size_t total = (size_t)M * F;
-    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < total; i += (size_t)gridDim.x * TPB) {
-        const int m = (int)(i / F), f = (int)(i % F);
+    const int units = F / 8;
+    for (int i = blockIdx.x * TPB + threadIdx.x; i < M * units; i += gridDim.x * TPB) {
+        const int m = i / units, k8 = i % units, f = k8 * 8;
         const int cg = interleaved ? ((f >> 4) << 5) + (f & 15) : f;
         const int cu = interleaved ? cg + 16 : F + f;
-        const float g = sum_splits(partial + (size_t)m * ld + cg, n_split, split_stride);
-        const float u = sum_splits(partial + (size_t)m * ld + cu, n_split, split_stride);
-        act[i] = g / (1.f + expf(-g)) * u;
+        const float r = row_inv_rms(ns.ssq, ns.n_ssq, m, ns.d, ns.eps);
+        const float* pg = partial + (size_t)m * ld + cg;
+        const float* pu = partial + (size_t)m * ld + cu;
+        const float4 g0 = sum_splits4(pg, n_split, split_stride), g1 = sum_splits4(pg + 4, n_split, split_stride);
+        const float4 u0 = sum_splits4(pu, n_split, split_stride), u1 = sum_splits4(pu + 4, n_split, split_stride);
+        const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+        const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float ge = g[e] * r;
+            v[e] = ge / (1.f + expf(-ge)) * (u[e] * r);
+        }
+        emit_operand(xo, m, k8, F, v, nullptr);
     }
 }
 
-// One workgroup per row: sum the q|k|v partial ranges, rotate q and k at the row's absolute
-// position (pairs (i, i+hd/2), angle from the table), write q, and put k and v -- rounded to the
-// cache's storage type -- into the row's slot at that position.
+// One 64-lane workgroup per (row, head of the q|k|v projection): sum the partial ranges, rotate
+// q and k heads at the row's absolute position (pairs (i, i+hd/2), angle from the table), write q,
+// and put k and v -- rounded to the cache's storage type -- into the row's slot at that position.
 template <bool BF16>
-__global__ void __launch_bounds__(TPB) rope_append_kernel(const float* __restrict__ partial, int n_split,
-                                                          size_t split_stride, int ld, StepTables t, CacheGeom g,
-                                                          int n_q_heads, int layer, const float* __restrict__ cos_sin,
-                                                          void* cache, float* __restrict__ q_out)
+__global__ void __launch_bounds__(64) rope_append_kernel(const float* __restrict__ partial, int n_split,
+                                                         size_t split_stride, int ld, StepTables t, CacheGeom g,
+                                                         int n_q_heads, int layer, const float* __restrict__ cos_sin,
+                                                         NormScale ns, void* cache, float* __restrict__ q_out)
 {
-    const int m = blockIdx.x;
+    const int m = blockIdx.x, head = blockIdx.y;
     const int pos = t.row_pos[m];
     const int hd = g.head_dim, half = hd >> 1;
-    const int dq = n_q_heads * hd, dkv = g.n_kv_heads * hd;
-    const float* row = partial + (size_t)m * ld;
+    const int dq = n_q_heads * hd;
+    const float* row = partial + (size_t)m * ld + head * hd;
     if (pos < 0) {   // row of a skipped sequence: defined output, no cache write
-        for (int i = threadIdx.x; i < dq; i += TPB) q_out[(size_t)m * dq + i] = 0.f;
+        if (head < n_q_heads)
+            for (int i = threadIdx.x; i < hd; i += 64) q_out[(size_t)m * dq + head * hd + i] = 0.f;
         return;
     }
     const int slot = t.seq_slot[t.row_seq[m]];
-    const float* cs = cos_sin + (size_t)pos * hd;   // [half][2]
-    // rotation pairs of q and k
-    const int n_pairs = (n_q_heads + g.n_kv_heads) * half;
-    for (int p = threadIdx.x; p < n_pairs; p += TPB) {
-        const int head = p / half, i = p % half;
-        const int col = head * hd + i;   // q heads then k heads are contiguous in the GEMM output
-        const float a = sum_splits(row + col, n_split, split_stride);
-        const float b = sum_splits(row + col + half, n_split, split_stride);
-        const float c = cs[2 * i], s = cs[2 * i + 1];
-        const float ra = a * c - b * s, rb = a * s + b * c;
-        if (head < n_q_heads) {
-            q_out[(size_t)m * dq + col] = ra;
-            q_out[(size_t)m * dq + col + half] = rb;
-        } else {
-            const int kh = head - n_q_heads;
-            const size_t base = cache_head_base(g, layer, slot, kh);
-            if constexpr (BF16) {
-                __bf16* c16 = static_cast<__bf16*>(cache);
-                c16[base + tiled_k_offset(hd, pos, i)] = static_cast<__bf16>(ra);
-                c16[base + tiled_k_offset(hd, pos, i + half)] = static_cast<__bf16>(rb);
+    const float rs = row_inv_rms(ns.ssq, ns.n_ssq, m, ns.d, ns.eps);   // the attention norm's row scale
+    if (head < n_q_heads + g.n_kv_heads) {
+        const float* cs = cos_sin + (size_t)pos * hd;   // [half][2]
+        for (int i = threadIdx.x; i < half; i += 64) {
+            const float a = sum_splits(row + i, n_split, split_stride) * rs;
+            const float b = sum_splits(row + i + half, n_split, split_stride) * rs;
+            const float c = cs[2 * i], s = cs[2 * i + 1];
+            const float ra = a * c - b * s, rb = a * s + b * c;
+            if (head < n_q_heads) {
+                q_out[(size_t)m * dq + head * hd + i] = ra;
+                q_out[(size_t)m * dq + head * hd + i + half] = rb;
             } else {
-                float* c32 = static_cast<float*>(cache);
-                c32[base + plain_offset(g, 0, pos, i)] = ra;
-                c32[base + plain_offset(g, 0, pos, i + half)] = rb;
+                const size_t base = cache_head_base(g, layer, slot, head - n_q_heads);
+                if constexpr (BF16) {
+                    __bf16* c16 = static_cast<__bf16*>(cache);
+                    c16[base + tiled_k_offset(hd, pos, i)] = static_cast<__bf16>(ra);
+                    c16[base + tiled_k_offset(hd, pos, i + half)] = static_cast<__bf16>(rb);
+                } else {
+                    float* c32 = static_cast<float*>(cache);
+                    c32[base + plain_offset(g, 0, pos, i)] = ra;
+                    c32[base + plain_offset(g, 0, pos, i + half)] = rb;
+                }
             }
         }
-    }
-    for (int e = threadIdx.x; e < dkv; e += TPB) {
-        const int kh = e / hd, i = e % hd;
-        const float v = sum_splits(row + dq + dkv + e, n_split, split_stride);
-        const size_t base = cache_head_base(g, layer, slot, kh);
-        if constexpr (BF16)
-            static_cast<__bf16*>(cache)[base + tiled_v_offset(hd, pos, i)] = static_cast<__bf16>(v);
-        else
-            static_cast<float*>(cache)[base + plain_offset(g, 1, pos, i)] = v;
+    } else {
+        const size_t base = cache_head_base(g, layer, slot, head - n_q_heads - g.n_kv_heads);
+        for (int i = threadIdx.x; i < hd; i += 64) {
+            const float v = sum_splits(row + i, n_split, split_stride) * rs;
+            if constexpr (BF16)
+                static_cast<__bf16*>(cache)[base + tiled_v_offset(hd, pos, i)] = static_cast<__bf16>(v);
+            else
+                static_cast<float*>(cache)[base + plain_offset(g, 1, pos, i)] = v;
+        }
     }
 }
 
 __global__ void __launch_bounds__(TPB) reduce_splits_kernel(const float* __restrict__ partial, int n_split,
-                                                            size_t split_stride, int M, int N, int ld,
+                                                            size_t split_stride, int M, int N, int ld, NormScale ns,
                                                             float* __restrict__ out)
 {
     const size_t total = (size_t)M * N;
     for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < total; i += (size_t)gridDim.x * TPB) {
         const int m = (int)(i / N), n = (int)(i % N);
-        out[i] = sum_splits(partial + (size_t)m * ld + n, n_split, split_stride);
+        out[i] = sum_splits(partial + (size_t)m * ld + n, n_split, split_stride)
+                 * row_inv_rms(ns.ssq, ns.n_ssq, m, ns.d, ns.eps);
     }
 }
 
@@ -210,56 +266,71 @@ CacheGeom make_cache_geom(const spec_model_cfg& c)
     return g;
 }
 
-int launch_embed_rmsnorm(int dtype, const void* tok_embed, const int32_t* row_tok, const float* gain, float eps, int M,
-                         int d, float* x, float* h, hipStream_t s)
+int launch_embed(int dtype, const void* tok_embed, const int32_t* row_tok, int M, int d, float* x, float* ssq,
+                 const float* gain, const XOut& xo, hipStream_t s)
 {
+    if (d % 8) return fail(SPEC_ERR_SHAPE, "d_model must be a multiple of 8");
+    const dim3 grid(M, ssq_chunks(d));
     if (dtype == SPEC_DTYPE_BF16)
-        hipLaunchKernelGGL(embed_rmsnorm_kernel<__bf16>, dim3(M), dim3(TPB), 0, s, (const __bf16*)tok_embed, row_tok, gain,
-                           eps, d, x, h);
+        hipLaunchKernelGGL((resid_kernel<__bf16, true>), grid, dim3(UNIT_TPB), 0, s, (const __bf16*)tok_embed, row_tok,
+                           nullptr, 0, 0, 0, d, x, ssq, gain, xo);
     else
-        hipLaunchKernelGGL(embed_rmsnorm_kernel<float>, dim3(M), dim3(TPB), 0, s, (const float*)tok_embed, row_tok, gain,
-                           eps, d, x, h);
-    SPECV_LAUNCH_CHECK("embed_rmsnorm_kernel");
+        hipLaunchKernelGGL((resid_kernel<float, true>), grid, dim3(UNIT_TPB), 0, s, (const float*)tok_embed, row_tok,
+                           nullptr, 0, 0, 0, d, x, ssq, gain, xo);
+    SPECV_LAUNCH_CHECK("resid_kernel<embed>");
     return SPEC_OK;
 }
 
-int launch_resid_rmsnorm(const float* partial, int n_split, size_t split_stride, int ld, const float* gain, float eps,
-                         int M, int d, float* x, float* h, hipStream_t s)
+int launch_resid(const float* partial, int n_split, size_t split_stride, int ld, int M, int d, float* x, float* ssq,
+                 const float* gain, const XOut& xo, hipStream_t s)
 {
-    hipLaunchKernelGGL(resid_rmsnorm_kernel, dim3(M), dim3(TPB), 0, s, partial, n_split, split_stride, ld, gain, eps, d,
-                       x, h);
-    SPECV_LAUNCH_CHECK("resid_rmsnorm_kernel");
+    if (d % 8 || ld % 4 || split_stride % 4) return fail(SPEC_ERR_SHAPE, "residual rows must be multiples of 8 wide");
+    const dim3 grid(M, ssq_chunks(d));
+    hipLaunchKernelGGL((resid_kernel<float, false>), grid, dim3(UNIT_TPB), 0, s, nullptr, nullptr, partial, n_split,
+                       split_stride, ld, d, x, ssq, gain, xo);
+    SPECV_LAUNCH_CHECK("resid_kernel");
+    return SPEC_OK;
+}
+
+int launch_rmsnorm_apply(const float* x, const float* ssq, const float* gain, float eps, int M, int d, float* h,
+                         hipStream_t s)
+{
+    hipLaunchKernelGGL(rmsnorm_apply_kernel, dim3(M), dim3(TPB), 0, s, x, ssq, ssq_chunks(d), gain, eps, d, h);
+    SPECV_LAUNCH_CHECK("rmsnorm_apply_kernel");
     return SPEC_OK;
 }
 
 int launch_silu_mul(const float* partial, int n_split, size_t split_stride, int ld, int M, int F, bool interleaved,
-                    float* act, hipStream_t s)
+                    const NormScale& ns, const XOut& xo, hipStream_t s)
 {
-    hipLaunchKernelGGL(silu_mul_kernel, dim3(blocks_for((size_t)M * F)), dim3(TPB), 0, s, partial, n_split,
-                       split_stride, ld, M, F, interleaved ? 1 : 0, act);
+    if (F % 8 || ld % 4 || split_stride % 4) return fail(SPEC_ERR_SHAPE, "d_ffn must be a multiple of 8");
+    hipLaunchKernelGGL(silu_mul_kernel, dim3(blocks_for((size_t)M * F / 8)), dim3(TPB), 0, s, partial, n_split,
+                       split_stride, ld, M, F, interleaved ? 1 : 0, ns, xo);
     SPECV_LAUNCH_CHECK("silu_mul_kernel");
     return SPEC_OK;
 }
 
 int launch_rope_append(const float* partial, int n_split, size_t split_stride, int ld, const StepTables& t, int M,
-                       const CacheGeom& g, int n_q_heads, int layer, const float* cos_sin, void* cache, float* q_out,
-                       hipStream_t s)
+                       const CacheGeom& g, int n_q_heads, int layer, const float* cos_sin, const NormScale& ns,
+                       void* cache, float* q_out, hipStream_t s)
 {
+    const dim3 grid(M, n_q_heads + 2 * g.n_kv_heads);
     if (g.dtype == SPEC_DTYPE_BF16)
-        hipLaunchKernelGGL(rope_append_kernel<true>, dim3(M), dim3(TPB), 0, s, partial, n_split, split_stride, ld, t, g,
-                           n_q_heads, layer, cos_sin, cache, q_out);
+        hipLaunchKernelGGL(rope_append_kernel<true>, grid, dim3(64), 0, s, partial, n_split, split_stride, ld, t, g,
+                           n_q_heads, layer, cos_sin, ns, cache, q_out);
     else
-        hipLaunchKernelGGL(rope_append_kernel<false>, dim3(M), dim3(TPB), 0, s, partial, n_split, split_stride, ld, t, g,
-                           n_q_heads, layer, cos_sin, cache, q_out);
+        hipLaunchKernelGGL(rope_append_kernel<false>, grid, dim3(64), 0, s, partial, n_split, split_stride, ld, t, g,
+                           n_q_heads, layer, cos_sin, ns, cache, q_out);
     SPECV_LAUNCH_CHECK("rope_append_kernel");
     return SPEC_OK;
 }
 
-int launch_reduce_splits(const float* partial, int n_split, size_t split_stride, int M, int N, int ld, float* out,
-                         hipStream_t s)
+int launch_reduce_splits(const float* partial, int n_split, size_t split_stride, int M, int N, int ld,
+                         const float* ssq, int n_ssq, int d, float eps, float* out, hipStream_t s)
 {
+    NormScale ns{ssq, n_ssq, d, eps};
     hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks_for((size_t)M * N)), dim3(TPB), 0, s, partial, n_split,
-                       split_stride, M, N, ld, out);
+                       split_stride, M, N, ld, ns, out);
     SPECV_LAUNCH_CHECK("reduce_splits_kernel");
     return SPEC_OK;
 }

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <vector>
 
+#include "frag.h"
 #include "handle.h"
 
 namespace specv {
@@ -43,6 +44,7 @@ int forward_init(spec_handle* h, int max_rows)
     };
     A(&h->x, (size_t)max_rows * z.d);
     A(&h->hn, (size_t)max_rows * z.d);
+    A(&h->ssq, (size_t)max_rows * ssq_chunks(z.d));
     A(&h->q, (size_t)max_rows * z.dq);
     A(&h->att, (size_t)max_rows * z.dq);
     A(&h->act, (size_t)max_rows * z.F);
@@ -50,13 +52,19 @@ int forward_init(spec_handle* h, int max_rows)
     A(&h->cos_sin, (size_t)c.max_kv_len * c.head_dim);
     size_t part = 0;
     if (c.dtype == SPEC_DTYPE_BF16) {
+        // operand fragments: the widest GEMM input (d_model, q width or d_ffn), both planes, at the
+        // row-tile count of the largest step; zeroed once so that padding blocks stay zero
+        const int kmax = std::max(std::max(z.d, z.dq), z.F);
+        const size_t xf_bytes = xfrag_uint4s(gemm_row_tiles(max_rows), 2, kmax) * sizeof(uint4);
+        if (rc == SPEC_OK) rc = a.alloc(&h->xf, xf_bytes);
+        if (rc == SPEC_OK && hipMemset(h->xf, 0, xf_bytes) != hipSuccess) rc = fail(SPEC_ERR_DEVICE, "hipMemset failed");
         // partial-sum space for the largest GEMM at any row count
         const int Ns[G_COUNT] = {z.nqkv, z.d, 2 * z.F, z.d, z.V};
         const int Ks[G_COUNT] = {z.d, z.dq, z.d, z.F, z.d};
         for (int M = 16; M <= (max_rows + 15) / 16 * 16 && M <= 352; M += 16)
             for (int i = 0; i < G_COUNT; ++i) {
                 const int rows = M < max_rows ? M : max_rows;
-                const size_t e = gemm_partial_elems(plan_gemm(rows, Ns[i], Ks[i], h->cu_count), rows);
+                const size_t e = gemm_partial_elems(plan_gemm(rows, Ns[i], Ks[i], h->cu_count, true), rows);
                 if (e > part) part = e;
             }
         h->attn_plan = plan_attention(c.max_kv_len, c.max_batch, c.n_kv_heads, h->cu_count);
@@ -101,51 +109,77 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
         if (rc) return rc;                      \
     } while (0)
 
-    // A GEMM leaves either K-range partial sums (bf16) or the whole result (fp32) in h->partial;
-    // the consumer is told how many ranges to add and the row stride.
+    // bf16 path: every producer writes the next GEMM's operand as fragments of (value * gain); the
+    // GEMM leaves K-range partial sums in h->partial, and its consumer adds them up and applies the
+    // row's 1/rms where the operand was a normalised residual.  fp32 path: plain rows, normalisation
+    // materialised, GEMM results whole.
     struct Out {
         int n_split;
         size_t stride;
         int ld;
     };
-    auto gemm = [&](const float* xin, const void* w, int N, int K, Out* o) -> int {
+    const int n_ssq = ssq_chunks(z.d);
+    const int mt = bf16 ? gemm_row_tiles(M) : 0;
+    const int planes = h->split_act ? 2 : 1;
+    const XOut to_xf{bf16 ? h->xf : nullptr, mt, planes, nullptr};            // operand of QKV / gate-up / LM head
+    const XOut to_att{bf16 ? h->xf : nullptr, mt, planes, bf16 ? nullptr : h->att};
+    const XOut to_act{bf16 ? h->xf : nullptr, mt, planes, bf16 ? nullptr : h->act};
+    const NormScale scaled{bf16 ? h->ssq : nullptr, n_ssq, z.d, c.rms_eps};
+    const NormScale unscaled{nullptr, 0, 0, 0.f};
+    auto gemm = [&](const float* plain_in, const float* gain, const void* w, int N, int K, Out* o) -> int {
         if (bf16) {
-            const GemmPlan p = plan_gemm(M, N, K, h->cu_count);
+            const GemmPlan p = plan_gemm(M, N, K, h->cu_count, h->split_act);
             o->n_split = p.n_split;
             o->ld = p.n_pad;
             o->stride = (size_t)M * p.n_pad;
-            return launch_gemm_bf16(p, xin, w, M, N, K, h->split_act, h->partial, s);
+            ProfScope ps_(&h->prof, SPEC_PROF_GEMM, s);
+            return launch_gemm_bf16(p, h->xf, w, M, N, K, h->partial, s);
         }
         o->n_split = 1;
         o->ld = N;
         o->stride = 0;
-        return launch_gemm_f32(xin, (const float*)w, M, N, K, h->partial, s);
+        if (gain) {
+            ProfScope ps_(&h->prof, SPEC_PROF_GLUE, s);
+            int r = launch_rmsnorm_apply(plain_in, h->ssq, gain, c.rms_eps, M, z.d, h->hn, s);
+            if (r) return r;
+            plain_in = h->hn;
+        }
+        ProfScope ps_(&h->prof, SPEC_PROF_GEMM, s);
+        return launch_gemm_f32(plain_in, (const float*)w, M, N, K, h->partial, s);
     };
 
-    RUN(SPEC_PROF_GLUE, launch_embed_rmsnorm(c.dtype, h->tok_embed, t.row_tok, h->layers[0].attn_norm, c.rms_eps, M, z.d, h->x, h->hn, s));
+    RUN(SPEC_PROF_GLUE, launch_embed(c.dtype, h->tok_embed, t.row_tok, M, z.d, h->x, h->ssq, h->layers[0].attn_norm, to_xf, s));
     Out o;
     for (int l = 0; l < c.n_layers; ++l) {
         const spec_layer_weights& w = h->layers[l];
-        RUN(SPEC_PROF_GEMM, gemm(h->hn, w.w_qkv, z.nqkv, z.d, &o));
-        RUN(SPEC_PROF_GLUE, launch_rope_append(h->partial, o.n_split, o.stride, o.ld, t, M, h->geom, c.n_q_heads, l, h->cos_sin,
-                               h->kv_cache, h->q, s));
-        rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache, h->q, h->attn_part_o,
-                              h->attn_part_ml, h->att, c.max_lookahead + 1, &h->prof, s);
+        rc = gemm(h->x, w.attn_norm, w.w_qkv, z.nqkv, z.d, &o);
         if (rc) return rc;
-        RUN(SPEC_PROF_GEMM, gemm(h->att, w.w_o, z.d, z.dq, &o));
-        RUN(SPEC_PROF_GLUE, launch_resid_rmsnorm(h->partial, o.n_split, o.stride, o.ld, w.ffn_norm, c.rms_eps, M, z.d, h->x, h->hn, s));
-        RUN(SPEC_PROF_GEMM, gemm(h->hn, w.w_gate_up, 2 * z.F, z.d, &o));
-        RUN(SPEC_PROF_GLUE, launch_silu_mul(h->partial, o.n_split, o.stride, o.ld, M, z.F, bf16, h->act, s));
-        RUN(SPEC_PROF_GEMM, gemm(h->act, w.w_down, z.d, z.F, &o));
+        RUN(SPEC_PROF_GLUE, launch_rope_append(h->partial, o.n_split, o.stride, o.ld, t, M, h->geom, c.n_q_heads, l, h->cos_sin,
+                               scaled, h->kv_cache, h->q, s));
+        rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache, h->q, h->attn_part_o,
+                              h->attn_part_ml, to_att, c.max_lookahead + 1, &h->prof, s);
+        if (rc) return rc;
+        rc = gemm(h->att, nullptr, w.w_o, z.d, z.dq, &o);
+        if (rc) return rc;
+        RUN(SPEC_PROF_GLUE, launch_resid(h->partial, o.n_split, o.stride, o.ld, M, z.d, h->x, h->ssq, w.ffn_norm, to_xf, s));
+        rc = gemm(h->x, w.ffn_norm, w.w_gate_up, 2 * z.F, z.d, &o);
+        if (rc) return rc;
+        RUN(SPEC_PROF_GLUE, launch_silu_mul(h->partial, o.n_split, o.stride, o.ld, M, z.F, bf16, scaled, to_act, s));
+        rc = gemm(h->act, nullptr, w.w_down, z.d, z.F, &o);
+        if (rc) return rc;
         const float* next_gain = (l + 1 < c.n_layers) ? h->layers[l + 1].attn_norm : h->final_norm;
-        RUN(SPEC_PROF_GLUE, launch_resid_rmsnorm(h->partial, o.n_split, o.stride, o.ld, next_gain, c.rms_eps, M, z.d, h->x, h->hn, s));
+        RUN(SPEC_PROF_GLUE, launch_resid(h->partial, o.n_split, o.stride, o.ld, M, z.d, h->x, h->ssq, next_gain, to_xf, s));
     }
     if (bf16) {
-        RUN(SPEC_PROF_GEMM, gemm(h->hn, h->lm_head, z.V, z.d, &o));
-        RUN(SPEC_PROF_GLUE, launch_reduce_splits(h->partial, o.n_split, o.stride, M, z.V, o.ld, logits_out, s));
+        rc = gemm(h->x, h->final_norm, h->lm_head, z.V, z.d, &o);
+        if (rc) return rc;
+        RUN(SPEC_PROF_GLUE, launch_reduce_splits(h->partial, o.n_split, o.stride, M, z.V, o.ld, h->ssq, n_ssq, z.d, c.rms_eps,
+                                 logits_out, s));
     } else {
+        RUN(SPEC_PROF_GLUE, launch_rmsnorm_apply(h->x, h->ssq, h->final_norm, c.rms_eps, M, z.d, h->hn, s));
         RUN(SPEC_PROF_GEMM, launch_gemm_f32(h->hn, (const float*)h->lm_head, M, z.V, z.d, logits_out, s));
     }
+    (void)unscaled;
 #undef RUN
     return SPEC_OK;
 }

@@ -8,53 +8,59 @@
 //    so every lane issues plain 16-byte loads that coalesce perfectly and each wave streams a
 //    contiguous region.  The loads for the next K chunk are in flight while the current one is
 //    multiplied (two register buffers), and nothing but W goes through that pipe.
-//  * X (a few hundred KiB, L2 resident) is staged through LDS once per workgroup and K chunk, already
-//    in operand order, and shared by the four wavefronts.  With split_x each activation is fed as
-//    a bf16 head plus a bf16 remainder (two matrix instructions): the matrix cores have ample slack
-//    at these shapes, and activation rounding drops to ~2^-17.
+//  * X (a few hundred KiB, L2 resident) arrives already as bf16 operand fragments (frag.h), written
+//    that way by the kernel that produced it, and is staged through LDS once per workgroup and K
+//    chunk with plain 16-byte copies, shared by the four wavefronts, double buffered.  With two
+//    planes each activation is a bf16 head plus a bf16 remainder (two matrix instructions): the
+//    matrix cores have ample slack at these shapes, and activation rounding drops to ~2^-17.
+//  * RMSNorm costs nothing here: the producer multiplies by the gain, and the row's 1/rms factors
+//    out of the dot product, so the consumer of the GEMM's result applies it as a row scale.
 //  * K is cut into ranges across workgroups so that the grid fills all 256 compute units even when
 //    N is small; range sums are left in a partial buffer in a fixed order and added up by the
 //    consumer kernel (no floating-point atomics: bit-reproducible).
 #include "common.h"
+#include "frag.h"
 
 namespace specv {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-union Frag {
-    uint4 u;
-    bf16x8 v;
-};
-
-__device__ __forceinline__ void split8(const float4& a, const float4& b, uint4& hi, uint4& lo, bool want_lo)
+// Workgroup index -> (K range, column block).  Workgroups are dealt round-robin to the 8 XCDs, each
+// with its own L2; ranges are assigned so that all workgroups of one K range run on one XCD and the
+// slice of X they share stays in that L2.  n_split is a power of two.
+__device__ __forceinline__ void map_block(int i, int n_split, int* s, int* nb)
 {
-    const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    Frag h, l;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const __bf16 hb = static_cast<__bf16>(x[e]);          // round to nearest even
-        h.v[e] = hb;
-        l.v[e] = static_cast<__bf16>(x[e] - static_cast<float>(hb));
+    const int x = i & 7, j = i >> 3;
+    if (n_split >= 8) {
+        const int hi = n_split >> 3;
+        *s = x + 8 * (j % hi);
+        *nb = j / hi;
+    } else {
+        const int per = 8 / n_split;
+        *s = x % n_split;
+        *nb = j * per + x / n_split;
     }
-    hi = h.u;
-    if (want_lo) lo = l.u;
 }
 
-template <int MT, int NT, int KC, bool SPLIT>
-__global__ void __launch_bounds__(256) gemm_skinny_kernel(const float* __restrict__ X, const uint4* __restrict__ Wp,
-                                                          float* __restrict__ partial, int M, int K, int n_tiles,
-                                                          int kb_total, int kb_per_split)
-{
-    constexpr int PLANES = SPLIT ? 2 : 1;
-    constexpr int UNITS = MT * 16 * KC * 4;             // 8-element groups of X per chunk
-    constexpr int UPT = (UNITS + 255) / 256;            // per thread
-    __shared__ uint4 xs[PLANES][MT][KC][64];
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// All global loads below are unconditional (addresses clamped into range, W zeroed by selects past
+// the K range): with no branch around a load the compiler can count outstanding loads exactly, so
+// a wait for X never turns into a wait for the whole W stream.
+template <int MT, int NT, int KC, int PLANES>
+__global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restrict__ Xf, const u32x4* __restrict__ Wp,
+                                                          float* __restrict__ partial, int M, int n_tiles,
+                                                          int kb_total, int kb_per_split, int n_split, int n_blocks)
+{
+    constexpr int CHUNK_U4 = KC * PLANES * MT * 64;     // 16-byte units per X chunk (contiguous in Xf)
+    constexpr int UPT = (CHUNK_U4 + 255) / 256;         // per thread
+    __shared__ u32x4 xs[2][CHUNK_U4];                   // two chunk buffers
+
+    int split, nblk;
+    map_block(blockIdx.x, n_split, &split, &nblk);
+    if (nblk >= n_blocks) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tile0 = (blockIdx.x * 4 + wave) * NT;
-    const int kb0 = blockIdx.y * kb_per_split;
+    const int tile0 = (nblk * 4 + wave) * NT;
+    const int kb0 = split * kb_per_split;
     const int kb1 = min(kb0 + kb_per_split, kb_total);
 
     floatx4 acc[MT][NT];
@@ -63,88 +69,87 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const float* __restric
 #pragma unroll
         for (int i = 0; i < NT; ++i) acc[a][i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    uint4 wa[KC][NT], wb[KC][NT];
-    float4 xr[UPT][2];
+    u32x4 wa[KC][NT], wb[KC][NT];
+    u32x4 xr[UPT];
+    int xoff[UPT];
+#pragma unroll
+    for (int u = 0; u < UPT; ++u) xoff[u] = min(u * 256 + (int)threadIdx.x, CHUNK_U4 - 1);   // surplus threads repeat
 
-    auto load_w = [&](int kbase, uint4(&dst)[KC][NT]) {
+    const u32x4* wbase[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) wbase[i] = Wp + (size_t)min(tile0 + i, n_tiles - 1) * kb_total * 64 + lane;
+
+    auto load_w = [&](int kbase, u32x4(&dst)[KC][NT]) {
 #pragma unroll
         for (int c = 0; c < KC; ++c)
 #pragma unroll
-            for (int i = 0; i < NT; ++i) {
-                const int kb = kbase + c, tile = tile0 + i;
-                dst[c][i] = (kb < kb1 && tile < n_tiles) ? Wp[((size_t)tile * kb_total + kb) * 64 + lane]
-                                                         : make_uint4(0, 0, 0, 0);
-            }
+            for (int i = 0; i < NT; ++i) dst[c][i] = wbase[i][(size_t)min(kbase + c, kb_total - 1) * 64];
+    };
+    auto mask_w = [&](int kbase, u32x4(&w)[KC][NT]) {   // K blocks past the range contribute nothing
+#pragma unroll
+        for (int c = 0; c < KC; ++c) {
+            const bool ok = kbase + c < kb1;
+#pragma unroll
+            for (int i = 0; i < NT; ++i) w[c][i] = ok ? w[c][i] : u32x4{0u, 0u, 0u, 0u};
+        }
     };
     auto load_x = [&](int kbase) {
+        // fragment buffers carry XFRAG_PAD_KB zeroed blocks past kb_total, so a chunk may overhang
+        const u32x4* src = Xf + (size_t)min(kbase, kb_total) * (PLANES * MT * 64);
 #pragma unroll
-        for (int u = 0; u < UPT; ++u) {
-            const int unit = u * 256 + threadIdx.x;
-            const int row = unit / (KC * 4), kg = unit % (KC * 4);
-            const int kb = kbase + kg / 4;
-            xr[u][0] = xr[u][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (unit < UNITS && row < M && kb < kb1) {
-                const float4* p = reinterpret_cast<const float4*>(X + (size_t)row * K + kb * 32 + (kg & 3) * 8);
-                xr[u][0] = p[0];
-                xr[u][1] = p[1];
-            }
-        }
+        for (int u = 0; u < UPT; ++u) xr[u] = src[xoff[u]];
     };
-    auto store_x = [&]() {
+    auto store_x = [&](int buf) {
 #pragma unroll
-        for (int u = 0; u < UPT; ++u) {
-            const int unit = u * 256 + threadIdx.x;
-            if (unit < UNITS) {
-                const int row = unit / (KC * 4), kg = unit % (KC * 4);
-                uint4 hi, lo;
-                split8(xr[u][0], xr[u][1], hi, lo, SPLIT);
-                const int l = (kg & 3) * 16 + (row & 15);
-                xs[0][row >> 4][kg >> 2][l] = hi;
-                if constexpr (SPLIT) xs[PLANES - 1][row >> 4][kg >> 2][l] = lo;
-            }
-        }
+        for (int u = 0; u < UPT; ++u) xs[buf][xoff[u]] = xr[u];
     };
-    auto compute = [&](const uint4(&w)[KC][NT]) {
+    auto compute = [&](const u32x4(&w)[KC][NT], int buf) {
 #pragma unroll
         for (int c = 0; c < KC; ++c)
 #pragma unroll
             for (int a = 0; a < MT; ++a) {
-                Frag xh, xl;
-                xh.u = xs[0][a][c][lane];
-                if constexpr (SPLIT) xl.u = xs[PLANES - 1][a][c][lane];
+                const bf16x8 xh = __builtin_bit_cast(bf16x8, xs[buf][((c * PLANES + 0) * MT + a) * 64 + lane]);
+                bf16x8 xl = xh;
+                if constexpr (PLANES == 2) xl = __builtin_bit_cast(bf16x8, xs[buf][((c * PLANES + 1) * MT + a) * 64 + lane]);
 #pragma unroll
                 for (int i = 0; i < NT; ++i) {
-                    Frag wf;
-                    wf.u = w[c][i];
-                    acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xh.v, wf.v, acc[a][i], 0, 0, 0);
-                    if constexpr (SPLIT)
-                        acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xl.v, wf.v, acc[a][i], 0, 0, 0);
+                    const bf16x8 wf = __builtin_bit_cast(bf16x8, w[c][i]);
+                    acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xh, wf, acc[a][i], 0, 0, 0);
+                    if constexpr (PLANES == 2)
+                        acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xl, wf, acc[a][i], 0, 0, 0);
                 }
             }
     };
 
-    // Order inside an iteration: X loads (older) first, then the next chunk's W loads, so that
-    // waiting for X does not wait for the W stream.
+    // The W stream starts first; afterwards X loads are always issued before the W loads of the same
+    // step, so that waiting for X (older) leaves the W loads (younger) in flight.
     load_w(kb0, wa);
+    load_x(kb0);
+    store_x(0);
+    load_x(kb0 + KC);
+    load_w(kb0 + KC, wb);
+    __syncthreads();
+    // step c: multiply chunk c from LDS buffer c%2 while chunk c+1's X (already in registers) is
+    // copied into the other buffer and the loads of chunk c+2 are issued.  K blocks past the range
+    // meet zeroed W (and, past kb_total, the zero padding of the fragment buffer), so ranges need not
+    // be whole chunks and an odd chunk count simply ends with one idle half step.
     for (int kbase = kb0; kbase < kb1; kbase += 2 * KC) {
-        load_x(kbase);
-        load_w(kbase + KC, wb);
-        __syncthreads();            // previous chunk's readers are done with xs
-        store_x();
+        mask_w(kbase, wa);
+        compute(wa, 0);
+        store_x(1);
+        load_x(kbase + 2 * KC);
+        load_w(kbase + 2 * KC, wa);
         __syncthreads();
-        compute(wa);
-        if (kbase + KC < kb1) {
-            load_x(kbase + KC);
-            load_w(kbase + 2 * KC, wa);
-            __syncthreads();
-            store_x();
-            __syncthreads();
-            compute(wb);
-        }
+        mask_w(kbase + KC, wb);
+        compute(wb, 1);
+        store_x(0);
+        load_x(kbase + 3 * KC);
+        load_w(kbase + 3 * KC, wb);
+        __syncthreads();
     }
 
     const int n_pad = n_tiles * 16;
-    float* out = partial + (size_t)blockIdx.y * M * n_pad;
+    float* out = partial + (size_t)split * M * n_pad;
     const int g = lane >> 4, c = lane & 15;
 #pragma unroll
     for (int a = 0; a < MT; ++a)
@@ -159,6 +164,23 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const float* __restric
                 }
             }
         }
+}
+
+// fp32 row-major X[M][K] (optionally times gain[K]) -> fragment buffer
+__global__ void __launch_bounds__(256) pack_x_kernel(const float* __restrict__ X, const float* __restrict__ gain, int M,
+                                                     int K, int mt_count, int planes, uint4* __restrict__ xf)
+{
+    const int units = K / 8;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < M * units; i += gridDim.x * 256) {
+        const int m = i / units, k8 = i % units;
+        const float4 a = *reinterpret_cast<const float4*>(X + (size_t)m * K + k8 * 8);
+        const float4 b = *reinterpret_cast<const float4*>(X + (size_t)m * K + k8 * 8 + 4);
+        float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        if (gain)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= gain[k8 * 8 + e];
+        store_x_unit(xf, mt_count, planes, m, k8, v);
+    }
 }
 
 // Plain fp32 product for the small fp32 configurations: 16x16 output tile per workgroup, K in
@@ -202,16 +224,18 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const uint16_t* __rest
 }
 
 template <int MT, int NT, int KC>
-int launch_variant(const GemmPlan& p, const float* x, const void* w, int M, int K, int n_tiles, bool split,
-                   float* partial, hipStream_t s)
+int launch_variant(const GemmPlan& p, const void* xf, const void* w, int M, int K, int n_tiles, float* partial,
+                   hipStream_t s)
 {
-    dim3 grid((n_tiles + 4 * NT - 1) / (4 * NT), p.n_split);
-    if (split)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, true>), grid, dim3(256), 0, s, x, (const uint4*)w, partial, M,
-                           K, n_tiles, K / 32, p.kb_per_split);
+    const int n_blocks = (n_tiles + 4 * NT - 1) / (4 * NT);
+    int grid = n_blocks * p.n_split;
+    if (p.n_split < 8) grid = (n_blocks + (8 / p.n_split) - 1) / (8 / p.n_split) * 8;
+    if (p.planes == 2)
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 2>), dim3(grid), dim3(256), 0, s, (const u32x4*)xf,
+                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks);
     else
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, false>), grid, dim3(256), 0, s, x, (const uint4*)w, partial,
-                           M, K, n_tiles, K / 32, p.kb_per_split);
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 1>), dim3(grid), dim3(256), 0, s, (const u32x4*)xf,
+                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks);
     SPECV_LAUNCH_CHECK("gemm_skinny_kernel");
     return SPEC_OK;
 }
@@ -219,9 +243,9 @@ int launch_variant(const GemmPlan& p, const float* x, const void* w, int M, int 
 struct Variant {
     int mt, nt, kc;
 };
-// row tiles -> (column tiles per wave, K blocks per LDS chunk); LDS = planes * mt * kc KiB
-constexpr Variant kVariants[] = {{1, 2, 8}, {2, 2, 8}, {3, 2, 8}, {4, 2, 8}, {6, 1, 4},
-                                 {8, 1, 4}, {11, 1, 2}, {16, 1, 2}, {22, 1, 2}};
+// row tiles -> (column tiles per wave, K blocks per LDS chunk); LDS = 2 buffers * planes * mt * kc KiB
+constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {6, 1, 2},
+                                 {8, 1, 2}, {11, 1, 1}, {16, 1, 1}, {22, 1, 1}};
 
 const Variant* pick_variant(int M)
 {
@@ -231,52 +255,70 @@ const Variant* pick_variant(int M)
     return nullptr;
 }
 
+int g_wg_target = 0;   // workgroups per launch to aim for; 0 = two per compute unit
+
 }  // namespace
 
-GemmPlan plan_gemm(int M, int N, int K, int cu_count)
+void set_gemm_wg_target(int t) { g_wg_target = t; }
+
+int gemm_row_tiles(int M)
+{
+    const Variant* v = pick_variant(M);
+    return v ? v->mt : 0;
+}
+
+GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
 {
     GemmPlan p{};
     const Variant* v = pick_variant(M);
     p.mt = v ? v->mt : 0;
     p.nt = v ? v->nt : 1;
-    const int kc = v ? v->kc : 8;
+    p.planes = split_x ? 2 : 1;
+    const int kc = v ? v->kc : 4;
     p.n_pad = (N + 15) / 16 * 16;
     const int n_tiles = p.n_pad / 16;
     const int wg_x = (n_tiles + 4 * p.nt - 1) / (4 * p.nt);
     const int kb_total = K / 32;
-    // enough workgroups to keep two per compute unit busy, K ranges a whole number of LDS chunks,
-    // and never more than 16 ranges (partial sums cost M*N*4 bytes each way per range)
-    int want = (2 * cu_count + wg_x - 1) / wg_x;
-    if (want < 1) want = 1;
-    if (want > 16) want = 16;
-    int per = (kb_total + want - 1) / want;
-    per = (per + 2 * kc - 1) / (2 * kc) * (2 * kc);
-    if (per > kb_total) per = kb_total;
-    p.kb_per_split = per;
-    p.n_split = (kb_total + per - 1) / per;
+    // K ranges: a power of two, enough of them that the launch has about `target` workgroups, at
+    // most 16 (each range costs M*N*4 bytes of partial sums each way) and at least two LDS chunks long
+    const int target = g_wg_target > 0 ? g_wg_target : 2 * cu_count;
+    int s = 1;
+    while (s < 16 && wg_x * s < target && (kb_total + 2 * s - 1) / (2 * s) >= 2 * kc) s *= 2;
+    p.n_split = s;
+    p.kb_per_split = (kb_total + s - 1) / s;
     return p;
 }
 
 size_t gemm_partial_elems(const GemmPlan& p, int M) { return (size_t)p.n_split * M * p.n_pad; }
 
-int launch_gemm_bf16(const GemmPlan& p, const float* x, const void* w_packed, int M, int N, int K, bool split_x,
-                     float* partial, hipStream_t s)
+int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packed, int M, int N, int K, float* partial,
+                     hipStream_t s)
 {
     if (M < 1 || M > 352) return fail(SPEC_ERR_SHAPE, "GEMM supports 1..352 rows, got %d", M);
     if (K % 32) return fail(SPEC_ERR_SHAPE, "GEMM needs K %% 32 == 0, got %d", K);
     const int n_tiles = (N + 15) / 16;
     switch (p.mt) {
-    case 1: return launch_variant<1, 2, 8>(p, x, w_packed, M, K, n_tiles, split_x, partial, s);
-    case 2: return launch_variant<2, 2, 8>(p, x, w_packed, M, K, n_tiles, split_x, partial, s);
-    case 3: return launch_variant<3, 2, 8>(p, x, w_packed, M, K, n_tiles, split_x, partial, s);
-    case 4: return launch_variant<4, 2, 8>(p, x, w_packed, M, K, n_tiles, split_x, partial, s);
-    case 6: return launch_variant<6, 1, 4>(p, x, w_packed, M, K, n_tiles, split_x, partial, s);
-    case 8: return launch_variant<8, 1, 4>(p, x, w_packed, M, K, n_tiles, split_x, partial, s);
-    case 11: return launch_variant<11, 1, 2>(p, x, w_packed, M, K, n_tiles, split_x, partial, s);
-    case 16: return launch_variant<16, 1, 2>(p, x, w_packed, M, K, n_tiles, split_x, partial, s);
-    case 22: return launch_variant<22, 1, 2>(p, x, w_packed, M, K, n_tiles, split_x, partial, s);
+    case 1: return launch_variant<1, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 2: return launch_variant<2, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 3: return launch_variant<3, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 4: return launch_variant<4, 2, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 6: return launch_variant<6, 1, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 8: return launch_variant<8, 1, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 11: return launch_variant<11, 1, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 16: return launch_variant<16, 1, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 22: return launch_variant<22, 1, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
     default: return fail(SPEC_ERR_SHAPE, "no GEMM variant for %d rows", M);
     }
+}
+
+int launch_pack_x(const float* x, const float* gain, int M, int K, int mt_count, int planes, void* x_frags, hipStream_t s)
+{
+    const int total = M * (K / 8);
+    int blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(pack_x_kernel, dim3(blocks), dim3(256), 0, s, x, gain, M, K, mt_count, planes, (uint4*)x_frags);
+    SPECV_LAUNCH_CHECK("pack_x_kernel");
+    return SPEC_OK;
 }
 
 int launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* y, hipStream_t s)
@@ -314,11 +356,15 @@ extern "C" int spec_pack_weight(const void* src, void* dst, int32_t n_out, int32
     return SPEC_OK;
 }
 
+extern "C" void spec_k_set_gemm_wg_target(int32_t workgroups) { set_gemm_wg_target(workgroups); }
+
 extern "C" size_t spec_k_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K)
 {
-    if (M < 1 || M > 352 || N < 1 || K < 32) return 0;
-    GemmPlan p = plan_gemm(M, N, K, 256);
-    return gemm_partial_elems(p, M) * sizeof(float);
+    if (M < 1 || M > 352 || N < 1 || K < 32 || K % 32) return 0;
+    GemmPlan p = plan_gemm(M, N, K, 256, true);
+    // partial sums of the widest plan (16 ranges) + the X fragment buffer (both planes)
+    const size_t part = (size_t)16 * M * p.n_pad * sizeof(float);
+    return part + xfrag_uint4s(p.mt, 2, K) * sizeof(uint4) + 256;
 }
 
 extern "C" int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, int32_t M, int32_t N, int32_t K,
@@ -326,10 +372,15 @@ extern "C" int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, 
 {
     if (!x || !w_packed || !y || !workspace) return fail(SPEC_ERR_INVALID_ARG, "spec_k_gemm_bf16: null pointer");
     if (M < 1 || M > 352 || N < 1 || K < 32 || K % 32) return fail(SPEC_ERR_SHAPE, "spec_k_gemm_bf16: unsupported shape");
-    GemmPlan p = plan_gemm(M, N, K, 256);
-    int rc = launch_gemm_bf16(p, x, w_packed, M, N, K, split_x != 0, (float*)workspace, (hipStream_t)stream);
+    GemmPlan p = plan_gemm(M, N, K, 256, split_x != 0);
+    float* partial = (float*)workspace;
+    char* xf = (char*)workspace + (((size_t)16 * M * p.n_pad * sizeof(float) + 255) & ~(size_t)255);
+    SPECV_HIP(hipMemsetAsync(xf, 0, xfrag_uint4s(p.mt, p.planes, K) * sizeof(uint4), (hipStream_t)stream));
+    int rc = launch_pack_x(x, nullptr, M, K, p.mt, p.planes, xf, (hipStream_t)stream);
     if (rc) return rc;
-    return launch_reduce_splits((const float*)workspace, p.n_split, (size_t)M * p.n_pad, M, N, p.n_pad, y,
+    rc = launch_gemm_bf16(p, xf, w_packed, M, N, K, partial, (hipStream_t)stream);
+    if (rc) return rc;
+    return launch_reduce_splits(partial, p.n_split, (size_t)M * p.n_pad, M, N, p.n_pad, nullptr, 0, 0, 0.f, y,
                                 (hipStream_t)stream);
 }
 

@@ -40,7 +40,9 @@ struct spec_handle {
     specv::AttnPlan attn_plan{};
     bool split_act = true;     // feed activations to the matrix cores as bf16 head + remainder
     float* x = nullptr;        // [rows][d_model] residual stream
-    float* hn = nullptr;       // [rows][d_model] normalised activations
+    float* hn = nullptr;       // [rows][d_model] normalised activations (fp32 path only)
+    void* xf = nullptr;        // operand fragments of the current GEMM's input (bf16 path)
+    float* ssq = nullptr;      // [rows][ssq chunks] partial sums of squares of x
     float* q = nullptr;        // [rows][n_q_heads*head_dim] rotated queries
     float* att = nullptr;      // [rows][n_q_heads*head_dim] attention output
     float* act = nullptr;      // [rows][d_ffn]
