@@ -46,8 +46,11 @@ int spec_k_gemm_f32(const float* x, const float* w, float* y, int32_t M, int32_t
  * Between profile_begin and profile_end every kernel (or short group of kernels) of a step is
  * bracketed by two events; profile_end synchronises the stream, adds the elapsed times per class
  * into ms[SPEC_PROF_COUNT] and the number of bracketed launches into launches[SPEC_PROF_COUNT]
- * (host arrays), and switches timing off again.  Event recording costs a little time per launch,
- * so profiled steps are slower than plain ones; kernel durations themselves are unaffected. */
+ * (host arrays), and switches timing off again.  If empty_pair_ms is not NULL it receives what a
+ * start/stop event pair measures with no work in between (median of 33 pairs on the same stream):
+ * every bracketed time contains about that much event handling on top of the kernel's execution.
+ * Event recording costs a little time per launch, so profiled steps are slower than plain ones;
+ * kernel durations themselves are unaffected. */
 enum {
     SPEC_PROF_GEMM = 0,          /* projection GEMMs (QKV, O, gate/up, down, LM head) */
     SPEC_PROF_ATTENTION = 1,     /* windowed-causal attention, position-chunk pass */
@@ -60,7 +63,8 @@ enum {
 };
 struct spec_handle;
 int spec_verify_profile_begin(struct spec_handle* h);
-int spec_verify_profile_end(struct spec_handle* h, void* stream, double* ms, int32_t* launches);
+int spec_verify_profile_end(struct spec_handle* h, void* stream, double* ms, int32_t* launches,
+                            double* empty_pair_ms);
 
 #ifdef __cplusplus
 }

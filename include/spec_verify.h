@@ -78,8 +78,9 @@ typedef struct {
  *   w_down    out = d_model; in = d_ffn
  *   lm_head   out = vocab; in = d_model
  * fp32: stored exactly so, rows contiguous.
- * bf16: stored in the streaming tile order produced by spec_pack_weight (below), which lets a
- *       64-lane wavefront fetch each 16x32 MFMA operand tile as one contiguous 1 KiB read. */
+ * bf16: stored in the streaming tile order produced by spec_pack_weight (below): a 64-lane
+ *       wavefront fetches each 16x32 MFMA operand tile as one contiguous 1 KiB read, and the
+ *       whole matrix is read in long sequential streams. */
 typedef struct {
     const float* attn_norm;
     const void* w_qkv;
@@ -96,16 +97,23 @@ typedef struct {
     const spec_layer_weights* layers;   /* host array of n_layers entries (copied at init) */
 } spec_weights;
 
-/* Size in bytes of the packed form of a bf16 [n_out][n_in] matrix (n_out padded to 16). */
+/* Size in bytes of the packed form of a bf16 [n_out][n_in] matrix (n_out padded to 16 rows,
+ * n_in/32 padded to a multiple of 4 blocks); 0 if n_in is not a multiple of 32. */
 size_t spec_packed_weight_bytes(int32_t n_out, int32_t n_in);
 
 /* Repack a row-major bf16 [n_out][n_in] device matrix into the streaming tile order.
- * Tile (j, kb) covers output features 16j..16j+15 and input features 32kb..32kb+31 and occupies
- * 512 consecutive elements at ((j*(n_in/32) + kb)*512); inside a tile, element (lane, e) with
- * lane in [0,64), e in [0,8) holds W[16j + lane%16][32kb + 8*(lane/16) + e].  Rows beyond n_out
- * are zero.  With interleave_halves != 0 (used for w_gate_up) tile index j takes its 16 rows from
- * the first half of the matrix when j is even (rows 16*(j/2)..) and from the second half when j
- * is odd, so a gate tile and the matching up tile are neighbours; n_out/2 must be a multiple of 16.
+ * A tile covers output features 16j..16j+15 and input features 32kb..32kb+31 and is 512
+ * consecutive elements (1 KiB): element (lane, e), lane in [0,64), e in [0,8), holds
+ * W[16j + lane%16][32kb + 8*(lane/16) + e] -- the register layout of the 16x16x32 bf16 matrix
+ * instruction's operand, so a wavefront fetches a tile with one 16-byte load per lane.
+ * Tiles are ordered [kb/4][j][kb%4]: the 4 K blocks of one column tile are adjacent, then the next
+ * column tile, and only then the next group of 4 K blocks.  The tiles that the compute units read
+ * at the same time (neighbouring column tiles, same K blocks) are therefore neighbours in memory
+ * and the whole matrix is swept in a few long sequential streams.  Rows beyond n_out and K blocks
+ * beyond n_in/32 are zero.
+ * With interleave_halves != 0 (used for w_gate_up) tile index j takes its 16 rows from the first
+ * half of the matrix when j is even (rows 16*(j/2)..) and from the second half when j is odd, so a
+ * gate tile and the matching up tile are neighbours; n_out/2 must be a multiple of 16.
  * n_in must be a multiple of 32.  src and dst must not overlap. */
 int spec_pack_weight(const void* src_row_major, void* dst_packed, int32_t n_out, int32_t n_in,
                      int32_t interleave_halves, void* stream);

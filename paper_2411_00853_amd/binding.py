@@ -85,7 +85,8 @@ def lib():
         L.spec_k_set_gemm_wg_target.restype = None
         L.spec_k_set_gemm_wg_target.argtypes = [C.c_int32]
         L.spec_verify_profile_begin.argtypes = [C.c_void_p]
-        L.spec_verify_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+        L.spec_verify_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32),
+                                              C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -275,9 +276,11 @@ def spec_verify_profile_begin(h: Handle):
 
 
 def spec_verify_profile_end(h: Handle, stream=None):
-    """Returns {class name: (total ms, bracketed launches)} since spec_verify_profile_begin."""
+    """Returns ({class name: (total ms, bracketed launches)}, empty event-pair ms) since
+    spec_verify_profile_begin."""
     n = len(PROF_CLASSES)
     ms = (C.c_double * n)()
     cnt = (C.c_int32 * n)()
-    _check(lib().spec_verify_profile_end(h.ptr, _stream(stream), ms, cnt))
-    return {PROF_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
+    empty = C.c_double(0.0)
+    _check(lib().spec_verify_profile_end(h.ptr, _stream(stream), ms, cnt, C.byref(empty)))
+    return {PROF_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}, float(empty.value)

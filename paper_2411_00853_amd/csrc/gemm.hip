@@ -42,6 +42,7 @@ __device__ __forceinline__ void map_block(int i, int n_split, int* s, int* nb)
 }
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int WPACK_KG = 4;   // K blocks per group of the packed weight order
 
 // All global loads below are unconditional (addresses clamped into range, W zeroed by selects past
 // the K range): with no branch around a load the compiler can count outstanding loads exactly, so
@@ -75,15 +76,22 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
 #pragma unroll
     for (int u = 0; u < UPT; ++u) xoff[u] = min(u * 256 + (int)threadIdx.x, CHUNK_U4 - 1);   // surplus threads repeat
 
+    // W tile order: [K group of 4 blocks][column tile][block in group][lane] -- the chunk a workgroup
+    // reads in one step (its 4*NT tiles, KC blocks) is one contiguous run, and workgroups of
+    // neighbouring column blocks read neighbouring runs
     const u32x4* wbase[NT];
 #pragma unroll
-    for (int i = 0; i < NT; ++i) wbase[i] = Wp + (size_t)min(tile0 + i, n_tiles - 1) * kb_total * 64 + lane;
+    for (int i = 0; i < NT; ++i) wbase[i] = Wp + (size_t)min(tile0 + i, n_tiles - 1) * (WPACK_KG * 64) + lane;
+    const size_t group_stride = (size_t)n_tiles * (WPACK_KG * 64);
 
     auto load_w = [&](int kbase, u32x4(&dst)[KC][NT]) {
 #pragma unroll
-        for (int c = 0; c < KC; ++c)
+        for (int c = 0; c < KC; ++c) {
+            const int kb = min(kbase + c, kb_total - 1);
+            const size_t off = (size_t)(kb / WPACK_KG) * group_stride + (kb % WPACK_KG) * 64;
 #pragma unroll
-            for (int i = 0; i < NT; ++i) dst[c][i] = wbase[i][(size_t)min(kbase + c, kb_total - 1) * 64];
+            for (int i = 0; i < NT; ++i) dst[c][i] = wbase[i][off];
+        }
     };
     auto mask_w = [&](int kbase, u32x4(&w)[KC][NT]) {   // K blocks past the range contribute nothing
 #pragma unroll
@@ -210,15 +218,20 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const uint16_t* __rest
                                                           int n_out, int n_in, int n_tiles, int interleave)
 {
     const int kb_total = n_in / 32;
-    const size_t total = (size_t)n_tiles * kb_total * 64;
+    const int kb_pad = (kb_total + WPACK_KG - 1) / WPACK_KG * WPACK_KG;
+    const size_t total = (size_t)n_tiles * kb_pad * 64;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        // i = ((group * n_tiles + tile) * WPACK_KG + block in group) * 64 + lane
         const int lane = (int)(i & 63);
-        const size_t tk = i >> 6;
-        const int kb = (int)(tk % kb_total), j = (int)(tk / kb_total);
+        size_t r = i >> 6;
+        const int kbi = (int)(r % WPACK_KG); r /= WPACK_KG;
+        const int j = (int)(r % n_tiles);
+        const int kb = (int)(r / n_tiles) * WPACK_KG + kbi;
         int row = j * 16 + (lane & 15);
         if (interleave) row = ((j & 1) ? n_out / 2 : 0) + (j >> 1) * 16 + (lane & 15);
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (row < n_out) v = *reinterpret_cast<const uint4*>(src + (size_t)row * n_in + kb * 32 + (lane >> 4) * 8);
+        if (row < n_out && kb < kb_total)
+            v = *reinterpret_cast<const uint4*>(src + (size_t)row * n_in + kb * 32 + (lane >> 4) * 8);
         dst[i] = v;
     }
 }
@@ -279,13 +292,15 @@ GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
     const int n_tiles = p.n_pad / 16;
     const int wg_x = (n_tiles + 4 * p.nt - 1) / (4 * p.nt);
     const int kb_total = K / 32;
-    // K ranges: a power of two, enough of them that the launch has about `target` workgroups, at
+    // K ranges: a power of two, enough of them that the launch has about `target` workgroups (one
+    // per compute unit measured best: more ranges only add partial-sum traffic), at
     // most 16 (each range costs M*N*4 bytes of partial sums each way) and at least two LDS chunks long
-    const int target = g_wg_target > 0 ? g_wg_target : 2 * cu_count;
+    const int target = g_wg_target > 0 ? g_wg_target : cu_count;
     int s = 1;
     while (s < 16 && wg_x * s < target && (kb_total + 2 * s - 1) / (2 * s) >= 2 * kc) s *= 2;
     p.n_split = s;
-    p.kb_per_split = (kb_total + s - 1) / s;
+    // ranges start on a K group of the packed order so that every chunk is one contiguous run
+    p.kb_per_split = ((kb_total + s - 1) / s + WPACK_KG - 1) / WPACK_KG * WPACK_KG;
     return p;
 }
 
@@ -336,7 +351,8 @@ using namespace specv;
 extern "C" size_t spec_packed_weight_bytes(int32_t n_out, int32_t n_in)
 {
     if (n_out <= 0 || n_in <= 0 || n_in % 32) return 0;
-    return (size_t)((n_out + 15) / 16 * 16) * n_in * 2;
+    const size_t kb_pad = (size_t)(n_in / 32 + WPACK_KG - 1) / WPACK_KG * WPACK_KG;
+    return (size_t)((n_out + 15) / 16) * kb_pad * 1024;
 }
 
 extern "C" int spec_pack_weight(const void* src, void* dst, int32_t n_out, int32_t n_in, int32_t interleave_halves,
@@ -347,7 +363,7 @@ extern "C" int spec_pack_weight(const void* src, void* dst, int32_t n_out, int32
     if (interleave_halves && (n_out % 32)) return fail(SPEC_ERR_SHAPE, "spec_pack_weight: interleaving needs n_out/2 %% 16 == 0");
     if (((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return fail(SPEC_ERR_INVALID_ARG, "spec_pack_weight: 16-byte alignment");
     const int n_tiles = (n_out + 15) / 16;
-    const size_t total = (size_t)n_tiles * (n_in / 32) * 64;
+    const size_t total = spec_packed_weight_bytes(n_out, n_in) / 16;
     size_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,

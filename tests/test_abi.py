@@ -36,7 +36,7 @@ def test_host_only_size_helpers(lib):
     from paper_2411_00853_amd import binding as sv
     from paper_2411_00853_amd import workload as wl
     assert sv.spec_packed_weight_bytes(4096, 4096) == 4096 * 4096 * 2
-    assert sv.spec_packed_weight_bytes(100, 64) == 112 * 64 * 2        # rows padded to 16
+    assert sv.spec_packed_weight_bytes(100, 64) == 7 * 4 * 1024        # 7 row tiles x (2 -> 4) K blocks x 1 KiB
     assert sv.spec_packed_weight_bytes(64, 100) == 0                   # n_in must be a multiple of 32
     cfg = sv.make_cfg(wl.SEVEN_B, 8, 2048 + 6, 5)
     # 32 layers x 8 slots x 32 heads x 2080 (padded) positions x 128 dims x (k,v) x 2 bytes
