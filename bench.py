@@ -32,7 +32,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU-oracle leg")
-    ap.add_argument("--no-split", action="store_true", help=argparse.SUPPRESS)
+    ap.add_argument("--attn-items-per-cu", type=int, default=0, help="tuning: attention work items per compute unit")
+    ap.add_argument("--gemm-wg-target", type=int, default=0, help="tuning: workgroups per GEMM launch")
     return ap.parse_args()
 
 
@@ -85,13 +86,13 @@ def main():
     t_setup = time.time()
     log(f"[bench] workload {w.name}: B={B} rows={w.rows} layers={shape.n_layers} d={shape.d_model} V={V}")
 
+    sv.spec_k_set_attn_items_per_cu(args.attn_items_per_cu)
+    sv.spec_k_set_gemm_wg_target(args.gemm_wg_target)
     weights, w_cpu = build_device_model(sv, wl, w, torch, want_cpu)
     cfg = sv.make_cfg(shape, B, w.max_kv_len, Kmax)
     kv = torch.empty(sv.spec_kv_cache_bytes(cfg), dtype=torch.uint8, device="cuda")
     kv_len = torch.zeros(B, dtype=torch.int32, device="cuda")
     h = sv.spec_verify_init(cfg, weights, kv, kv_len)
-    if args.no_split:
-        raise SystemExit("--no-split is not wired in this build")
 
     # synthetic cache contents: N(0,1) keys and values, one sequence at a time
     cpu_caches = []

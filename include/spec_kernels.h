@@ -39,6 +39,11 @@ int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, int32_t M, 
  * (0 = default, two per compute unit).  Process-wide; affects launches made after the call. */
 void spec_k_set_gemm_wg_target(int32_t workgroups);
 
+/* Tuning knob: wavefront work items (sequence, kv head, position chunk) per compute unit that the
+ * attention kernel's position split aims for (0 = default).  Set before spec_verify_init: the
+ * workspace for chunk results is sized with it.  Process-wide. */
+void spec_k_set_attn_items_per_cu(int32_t items);
+
 /* Same product for a plain fp32 W[N][K]. */
 int spec_k_gemm_f32(const float* x, const float* w, float* y, int32_t M, int32_t N, int32_t K, void* stream);
 

@@ -309,13 +309,17 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(StepTables t, CacheGeom g
 
 }  // namespace
 
+static int g_items_per_cu = 0;   // wavefront work items per compute unit to aim for; 0 = default
+void set_attn_items_per_cu(int n) { g_items_per_cu = n; }
+
 AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count)
 {
-    // One wavefront per (sequence, kv head, position chunk); the kernel's register footprint lets
-    // four wavefronts live on a compute unit, so aim for about two rounds of them when every
-    // sequence is at full length.  Chunks are whole 32-position cache blocks.
+    // One wavefront per (sequence, kv head, position chunk).  Measured on MI355X: a few long
+    // streams beat many short ones (each wavefront keeps 32 KiB in flight and HBM likes long
+    // sequential runs), so aim for two wavefronts per compute unit when every sequence is at full
+    // length.  Chunks are whole 32-position cache blocks.
     AttnPlan p{};
-    const long want_items = 8L * cu_count;
+    const long want_items = (long)(g_items_per_cu > 0 ? g_items_per_cu : 2) * cu_count;
     const long per = (long)batch * n_kv_heads;
     long chunks = want_items / per;
     if (chunks < 1) chunks = 1;

@@ -177,6 +177,7 @@ struct AttnPlan {
     int max_chunks;   // chunks per (sequence, kv head) at max_kv_len
 };
 AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count);
+void set_attn_items_per_cu(int n);
 size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
                            int cu_count);
 int launch_attention(const AttnPlan& p, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M,

@@ -132,6 +132,7 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
     // The W stream starts first; afterwards X loads are always issued before the W loads of the same
     // step, so that waiting for X (older) leaves the W loads (younger) in flight.
     load_w(kb0, wa);
+    __builtin_amdgcn_sched_barrier(0);   // keep the first W loads ahead of everything else
     load_x(kb0);
     store_x(0);
     load_x(kb0 + KC);
@@ -256,9 +257,13 @@ int launch_variant(const GemmPlan& p, const void* xf, const void* w, int M, int 
 struct Variant {
     int mt, nt, kc;
 };
-// row tiles -> (column tiles per wave, K blocks per LDS chunk); LDS = 2 buffers * planes * mt * kc KiB
+// row tiles -> (column tiles per wave, K blocks per LDS chunk); LDS = 2 buffers * planes * mt * kc KiB.
+// Up to 3 row tiles there is a second, wider variant (4 column tiles per wave, 2 K blocks per
+// chunk) for matrices with many columns.
 constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {6, 1, 2},
                                  {8, 1, 2}, {11, 1, 1}, {16, 1, 1}, {22, 1, 1}};
+constexpr int kWideMaxMt = 3;
+constexpr int kWideMinTiles = 340;   // column tiles from which the wide variant still fills the chip
 
 const Variant* pick_variant(int M)
 {
@@ -268,7 +273,7 @@ const Variant* pick_variant(int M)
     return nullptr;
 }
 
-int g_wg_target = 0;   // workgroups per launch to aim for; 0 = two per compute unit
+int g_wg_target = 0;   // workgroups per launch to aim for; 0 = two thirds of the compute units
 
 }  // namespace
 
@@ -287,15 +292,21 @@ GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
     p.mt = v ? v->mt : 0;
     p.nt = v ? v->nt : 1;
     p.planes = split_x ? 2 : 1;
-    const int kc = v ? v->kc : 4;
+    int kc = v ? v->kc : 4;
     p.n_pad = (N + 15) / 16 * 16;
     const int n_tiles = p.n_pad / 16;
+    if (p.mt <= kWideMaxMt && n_tiles >= kWideMinTiles) {
+        p.nt = 4;
+        kc = 2;
+    }
     const int wg_x = (n_tiles + 4 * p.nt - 1) / (4 * p.nt);
     const int kb_total = K / 32;
-    // K ranges: a power of two, enough of them that the launch has about `target` workgroups (one
-    // per compute unit measured best: more ranges only add partial-sum traffic), at
-    // most 16 (each range costs M*N*4 bytes of partial sums each way) and at least two LDS chunks long
-    const int target = g_wg_target > 0 ? g_wg_target : cu_count;
+    // K ranges: a power of two, just enough of them that the launch has about `target` workgroups.
+    // Measured on MI355X: every launch pays a few microseconds of ramp-up and tail whatever its
+    // size, and long-lived workgroups stream best, so fewer, longer ranges win as long as roughly
+    // two thirds of the compute units have a workgroup; more ranges only add partial-sum traffic
+    // (M*N*4 bytes each way per range).  At most 16 ranges, each at least two LDS chunks long.
+    const int target = g_wg_target > 0 ? g_wg_target : (2 * cu_count) / 3;
     int s = 1;
     while (s < 16 && wg_x * s < target && (kb_total + 2 * s - 1) / (2 * s) >= 2 * kc) s *= 2;
     p.n_split = s;
@@ -312,6 +323,14 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     if (M < 1 || M > 352) return fail(SPEC_ERR_SHAPE, "GEMM supports 1..352 rows, got %d", M);
     if (K % 32) return fail(SPEC_ERR_SHAPE, "GEMM needs K %% 32 == 0, got %d", K);
     const int n_tiles = (N + 15) / 16;
+    if (p.nt == 4) {
+        switch (p.mt) {
+        case 1: return launch_variant<1, 4, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+        case 2: return launch_variant<2, 4, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+        case 3: return launch_variant<3, 4, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+        default: return fail(SPEC_ERR_SHAPE, "no wide GEMM variant for %d rows", M);
+        }
+    }
     switch (p.mt) {
     case 1: return launch_variant<1, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
     case 2: return launch_variant<2, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
@@ -373,6 +392,7 @@ extern "C" int spec_pack_weight(const void* src, void* dst, int32_t n_out, int32
 }
 
 extern "C" void spec_k_set_gemm_wg_target(int32_t workgroups) { set_gemm_wg_target(workgroups); }
+extern "C" void spec_k_set_attn_items_per_cu(int32_t items) { set_attn_items_per_cu(items); }
 
 extern "C" size_t spec_k_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K)
 {
