@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn"])
+    ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn", "stress"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--attn-items-per-cu", type=int, default=0, help="tuning: attention work items per compute unit")
     ap.add_argument("--gemm-wg-target", type=int, default=0, help="tuning: workgroups per GEMM launch")
@@ -67,6 +67,84 @@ def build_device_model(sv, wl, w, torch, keep_cpu_rows):
     return out, cpu
 
 
+def bench_stress(args, torch, sv, wl):
+    """Sampling-kernel stress (vocab 128256, K=8, batch 64, T=0.7): the sampler alone, on caller-supplied
+    target logits.  Four independent input sets (2.2 GB) are rotated so that no step finds its
+    logits in the 256 MB memory-side cache."""
+    n_var = 4
+    sets = [wl.make_stress(device="cuda", variant=v) for v in range(n_var)]
+    s0 = sets[0]
+    B, K, V = len(s0.lookahead), 8, s0.vocab
+    h = sv.spec_verify_init(sv.sampler_cfg(V, B, K), None, None, None)
+    n_acc = torch.zeros(B, dtype=torch.int32, device="cuda")
+    out_tok = torch.zeros((B, K + 1), dtype=torch.int32, device="cuda")
+    look = list(s0.lookahead)
+
+    def step(i):
+        s = sets[i % n_var]
+        sv.spec_verify_step(h, look, s.uniforms, s.temperature, n_acc, out_tok, draft_tokens=s.draft_tokens,
+                            draft_logits=s.draft_logits, target_logits_in=s.target_logits)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    tic = time.perf_counter()
+    emitted = 0
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - tic) / args.steps * 1e3
+    acc_rates = []
+    for i in range(n_var):
+        step(i)
+        torch.cuda.synchronize()
+        emitted += int((n_acc + 1).sum().item())
+        acc_rates.append(float(n_acc.float().mean().item()) / K)
+    emitted /= n_var
+    sv.spec_verify_profile_begin(h)
+    for i in range(args.steps):
+        step(i)
+    prof, empty = sv.spec_verify_profile_end(h)
+    stat_bytes = B * (2 * K + 1) * V * 4
+    kernels = {}
+    for name, (ms_raw, cnt) in prof.items():
+        if cnt == 0:
+            continue
+        ms = max(ms_raw - empty * cnt, 0.0)
+        kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps}
+    st = kernels["sampler_stats"]
+    gbps = stat_bytes / (st["ms_per_step"] * 1e-3) / 1e9
+    result = {
+        "metric": "verified tokens/sec (sampling-kernel stress)", "value": emitted / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"sampler stress: vocab {V}, K {K}, batch {B}, T {s0.temperature}, Zipf(1.1)-ranked "
+                               f"target logits + N(0,0.5^2), draft = target + N(0,0.3^2); {n_var} input sets rotated"},
+        "scored_positions_per_s": B * (K + 1) / (ms_per_step * 1e-3), "acceptance_rate": sum(acc_rates) / n_var,
+        "kernels": kernels,
+        "roofline": {"kernel": "stats_kernel (softmax statistics of all target and draft rows)", "bound": "hbm",
+                     "achieved": gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": stat_bytes,
+                     "timing": f"HIP events around the launch, minus the empty event-pair time ({empty * 1e3:.2f} us)"},
+        "cpu_baseline": None,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        s = sets[0]
+        tl, dl, dt, u = s.target_logits.cpu(), s.draft_logits.cpu(), s.draft_tokens.cpu(), s.uniforms.cpu()
+        tic = time.perf_counter()
+        em = 0
+        for b in range(B):
+            a, _, _ = oracle.sample(tl[b * (K + 1):(b + 1) * (K + 1)], dl[b], dt[b].tolist(), u[b].tolist(), s.temperature)
+            em += a + 1
+        t_or = time.perf_counter() - tic
+        result["cpu_baseline"] = {"value": em / t_or, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"the sampler on all {B} sequences of one input set (single thread)",
+                                  "seconds": t_or}
+    print(json.dumps(result), flush=True)
+    h.close()
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -79,10 +157,12 @@ def main():
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU: there is no CPU fallback for the HIP path")
+    if args.workload == "stress":
+        return bench_stress(args, torch, sv, wl)
     w = {"7b": wl.workload_7b, "1b": wl.workload_1b, "dyn": wl.workload_dyn}[args.workload]()
     shape, B, Kmax, V = w.shape, w.batch, w.max_lookahead, w.shape.vocab
     want_cpu = not args.no_cpu_baseline
-    n_sample = min(2, B)       # sequences the CPU oracle is timed on
+    n_sample = min(8, B)       # sequences the CPU oracle is timed on (~10 s of CPU work at 7B-shape)
     t_setup = time.time()
     log(f"[bench] workload {w.name}: B={B} rows={w.rows} layers={shape.n_layers} d={shape.d_model} V={V}")
 

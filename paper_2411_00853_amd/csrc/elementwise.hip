@@ -21,19 +21,33 @@ __device__ __forceinline__ double block_sum(double v, double* sh)
     return r;
 }
 
+// Sum of the K ranges' partial sums at p, ranges in index order; the loads of 8 ranges are issued
+// together (indices past the end clamped, values dropped) so the latency is paid once per batch.
 __device__ __forceinline__ float sum_splits(const float* p, int n_split, size_t stride)
 {
-    float v = p[0];
-    for (int s = 1; s < n_split; ++s) v += p[(size_t)s * stride];
+    float v = 0.f;
+    for (int s0 = 0; s0 < n_split; s0 += 8) {
+        float a[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = p[(size_t)min(s0 + i, n_split - 1) * stride];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v += (s0 + i < n_split) ? a[i] : 0.f;
+    }
     return v;
 }
 
 __device__ __forceinline__ float4 sum_splits4(const float* p, int n_split, size_t stride)
 {
-    float4 v = *reinterpret_cast<const float4*>(p);
-    for (int s = 1; s < n_split; ++s) {
-        const float4 w = *reinterpret_cast<const float4*>(p + (size_t)s * stride);
-        v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < n_split; s0 += 8) {
+        float4 a[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = *reinterpret_cast<const float4*>(p + (size_t)min(s0 + i, n_split - 1) * stride);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const bool ok = s0 + i < n_split;
+            v.x += ok ? a[i].x : 0.f; v.y += ok ? a[i].y : 0.f; v.z += ok ? a[i].z : 0.f; v.w += ok ? a[i].w : 0.f;
+        }
     }
     return v;
 }
