@@ -323,6 +323,7 @@ AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count)
     const long per = (long)batch * n_kv_heads;
     long chunks = want_items / per;
     if (chunks < 1) chunks = 1;
+    if (chunks > 16) chunks = 16;   // the merge walks a row's chunks one after the other
     long keys = (max_kv_len + chunks - 1) / chunks;
     keys = (keys + 31) / 32 * 32;
     p.chunk_keys = (int)keys;

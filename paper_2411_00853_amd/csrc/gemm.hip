@@ -260,8 +260,10 @@ struct Variant {
 // row tiles -> (column tiles per wave, K blocks per LDS chunk); LDS = 2 buffers * planes * mt * kc KiB.
 // Up to 3 row tiles there is a second, wider variant (4 column tiles per wave, 2 K blocks per
 // chunk) for matrices with many columns.
-constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {6, 1, 2},
-                                 {8, 1, 2}, {11, 1, 1}, {16, 1, 1}, {22, 1, 1}};
+// From 6 row tiles on the matrix cores and the LDS reads of X start to matter: several column tiles
+// per wave (each X fragment read from LDS feeds that many products) keep LDS traffic per W byte down.
+constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {6, 4, 1},
+                                 {8, 4, 1}, {11, 4, 1}, {16, 2, 1}, {22, 2, 1}};
 constexpr int kWideMaxMt = 3;
 constexpr int kWideMinTiles = 340;   // column tiles from which the wide variant still fills the chip
 
@@ -328,6 +330,9 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
         case 1: return launch_variant<1, 4, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
         case 2: return launch_variant<2, 4, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
         case 3: return launch_variant<3, 4, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+        case 6: return launch_variant<6, 4, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+        case 8: return launch_variant<8, 4, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+        case 11: return launch_variant<11, 4, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
         default: return fail(SPEC_ERR_SHAPE, "no wide GEMM variant for %d rows", M);
         }
     }
@@ -336,11 +341,8 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     case 2: return launch_variant<2, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
     case 3: return launch_variant<3, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
     case 4: return launch_variant<4, 2, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 6: return launch_variant<6, 1, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 8: return launch_variant<8, 1, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 11: return launch_variant<11, 1, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 16: return launch_variant<16, 1, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 22: return launch_variant<22, 1, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 16: return launch_variant<16, 2, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
+    case 22: return launch_variant<22, 2, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
     default: return fail(SPEC_ERR_SHAPE, "no GEMM variant for %d rows", M);
     }
 }
