@@ -84,10 +84,12 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
     for (int i = 0; i < NT; ++i) wbase[i] = Wp + (size_t)min(tile0 + i, n_tiles - 1) * (WPACK_KG * 64) + lane;
     const size_t group_stride = (size_t)n_tiles * (WPACK_KG * 64);
 
+    // Loads past the end of the range are redirected to its last block (a cache hit, no new HBM
+    // traffic); the products of such blocks are suppressed by mask_w.
     auto load_w = [&](int kbase, u32x4(&dst)[KC][NT]) {
 #pragma unroll
         for (int c = 0; c < KC; ++c) {
-            const int kb = min(kbase + c, kb_total - 1);
+            const int kb = min(kbase + c, kb1 - 1);
             const size_t off = (size_t)(kb / WPACK_KG) * group_stride + (kb % WPACK_KG) * 64;
 #pragma unroll
             for (int i = 0; i < NT; ++i) dst[c][i] = wbase[i][off];
@@ -102,8 +104,9 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
         }
     };
     auto load_x = [&](int kbase) {
-        // fragment buffers carry XFRAG_PAD_KB zeroed blocks past kb_total, so a chunk may overhang
-        const u32x4* src = Xf + (size_t)min(kbase, kb_total) * (PLANES * MT * 64);
+        // fragment buffers carry XFRAG_PAD_KB zeroed blocks past kb_total, so the last chunk of the
+        // last range may overhang
+        const u32x4* src = Xf + (size_t)min(kbase, kb1 - 1) * (PLANES * MT * 64);
 #pragma unroll
         for (int u = 0; u < UPT; ++u) xr[u] = src[xoff[u]];
     };
@@ -138,23 +141,49 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
     load_x(kb0 + KC);
     load_w(kb0 + KC, wb);
     __syncthreads();
-    // step c: multiply chunk c from LDS buffer c%2 while chunk c+1's X (already in registers) is
-    // copied into the other buffer and the loads of chunk c+2 are issued.  K blocks past the range
-    // meet zeroed W (and, past kb_total, the zero padding of the fragment buffer), so ranges need not
-    // be whole chunks and an odd chunk count simply ends with one idle half step.
-    for (int kbase = kb0; kbase < kb1; kbase += 2 * KC) {
-        mask_w(kbase, wa);
+    // Chunk j is multiplied from LDS buffer j%2 while chunk j+1's X (already in registers) is copied
+    // into the other buffer and the loads of chunk j+2 are issued.  The main loop runs while both of
+    // its prefetches are inside the range; the last one to three chunks are finished below without
+    // loading anything past the range.  Only the last chunk can be partial (mask_w).
+    const int n_chunks = (kb1 - kb0 + KC - 1) / KC;
+    int j = 0;
+    for (; j + 3 < n_chunks; j += 2) {
+        const int kbase = kb0 + j * KC;
         compute(wa, 0);
         store_x(1);
         load_x(kbase + 2 * KC);
         load_w(kbase + 2 * KC, wa);
         __syncthreads();
-        mask_w(kbase + KC, wb);
         compute(wb, 1);
         store_x(0);
         load_x(kbase + 3 * KC);
         load_w(kbase + 3 * KC, wb);
         __syncthreads();
+    }
+    {
+        const int kbase = kb0 + j * KC;
+        const int left = n_chunks - j;   // 1, 2 or 3 (0 only for an empty range)
+        if (left == 3) {
+            compute(wa, 0);
+            store_x(1);
+            load_x(kbase + 2 * KC);
+            load_w(kbase + 2 * KC, wa);
+            __syncthreads();
+            compute(wb, 1);
+            store_x(0);
+            __syncthreads();
+            mask_w(kbase + 2 * KC, wa);
+            compute(wa, 0);
+        } else if (left == 2) {
+            compute(wa, 0);
+            store_x(1);
+            __syncthreads();
+            mask_w(kbase + KC, wb);
+            compute(wb, 1);
+        } else if (left == 1) {
+            mask_w(kbase, wa);
+            compute(wa, 0);
+        }
     }
 
     const int n_pad = n_tiles * 16;
