@@ -1,5 +1,5 @@
-"""ctypes binding of libspecverify.so: the same entry points as include/spec_verify.h and
-include/spec_kernels.h, taking torch tensors where the C side takes device pointers.  Argument
+"""ctypes binding of libspecverify.so: the same entry points as include/spec_verify.h,
+include/spec_decode.h and include/spec_kernels.h, taking torch tensors where the C side takes device pointers.  Argument
 marshalling only -- no arithmetic of the method happens here, and there is no fallback: if the
 HIP library is missing or fails to load, every call raises."""
 from __future__ import annotations
@@ -49,6 +49,20 @@ class spec_step_out(C.Structure):
     _fields_ = [("n_accepted", C.c_void_p), ("out_tokens", C.c_void_p), ("logits_out", C.c_void_p)]
 
 
+class spec_decode_cfg(C.Structure):
+    _fields_ = [("max_batch", C.c_int32), ("max_new_tokens", C.c_int32)]
+
+
+class spec_round_args(C.Structure):
+    _fields_ = [("lookahead", C.c_int32), ("draft_uniforms", C.c_void_p), ("verify_uniforms", C.c_void_p),
+                ("temperature", C.c_float)]
+
+
+class spec_decode_view(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("tokens", "n_tokens", "n_accepted", "draft_tokens", "draft_logits",
+                                          "target_logits", "prev_token", "last_token", "counters")]
+
+
 _lib = None
 
 
@@ -89,6 +103,12 @@ def lib():
         L.spec_verify_profile_begin.argtypes = [C.c_void_p]
         L.spec_verify_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32),
                                               C.POINTER(C.c_double)]
+        L.spec_decode_init.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(spec_decode_cfg), C.POINTER(C.c_void_p)]
+        L.spec_decode_destroy.restype = None
+        L.spec_decode_destroy.argtypes = [C.c_void_p]
+        L.spec_decode_begin.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.spec_decode_round.argtypes = [C.c_void_p, C.POINTER(spec_round_args), C.c_void_p]
+        L.spec_decode_get_view.argtypes = [C.c_void_p, C.POINTER(spec_decode_view)]
         _lib = L
     return _lib
 
@@ -228,6 +248,70 @@ def spec_kv_export(h: Handle, slot: int, pos0: int, dst: torch.Tensor, stream=No
 
 def spec_verify_poll(h: Handle, stream=None):
     _check(lib().spec_verify_poll(h.ptr, _stream(stream)))
+
+
+# ---- the decoding round (include/spec_decode.h) --------------------------------------------------
+
+class Decoder:
+    """Owns a spec_decoder* and keeps the two handles alive."""
+
+    def __init__(self, ptr, target: Handle, draft: Optional[Handle], max_batch: int, max_new_tokens: int):
+        self.ptr, self.target, self.draft = ptr, target, draft
+        self.max_batch, self.max_new_tokens = max_batch, max_new_tokens
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def close(self):
+        if getattr(self, "ptr", None):
+            lib().spec_decode_destroy(self.ptr)
+            self.ptr = None
+
+
+def spec_decode_init(target: Handle, draft: Optional[Handle], max_batch: int, max_new_tokens: int) -> Decoder:
+    out = C.c_void_p()
+    cfg = spec_decode_cfg(max_batch, max_new_tokens)
+    _check(lib().spec_decode_init(target.ptr, draft.ptr if draft is not None else None, C.byref(cfg), C.byref(out)))
+    return Decoder(out.value, target, draft, max_batch, max_new_tokens)
+
+
+def spec_decode_destroy(d: Decoder):
+    d.close()
+
+
+def spec_decode_begin(d: Decoder, seq_slot: torch.Tensor, prev_token: Optional[torch.Tensor],
+                      last_token: torch.Tensor, stream=None):
+    _check(lib().spec_decode_begin(d.ptr, seq_slot.numel(), _ptr(seq_slot, torch.int32), _ptr(prev_token, torch.int32),
+                                   _ptr(last_token, torch.int32), _stream(stream)))
+
+
+def spec_decode_round(d: Decoder, lookahead: int, draft_uniforms: Optional[torch.Tensor],
+                      verify_uniforms: torch.Tensor, temperature: float, stream=None):
+    args = spec_round_args(int(lookahead), _ptr(draft_uniforms, torch.float32), _ptr(verify_uniforms, torch.float32),
+                           float(temperature))
+    _check(lib().spec_decode_round(d.ptr, C.byref(args), _stream(stream)))
+
+
+def spec_decode_get_view(d: Decoder) -> spec_decode_view:
+    v = spec_decode_view()
+    _check(lib().spec_decode_get_view(d.ptr, C.byref(v)))
+    return v
+
+
+def device_array(ptr: Optional[int], shape, dtype, device="cuda") -> torch.Tensor:
+    """A copy of library-owned device memory as a tensor (spec_k_copy on the current stream; the
+    library's allocations are 256-byte granular, so rounding the size up to 16 bytes stays inside)."""
+    n = 1
+    for v in shape:
+        n *= int(v)
+    nbytes = n * torch.empty((), dtype=dtype).element_size()
+    raw = torch.empty((nbytes + 15) // 16 * 16, dtype=torch.uint8, device=device)
+    if nbytes:
+        _check(lib().spec_k_copy(C.c_void_p(ptr), _ptr(raw), raw.numel(), _stream(None)))
+    return raw[:nbytes].view(dtype).reshape(shape)
 
 
 # ---- single-kernel entry points (include/spec_kernels.h) -----------------------------------------

@@ -87,10 +87,24 @@ int launch_prepare(const StepTables& t, const LookaheadPack& ks, int B, int Kmax
                    int max_kv_len, bool has_cache, const int32_t* seq_slot, const int32_t* last_token,
                    const int32_t* draft_tokens, const int32_t* kv_len, int32_t* flag, hipStream_t s);
 
+// Where a plain draw (every K_b = 0: one token from each sequence's row) puts its results when the
+// sampler serves a proposing model instead of a verification.  tokens == NULL: verification mode.
+struct DrawEmit {
+    int32_t* tokens;       // tokens[b * stride + offset] = drawn token
+    int stride, offset;
+    int32_t* next_token;   // [B] the drawn token again: the next decode step's input
+    int32_t* kv_len;       // kv_len[slot] = cached length at the start of the step + kv_add
+    int kv_add;
+    float* logits_copy;    // the row the token was drawn from, copied to logits_copy + b * copy_stride
+    size_t copy_stride;
+};
+
+// uniforms: sequence b reads uniforms[b * u_stride + i] (i < K_b: proposal i; i = K_b: the final draw)
 int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax,
                    int V, int n_stat_rows, const float* target_logits, const float* draft_logits,
-                   const int32_t* draft_tokens, const float* uniforms, float temperature, int auto_rollback,
-                   int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens, Profiler* prof, hipStream_t s);
+                   const int32_t* draft_tokens, const float* uniforms, int u_stride, float temperature,
+                   int auto_rollback, int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens,
+                   const DrawEmit* emit, Profiler* prof, hipStream_t s);
 
 struct RollbackPack {
     int32_t slot[SPEC_MAX_BATCH];

@@ -112,7 +112,8 @@ template <bool VEC4>
 __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack ks, int B, int Kmax, int V,
                                                     int n_chunks, const float* __restrict__ target,
                                                     const float* __restrict__ draft, float inv_T,
-                                                    float* __restrict__ part_max, double* __restrict__ part_sum)
+                                                    float* __restrict__ part_max, double* __restrict__ part_sum,
+                                                    float* __restrict__ copy_out, size_t copy_stride)
 {
     __shared__ float smax[TPB / 64];
     __shared__ double ssum[TPB / 64];
@@ -141,6 +142,14 @@ __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack 
         for (int i = 0; i < PER; ++i) {
             int idx = i * TPB + threadIdx.x;
             v[i] = idx < lim ? row[base + idx] : -INFINITY;
+        }
+    }
+    if (copy_out) {   // plain-draw mode (one statistics row per sequence): keep the row for the verifier
+        float* dst = copy_out + (size_t)srow * copy_stride + base;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int idx = VEC4 ? ((i / 4) * TPB + (int)threadIdx.x) * 4 + (i & 3) : i * TPB + (int)threadIdx.x;
+            if (idx < lim) dst[idx] = v[i];
         }
     }
     float m = -INFINITY;
@@ -185,8 +194,8 @@ __global__ void __launch_bounds__(TPB) accept_mass_kernel(StepTables t, Lookahea
                                                           const float* __restrict__ target,
                                                           const float* __restrict__ draft,
                                                           const int32_t* __restrict__ draft_tokens,
-                                                          const float* __restrict__ uniforms, float inv_T_f,
-                                                          const float* __restrict__ part_max,
+                                                          const float* __restrict__ uniforms, int u_stride,
+                                                          float inv_T_f, const float* __restrict__ part_max,
                                                           const double* __restrict__ part_sum, SamplerWorkspace w)
 {
     __shared__ float row_m[2 * SPEC_MAX_LOOKAHEAD + 2];
@@ -215,7 +224,7 @@ __global__ void __launch_bounds__(TPB) accept_mass_kernel(StepTables t, Lookahea
             const double ep = exp((double)(lp - row_m[i]) * inv_T);
             const double eq = exp((double)(lq - row_m[K + 1 + i]) * inv_T);
             // keep iff u * q(x) < p(x)  <=>  u * eq * Zp < ep * Zq
-            const double u = (double)uniforms[b * (Kmax + 1) + i];
+            const double u = (double)uniforms[b * u_stride + i];
             if (!(u * eq * row_z[i] < ep * row_z[K + 1 + i])) { a = i; break; }
         }
         s_a = a;
@@ -263,10 +272,10 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
                                                          int n_res_chunks, const float* __restrict__ target,
                                                          const float* __restrict__ draft,
                                                          const int32_t* __restrict__ draft_tokens,
-                                                         const float* __restrict__ uniforms, float inv_T_f,
-                                                         SamplerWorkspace w, int auto_rollback, int32_t* kv_len,
-                                                         int32_t* __restrict__ n_accepted,
-                                                         int32_t* __restrict__ out_tokens)
+                                                         const float* __restrict__ uniforms, int u_stride,
+                                                         float inv_T_f, SamplerWorkspace w, int auto_rollback,
+                                                         int32_t* kv_len, int32_t* __restrict__ n_accepted,
+                                                         int32_t* __restrict__ out_tokens, DrawEmit emit)
 {
     __shared__ double r[RES_CHUNK];
     __shared__ double wave_tot[TPB / 64];
@@ -275,6 +284,13 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
     const int b = blockIdx.x;
     const int K = ks.k[b];
     if (!t.seq_ok[b]) {
+        if (emit.tokens) {   // plain draw: an invalid id makes whoever consumes it skip the sequence too
+            if (threadIdx.x == 0) {
+                emit.tokens[b * emit.stride + emit.offset] = -1;
+                emit.next_token[b] = -1;
+            }
+            return;
+        }
         if (threadIdx.x == 0) n_accepted[b] = -1;
         for (int i = threadIdx.x; i <= Kmax; i += TPB) out_tokens[b * (Kmax + 1) + i] = -1;
         return;
@@ -290,7 +306,7 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
         s_before = S;
         s_chunk = -1;
         if (S > 0.0) {
-            const double target_mass = (double)uniforms[b * (Kmax + 1) + K] * S;
+            const double target_mass = (double)uniforms[b * u_stride + K] * S;
             double c0 = 0.0;
             int pick = -1, last_pos = -1;
             double last_before = 0.0;
@@ -317,7 +333,7 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
         c_lo = 0;
         c_hi = n_res_chunks;
         before = 0.0;
-        target_mass = (double)uniforms[b * (Kmax + 1) + K];   // p_a sums to 1
+        target_mass = (double)uniforms[b * u_stride + K];   // p_a sums to 1
     }
     if (threadIdx.x == 0) s_tok = -1;
     int last_positive = -1;
@@ -389,6 +405,12 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
         int y = s_tok;
         if (y < 0) y = max(max(scratch[0], scratch[1]), max(scratch[2], scratch[3]));
         if (y < 0) y = 0;
+        if (emit.tokens) {
+            emit.tokens[b * emit.stride + emit.offset] = y;
+            emit.next_token[b] = y;
+            if (emit.kv_len) emit.kv_len[t.seq_slot[b]] = t.seq_n[b] + emit.kv_add;
+            return;
+        }
         n_accepted[b] = a;
         int32_t* o = out_tokens + b * (Kmax + 1);
         for (int i = 0; i < a; ++i) o[i] = draft_tokens[b * Kmax + i];
@@ -431,33 +453,40 @@ int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len
 
 int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax,
                    int V, int n_stat_rows, const float* target_logits, const float* draft_logits,
-                   const int32_t* draft_tokens, const float* uniforms, float temperature, int auto_rollback,
-                   int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens, Profiler* prof, hipStream_t s)
+                   const int32_t* draft_tokens, const float* uniforms, int u_stride, float temperature,
+                   int auto_rollback, int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens,
+                   const DrawEmit* emit, Profiler* prof, hipStream_t s)
 {
     const int n_stat_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
     const int n_res_chunks = (V + RES_CHUNK - 1) / RES_CHUNK;
     const float inv_T = 1.0f / temperature;
+    DrawEmit em{};
+    if (emit) {
+        if (n_stat_rows != B) return fail(SPEC_ERR_INVALID_ARG, "a plain draw needs every lookahead to be 0");
+        em = *emit;
+    }
     const bool vec4 = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(target_logits) & 15) == 0)
-                      && ((reinterpret_cast<uintptr_t>(draft_logits) & 15) == 0);
+                      && ((reinterpret_cast<uintptr_t>(draft_logits) & 15) == 0)
+                      && ((reinterpret_cast<uintptr_t>(em.logits_copy) & 15) == 0) && (em.copy_stride % 4 == 0);
     dim3 g1((unsigned)n_stat_rows * n_stat_chunks);
     {
     ProfScope ps(prof, SPEC_PROF_SAMPLER_STATS, s);
     if (vec4)
         hipLaunchKernelGGL(stats_kernel<true>, g1, dim3(TPB), 0, s, t, ks, B, Kmax, V, n_stat_chunks,
-                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum);
+                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum, em.logits_copy, em.copy_stride);
     else
         hipLaunchKernelGGL(stats_kernel<false>, g1, dim3(TPB), 0, s, t, ks, B, Kmax, V, n_stat_chunks,
-                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum);
+                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum, em.logits_copy, em.copy_stride);
     SPECV_LAUNCH_CHECK("stats_kernel");
     }
     ProfScope ps(prof, SPEC_PROF_SAMPLER_DRAW, s);
     hipLaunchKernelGGL(accept_mass_kernel, dim3(n_res_chunks, B), dim3(TPB), 0, s, t, ks, Kmax, V, n_stat_chunks,
-                       n_res_chunks, target_logits, draft_logits, draft_tokens, uniforms, inv_T, w.part_max,
+                       n_res_chunks, target_logits, draft_logits, draft_tokens, uniforms, u_stride, inv_T, w.part_max,
                        w.part_sum, w);
     SPECV_LAUNCH_CHECK("accept_mass_kernel");
     hipLaunchKernelGGL(final_draw_kernel, dim3(B), dim3(TPB), 0, s, t, ks, Kmax, V, n_res_chunks, target_logits,
-                       draft_logits, draft_tokens, uniforms, inv_T, w, auto_rollback, kv_len, n_accepted,
-                       out_tokens);
+                       draft_logits, draft_tokens, uniforms, u_stride, inv_T, w, auto_rollback, kv_len, n_accepted,
+                       out_tokens, em);
     SPECV_LAUNCH_CHECK("final_draw_kernel");
     return SPEC_OK;
 }

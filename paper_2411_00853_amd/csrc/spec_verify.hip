@@ -312,8 +312,8 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
                                  hipMemcpyDeviceToDevice, s));
     }
     return launch_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, n_stat, logits, args->draft_logits,
-                          args->draft_tokens, args->uniforms, args->temperature, args->auto_rollback,
-                          run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, &h->prof, s);
+                          args->draft_tokens, args->uniforms, Kmax + 1, args->temperature, args->auto_rollback,
+                          run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, nullptr, &h->prof, s);
 }
 
 extern "C" int spec_kv_rollback(spec_handle* h, const int32_t* seq_slot, const int32_t* new_len, int32_t n,

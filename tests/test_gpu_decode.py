@@ -1,0 +1,250 @@
+"""GPU parity of the whole speculative decoding round (draft loop + verification + bookkeeping,
+include/spec_decode.h) against the oracle's loop (oracle/decode.py).
+
+The GPU runs free; after every round the oracle is made to follow it token by token:
+  * logits: the oracle's draft model decodes the GPU's proposals one by one, the oracle's target
+    scores the GPU's window -- every row must agree with the GPU's (1e-4 fp32, 3e-2 bf16);
+  * decisions on identical logits: every proposal must be the oracle's inverse-CDF draw from the
+    GPU's own draft row, and n_accepted / emitted tokens the oracle's verification of the GPU's own
+    rows (margin rules of helpers.SamplerCheck);
+  * bookkeeping: output lists, the two trailing tokens, both cache lengths.
+A second test lets the oracle run free as well (fp32) and compares the generated text itself."""
+import pytest
+import torch
+
+import oracle
+from oracle import decode as od
+from paper_2411_00853_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = {"fp32": 1e-4, "bf16": 3e-2}
+
+
+class Pair:
+    """Target + draft on both sides, a batch of sequences with oracle-built caches."""
+
+    def __init__(self, t_shape, d_shape, contexts, max_kv_len, Kt, max_new, seed=5, std=0.05):
+        from test_gpu_forward import Rig
+        from paper_2411_00853_amd import binding as sv
+        self.sv = sv
+        B = len(contexts)
+        self.B, self.Kt = B, Kt
+        self.tg = Rig(t_shape, B, max_kv_len, Kt, seed=seed, std=std)
+        self.dr = Rig(d_shape, B, max_kv_len, 1, seed=seed + 1, std=std)
+        self.states = []
+        for b, ctx in enumerate(contexts):
+            st = od.SequenceState(list(ctx), self.tg.caches[b], 0, self.dr.caches[b], 0)
+            st.target_len = od.feed(self.tg.om, st.target_cache, 0, st.tokens, len(ctx) - 1)
+            st.draft_len = od.feed(self.dr.om, st.draft_cache, 0, st.tokens, len(ctx) - 2)
+            self.tg.set_cache(b, len(ctx) - 1)
+            self.dr.set_cache(b, len(ctx) - 2)
+            self.states.append(st)
+        self.dec = sv.spec_decode_init(self.tg.h, self.dr.h, B, max_new)
+        self.max_new = max_new
+        dev = "cuda"
+        sv.spec_decode_begin(self.dec, torch.arange(B, dtype=torch.int32, device=dev),
+                             torch.tensor([c[-2] for c in contexts], dtype=torch.int32, device=dev),
+                             torch.tensor([c[-1] for c in contexts], dtype=torch.int32, device=dev))
+
+    def view(self, K):
+        sv, v, B, Kt, V = self.sv, self.sv.spec_decode_get_view(self.dec), self.B, self.Kt, self.tg.shape.vocab
+        get = lambda p, shape, dt: sv.device_array(p, shape, dt).cpu()
+        out = {
+            "tokens": get(v.tokens, (B, self.max_new), torch.int32),
+            "n_tokens": get(v.n_tokens, (B,), torch.int32),
+            "n_accepted": get(v.n_accepted, (B,), torch.int32),
+            "draft_tokens": get(v.draft_tokens, (B, Kt), torch.int32),
+            "draft_logits": get(v.draft_logits, (B, Kt, V), torch.float32),
+            "target_logits": get(v.target_logits, (B * (K + 1), V), torch.float32),
+            "prev": get(v.prev_token, (B,), torch.int32),
+            "last": get(v.last_token, (B,), torch.int32),
+            "counters": get(v.counters, (3,), torch.int64),
+        }
+        torch.cuda.synchronize()
+        return out
+
+    def round(self, K, du, vu, T):
+        self.sv.spec_decode_round(self.dec, K, du.cuda(), vu.cuda(), T)
+        torch.cuda.synchronize()
+        self.sv.spec_verify_poll(self.tg.h)
+        self.sv.spec_verify_poll(self.dr.h)
+        return self.view(K)
+
+
+def follow_round(pair, g, K, du, vu, T, chk, tally):
+    """Make the oracle take the round the GPU took (g = the GPU's view after it) and compare."""
+    from helpers import CDF_MARGIN
+    tol = LOGIT_TOL[pair.tg.shape.dtype]
+    for b, st in enumerate(pair.states):
+        L = len(st.tokens)
+        a = int(g["n_accepted"][b])
+        props = g["draft_tokens"][b, :K].tolist()
+        # ---- draft side: oracle decodes the GPU's proposals -----------------------------------
+        st.draft_len = od.feed(pair.dr.om, st.draft_cache, st.draft_len, st.tokens, L - 1)
+        cur = st.tokens[-1]
+        for i in range(K):
+            want = pair.dr.om.decode_one(st.draft_cache, L - 1 + i, cur)
+            got = g["draft_logits"][b, i]
+            err = (want - got).abs().max().item()
+            tally["draft_err"] = max(tally["draft_err"], err)
+            assert err <= tol, f"draft logits row {i} of sequence {b}: max-abs error {err}"
+            # the proposal is the inverse-CDF draw from the GPU's own row
+            y, dg = od.draw(got.contiguous(), T, float(du[b, i]))
+            if min(dg.final_target - dg.final_cdf_lo, dg.final_cdf_hi - dg.final_target) > CDF_MARGIN:
+                assert props[i] == y, f"proposal {i} of sequence {b}: {props[i]} != oracle {y}"
+                tally["draws_exact"] += 1
+            else:
+                tally["draws_margin"] += 1
+            cur = props[i]
+        st.draft_len = L - 1 + K
+        # ---- target side ---------------------------------------------------------------------
+        want = pair.tg.om.verify_sequential(st.target_cache, L - 1, [st.tokens[-1]] + props)
+        got = g["target_logits"][b * (K + 1):(b + 1) * (K + 1)]
+        err = (want - got).abs().max().item()
+        tally["target_err"] = max(tally["target_err"], err)
+        assert err <= tol, f"target logits of sequence {b}: max-abs error {err}"
+        # verification on the GPU's own rows: the emitted tokens of this round are the tail of its list
+        n_out = int(g["n_tokens"][b])
+        emitted = g["tokens"][b, n_out - (a + 1):n_out].tolist()
+        out_gpu = emitted + [-1] * (pair.Kt - a)
+        chk.compare(got.contiguous(), g["draft_logits"][b].contiguous(), props, vu[b, :K + 1].tolist(), T, a, out_gpu,
+                    pair.Kt)
+        # ---- bookkeeping ---------------------------------------------------------------------
+        assert emitted[:a] == props[:a]
+        st.tokens.extend(emitted)
+        st.target_len = L + a
+        st.draft_len = min(st.draft_len, L + a)
+        assert n_out == len(st.tokens) - tally["ctx_len"][b]
+        assert int(g["last"][b]) == st.tokens[-1] and int(g["prev"][b]) == st.tokens[-2]
+    kt = pair.tg.kv_len.cpu().tolist()
+    kd = pair.dr.kv_len.cpu().tolist()
+    for b, st in enumerate(pair.states):
+        assert kt[b] == len(st.tokens) - 1 and kd[b] == len(st.tokens) - 2
+
+
+def run_following(t_shape, d_shape, contexts, K, Kt, rounds, T, seed):
+    from helpers import SamplerCheck
+    pair = Pair(t_shape, d_shape, contexts, 96, Kt, 64, seed=seed)
+    chk = SamplerCheck()
+    tally = {"draft_err": 0.0, "target_err": 0.0, "draws_exact": 0, "draws_margin": 0,
+             "ctx_len": [len(c) for c in contexts]}
+    rng = wl.Rng(seed, "cpu")
+    B = len(contexts)
+    kept = 0
+    for r in range(rounds):
+        du = rng.uniform(wl.S_UNIFORMS + 10 + 2 * r, (B, Kt))
+        vu = rng.uniform(wl.S_UNIFORMS + 11 + 2 * r, (B, Kt + 1))
+        g = pair.round(K, du, vu, T)
+        follow_round(pair, g, K, du, vu, T, chk, tally)
+        kept += int(g["n_accepted"].sum())
+        c = g["counters"].tolist()
+        assert c[0] == B * (r + 1) and c[1] == kept and c[2] == kept + B * (r + 1)
+    # the generated text is in the output lists
+    g = pair.view(K)
+    for b, st in enumerate(pair.states):
+        n = int(g["n_tokens"][b])
+        assert g["tokens"][b, :n].tolist() == st.tokens[len(contexts[b]):]
+    return pair, chk, tally, kept
+
+
+CONTEXTS = [[5, 17, 3, 88, 41, 2, 60], [9, 1], [7] * 33 + [4, 250, 6]]
+
+
+def test_rounds_fp32_oracle_follows_gpu():
+    t_shape = wl.ModelShape(2, 256, 4, 4, 64, 512, 301, dtype="fp32")     # vocabulary not a multiple of 4
+    d_shape = wl.ModelShape(1, 128, 2, 2, 64, 256, 301, dtype="fp32")
+    pair, chk, tally, kept = run_following(t_shape, d_shape, CONTEXTS, K=4, Kt=4, rounds=5, T=1.0, seed=31)
+    assert chk.exact_accept >= 13 and chk.exact_token >= 12
+    assert tally["draws_exact"] >= 55
+    assert 0 < kept < 5 * 3 * 4, "both outcomes should occur"
+
+
+def test_rounds_bf16_lookahead_below_maximum():
+    t_shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
+    d_shape = wl.ModelShape(1, 128, 2, 1, 64, 256, 1000)
+    pair, chk, tally, kept = run_following(t_shape, d_shape, CONTEXTS, K=3, Kt=5, rounds=4, T=0.8, seed=32)
+    assert chk.exact_accept >= 10
+    assert tally["draft_err"] < 5e-3 and tally["target_err"] < 5e-3
+
+
+def test_free_running_text_equals_the_oracles_fp32():
+    """Both sides run on their own from the same start; the generated text must be the same for as
+    long as no decision of the oracle's run was closer to its threshold than the margins that the
+    1e-4 logit tolerance can move."""
+    t_shape = wl.ModelShape(2, 256, 4, 4, 64, 512, 300, dtype="fp32")
+    d_shape = wl.ModelShape(1, 128, 2, 2, 64, 256, 300, dtype="fp32")
+    K, R, T, seed = 3, 6, 1.0, 41
+    pair = Pair(t_shape, d_shape, CONTEXTS, 96, K, 64, seed=seed)
+    B = len(CONTEXTS)
+    rng = wl.Rng(seed, "cpu")
+    du = [rng.uniform(wl.S_UNIFORMS + 100 + r, (B, K)) for r in range(R)]
+    vu = [rng.uniform(wl.S_UNIFORMS + 200 + r, (B, K + 1)) for r in range(R)]
+    for r in range(R):
+        g = pair.round(K, du[r], vu[r], T)
+    compared = 0
+    for b, st in enumerate(pair.states):
+        trace = od.speculative_decode(pair.tg.om, pair.dr.om, st, R, K, T, [u[b].tolist() for u in du],
+                                      [u[b].tolist() for u in vu])
+        safe = 0   # tokens generated before the first decision that is too close to call
+        for r, t in enumerate(trace):
+            gaps = [min(d.final_target - d.final_cdf_lo, d.final_cdf_hi - d.final_target) for d in t.draft_diags]
+            gaps.append(min(t.diag.final_target - t.diag.final_cdf_lo, t.diag.final_cdf_hi - t.diag.final_target))
+            margins = [abs(float(vu[r][b, i]) - t.diag.accept_ratio[i])
+                       for i in range(min(t.n_accepted + 1, K))]
+            if min(gaps) < 5e-5 or (margins and min(margins) < 1e-3):   # what a 1e-4 logit error can move
+                break
+            safe += len(t.emitted)
+        n = int(g["n_tokens"][b])
+        got = g["tokens"][b, :n].tolist()
+        want = st.tokens[len(CONTEXTS[b]):]
+        assert got[:safe] == want[:safe], f"sequence {b}: text differs inside the safe prefix ({safe} tokens)"
+        compared += safe
+    assert compared >= 20, "too few tokens compared for the test to mean anything"
+
+
+def test_plain_sampling_rounds_without_a_draft():
+    """lookahead 0, no draft model: one token per round drawn from the target -- the baseline loop."""
+    from test_gpu_forward import Rig
+    from paper_2411_00853_amd import binding as sv
+    shape = wl.ModelShape(2, 256, 4, 4, 64, 512, 300, dtype="fp32")
+    rig = Rig(shape, 2, 64, 0, seed=7, std=0.05)
+    ctxs = [[3, 4, 5, 6], [10, 11]]
+    sts = []
+    for b, c in enumerate(ctxs):
+        st = od.SequenceState(list(c), rig.caches[b], 0)
+        st.target_len = od.feed(rig.om, st.target_cache, 0, st.tokens, len(c) - 1)
+        rig.set_cache(b, len(c) - 1)
+        sts.append(st)
+    dec = sv.spec_decode_init(rig.h, None, 2, 16)
+    sv.spec_decode_begin(dec, torch.arange(2, dtype=torch.int32, device="cuda"), None,
+                         torch.tensor([c[-1] for c in ctxs], dtype=torch.int32, device="cuda"))
+    R, T = 6, 0.9
+    us = wl.Rng(3, "cpu").uniform(wl.S_UNIFORMS + 5, (R, 2, 1))
+    for r in range(R):
+        sv.spec_decode_round(dec, 0, None, us[r].contiguous().cuda(), T)
+    torch.cuda.synchronize()
+    sv.spec_verify_poll(rig.h)
+    v = sv.spec_decode_get_view(dec)
+    toks = sv.device_array(v.tokens, (2, 16), torch.int32).cpu()
+    n = sv.device_array(v.n_tokens, (2,), torch.int32).cpu().tolist()
+    assert n == [R, R]
+    for b, st in enumerate(sts):
+        want = od.autoregressive_decode(rig.om, st, R, T, us[:, b, 0].tolist())
+        assert toks[b, :R].tolist() == want   # fp32, and these seeds keep clear of the CDF edges
+    with pytest.raises(sv.SpecError):
+        sv.spec_decode_round(dec, 2, None, us[0].contiguous().cuda(), T)
+
+
+def test_argument_errors():
+    from test_gpu_forward import Rig
+    from paper_2411_00853_amd import binding as sv
+    a = Rig(wl.ModelShape(1, 128, 2, 2, 64, 256, 300, dtype="fp32"), 2, 64, 2, seed=1)
+    b = Rig(wl.ModelShape(1, 128, 2, 2, 64, 256, 301, dtype="fp32"), 2, 64, 1, seed=2)
+    with pytest.raises(sv.SpecError):
+        sv.spec_decode_init(a.h, b.h, 2, 8)          # vocabularies differ
+    with pytest.raises(sv.SpecError):
+        sv.spec_decode_init(a.h, None, 3, 8)         # more sequences than the handle holds
+    dec = sv.spec_decode_init(a.h, None, 2, 8)
+    with pytest.raises(sv.SpecError):
+        sv.spec_decode_round(dec, 0, None, torch.zeros(2, 3, device="cuda"), 1.0)   # no active batch
