@@ -30,7 +30,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn", "stress", "copy"])
+    ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn", "stress", "copy", "decode"])
+    ap.add_argument("--temperature", type=float, default=0.0, help="decode workload: sampling temperature (0 = default 4.0)")
+    ap.add_argument("--lookahead", type=int, default=5, help="decode workload: proposals per round")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--layers", type=int, default=0,
                     help="build only this many decoder layers (for hardware-counter runs, where every dispatch is slow; "
@@ -141,7 +143,7 @@ def bench_stress(args, torch, sv, wl):
         "roofline": {"kernel": "stats_kernel (softmax statistics of all target and draft rows)", "bound": "hbm",
                      "achieved": gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes_per_launch": stat_bytes,
-                     "empty_event_pair_us": empty * 1e3, "timing": "HIP events around the launch on the launch stream"},
+                     "empty_event_pair_us": empty * 1e3, "timing": "HIP events recorded before and after the launch on the launch stream"},
         "cpu_baseline": None,
     }
     if not args.no_cpu_baseline:
@@ -159,6 +161,99 @@ def bench_stress(args, torch, sv, wl):
                                   "seconds": t_or}
     print(json.dumps(result), flush=True)
     h.close()
+
+
+def synthetic_model(sv, wl, torch, shape, seed, n_slots, max_kv_len, max_lookahead, kv_lens):
+    """Random-weight model of a given shape with N(0,1) cache contents: (handle, kv_len tensor, keep-alive)."""
+    from dataclasses import replace
+    w = replace(wl.workload_7b(), shape=shape, seed=seed)
+    weights, _ = build_device_model(sv, wl, w, torch, False)
+    cfg = sv.make_cfg(shape, n_slots, max_kv_len, max_lookahead)
+    kv = torch.empty(sv.spec_kv_cache_bytes(cfg), dtype=torch.uint8, device="cuda")
+    kv_len = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
+    h = sv.spec_verify_init(cfg, weights, kv, kv_len)
+    rng = wl.Rng(seed, "cuda")
+    for b, n in enumerate(kv_lens):
+        plain = torch.empty((shape.n_layers, 2, shape.n_kv_heads, n, shape.head_dim), dtype=shape.torch_dtype, device="cuda")
+        for l in range(shape.n_layers):
+            plain[l] = rng.normal(wl.S_KV + b * 4096 + l, (2, shape.n_kv_heads, n, shape.head_dim), 1.0, shape.torch_dtype)
+        sv.spec_kv_import(h, b, 0, plain)
+        del plain
+    kv_len.copy_(torch.tensor(list(kv_lens), dtype=torch.int32))
+    torch.cuda.synchronize()
+    return h, kv_len, (weights, kv)
+
+
+def bench_decode(args, torch, sv, wl):
+    """The whole loop: a 1B-shape draft proposes K tokens per round, the 7B-shape target verifies them;
+    compared with plain sampling from the target (one token per pass).  Random weights: the two models
+    are unrelated, so how often a proposal is kept is set by the temperature alone (flatter
+    distributions agree more); the kept fraction is reported with the speed-up it produced."""
+    B, K, n0 = 8, args.lookahead, 2048
+    T = args.temperature if args.temperature > 0 else 4.0
+    R, W = args.steps, max(args.warmup, 2)
+    rounds_total = R + W
+    max_kv = n0 + (rounds_total + 2) * (K + 1) + 8
+    t_setup = time.time()
+    tg, tg_len, keep_t = synthetic_model(sv, wl, torch, wl.SEVEN_B, wl.SEED_BASE + 2, B, max_kv, K, [n0] * B)
+    dr, dr_len, keep_d = synthetic_model(sv, wl, torch, wl.ONE_B, wl.SEED_BASE + 3, B, max_kv, 1, [n0 - 1] * B)
+    log(f"[bench] decode setup {time.time() - t_setup:.1f}s")
+    rng = wl.Rng(wl.SEED_BASE + 4, "cuda")
+    V = wl.SEVEN_B.vocab
+    slots = torch.arange(B, dtype=torch.int32, device="cuda")
+    prev = rng.randint(wl.S_TOKENS + 1, (B,), V).to(torch.int32)
+    last = rng.randint(wl.S_TOKENS + 2, (B,), V).to(torch.int32)
+    du = rng.uniform(wl.S_UNIFORMS + 1, (rounds_total, B, K))
+    vu = rng.uniform(wl.S_UNIFORMS + 2, (rounds_total, B, K + 1))
+
+    def counters(dec):
+        v = sv.spec_decode_get_view(dec)
+        return sv.device_array(v.counters, (3,), torch.int64).cpu().tolist()
+
+    dec = sv.spec_decode_init(tg, dr, B, rounds_total * (K + 1))
+    sv.spec_decode_begin(dec, slots, prev, last)
+    for r in range(W):
+        sv.spec_decode_round(dec, K, du[r], vu[r], T)
+    torch.cuda.synchronize()
+    c0 = counters(dec)
+    tic = time.perf_counter()
+    for r in range(W, W + R):
+        sv.spec_decode_round(dec, K, du[r], vu[r], T)
+    torch.cuda.synchronize()
+    t_spec = time.perf_counter() - tic
+    c1 = counters(dec)
+    sv.spec_verify_poll(tg)
+    sv.spec_verify_poll(dr)
+    seq_rounds, kept, emitted = (c1[i] - c0[i] for i in range(3))
+    dec.close()
+
+    # plain sampling from the target from the same starting point
+    sv.spec_kv_rollback(tg, list(range(B)), [n0] * B)
+    base = sv.spec_decode_init(tg, None, B, rounds_total)
+    sv.spec_decode_begin(base, slots, None, last)
+    u0 = vu[:, :, :1].contiguous()
+    for r in range(W):
+        sv.spec_decode_round(base, 0, None, u0[r], T)
+    torch.cuda.synchronize()
+    tic = time.perf_counter()
+    for r in range(W, W + R):
+        sv.spec_decode_round(base, 0, None, u0[r], T)
+    torch.cuda.synchronize()
+    t_base = time.perf_counter() - tic
+    sv.spec_verify_poll(tg)
+    base.close()
+    spec_tps, base_tps = emitted / t_spec, B * R / t_base
+    print(json.dumps({
+        "metric": "emitted tokens/sec, speculative decoding loop", "value": spec_tps, "unit": "tokens/s", "n_gpus": 1,
+        "steps": R, "warmup": W, "ms_per_step": t_spec / R * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"decode loop: target 7B-shape, draft 1B-shape (unrelated random weights), batch {B}, "
+                               f"{n0} cached tokens, K {K}, T {T}; a step is one round (K draft decodes + verification)"},
+        "plain_sampling_tokens_per_s": base_tps, "plain_sampling_ms_per_token_step": t_base / R * 1e3,
+        "speedup_over_plain_sampling": spec_tps / base_tps, "kept_fraction": kept / max(seq_rounds * K, 1),
+        "tokens_per_round_per_sequence": emitted / max(seq_rounds, 1), "roofline": None, "cpu_baseline": None}), flush=True)
+    tg.close()
+    dr.close()
 
 
 def bench_copy(args, torch, sv):
@@ -196,6 +291,8 @@ def main():
         return bench_stress(args, torch, sv, wl)
     if args.workload == "copy":
         return bench_copy(args, torch, sv)
+    if args.workload == "decode":
+        return bench_decode(args, torch, sv, wl)
     w = {"7b": wl.workload_7b, "1b": wl.workload_1b, "dyn": wl.workload_dyn}[args.workload]()
     if args.layers > 0:
         from dataclasses import replace
@@ -292,8 +389,9 @@ def main():
     alg = {"gemm": gemm_bytes, "attention": attn_bytes, "sampler_stats": stat_bytes}
     kernels = {}
     for name, (ms_raw, cnt) in prof.items():
-        # bracketed times are used as measured; they contain some event handling (an empty start/stop
-        # pair alone measures empty_event_pair_us), so they run a few percent above rocprofv3's durations
+        # bracketed times are used as measured: the interval is the launch's whole slot on the stream
+        # (dispatch latency included), about 2.4 us longer than the kernel-trace duration of the dispatch.
+        # Events attached to the dispatch itself (hipExtLaunchKernelGGL) read longer still, so they are not used.
         ms = ms_raw
         e = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps}
         if name in alg and ms > 0:
@@ -308,7 +406,7 @@ def main():
                 "avg_launch_us": g["ms_per_step"] / g["launches_per_step"] * 1e3,
                 "algorithmic_bytes_per_launch": gemm_bytes / g["launches_per_step"],
                 "empty_event_pair_us": empty_pair_ms * 1e3,
-                "timing": f"HIP events around each launch on the launch stream, {args.steps} steps after the timed region"}
+                "timing": f"HIP events recorded before and after each launch on the launch stream, {args.steps} steps after the timed region; the interval holds the launch's whole slot on the stream (about 2.4 us more than the kernel-trace duration of the same dispatch)"}
 
     result = {
         "metric": "verified tokens/sec at 7B-shape K=5 batch 8; % HBM/MFMA roofline" if w.name == "7b" and not args.layers
