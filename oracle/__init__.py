@@ -51,6 +51,12 @@ class SampleDiag(C.Structure):
                 ("final_is_residual", C.c_int32)]
 
 
+class TreeDiag(C.Structure):
+    _fields_ = [("accept_ratio", C.c_double * 16), ("final_S", C.c_double), ("final_target", C.c_double),
+                ("final_cdf_lo", C.c_double), ("final_cdf_hi", C.c_double), ("final_node", C.c_int32),
+                ("final_level", C.c_int32)]
+
+
 _lib = None
 
 
@@ -180,6 +186,50 @@ def sample(target_logits: torch.Tensor, draft_logits: torch.Tensor, draft_tokens
     if rc:
         raise ValueError("oracle_sample rejected its arguments")
     return int(na.value), list(out), diag
+
+
+def tree_sample(parent: Sequence[int], tokens: Sequence[int], target_logits: torch.Tensor,
+                draft_logits: torch.Tensor, uniforms: Sequence[float], temperature: float):
+    """One sequence's token tree.  target_logits, draft_logits [N+1,V] fp32 (row 0: the root, row i+1:
+    node i), uniforms [N+1].  Returns (n_accepted, path, out_tokens [N+1], TreeDiag)."""
+    N = len(tokens)
+    V = target_logits.shape[-1]
+    assert len(parent) == N and target_logits.shape == (N + 1, V) and draft_logits.shape[0] >= N + 1
+    assert target_logits.dtype == torch.float32 and draft_logits.dtype == torch.float32
+    par = (C.c_int32 * max(N, 1))(*[int(v) for v in parent])
+    tok = (C.c_int32 * max(N, 1))(*[int(v) for v in tokens])
+    us = (C.c_float * (N + 1))(*[float(u) for u in uniforms[:N + 1]])
+    na = C.c_int32(0)
+    path = (C.c_int32 * max(N, 1))()
+    out = (C.c_int32 * (N + 1))()
+    diag = TreeDiag()
+    rc = lib().oracle_tree_sample(C.c_int32(V), C.c_int32(N), par, tok, _fptr(target_logits), _fptr(draft_logits),
+                                  us, C.c_float(temperature), C.byref(na), path, out, C.byref(diag))
+    if rc:
+        raise ValueError("oracle_tree_sample rejected its arguments")
+    return int(na.value), list(path)[:int(na.value)], list(out), diag
+
+
+def tree_paths(parent: Sequence[int]):
+    """For every node its path from the root (list of node indices ending in the node itself)."""
+    paths = []
+    for i, p in enumerate(parent):
+        paths.append((paths[p] if p >= 0 else []) + [i])
+    return paths
+
+
+def tree_logits(model: "Model", cache: torch.Tensor, n: int, last_token: int, parent: Sequence[int],
+                tokens: Sequence[int]) -> torch.Tensor:
+    """Rows [N+1,V]: row 0 = the model's distribution after the last token, row i+1 after the path
+    to node i -- each by ordinary decoding along that path (the definition; shared prefixes are
+    simply decoded again).  Cache entries from position n on are scratch."""
+    V = model.shape.vocab
+    rows = torch.empty((len(tokens) + 1, V), dtype=torch.float32)
+    rows[0] = model.decode_one(cache, n, int(last_token))
+    for i, path in enumerate(tree_paths(parent)):
+        lg = model.verify_sequential(cache, n, [int(last_token)] + [int(tokens[j]) for j in path])
+        rows[i + 1] = lg[-1]
+    return rows
 
 
 def softmax(logits: torch.Tensor, temperature: float) -> torch.Tensor:

@@ -413,6 +413,82 @@ int32_t oracle_inverse_cdf(int32_t V, const double* r, double target, double* lo
     return last_pos;
 }
 
+int oracle_tree_sample(int32_t V, int32_t N, const int32_t* parent, const int32_t* tokens,
+                       const float* target_logits, const float* draft_logits, const float* uniforms, float T,
+                       int32_t* n_accepted, int32_t* path, int32_t* out_tokens, oracle_tree_diag* diag)
+{
+    if (V <= 0 || N < 0 || !(T > 0.0f)) return -1;
+    for (int i = 0; i < N; ++i)
+        if (parent[i] < -1 || parent[i] >= i || tokens[i] < 0 || tokens[i] >= V) return -1;
+    double* r = (double*)malloc(sizeof(double) * V);
+    double* q = (double*)malloc(sizeof(double) * V);
+    double* t = (double*)malloc(sizeof(double) * V);
+    if (diag) {
+        memset(diag, 0, sizeof(*diag));
+        for (int i = 0; i < 16; ++i) diag->accept_ratio[i] = -1.0;
+    }
+    int cur = -1, a = 0, level = 0;
+    double S = 1.0;     /* r is kept unnormalised: the distribution is r / S (S = 1 while r is p itself) */
+    for (;;) {
+        /* arrive at a node: r = its target distribution, q = the draft's */
+        oracle_softmax(V, target_logits + (size_t)(cur + 1) * V, T, r);
+        oracle_softmax(V, draft_logits + (size_t)(cur + 1) * V, T, q);
+        level = 0;
+        S = 1.0;
+        int moved = 0;
+        for (int c = cur + 1; c < N; ++c) {
+            if (parent[c] != cur) continue;
+            const int x = tokens[c];
+            const double rx = r[x] / S;
+            if (diag && c < 16) {
+                double ratio = q[x] > 0.0 ? rx / q[x] : (rx > 0.0 ? INFINITY : 0.0);
+                diag->accept_ratio[c] = ratio < 1.0 ? ratio : 1.0;
+            }
+            if ((double)uniforms[c] * q[x] < rx) {
+                path[a] = c;
+                out_tokens[a] = x;
+                ++a;
+                cur = c;
+                moved = 1;
+                break;
+            }
+            /* rejected: r <- max(0, r/S - q) */
+            double S_new = 0.0;
+            for (int v = 0; v < V; ++v) {
+                const double pv = r[v] / S;
+                t[v] = pv > q[v] ? pv - q[v] : 0.0;
+                S_new += t[v];
+            }
+            if (S_new > 0.0) {   /* S_new <= 0 cannot happen in exact arithmetic; then r stays */
+                memcpy(r, t, sizeof(double) * V);
+                S = S_new;
+                ++level;
+            }
+        }
+        if (!moved) break;
+    }
+    if (level == 0) {
+        S = 0.0;
+        for (int v = 0; v < V; ++v) S += r[v];
+    }
+    double target = (double)uniforms[N] * S, lo, hi;
+    const int y = oracle_inverse_cdf(V, r, target, &lo, &hi);
+    out_tokens[a] = y;
+    for (int i = a + 1; i <= N; ++i) out_tokens[i] = -1;
+    for (int i = a; i < N; ++i) path[i] = -1;
+    *n_accepted = a;
+    if (diag) {
+        diag->final_S = S;
+        diag->final_target = target;
+        diag->final_cdf_lo = lo;
+        diag->final_cdf_hi = hi;
+        diag->final_node = cur;
+        diag->final_level = level;
+    }
+    free(r); free(q); free(t);
+    return 0;
+}
+
 int oracle_sample(int32_t V, int32_t K, const float* target_logits, const float* draft_logits,
                   const int32_t* draft_tokens, const float* uniforms, float T,
                   int32_t* n_accepted, int32_t* out_tokens, oracle_sample_diag* diag)

@@ -106,6 +106,35 @@ int oracle_sample(int32_t vocab, int32_t K, const float* target_logits, const fl
                   const int32_t* draft_tokens, const float* uniforms, float temperature,
                   int32_t* n_accepted, int32_t* out_tokens, oracle_sample_diag* diag);
 
+/* Diagnostics of one sequence's tree verification. */
+typedef struct {
+    double accept_ratio[16];  /* per node i < 16: min(1, r(x_i)/q(x_i)) if the node was tested, else -1 */
+    double final_S;
+    double final_target;
+    double final_cdf_lo;
+    double final_cdf_hi;
+    int32_t final_node;       /* node whose rows the final draw used (-1 = root) */
+    int32_t final_level;      /* rejections at that node before the draw (0: its target distribution) */
+} oracle_tree_diag;
+
+/* Verification of a token tree (the tree-structured candidates of the paper's section on
+ * EAGLE-style decoding; the accept rule is the multi-candidate form of the same rejection sampling:
+ * the children of a node are independent draws from the draft distribution at that node).
+ * Nodes 0..N-1 in topological order: parent[i] = -1 (child of the root, i.e. of the sequence's last
+ * token) or an index < i.  Row 0 of target_logits / draft_logits belongs to the root, row i+1 to
+ * node i: the target's and the draft's next-token distributions after the path to that node.
+ * Walk from the root: at the current node with target distribution p and draft distribution q, set
+ * r = p; try its children in index order: child c with token x is kept iff u_c * q(x) < r(x); a kept
+ * child becomes the current node; after a rejection r <- max(0, r - q) / sum(max(0, r - q)).  When no
+ * child is left (a leaf, or all rejected) the final token is drawn from r by inverse CDF with
+ * u_N (target u_N * S over the unnormalised r, as in oracle_sample).
+ * uniforms [N+1]; path [N]: kept node indices root-down; out_tokens [N+1]: their tokens, the final
+ * token, then -1. */
+int oracle_tree_sample(int32_t vocab, int32_t N, const int32_t* parent, const int32_t* tokens,
+                       const float* target_logits, const float* draft_logits, const float* uniforms,
+                       float temperature, int32_t* n_accepted, int32_t* path, int32_t* out_tokens,
+                       oracle_tree_diag* diag);
+
 /* Building blocks, exported so tests can pin them one by one. */
 void oracle_softmax(int32_t vocab, const float* logits, float temperature, double* p);
 void oracle_residual(int32_t vocab, const double* p, const double* q, double* r, double* S);
