@@ -164,6 +164,46 @@ typedef struct {
  * rejected position a, or r = p_K when all K drafts were kept. */
 int spec_verify_step(spec_handle* h, const spec_step_args* args, const spec_step_out* out, void* stream);
 
+/* Verification of a token TREE per sequence (the tree-structured candidates of the paper's
+ * section on EAGLE-style decoding) instead of a chain.  Sequence b proposes N_b <= Kmax nodes in
+ * topological order; parent[b][i] is -1 (child of the root = the sequence's last token) or the
+ * index (< i) of another node; the children of one node are independent draws from the draft
+ * distribution at that node.  Window slot 0 is the root, slot i+1 node i: the decoder pass scores
+ * all N_b+1 tokens at once, every token attending to the cache and to the slots on its own path
+ * only, at rotary position n_b + depth.  Target row j / draft row j (draft_logits[b][j]) are the two
+ * models' next-token distributions after the path to slot j.
+ * The walk starts at the root with r = p (the target row of the current node) and q (its draft
+ * row): the node's children are tried in index order; child c with token x is kept iff
+ * uniforms[b][c] * q(x) < r(x), and then becomes the current node; every rejection replaces r by
+ * max(0, r - q) renormalised.  When the current node has no child left, the final token is drawn
+ * from r by inverse CDF (as in spec_verify_step) with uniforms[b][N_b].
+ * A chain (parent[i] = i-1) gives exactly spec_verify_step.
+ * With auto_rollback the kept nodes' keys and values are moved to positions n_b+1..n_b+a and
+ * kv_len[slot] = n_b + a + 1; without it the window stays as scored and kv_len = n_b + N_b + 1. */
+typedef struct {
+    int32_t batch;
+    const int32_t* n_nodes;        /* HOST int32[B]: N_b in 0 .. Kmax */
+    const int32_t* seq_slot;       /* device int32[B] */
+    const int32_t* last_token;     /* device int32[B] */
+    const int32_t* parent;         /* device int32[B][Kmax] */
+    const int32_t* draft_tokens;   /* device int32[B][Kmax] */
+    const float* draft_logits;     /* device fp32[B][Kmax+1][V]: row 0 the root's, row i+1 node i's
+                                      (rows of nodes without children are never read) */
+    const float* uniforms;         /* device fp32[B][Kmax+1]: [b][i] tests node i, [b][N_b] the final draw */
+    float temperature;
+    const float* target_logits_in; /* optional device fp32[M][V], M = sum(N_b+1): skip the decoder pass */
+    int32_t auto_rollback;
+} spec_tree_args;
+
+typedef struct {
+    int32_t* n_accepted;           /* device int32[B]: kept nodes a (-1: sequence skipped) */
+    int32_t* out_tokens;           /* device int32[B][Kmax+1]: their tokens, the final token, then -1 */
+    int32_t* path;                 /* device int32[B][Kmax]: kept node indices root-down, then -1 */
+    float* logits_out;             /* optional device fp32[M][V] */
+} spec_tree_out;
+
+int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args, const spec_tree_out* out, void* stream);
+
 /* Set kv_len[seq_slot[i]] = new_len[i] for i < n (host arrays, n <= SPEC_MAX_BATCH).  The cache is
  * contiguous per slot, so dropping rejected positions moves no data; stale entries are never read
  * and are overwritten by the next append.  new_len must satisfy 0 <= new_len <= kv_len[slot]. */

@@ -49,6 +49,18 @@ class spec_step_out(C.Structure):
     _fields_ = [("n_accepted", C.c_void_p), ("out_tokens", C.c_void_p), ("logits_out", C.c_void_p)]
 
 
+class spec_tree_args(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_nodes", C.POINTER(C.c_int32)), ("seq_slot", C.c_void_p),
+                ("last_token", C.c_void_p), ("parent", C.c_void_p), ("draft_tokens", C.c_void_p),
+                ("draft_logits", C.c_void_p), ("uniforms", C.c_void_p), ("temperature", C.c_float),
+                ("target_logits_in", C.c_void_p), ("auto_rollback", C.c_int32)]
+
+
+class spec_tree_out(C.Structure):
+    _fields_ = [("n_accepted", C.c_void_p), ("out_tokens", C.c_void_p), ("path", C.c_void_p),
+                ("logits_out", C.c_void_p)]
+
+
 class spec_decode_cfg(C.Structure):
     _fields_ = [("max_batch", C.c_int32), ("max_new_tokens", C.c_int32)]
 
@@ -85,6 +97,7 @@ def lib():
         L.spec_verify_init.argtypes = [C.POINTER(spec_model_cfg), C.POINTER(spec_weights), C.c_void_p, C.c_size_t,
                                        C.c_void_p, C.POINTER(C.c_void_p)]
         L.spec_verify_step.argtypes = [C.c_void_p, C.POINTER(spec_step_args), C.POINTER(spec_step_out), C.c_void_p]
+        L.spec_verify_tree_step.argtypes = [C.c_void_p, C.POINTER(spec_tree_args), C.POINTER(spec_tree_out), C.c_void_p]
         L.spec_kv_rollback.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.c_void_p]
         L.spec_kv_import.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.spec_kv_export.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
@@ -228,6 +241,23 @@ def spec_verify_step(h: Handle, lookahead: Sequence[int], uniforms: torch.Tensor
                           int(auto_rollback))
     out = spec_step_out(_ptr(n_accepted, torch.int32), _ptr(out_tokens, torch.int32), _ptr(logits_out, torch.float32))
     _check(lib().spec_verify_step(h.ptr, C.byref(args), C.byref(out), _stream(stream)))
+
+
+def spec_verify_tree_step(h: Handle, n_nodes: Sequence[int], parent: Optional[torch.Tensor],
+                          draft_tokens: Optional[torch.Tensor], draft_logits: torch.Tensor, uniforms: torch.Tensor,
+                          temperature: float, n_accepted: torch.Tensor, out_tokens: torch.Tensor, path: torch.Tensor,
+                          seq_slot: Optional[torch.Tensor] = None, last_token: Optional[torch.Tensor] = None,
+                          target_logits_in: Optional[torch.Tensor] = None, logits_out: Optional[torch.Tensor] = None,
+                          auto_rollback: bool = True, stream=None):
+    B = len(n_nodes)
+    ns = (C.c_int32 * B)(*[int(k) for k in n_nodes])
+    args = spec_tree_args(B, ns, _ptr(seq_slot, torch.int32), _ptr(last_token, torch.int32),
+                          _ptr(parent, torch.int32), _ptr(draft_tokens, torch.int32),
+                          _ptr(draft_logits, torch.float32), _ptr(uniforms, torch.float32), float(temperature),
+                          _ptr(target_logits_in, torch.float32), int(auto_rollback))
+    out = spec_tree_out(_ptr(n_accepted, torch.int32), _ptr(out_tokens, torch.int32), _ptr(path, torch.int32),
+                        _ptr(logits_out, torch.float32))
+    _check(lib().spec_verify_tree_step(h.ptr, C.byref(args), C.byref(out), _stream(stream)))
 
 
 def spec_kv_rollback(h: Handle, seq_slot: Sequence[int], new_len: Sequence[int], stream=None):

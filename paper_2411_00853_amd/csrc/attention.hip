@@ -64,13 +64,15 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
 
     // queries, pre-scaled by log2(e)/sqrt(hd), as bf16 head + remainder operand fragments
     Frag qh[RT][STEPS], ql[RT][STEPS];
-    int limit[RT];
+    int n_vis[RT];           // cached positions below this are visible to the query (0 for padding rows)
+    uint32_t wmask[RT];      // window slots (positions n + i) the query attends to
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         const int r = rt * 16 + c16;
         const bool real = r < rows;
         const int j = real ? r / group : 0, hl = real ? r % group : 0;
-        limit[rt] = real ? n + j : -1;   // last visible position of this query
+        n_vis[rt] = real ? n : 0;
+        wmask[rt] = real ? t.row_mask[row0 + j] : 0u;
         const float4* src = reinterpret_cast<const float4*>(q + (size_t)(row0 + j) * dq + (hkv * group + hl) * HD + 8 * gq);
         const float sc = real ? scale_log2e : 0.f;   // rows past the window contribute zeros
 #pragma unroll
@@ -144,7 +146,9 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int key = kbase + (e < 4 ? 4 * gq + e : 16 + 4 * gq + e - 4);
-                    if (key > limit[rt] || kbase >= key1) sv[e] = -INFINITY;
+                    const int w = key - n;   // window slot, if >= 0
+                    const bool vis = key < n_vis[rt] || (w >= 0 && w < 32 && ((wmask[rt] >> w) & 1u));
+                    if (!vis || kbase >= key1) sv[e] = -INFINITY;
                 }
             }
             float mx = sv[0];
@@ -267,6 +271,8 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(StepTables t, CacheGeom g
         return;
     }
     const int n_keys = pos + 1;
+    const int n_cached = t.seq_n[t.row_seq[m]];
+    const uint32_t wmask = t.row_mask[m];
     const int slot = t.seq_slot[t.row_seq[m]];
     const int hkv = hq / (n_q_heads / g.n_kv_heads);
     const float* kbase = cache + cache_head_base(g, layer, slot, hkv) + plain_offset(g, 0, 0, 0);
@@ -280,6 +286,7 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(StepTables t, CacheGeom g
         float a = 0.f;
         for (int e = 0; e < hd; ++e) a = fmaf(qs[e], kbase[(size_t)k * hd + e], a);
         a *= scale;
+        if (k >= n_cached && !((wmask >> (k - n_cached)) & 1u)) a = -INFINITY;   // window slot not on this row's path
         sc[k] = a;
         mx = fmaxf(mx, a);
     }

@@ -66,8 +66,10 @@ struct StepTables {
     int32_t* seq_ok;     // [B] 1 = sequence takes part, 0 = skipped (device-side error)
     int32_t* seq_slot;   // [B] cache slot (copied so later kernels need not re-validate)
     int32_t* row_seq;    // [M]
-    int32_t* row_pos;    // [M] absolute position n_b + j (or -1 for rows of skipped sequences)
+    int32_t* row_pos;    // [M] cache position n_b + j of the row's key/value (or -1 for rows of skipped sequences)
     int32_t* row_tok;    // [M] token id fed at this row
+    int32_t* row_rope;   // [M] position the rotary embedding uses: n_b + depth of the row in its window
+    uint32_t* row_mask;  // [M] bit i set: the row attends to window slot i (position n_b + i)
 };
 
 // ---- sampler (sampler.hip) ---------------------------------------------------------------------
@@ -105,6 +107,17 @@ int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const Lookahe
                    const int32_t* draft_tokens, const float* uniforms, int u_stride, float temperature,
                    int auto_rollback, int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens,
                    const DrawEmit* emit, Profiler* prof, hipStream_t s);
+
+// Token-tree variants: parent/tokens [B][Kmax], draft logits [B][Kmax+1][V] (row 0: the root)
+int launch_prepare_tree(const StepTables& t, const LookaheadPack& ks, int B, int Kmax, int V, int max_batch,
+                        int max_kv_len, bool has_cache, const int32_t* seq_slot, const int32_t* last_token,
+                        const int32_t* parent, const int32_t* tokens, const int32_t* kv_len, int32_t* flag,
+                        hipStream_t s);
+int launch_tree_sampler(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax,
+                        int V, int n_stat_rows, const float* target_logits, const float* draft_logits,
+                        const int32_t* parent, const int32_t* tokens, const float* uniforms, float temperature,
+                        int auto_rollback, int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens,
+                        int32_t* path, Profiler* prof, hipStream_t s);
 
 struct RollbackPack {
     int32_t slot[SPEC_MAX_BATCH];
@@ -164,6 +177,9 @@ int launch_reduce_splits(const float* partial, int n_split, size_t split_stride,
                          const float* ssq, int n_ssq, int d, float eps, float* out, hipStream_t s);
 int launch_kv_copy(const CacheGeom& g, void* cache, int slot, int pos0, int n_pos, void* plain, bool to_cache,
                    hipStream_t s);
+// keys/values of the kept path (slot path[k]+1 of the window) moved to positions n+1..n+a, all layers
+int launch_kv_compact(const CacheGeom& g, void* cache, const StepTables& t, int B, int Kmax, const int32_t* n_accepted,
+                      const int32_t* path, hipStream_t s);
 
 // Y[M][N] (+)= X[M][K] * W[N][K]^T.  bf16: W packed, result left as n_split partial sums in
 // `partial` ([n_split][M][N_pad]); the plan says how many.  fp32: direct result (n_split = 1).

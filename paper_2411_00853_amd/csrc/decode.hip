@@ -207,6 +207,8 @@ extern "C" int spec_decode_init(spec_handle* target, spec_handle* draft, const s
             t->row_seq = draft->tables.row_seq;
             t->row_pos = draft->tables.row_pos;
             t->row_tok = draft->tables.row_tok;
+            t->row_rope = draft->tables.row_rope;
+            t->row_mask = draft->tables.row_mask;
         }
     }
     if (rc != SPEC_OK) {

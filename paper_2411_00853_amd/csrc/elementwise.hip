@@ -193,7 +193,7 @@ __global__ void __launch_bounds__(64) rope_append_kernel(const float* __restrict
     const int slot = t.seq_slot[t.row_seq[m]];
     const float rs = row_inv_rms(ns.ssq, ns.n_ssq, m, ns.d, ns.eps);   // the attention norm's row scale
     if (head < n_q_heads + g.n_kv_heads) {
-        const float* cs = cos_sin + (size_t)pos * hd;   // [half][2]
+        const float* cs = cos_sin + (size_t)t.row_rope[m] * hd;   // [half][2]; depth in the window, not the slot
         for (int i = threadIdx.x; i < half; i += 64) {
             const float a = sum_splits(row + i, n_split, split_stride) * rs;
             const float b = sum_splits(row + i + half, n_split, split_stride) * rs;
@@ -365,6 +365,52 @@ int launch_reduce_splits(const float* partial, int n_split, size_t split_stride,
     hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks_for((size_t)M * N)), dim3(TPB), 0, s, partial, n_split,
                        split_stride, M, N, ld, ns, out);
     SPECV_LAUNCH_CHECK("reduce_splits_kernel");
+    return SPEC_OK;
+}
+
+// After a tree was verified: the kept nodes' keys and values move from their window slots to the
+// positions right behind the root, in path order.  Sources increase along a path and are never
+// below their destination, and each thread moves the same dims in every step, so moving in place,
+// one path node after the other, never overwrites an entry that is still needed.
+template <bool BF16>
+__global__ void __launch_bounds__(64) kv_compact_kernel(CacheGeom g, void* cache, StepTables t, int Kmax,
+                                                        const int32_t* __restrict__ n_accepted,
+                                                        const int32_t* __restrict__ path)
+{
+    const int b = blockIdx.x;
+    if (!t.seq_ok[b]) return;
+    const int a = n_accepted[b];
+    const int n = t.seq_n[b], hd = g.head_dim;
+    const int layer = blockIdx.y / g.n_kv_heads, head = blockIdx.y % g.n_kv_heads;
+    const size_t base = cache_head_base(g, layer, t.seq_slot[b], head);
+    for (int k = 1; k <= a; ++k) {
+        const int node = path[b * Kmax + k - 1];
+        if (node < 0 || node >= Kmax) return;   // cannot happen: the walk writes a valid indices first
+        const int src = n + node + 1, dst = n + k;
+        if (src == dst) continue;
+        for (int i = threadIdx.x; i < hd; i += 64) {
+            if constexpr (BF16) {
+                uint16_t* c = static_cast<uint16_t*>(cache);
+                c[base + tiled_k_offset(hd, dst, i)] = c[base + tiled_k_offset(hd, src, i)];
+                c[base + tiled_v_offset(hd, dst, i)] = c[base + tiled_v_offset(hd, src, i)];
+            } else {
+                float* c = static_cast<float*>(cache);
+                c[base + plain_offset(g, 0, dst, i)] = c[base + plain_offset(g, 0, src, i)];
+                c[base + plain_offset(g, 1, dst, i)] = c[base + plain_offset(g, 1, src, i)];
+            }
+        }
+    }
+}
+
+int launch_kv_compact(const CacheGeom& g, void* cache, const StepTables& t, int B, int Kmax, const int32_t* n_accepted,
+                      const int32_t* path, hipStream_t s)
+{
+    const dim3 grid(B, g.n_layers * g.n_kv_heads);
+    if (g.dtype == SPEC_DTYPE_BF16)
+        hipLaunchKernelGGL(kv_compact_kernel<true>, grid, dim3(64), 0, s, g, cache, t, Kmax, n_accepted, path);
+    else
+        hipLaunchKernelGGL(kv_compact_kernel<false>, grid, dim3(64), 0, s, g, cache, t, Kmax, n_accepted, path);
+    SPECV_LAUNCH_CHECK("kv_compact_kernel");
     return SPEC_OK;
 }
 

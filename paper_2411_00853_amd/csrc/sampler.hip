@@ -91,6 +91,8 @@ __global__ void __launch_bounds__(TPB) prepare_kernel(StepTables t, LookaheadPac
         int r = row0[b] + j;
         t.row_seq[r] = b;
         t.row_pos[r] = ok ? n + j : -1;
+        t.row_rope[r] = ok ? n + j : 0;
+        t.row_mask[r] = (2u << j) - 1u;   // causal window: slots 0..j
         int tok = (j == 0) ? t0 : draft_tokens[b * Kmax + j - 1];
         t.row_tok[r] = ok ? tok : 0;
     }
@@ -100,16 +102,18 @@ __global__ void __launch_bounds__(TPB) prepare_kernel(StepTables t, LookaheadPac
 // Pass 1: per (row, chunk) maximum and sum of exp((l - max)/T).
 // Statistics rows of sequence b: K_b+1 target rows, then K_b draft rows.
 // ---------------------------------------------------------------------------------------------
+// draft_rows: draft logits rows per sequence in memory (Kmax for a chain of proposals; Kmax+1 for
+// a tree, whose root has a row of its own)
 __device__ __forceinline__ const float* stat_row_ptr(const StepTables& t, const LookaheadPack& ks, int b, int local,
-                                                     int Kmax, int V, const float* target, const float* draft)
+                                                     int draft_rows, int V, const float* target, const float* draft)
 {
     const int K = ks.k[b];
     if (local <= K) return target + (size_t)(t.seq_row0[b] + local) * V;
-    return draft + ((size_t)b * Kmax + (local - K - 1)) * V;
+    return draft + ((size_t)b * draft_rows + (local - K - 1)) * V;
 }
 
 template <bool VEC4>
-__global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack ks, int B, int Kmax, int V,
+__global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack ks, int B, int draft_rows, int V,
                                                     int n_chunks, const float* __restrict__ target,
                                                     const float* __restrict__ draft, float inv_T,
                                                     float* __restrict__ part_max, double* __restrict__ part_sum,
@@ -122,7 +126,7 @@ __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack 
     // find the sequence of this statistics row (B <= 256: a short scan of the prefix array)
     int b = 0;
     while (b + 1 < B && t.seq_stat0[b + 1] <= srow) ++b;
-    const float* row = stat_row_ptr(t, ks, b, srow - t.seq_stat0[b], Kmax, V, target, draft);
+    const float* row = stat_row_ptr(t, ks, b, srow - t.seq_stat0[b], draft_rows, V, target, draft);
     const int base = chunk * STAT_CHUNK;
     const int lim = min(STAT_CHUNK, V - base);
 
@@ -420,6 +424,313 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Token trees.  Window slot 0 is the sequence's last token (the root), slot i+1 is node i; the
+// nodes come in topological order with parent[i] = -1 (child of the root) or an index < i.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(TPB) prepare_tree_kernel(StepTables t, LookaheadPack ks, int B, int Kmax, int V,
+                                                           int max_batch, int max_kv_len, int has_cache,
+                                                           const int32_t* __restrict__ seq_slot,
+                                                           const int32_t* __restrict__ last_token,
+                                                           const int32_t* __restrict__ parent,
+                                                           const int32_t* __restrict__ tokens,
+                                                           const int32_t* __restrict__ kv_len, int32_t* flag)
+{
+    __shared__ int row0[SPEC_MAX_BATCH + 1];
+    const int b = threadIdx.x;
+    if (b == 0) {
+        int r = 0, st = 0;
+        for (int i = 0; i < B; ++i) {
+            row0[i] = r;
+            t.seq_row0[i] = r;
+            t.seq_stat0[i] = st;
+            r += ks.k[i] + 1;
+            st += 2 * ks.k[i] + 2;   // target and draft row of the root and of every node
+        }
+        row0[B] = r;
+        t.seq_row0[B] = r;
+        t.seq_stat0[B] = st;
+    }
+    __syncthreads();
+    if (b >= B) return;
+    const int N = ks.k[b];
+    int ok = 1, err = 0;
+    int slot = b, n = 0;
+    if (has_cache) {
+        slot = seq_slot[b];
+        if (slot < 0 || slot >= max_batch) {
+            ok = 0;
+            err = SPEC_ERR_INVALID_ARG;
+            slot = 0;
+        } else {
+            for (int i = 0; i < b; ++i)
+                if (seq_slot[i] == slot) { ok = 0; err = SPEC_ERR_INVALID_ARG; }
+            n = kv_len[slot];
+            if (n < 0 || n + N + 1 > max_kv_len) { ok = 0; err = SPEC_ERR_KV_OVERFLOW; }
+        }
+    }
+    const int t0 = last_token ? last_token[b] : 0;
+    if (t0 < 0 || t0 >= V) { ok = 0; err = SPEC_ERR_TOKEN_RANGE; }
+    for (int i = 0; i < N; ++i) {
+        const int x = tokens[b * Kmax + i], p = parent[b * Kmax + i];
+        if (x < 0 || x >= V) { ok = 0; err = SPEC_ERR_TOKEN_RANGE; }
+        if (p < -1 || p >= i) { ok = 0; err = SPEC_ERR_INVALID_ARG; }
+    }
+    if (!ok) atomicCAS(flag, 0, err);
+    t.seq_n[b] = ok ? n : 0;
+    t.seq_ok[b] = ok;
+    t.seq_slot[b] = slot;
+    // slot j: depth and the set of slots on its path (itself included)
+    int depth[SPEC_MAX_LOOKAHEAD + 1];
+    uint32_t mask[SPEC_MAX_LOOKAHEAD + 1];
+    depth[0] = 0;
+    mask[0] = 1u;
+    for (int j = 0; j <= N; ++j) {
+        if (j > 0) {
+            const int ps = ok ? parent[b * Kmax + j - 1] + 1 : 0;   // parent's slot
+            depth[j] = depth[ps] + 1;
+            mask[j] = mask[ps] | (1u << j);
+        }
+        const int r = row0[b] + j;
+        t.row_seq[r] = b;
+        t.row_pos[r] = ok ? n + j : -1;
+        t.row_rope[r] = ok ? n + depth[j] : 0;
+        t.row_mask[r] = mask[j];
+        const int tok = (j == 0) ? t0 : tokens[b * Kmax + j - 1];
+        t.row_tok[r] = ok ? tok : 0;
+    }
+}
+
+struct TreeOut {
+    int32_t* n_accepted;   // [B]
+    int32_t* out_tokens;   // [B][Kmax+1]
+    int32_t* path;         // [B][Kmax] kept node indices root-down, then -1
+};
+
+// The walk of one sequence's tree (one workgroup).  At the current node r starts as the target
+// distribution p; a child with token x is kept iff u * q(x) < r(x); every rejection replaces r by
+// max(0, r - q) renormalised.  r is never materialised: r_k(v) is recomputed from p(v), q(v) and the
+// masses S_1..S_k of the earlier levels, so a rejection costs one pass over the two logits rows.
+__global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadPack ks, int Kmax, int V,
+                                                        int n_stat_chunks, const float* __restrict__ target,
+                                                        const float* __restrict__ draft,
+                                                        const int32_t* __restrict__ parent,
+                                                        const int32_t* __restrict__ tokens,
+                                                        const float* __restrict__ uniforms, float inv_T_f,
+                                                        const float* __restrict__ part_max,
+                                                        const double* __restrict__ part_sum, int auto_rollback,
+                                                        int32_t* kv_len, TreeOut out)
+{
+    constexpr int MAXN = SPEC_MAX_LOOKAHEAD;
+    __shared__ float row_m[2 * MAXN + 2];
+    __shared__ double row_z[2 * MAXN + 2];
+    __shared__ double level_S[MAXN + 1];     // level_S[k]: mass of the unnormalised r_k, k >= 1
+    __shared__ double wsum[TPB / 64];
+    __shared__ double r[RES_CHUNK];
+    __shared__ int s_flag, s_tok, s_chunk;
+    __shared__ double s_val, s_before, s_target;
+    const int b = blockIdx.x;
+    const int N = ks.k[b];
+    if (!t.seq_ok[b]) {
+        if (threadIdx.x == 0) out.n_accepted[b] = -1;
+        for (int i = threadIdx.x; i <= Kmax; i += TPB) out.out_tokens[b * (Kmax + 1) + i] = -1;
+        for (int i = threadIdx.x; i < Kmax; i += TPB) out.path[b * Kmax + i] = -1;
+        return;
+    }
+    const double inv_T = (double)inv_T_f;
+    const int st0 = t.seq_stat0[b];
+    if ((int)threadIdx.x < 2 * N + 2)
+        combine_row(part_max + (size_t)(st0 + threadIdx.x) * n_stat_chunks,
+                    part_sum + (size_t)(st0 + threadIdx.x) * n_stat_chunks, n_stat_chunks, inv_T,
+                    &row_m[threadIdx.x], &row_z[threadIdx.x]);
+    __syncthreads();
+    const float* trow0 = target + (size_t)t.seq_row0[b] * V;
+    const float* drow0 = draft + (size_t)b * (Kmax + 1) * V;
+    const int32_t* par = parent + b * Kmax;
+    const int32_t* tok = tokens + b * Kmax;
+
+    int cur = -1, level = 0, a = 0;
+    const float* prow = trow0;
+    const float* qrow = drow0;
+    float mp = row_m[0], mq = row_m[N + 1];
+    double izp = 1.0 / row_z[0], izq = 1.0 / row_z[N + 1];
+    // r_level(v) from the two rows (level and the masses are uniform over the workgroup)
+    auto resid = [&](float lp, float lq, int lev) -> double {
+        double pv = (double)__expf((lp - mp) * inv_T_f) * izp;
+        if (lev > 0) {
+            const double qv = (double)__expf((lq - mq) * inv_T_f) * izq;
+            pv = pv > qv ? pv - qv : 0.0;
+            for (int k = 1; k < lev; ++k) {
+                pv = pv / level_S[k];
+                pv = pv > qv ? pv - qv : 0.0;
+            }
+        }
+        return pv;
+    };
+    auto block_sum = [&](double v) -> double {
+        v = wave_sum(v);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = v;
+        __syncthreads();
+        return (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+    };
+
+    for (int c = 0; c < N; ++c) {
+        if (par[c] != cur) continue;
+        if (threadIdx.x == 0) {
+            const int x = tok[c];
+            const double u = (double)uniforms[b * (Kmax + 1) + c];
+            const double ep = exp((double)(prow[x] - mp) * inv_T);
+            const double eq = exp((double)(qrow[x] - mq) * inv_T);
+            bool keep;
+            if (level == 0) {
+                keep = u * eq * row_z[cur + 1] < ep * row_z[N + 1 + cur + 1];   // u q(x) < p(x), division-free
+            } else {
+                const double qx = eq * izq;
+                double rx = ep * izp;
+                rx = rx > qx ? rx - qx : 0.0;
+                for (int k = 1; k < level; ++k) {
+                    rx = rx / level_S[k];
+                    rx = rx > qx ? rx - qx : 0.0;
+                }
+                keep = u * qx * level_S[level] < rx;   // u q(x) < r(x) / S
+            }
+            s_flag = keep ? 1 : 0;
+        }
+        __syncthreads();
+        const bool keep = s_flag != 0;
+        __syncthreads();
+        if (keep) {
+            if (threadIdx.x == 0) {
+                out.path[b * Kmax + a] = c;
+                out.out_tokens[b * (Kmax + 1) + a] = tok[c];
+            }
+            ++a;
+            cur = c;
+            level = 0;
+            prow = trow0 + (size_t)(c + 1) * V;
+            qrow = drow0 + (size_t)(c + 1) * V;
+            mp = row_m[c + 1];
+            mq = row_m[N + 1 + c + 1];
+            izp = 1.0 / row_z[c + 1];
+            izq = 1.0 / row_z[N + 1 + c + 1];
+            continue;
+        }
+        // rejected: mass of max(0, r/S - q)
+        double acc = 0.0;
+        const double div = level > 0 ? level_S[level] : 1.0;
+        for (int v = threadIdx.x; v < V; v += TPB) {
+            const float lq = qrow[v];
+            double pv = resid(prow[v], lq, level);
+            if (level > 0) pv = pv / div;
+            const double qv = (double)__expf((lq - mq) * inv_T_f) * izq;
+            acc += pv > qv ? pv - qv : 0.0;
+        }
+        const double S_new = block_sum(acc);
+        if (S_new > 0.0) {   // <= 0 cannot happen in exact arithmetic; then r stays as it is
+            if (threadIdx.x == 0) level_S[level + 1] = S_new;
+            ++level;
+        }
+        __syncthreads();
+    }
+
+    // final draw from r_level of the current node: chunk masses, then a scan inside one chunk
+    const int n_res_chunks = (V + RES_CHUNK - 1) / RES_CHUNK;
+    constexpr int PER = RES_CHUNK / TPB;
+    double total = 0.0;   // meaningful in thread 0
+    __shared__ double mass[64];
+    for (int c0 = 0; c0 < n_res_chunks; c0 += 64) {
+        for (int cc = c0; cc < min(c0 + 64, n_res_chunks); ++cc) {
+            const int base = cc * RES_CHUNK;
+            const int lim = min(RES_CHUNK, V - base);
+            double acc = 0.0;
+            for (int i = threadIdx.x; i < lim; i += TPB) acc += resid(prow[base + i], qrow[base + i], level);
+            const double m = block_sum(acc);
+            if (threadIdx.x == 0) mass[cc - c0] = m;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0)
+            for (int cc = c0; cc < min(c0 + 64, n_res_chunks); ++cc) total += mass[cc - c0];
+        if (n_res_chunks > 64) __syncthreads();
+    }
+    // (vocabularies beyond 64 chunks of 4096 would need the masses kept in global memory; the
+    // launch wrapper rejects them)
+    if (threadIdx.x == 0) {
+        const double target_mass = (double)uniforms[b * (Kmax + 1) + N] * total;
+        double c0 = 0.0, last_before = 0.0;
+        int pick = -1, last_pos = -1;
+        for (int cc = 0; cc < n_res_chunks; ++cc) {
+            if (mass[cc] > 0.0) { last_pos = cc; last_before = c0; }
+            if (c0 + mass[cc] > target_mass) { pick = cc; break; }
+            c0 += mass[cc];
+        }
+        if (pick < 0) { pick = last_pos; c0 = last_before; }
+        if (pick < 0) { pick = 0; c0 = 0.0; }
+        s_chunk = pick;
+        s_before = c0;
+        s_target = target_mass;
+        s_tok = -1;
+    }
+    __syncthreads();
+    {
+        const int base = s_chunk * RES_CHUNK;
+        const int lim = min(RES_CHUNK, V - base);
+        const double before = s_before, target_mass = s_target;
+        for (int i = threadIdx.x; i < RES_CHUNK; i += TPB)
+            r[i] = i < lim ? resid(prow[base + i], qrow[base + i], level) : 0.0;
+        __syncthreads();
+        double loc = 0.0;
+        int my_last = -1;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const double x = r[threadIdx.x * PER + i];
+            loc += x;
+            if (x > 0.0) my_last = base + threadIdx.x * PER + i;
+        }
+        double inc = loc;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double up = __shfl_up(inc, o);
+            if ((int)(threadIdx.x & 63) >= o) inc += up;
+        }
+        if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
+        __syncthreads();
+        double off = before;
+        for (int wv = 0; wv < (int)(threadIdx.x >> 6); ++wv) off += wsum[wv];
+        inc += off;
+        const double exc = inc - loc;
+        if (inc > target_mass && !(exc > target_mass)) {
+            double cdf = exc;
+            int y = -1;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                cdf += r[threadIdx.x * PER + i];
+                if (y < 0 && cdf > target_mass) y = base + threadIdx.x * PER + i;
+            }
+            if (y < 0) y = my_last;
+            if (y >= 0) atomicMax(&s_tok, y);
+        }
+        int wl = my_last;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) wl = max(wl, __shfl_xor(wl, o));
+        __syncthreads();
+        int* scratch = reinterpret_cast<int*>(wsum);
+        if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = wl;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int y = s_tok;
+            if (y < 0) y = max(max(scratch[0], scratch[1]), max(scratch[2], scratch[3]));
+            if (y < 0) y = 0;
+            out.n_accepted[b] = a;
+            int32_t* o = out.out_tokens + b * (Kmax + 1);
+            o[a] = y;
+            for (int i = a + 1; i <= Kmax; ++i) o[i] = -1;
+            for (int i = a; i < Kmax; ++i) out.path[b * Kmax + i] = -1;
+            if (kv_len) kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : N) + 1;
+        }
+    }
+}
+
 // kv_len[slot] = len where 0 <= len <= kv_len[slot]; anything else leaves the slot alone and flags.
 __global__ void __launch_bounds__(TPB) rollback_kernel(RollbackPack p, int n, int max_batch, int32_t* kv_len,
                                                        int32_t* flag)
@@ -441,6 +752,48 @@ int launch_prepare(const StepTables& t, const LookaheadPack& ks, int B, int Kmax
     hipLaunchKernelGGL(prepare_kernel, dim3(1), dim3(TPB), 0, s, t, ks, B, Kmax, V, max_batch, max_kv_len,
                        has_cache ? 1 : 0, seq_slot, last_token, draft_tokens, kv_len, flag);
     SPECV_LAUNCH_CHECK("prepare_kernel");
+    return SPEC_OK;
+}
+
+int launch_prepare_tree(const StepTables& t, const LookaheadPack& ks, int B, int Kmax, int V, int max_batch,
+                        int max_kv_len, bool has_cache, const int32_t* seq_slot, const int32_t* last_token,
+                        const int32_t* parent, const int32_t* tokens, const int32_t* kv_len, int32_t* flag,
+                        hipStream_t s)
+{
+    hipLaunchKernelGGL(prepare_tree_kernel, dim3(1), dim3(TPB), 0, s, t, ks, B, Kmax, V, max_batch, max_kv_len,
+                       has_cache ? 1 : 0, seq_slot, last_token, parent, tokens, kv_len, flag);
+    SPECV_LAUNCH_CHECK("prepare_tree_kernel");
+    return SPEC_OK;
+}
+
+int launch_tree_sampler(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax,
+                        int V, int n_stat_rows, const float* target_logits, const float* draft_logits,
+                        const int32_t* parent, const int32_t* tokens, const float* uniforms, float temperature,
+                        int auto_rollback, int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens,
+                        int32_t* path, Profiler* prof, hipStream_t s)
+{
+    const int n_stat_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
+    if ((V + RES_CHUNK - 1) / RES_CHUNK > 64)
+        return fail(SPEC_ERR_SHAPE, "tree verification supports vocabularies up to %d", 64 * RES_CHUNK);
+    const float inv_T = 1.0f / temperature;
+    const bool vec4 = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(target_logits) & 15) == 0)
+                      && ((reinterpret_cast<uintptr_t>(draft_logits) & 15) == 0);
+    dim3 g1((unsigned)n_stat_rows * n_stat_chunks);
+    {
+        ProfScope ps(prof, SPEC_PROF_SAMPLER_STATS, s);
+        if (vec4)
+            hipLaunchKernelGGL(stats_kernel<true>, g1, dim3(TPB), 0, s, t, ks, B, Kmax + 1, V, n_stat_chunks,
+                               target_logits, draft_logits, inv_T, w.part_max, w.part_sum, (float*)nullptr, (size_t)0);
+        else
+            hipLaunchKernelGGL(stats_kernel<false>, g1, dim3(TPB), 0, s, t, ks, B, Kmax + 1, V, n_stat_chunks,
+                               target_logits, draft_logits, inv_T, w.part_max, w.part_sum, (float*)nullptr, (size_t)0);
+        SPECV_LAUNCH_CHECK("stats_kernel");
+    }
+    ProfScope ps(prof, SPEC_PROF_SAMPLER_DRAW, s);
+    TreeOut o{n_accepted, out_tokens, path};
+    hipLaunchKernelGGL(tree_walk_kernel, dim3(B), dim3(TPB), 0, s, t, ks, Kmax, V, n_stat_chunks, target_logits,
+                       draft_logits, parent, tokens, uniforms, inv_T, w.part_max, w.part_sum, auto_rollback, kv_len, o);
+    SPECV_LAUNCH_CHECK("tree_walk_kernel");
     return SPEC_OK;
 }
 

@@ -161,7 +161,7 @@ extern "C" int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* w
 
     const int B = cfg->max_batch, Kmax = cfg->max_lookahead, V = cfg->vocab;
     const int max_rows = B * (Kmax + 1);
-    const int max_stat = B * (2 * Kmax + 1);
+    const int max_stat = B * (2 * Kmax + 2);   // a tree has a draft row for its root as well
     const int n_stat_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
     const int n_res_chunks = (V + RES_CHUNK - 1) / RES_CHUNK;
     Arena& a = h->arena;
@@ -178,6 +178,8 @@ extern "C" int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* w
     A(&h->tables.row_seq, max_rows);
     A(&h->tables.row_pos, max_rows);
     A(&h->tables.row_tok, max_rows);
+    A(&h->tables.row_rope, max_rows);
+    A(&h->tables.row_mask, max_rows);
     A(&h->sampler.part_max, (size_t)max_stat * n_stat_chunks);
     A(&h->sampler.part_sum, (size_t)max_stat * n_stat_chunks);
     A(&h->sampler.chunk_mass, (size_t)B * n_res_chunks);
@@ -314,6 +316,66 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     return launch_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, n_stat, logits, args->draft_logits,
                           args->draft_tokens, args->uniforms, Kmax + 1, args->temperature, args->auto_rollback,
                           run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, nullptr, &h->prof, s);
+}
+
+extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args, const spec_tree_out* out, void* stream)
+{
+    if (!h || !args || !out) return fail(SPEC_ERR_INVALID_ARG, "NULL handle, args or out");
+    const spec_model_cfg& c = h->cfg;
+    const int B = args->batch, Kmax = c.max_lookahead;
+    if (B < 1 || B > c.max_batch) return fail(SPEC_ERR_INVALID_ARG, "batch %d outside 1..%d", B, c.max_batch);
+    if (!args->n_nodes) return fail(SPEC_ERR_INVALID_ARG, "n_nodes is NULL");
+    if (!(args->temperature > 0.f)) return fail(SPEC_ERR_INVALID_ARG, "temperature must be > 0");
+    if (!args->uniforms) return fail(SPEC_ERR_INVALID_ARG, "uniforms is NULL");
+    if (!out->n_accepted || !out->out_tokens || !out->path)
+        return fail(SPEC_ERR_INVALID_ARG, "n_accepted, out_tokens or path is NULL");
+    LookaheadPack ks;
+    memset(&ks, 0, sizeof(ks));
+    int M = 0, any = 0;
+    for (int b = 0; b < B; ++b) {
+        const int k = args->n_nodes[b];
+        if (k < 0 || k > Kmax) return fail(SPEC_ERR_INVALID_ARG, "n_nodes[%d] = %d outside 0..%d", b, k, Kmax);
+        ks.k[b] = (uint8_t)k;
+        M += k + 1;
+        any |= k;
+    }
+    if (!args->draft_logits) return fail(SPEC_ERR_INVALID_ARG, "draft_logits is NULL");
+    if (any && (!args->draft_tokens || !args->parent))
+        return fail(SPEC_ERR_INVALID_ARG, "draft_tokens or parent is NULL");
+    const bool run_model = args->target_logits_in == nullptr;
+    if (run_model) {
+        if (!h->has_model) return fail(SPEC_ERR_INVALID_ARG, "sampler-only handle needs target_logits_in");
+        if (!args->seq_slot || !args->last_token) return fail(SPEC_ERR_INVALID_ARG, "seq_slot or last_token is NULL");
+    }
+    hipStream_t s = (hipStream_t)stream;
+    int rc;
+    {
+        ProfScope ps(&h->prof, SPEC_PROF_PREPARE, s);
+        rc = launch_prepare_tree(h->tables, ks, B, Kmax, c.vocab, c.max_batch, c.max_kv_len, run_model, args->seq_slot,
+                                 run_model ? args->last_token : nullptr, args->parent, args->draft_tokens, h->kv_len,
+                                 h->flag, s);
+    }
+    if (rc) return rc;
+    const float* logits = args->target_logits_in;
+    if (run_model) {
+        float* dst = out->logits_out ? out->logits_out : h->logits;
+        rc = forward_run(h, ks, B, M, dst, s);
+        if (rc) return rc;
+        logits = dst;
+    } else if (out->logits_out) {
+        SPECV_HIP(hipMemcpyAsync(out->logits_out, logits, (size_t)M * c.vocab * sizeof(float),
+                                 hipMemcpyDeviceToDevice, s));
+    }
+    rc = launch_tree_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, 2 * M, logits, args->draft_logits,
+                             args->parent, args->draft_tokens, args->uniforms, args->temperature,
+                             args->auto_rollback, run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens,
+                             out->path, &h->prof, s);
+    if (rc) return rc;
+    if (run_model && args->auto_rollback) {
+        ProfScope ps(&h->prof, SPEC_PROF_GLUE, s);
+        rc = launch_kv_compact(h->geom, h->kv_cache, h->tables, B, Kmax, out->n_accepted, out->path, s);
+    }
+    return rc;
 }
 
 extern "C" int spec_kv_rollback(spec_handle* h, const int32_t* seq_slot, const int32_t* new_len, int32_t n,

@@ -104,3 +104,39 @@ def check_sampler_against_oracle(tl_rows, dl, toks, us, lookahead, T, Kmax, na, 
                     toks[b, :K].tolist() if Kmax else [], us[b, :K + 1].tolist(), T, int(na[b]), ot[b].tolist(), Kmax)
         r0 += K + 1
     return chk
+
+
+class TreeCheck:
+    """Margin-aware comparison of one sequence's tree verification with the oracle's."""
+
+    def __init__(self):
+        self.exact_walk = self.margin_walk = self.exact_token = self.margin_token = 0
+
+    def compare(self, parent, toks, tl, dl, us, T, a_gpu, path_gpu, out_gpu, Kmax):
+        N = len(toks)
+        a, path, out, d = oracle.tree_sample(parent, toks, tl.contiguous(), dl.contiguous(), us, T)
+        tested = [i for i in range(min(N, 16)) if d.accept_ratio[i] >= 0.0]
+        margins = {i: abs(float(us[i]) - d.accept_ratio[i]) for i in tested}
+        gp = [int(v) for v in path_gpu[:max(a_gpu, 0)]]
+        if a_gpu != a or gp != path:
+            # the two walks may only part ways at a node whose test is inside the margin
+            k = 0
+            while k < min(len(gp), len(path)) and gp[k] == path[k]:
+                k += 1
+            assert any(m <= ACCEPT_MARGIN for m in margins.values()), \
+                f"walk {gp} != oracle {path}, margins {margins}"
+            self.margin_walk += 1
+            return
+        self.exact_walk += 1
+        assert list(out_gpu[:a]) == [toks[i] for i in path]
+        assert all(t == -1 for t in out_gpu[a + 1:Kmax + 1]) and all(int(v) == -1 for v in path_gpu[a:Kmax])
+        lo_gap = d.final_target - d.final_cdf_lo
+        hi_gap = d.final_cdf_hi - d.final_target
+        # the mass scale of r at level k >= 1 is S_k, so compare gaps relative to it
+        scale = d.final_S if d.final_S > 0 else 1.0
+        if lo_gap > CDF_MARGIN * scale and hi_gap > CDF_MARGIN * scale:
+            assert int(out_gpu[a]) == out[a], f"final token {out_gpu[a]} != oracle {out[a]} (gaps {lo_gap:.3e}, {hi_gap:.3e})"
+            self.exact_token += 1
+        else:
+            assert 0 <= int(out_gpu[a]) < tl.shape[1]
+            self.margin_token += 1

@@ -106,7 +106,7 @@ def _check_step(rig, slots, t0, lookahead, T, seed, perturb=0.3):
     kl = rig.kv_len.cpu().tolist()
     for b, s in enumerate(slots):
         if rig.shape.dtype == "fp32":
-            assert kl[s] == n_before[s] + int(na[b]) + 1
+            assert kl[s] == n_before[b] + int(na[b]) + 1
     return err, chk, na, ot, logits, want
 
 
