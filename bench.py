@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn", "stress", "copy", "decode"])
+    ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn", "stress", "copy", "decode", "tree"])
     ap.add_argument("--temperature", type=float, default=0.0, help="decode workload: sampling temperature (0 = default 4.0)")
     ap.add_argument("--lookahead", type=int, default=5, help="decode workload: proposals per round")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU-oracle leg")
@@ -256,6 +256,68 @@ def bench_decode(args, torch, sv, wl):
     dr.close()
 
 
+def bench_tree(args, torch, sv, wl):
+    """Token-tree verification at 7B-shape: 8 sequences x (10 nodes + root) = 88 window rows per step."""
+    w = wl.workload_tree()
+    shape, B, N, V = w.shape, w.batch, w.max_lookahead, w.shape.vocab
+    weights, _ = build_device_model(sv, wl, w, torch, False)
+    cfg = sv.make_cfg(shape, B, w.max_kv_len, N)
+    kv = torch.empty(sv.spec_kv_cache_bytes(cfg), dtype=torch.uint8, device="cuda")
+    kv_len = torch.zeros(B, dtype=torch.int32, device="cuda")
+    h = sv.spec_verify_init(cfg, weights, kv, kv_len)
+    rng = wl.Rng(w.seed, "cuda")
+    for b in range(B):
+        n = w.kv_lens[b]
+        plain = torch.empty((shape.n_layers, 2, shape.n_kv_heads, n, shape.head_dim), dtype=shape.torch_dtype, device="cuda")
+        for l in range(shape.n_layers):
+            plain[l] = rng.normal(wl.S_KV + b * 4096 + l, (2, shape.n_kv_heads, n, shape.head_dim), 1.0, shape.torch_dtype)
+        sv.spec_kv_import(h, b, 0, plain)
+        del plain
+    kv_len.copy_(torch.tensor(w.kv_lens, dtype=torch.int32))
+    t0, _ = wl.make_context(w, "cuda")
+    par, toks, dl = wl.make_tree_drafts(w, wl.TREE10_PARENT, "cuda")
+    us = wl.make_uniforms(w, "cuda")
+    slots = torch.arange(B, dtype=torch.int32, device="cuda")
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ot = torch.zeros((B, N + 1), dtype=torch.int32, device="cuda")
+    pt = torch.zeros((B, N), dtype=torch.int32, device="cuda")
+    slot_list, len_list, nodes = list(range(B)), list(w.kv_lens), [N] * B
+
+    def step(first=False):
+        if not first:
+            sv.spec_kv_rollback(h, slot_list, len_list)
+        sv.spec_verify_tree_step(h, nodes, par, toks, dl, us, w.temperature, na, ot, pt, seq_slot=slots, last_token=t0,
+                                 auto_rollback=True)
+
+    step(True)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sv.spec_verify_poll(h)
+    tic = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - tic) / args.steps * 1e3
+    emitted = int((na + 1).sum().item())
+    sv.spec_verify_profile_begin(h)
+    for _ in range(args.steps):
+        step()
+    prof, _ = sv.spec_verify_profile_end(h)
+    kernels = {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps} for k, v in prof.items() if v[1]}
+    rows = B * (N + 1)
+    print(json.dumps({
+        "metric": "verified tokens/sec (token-tree verification)", "value": emitted / (ms * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"7B-shape target, batch {B}, {w.kv_lens[0]} cached tokens, tree of {N} nodes per sequence "
+                               f"(parents {list(wl.TREE10_PARENT)}), T {w.temperature}; independent N(0,1.28^2) draft rows"},
+        "rows_per_step": rows, "scored_positions_per_s": rows / (ms * 1e-3), "emitted_tokens_per_step": emitted,
+        "kept_nodes_per_sequence": float(na.float().mean().item()), "kernels": kernels, "roofline": None,
+        "cpu_baseline": None}), flush=True)
+    h.close()
+
+
 def bench_copy(args, torch, sv):
     """A plain streaming copy of 1 GiB (spec_k_copy): the yardstick that achieved bandwidth and the HBM
     byte counters of the other kernels are scaled by."""
@@ -293,6 +355,8 @@ def main():
         return bench_copy(args, torch, sv)
     if args.workload == "decode":
         return bench_decode(args, torch, sv, wl)
+    if args.workload == "tree":
+        return bench_tree(args, torch, sv, wl)
     w = {"7b": wl.workload_7b, "1b": wl.workload_1b, "dyn": wl.workload_dyn}[args.workload]()
     if args.layers > 0:
         from dataclasses import replace

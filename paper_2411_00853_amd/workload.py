@@ -211,6 +211,31 @@ def workload_dyn(batch: int = 32) -> Workload:
     return Workload("dyn", SEVEN_B, batch, tuple(n), tuple(k), 10, 4096 + 11, 1.0, seed, "synthetic")
 
 
+# A drafted token tree of 10 nodes (3 candidates for the first token, 2 for the second below the
+# first two of them, then single continuations): depth 4, 5 leaves.
+TREE10_PARENT = (-1, -1, -1, 0, 0, 1, 3, 3, 4, 6)
+
+
+def workload_tree() -> Workload:
+    """7B-shape target, 8 sequences of 2048 cached tokens, each verifying the 10-node tree above
+    (11 window rows per sequence; `lookahead` holds the node count)."""
+    n_nodes = len(TREE10_PARENT)
+    return Workload("tree", SEVEN_B, 8, (2048,) * 8, (n_nodes,) * 8, n_nodes, 2048 + n_nodes + 1, 1.0,
+                    SEED_BASE + 4000, "synthetic")
+
+
+def make_tree_drafts(w: Workload, parent, device="cpu", logit_std: float = 1.28):
+    """Draft logits rows [B][N+1][V] (row 0: the root's, row i+1: node i's), independent of the target,
+    N(0, logit_std^2); node tokens drawn from softmax(row of their parent / T)."""
+    rng = Rng(w.seed, device)
+    B, N, V = w.batch, w.max_lookahead, w.shape.vocab
+    logits = rng.normal(S_DRAFT_NOISE, (B, N + 1, V), logit_std)
+    idx = torch.tensor([p + 1 for p in parent], device=device)
+    tokens = pick_tokens(rng, logits[:, idx, :], w.temperature, S_DRAFT_PICK)
+    par = torch.tensor(parent, dtype=torch.int32, device=device).repeat(B, 1).contiguous()
+    return par, tokens, logits
+
+
 def scaled(w: Workload, **shape_overrides) -> Workload:
     """Same workload on a reduced model shape (used for CPU-sized test cases)."""
     return replace(w, shape=replace(w.shape, **shape_overrides))

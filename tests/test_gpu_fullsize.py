@@ -178,6 +178,76 @@ def test_dynamic_lookahead_sampled_sequences(weights7b):
         rig.close()
 
 
+def test_7b_shape_token_tree(weights7b):
+    """The 10-node tree per sequence at 7B-shape (88 window rows): logits of two sequences' nodes
+    against the oracle decoding along every root-to-leaf path, decisions on identical logits, and
+    for all sequences the bookkeeping and the compacted cache length."""
+    from helpers import TreeCheck
+    w = wl.workload_tree()
+    sv = None
+    rig = BigRig(weights7b, w.batch, w.max_kv_len, w.max_lookahead)
+    try:
+        sv, shape = rig.sv, w.shape
+        B, N, V = w.batch, w.max_lookahead, shape.vocab
+        check = [0, 5]
+        caches = {b: rig.fill_slot(w, b, w.kv_lens[b], b, b in check) for b in range(B)}
+        t0, _ = wl.make_context(w, "cuda")
+        par, toks, dl = wl.make_tree_drafts(w, wl.TREE10_PARENT, "cuda")
+        us = wl.make_uniforms(w, "cuda")
+        M = B * (N + 1)
+        na = torch.zeros(B, dtype=torch.int32, device="cuda")
+        ot = torch.zeros((B, N + 1), dtype=torch.int32, device="cuda")
+        pt = torch.zeros((B, N), dtype=torch.int32, device="cuda")
+        lo = torch.zeros((M, V), dtype=torch.float32, device="cuda")
+        sv.spec_verify_tree_step(rig.h, [N] * B, par, toks, dl, us, w.temperature, na, ot, pt,
+                                 seq_slot=torch.arange(B, dtype=torch.int32, device="cuda"), last_token=t0,
+                                 logits_out=lo, auto_rollback=True)
+        torch.cuda.synchronize()
+        sv.spec_verify_poll(rig.h)
+        na_c, ot_c, pt_c, lo_c = na.cpu(), ot.cpu(), pt.cpu(), lo.cpu()
+        toks_c, dl_c, us_c, t0_c = toks.cpu(), dl.cpu(), us.cpu(), t0.cpu()
+        parent = list(wl.TREE10_PARENT)
+        kl = rig.kv_len.cpu().tolist()
+        for b in range(B):
+            a = int(na_c[b])
+            assert 0 <= a <= 4 and kl[b] == w.kv_lens[b] + a + 1          # the tree is 4 deep
+            path = pt_c[b, :a].tolist()
+            assert all(parent[path[k]] == (path[k - 1] if k else -1) for k in range(a))
+            assert ot_c[b, :a].tolist() == [int(toks_c[b, i]) for i in path] and 0 <= int(ot_c[b, a]) < V
+        assert torch.isfinite(lo_c).all()
+        paths = oracle.tree_paths(parent)
+        leaves = [i for i in range(N) if i not in parent]
+        worst = 0.0
+        chk = TreeCheck()
+        t = time.time()
+        for b in check:
+            want = torch.zeros((N + 1, V))
+            for leaf in leaves:
+                rows = rig.om.verify_rows([caches[b]], [w.kv_lens[b]],
+                                          [[int(t0_c[b])] + [int(toks_c[b, i]) for i in paths[leaf]]])
+                want[0] = rows[0]
+                for d, node in enumerate(paths[leaf]):
+                    want[node + 1] = rows[d + 1]
+            got = lo_c[b * (N + 1):(b + 1) * (N + 1)]
+            worst = max(worst, (got - want).abs().max().item())
+            # decisions: replay the walk on the oracle's logits through the sampler-only entry
+            na2 = torch.zeros(1, dtype=torch.int32, device="cuda")
+            ot2 = torch.zeros((1, N + 1), dtype=torch.int32, device="cuda")
+            pt2 = torch.zeros((1, N), dtype=torch.int32, device="cuda")
+            sv.spec_verify_tree_step(rig.h, [N], par[b:b + 1].contiguous(), toks[b:b + 1].contiguous(),
+                                     dl[b:b + 1].contiguous(), us[b:b + 1].contiguous(), w.temperature, na2, ot2, pt2,
+                                     target_logits_in=want.cuda())
+            torch.cuda.synchronize()
+            chk.compare(parent, toks_c[b].tolist(), want, dl_c[b], us_c[b].tolist(), w.temperature, int(na2[0]),
+                        pt2[0].cpu().tolist(), ot2[0].cpu().tolist(), N)
+        say(f"  [tree] oracle {time.time() - t:.1f}s; logits max-abs error {worst:.3e}; kept {na_c.tolist()}; "
+            f"exact walks {chk.exact_walk}, exact tokens {chk.exact_token}")
+        assert worst <= 3e-2
+        assert chk.exact_walk + chk.margin_walk == len(check)
+    finally:
+        rig.close()
+
+
 def test_sampler_stress_full():
     from helpers import check_sampler_against_oracle, run_sampler_gpu
     t = time.time()
