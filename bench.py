@@ -186,16 +186,18 @@ def synthetic_model(sv, wl, torch, shape, seed, n_slots, max_kv_len, max_lookahe
 
 def bench_decode(args, torch, sv, wl):
     """The whole loop: a 1B-shape draft proposes K tokens per round, the 7B-shape target verifies them;
-    compared with plain sampling from the target (one token per pass).  Random weights: the two models
-    are unrelated, so how often a proposal is kept is set by the temperature alone (flatter
-    distributions agree more); the kept fraction is reported with the speed-up it produced."""
-    B, K, n0 = 8, args.lookahead, 2048
+    compared with plain sampling from the target (one token per pass), at a fixed K and with the
+    lookahead controller choosing K every round.  Random weights: the two models are unrelated, so
+    how often a proposal is kept is set by the temperature alone (flatter distributions agree more);
+    the kept fraction is reported with the speed-up it produced."""
+    B, K, n0, Kt = 8, args.lookahead, 2048, max(args.lookahead, 8)
     T = args.temperature if args.temperature > 0 else 4.0
     R, W = args.steps, max(args.warmup, 2)
+    n_cal = 3
     rounds_total = R + W
-    max_kv = n0 + (rounds_total + 2) * (K + 1) + 8
+    max_kv = n0 + (rounds_total + 2 * n_cal + 2) * (Kt + 1) + 8
     t_setup = time.time()
-    tg, tg_len, keep_t = synthetic_model(sv, wl, torch, wl.SEVEN_B, wl.SEED_BASE + 2, B, max_kv, K, [n0] * B)
+    tg, tg_len, keep_t = synthetic_model(sv, wl, torch, wl.SEVEN_B, wl.SEED_BASE + 2, B, max_kv, Kt, [n0] * B)
     dr, dr_len, keep_d = synthetic_model(sv, wl, torch, wl.ONE_B, wl.SEED_BASE + 3, B, max_kv, 1, [n0 - 1] * B)
     log(f"[bench] decode setup {time.time() - t_setup:.1f}s")
     rng = wl.Rng(wl.SEED_BASE + 4, "cuda")
@@ -203,14 +205,20 @@ def bench_decode(args, torch, sv, wl):
     slots = torch.arange(B, dtype=torch.int32, device="cuda")
     prev = rng.randint(wl.S_TOKENS + 1, (B,), V).to(torch.int32)
     last = rng.randint(wl.S_TOKENS + 2, (B,), V).to(torch.int32)
-    du = rng.uniform(wl.S_UNIFORMS + 1, (rounds_total, B, K))
-    vu = rng.uniform(wl.S_UNIFORMS + 2, (rounds_total, B, K + 1))
+    n_u = rounds_total + 2 * n_cal
+    du = rng.uniform(wl.S_UNIFORMS + 1, (n_u, B, Kt))
+    vu = rng.uniform(wl.S_UNIFORMS + 2, (n_u, B, Kt + 1))
 
     def counters(dec):
         v = sv.spec_decode_get_view(dec)
         return sv.device_array(v.counters, (3,), torch.int64).cpu().tolist()
 
-    dec = sv.spec_decode_init(tg, dr, B, rounds_total * (K + 1))
+    def restart():
+        sv.spec_kv_rollback(tg, list(range(B)), [n0] * B)
+        sv.spec_kv_rollback(dr, list(range(B)), [n0 - 1] * B)
+
+    # ---- fixed K ----
+    dec = sv.spec_decode_init(tg, dr, B, n_u * (Kt + 1))
     sv.spec_decode_begin(dec, slots, prev, last)
     for r in range(W):
         sv.spec_decode_round(dec, K, du[r], vu[r], T)
@@ -225,10 +233,48 @@ def bench_decode(args, torch, sv, wl):
     sv.spec_verify_poll(tg)
     sv.spec_verify_poll(dr)
     seq_rounds, kept, emitted = (c1[i] - c0[i] for i in range(3))
+
+    # ---- K chosen by the controller every round (the host reads n_accepted back each round) ----
+    restart()
+    sv.spec_decode_begin(dec, slots, prev, last)
+    view = sv.spec_decode_get_view(dec)
+
+    def timed_rounds(k, r0, n):
+        torch.cuda.synchronize()
+        tic = time.perf_counter()
+        for r in range(r0, r0 + n):
+            sv.spec_decode_round(dec, k, du[r], vu[r], T)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - tic) / n * 1e3
+
+    t1, t2 = timed_rounds(1, 0, n_cal), timed_rounds(Kt, n_cal, n_cal)      # cost model: round_ms(K) = a + b K
+    slope = max((t2 - t1) / (Kt - 1), 0.0)
+    ctl = sv.Lookahead(B, draft_ms=slope, verify_ms=max(t1 - slope, 1e-3), verify_ms_per_token=0.0, k_min=1, k_max=Kt)
+    k_now = ctl.next()
+    for r in range(2 * n_cal, 2 * n_cal + W):
+        sv.spec_decode_round(dec, k_now, du[r], vu[r], T)
+        ctl.update(sv.device_array(view.n_accepted, (B,), torch.int32).cpu().tolist(), k_now)
+        k_now = ctl.next()
+    c0 = counters(dec)
+    ks = []
+    tic = time.perf_counter()
+    for r in range(2 * n_cal + W, 2 * n_cal + W + R):
+        sv.spec_decode_round(dec, k_now, du[r], vu[r], T)
+        ks.append(k_now)
+        ctl.update(sv.device_array(view.n_accepted, (B,), torch.int32).cpu().tolist(), k_now)
+        k_now = ctl.next()
+    torch.cuda.synchronize()
+    t_dyn = time.perf_counter() - tic
+    c1 = counters(dec)
+    sv.spec_verify_poll(tg)
+    sv.spec_verify_poll(dr)
+    dyn_emitted = c1[2] - c0[2]
+    alpha_hat = sum(ctl.accept(b) for b in range(B)) / B
+    ctl.close()
     dec.close()
 
-    # plain sampling from the target from the same starting point
-    sv.spec_kv_rollback(tg, list(range(B)), [n0] * B)
+    # ---- plain sampling from the target from the same starting point ----
+    restart()
     base = sv.spec_decode_init(tg, None, B, rounds_total)
     sv.spec_decode_begin(base, slots, None, last)
     u0 = vu[:, :, :1].contiguous()
@@ -242,7 +288,7 @@ def bench_decode(args, torch, sv, wl):
     t_base = time.perf_counter() - tic
     sv.spec_verify_poll(tg)
     base.close()
-    spec_tps, base_tps = emitted / t_spec, B * R / t_base
+    spec_tps, base_tps, dyn_tps = emitted / t_spec, B * R / t_base, dyn_emitted / t_dyn
     print(json.dumps({
         "metric": "emitted tokens/sec, speculative decoding loop", "value": spec_tps, "unit": "tokens/s", "n_gpus": 1,
         "steps": R, "warmup": W, "ms_per_step": t_spec / R * 1e3, "higher_is_better": True, "scaling": "weak",
@@ -251,7 +297,12 @@ def bench_decode(args, torch, sv, wl):
                                f"{n0} cached tokens, K {K}, T {T}; a step is one round (K draft decodes + verification)"},
         "plain_sampling_tokens_per_s": base_tps, "plain_sampling_ms_per_token_step": t_base / R * 1e3,
         "speedup_over_plain_sampling": spec_tps / base_tps, "kept_fraction": kept / max(seq_rounds * K, 1),
-        "tokens_per_round_per_sequence": emitted / max(seq_rounds, 1), "roofline": None, "cpu_baseline": None}), flush=True)
+        "tokens_per_round_per_sequence": emitted / max(seq_rounds, 1),
+        "controller": {"tokens_per_s": dyn_tps, "speedup_over_plain_sampling": dyn_tps / base_tps,
+                       "speedup_over_fixed_K": dyn_tps / spec_tps, "mean_K": sum(ks) / len(ks),
+                       "K_histogram": {str(k): ks.count(k) for k in sorted(set(ks))},
+                       "estimated_acceptance": alpha_hat, "cost_model_ms": {"per_K": slope, "fixed": t1 - slope}},
+        "roofline": None, "cpu_baseline": None}), flush=True)
     tg.close()
     dr.close()
 

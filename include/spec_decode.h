@@ -85,6 +85,41 @@ typedef struct {
 /* Pointers into the decoder's device state (valid until destroy; contents follow the stream). */
 int spec_decode_get_view(spec_decoder* d, spec_decode_view* out);
 
+/* ---- choosing the lookahead -------------------------------------------------------------------
+ * The paper's theme is that the amount of speculative work should follow the data.  For the round
+ * above that is the choice of K: long windows pay when proposals are usually kept, short ones when
+ * they are not.  This controller keeps, per sequence, exponentially forgotten counts of proposals
+ * tested and kept, and picks for the next round the K that maximises the predicted tokens per
+ * millisecond of the whole batch:
+ *     alpha_b = (kept_b + prior_accept * prior_weight) / (tested_b + prior_weight)
+ *     tokens(K) = sum_b (1 - alpha_b^(K+1)) / (1 - alpha_b)        (K+1 when alpha_b = 1)
+ *     cost(K)   = K * draft_ms + verify_ms + K * verify_ms_per_token
+ *     K_next    = the smallest K in [k_min, k_max] with the largest tokens(K) / cost(K)
+ * After a round with lookahead K in which sequence b kept a_b proposals, a_b + 1 proposals were
+ * tested if a_b < K, else K:   tested_b <- forget * tested_b + min(a_b + 1, K),
+ * kept_b <- forget * kept_b + a_b.  Sequences with a_b < 0 (skipped) are left alone.
+ * All host-side, double precision, no device access: the caller copies n_accepted back itself. */
+typedef struct {
+    double draft_ms;             /* cost of one draft decode step for the batch */
+    double verify_ms;            /* cost of a verification with an empty window (K = 0) */
+    double verify_ms_per_token;  /* added cost per unit of K */
+    int32_t k_min, k_max;        /* 1 <= k_min <= k_max <= SPEC_MAX_LOOKAHEAD */
+    double forget;               /* in (0, 1]: weight of the past per round */
+    double prior_accept;         /* in [0, 1]: acceptance assumed before any evidence */
+    double prior_weight;         /* > 0: how many tested proposals the prior counts for */
+} spec_lookahead_cfg;
+
+typedef struct spec_lookahead spec_lookahead;
+
+int spec_lookahead_init(const spec_lookahead_cfg* cfg, int32_t batch, spec_lookahead** out);
+void spec_lookahead_destroy(spec_lookahead* c);
+/* n_accepted: HOST int32[batch] of the round just finished, which ran with lookahead K */
+int spec_lookahead_update(spec_lookahead* c, const int32_t* n_accepted, int32_t K);
+/* K for the next round (k_min..k_max), or a negative status */
+int32_t spec_lookahead_next(const spec_lookahead* c);
+/* current estimate alpha_b of one sequence (diagnostics); NaN if out of range */
+double spec_lookahead_accept(const spec_lookahead* c, int32_t b);
+
 #ifdef __cplusplus
 }
 #endif

@@ -109,3 +109,44 @@ def autoregressive_decode(model: Model, st: SequenceState, n_new: int, temperatu
         st.target_len = L
         new.append(y)
     return new
+
+
+# ---- choosing the lookahead ------------------------------------------------------------------------
+# The paper motivates sampling schemes that adapt to the data; it does not give one.  The rule below
+# is this project's reading (stated in full in include/spec_decode.h): per-sequence acceptance
+# estimates with exponential forgetting, and the K with the best predicted tokens per millisecond.
+
+class LookaheadRule:
+    def __init__(self, batch, draft_ms, verify_ms, verify_ms_per_token, k_min, k_max, forget=0.9,
+                 prior_accept=0.5, prior_weight=4.0):
+        self.c = (draft_ms, verify_ms, verify_ms_per_token)
+        self.k_min, self.k_max = k_min, k_max
+        self.forget, self.prior_accept, self.prior_weight = forget, prior_accept, prior_weight
+        self.tested = [0.0] * batch
+        self.kept = [0.0] * batch
+
+    def accept(self, b):
+        return (self.kept[b] + self.prior_accept * self.prior_weight) / (self.tested[b] + self.prior_weight)
+
+    def update(self, n_accepted, K):
+        for b, a in enumerate(n_accepted):
+            if a < 0:
+                continue
+            self.tested[b] = self.forget * self.tested[b] + float(min(a + 1, K))
+            self.kept[b] = self.forget * self.kept[b] + float(a)
+
+    def expected_tokens(self, K):
+        total = 0.0
+        for b in range(len(self.tested)):
+            al = self.accept(b)
+            total += (1.0 - al ** (K + 1)) / (1.0 - al) if al < 1.0 else float(K + 1)
+        return total
+
+    def next(self):
+        d, v, vt = self.c
+        best, best_k = -1.0, self.k_min
+        for K in range(self.k_min, self.k_max + 1):
+            rate = self.expected_tokens(K) / (K * d + v + K * vt)
+            if rate > best:
+                best, best_k = rate, K
+        return best_k

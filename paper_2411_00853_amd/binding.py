@@ -70,6 +70,12 @@ class spec_round_args(C.Structure):
                 ("temperature", C.c_float)]
 
 
+class spec_lookahead_cfg(C.Structure):
+    _fields_ = [("draft_ms", C.c_double), ("verify_ms", C.c_double), ("verify_ms_per_token", C.c_double),
+                ("k_min", C.c_int32), ("k_max", C.c_int32), ("forget", C.c_double), ("prior_accept", C.c_double),
+                ("prior_weight", C.c_double)]
+
+
 class spec_decode_view(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("tokens", "n_tokens", "n_accepted", "draft_tokens", "draft_logits",
                                           "target_logits", "prev_token", "last_token", "counters")]
@@ -122,6 +128,14 @@ def lib():
         L.spec_decode_begin.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.spec_decode_round.argtypes = [C.c_void_p, C.POINTER(spec_round_args), C.c_void_p]
         L.spec_decode_get_view.argtypes = [C.c_void_p, C.POINTER(spec_decode_view)]
+        L.spec_lookahead_init.argtypes = [C.POINTER(spec_lookahead_cfg), C.c_int32, C.POINTER(C.c_void_p)]
+        L.spec_lookahead_destroy.restype = None
+        L.spec_lookahead_destroy.argtypes = [C.c_void_p]
+        L.spec_lookahead_update.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
+        L.spec_lookahead_next.argtypes = [C.c_void_p]
+        L.spec_lookahead_next.restype = C.c_int32
+        L.spec_lookahead_accept.argtypes = [C.c_void_p, C.c_int32]
+        L.spec_lookahead_accept.restype = C.c_double
         _lib = L
     return _lib
 
@@ -329,6 +343,43 @@ def spec_decode_get_view(d: Decoder) -> spec_decode_view:
     v = spec_decode_view()
     _check(lib().spec_decode_get_view(d.ptr, C.byref(v)))
     return v
+
+
+class Lookahead:
+    """Owns a spec_lookahead* (host-side controller; no GPU needed)."""
+
+    def __init__(self, batch: int, draft_ms: float, verify_ms: float, verify_ms_per_token: float, k_min: int,
+                 k_max: int, forget: float = 0.9, prior_accept: float = 0.5, prior_weight: float = 4.0):
+        self.batch = batch
+        cfg = spec_lookahead_cfg(draft_ms, verify_ms, verify_ms_per_token, k_min, k_max, forget, prior_accept,
+                                 prior_weight)
+        out = C.c_void_p()
+        _check(lib().spec_lookahead_init(C.byref(cfg), batch, C.byref(out)))
+        self.ptr = out.value
+
+    def update(self, n_accepted: Sequence[int], K: int):
+        arr = (C.c_int32 * self.batch)(*[int(v) for v in n_accepted])
+        _check(lib().spec_lookahead_update(self.ptr, arr, int(K)))
+
+    def next(self) -> int:
+        k = int(lib().spec_lookahead_next(self.ptr))
+        if k < 0:
+            raise SpecError(k, last_error())
+        return k
+
+    def accept(self, b: int) -> float:
+        return float(lib().spec_lookahead_accept(self.ptr, int(b)))
+
+    def close(self):
+        if getattr(self, "ptr", None):
+            lib().spec_lookahead_destroy(self.ptr)
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def device_array(ptr: Optional[int], shape, dtype, device="cuda") -> torch.Tensor:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecverify.so")
 SOURCES = ["spec_verify.hip", "forward.hip", "sampler.hip", "gemm.hip", "attention.hip", "elementwise.hip",
-           "probe.hip", "decode.hip"]
+           "probe.hip", "decode.hip", "lookahead.hip"]
 # packed-fp32 instructions are disabled for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -132,7 +132,9 @@ def run_following(t_shape, d_shape, contexts, K, Kt, rounds, T, seed):
     rng = wl.Rng(seed, "cpu")
     B = len(contexts)
     kept = 0
+    Ks = K if isinstance(K, (list, tuple)) else [K] * rounds
     for r in range(rounds):
+        K = Ks[r]
         du = rng.uniform(wl.S_UNIFORMS + 10 + 2 * r, (B, Kt))
         vu = rng.uniform(wl.S_UNIFORMS + 11 + 2 * r, (B, Kt + 1))
         g = pair.round(K, du, vu, T)
@@ -166,6 +168,15 @@ def test_rounds_bf16_lookahead_below_maximum():
     pair, chk, tally, kept = run_following(t_shape, d_shape, CONTEXTS, K=3, Kt=5, rounds=4, T=0.8, seed=32)
     assert chk.exact_accept >= 10
     assert tally["draft_err"] < 5e-3 and tally["target_err"] < 5e-3
+
+
+def test_rounds_with_a_lookahead_that_changes_every_round():
+    """What the lookahead controller does to the loop: K differs from round to round."""
+    t_shape = wl.ModelShape(2, 256, 4, 4, 64, 512, 300, dtype="fp32")
+    d_shape = wl.ModelShape(1, 128, 2, 2, 64, 256, 300, dtype="fp32")
+    pair, chk, tally, kept = run_following(t_shape, d_shape, CONTEXTS, K=[3, 1, 5, 2, 1, 4], Kt=5, rounds=6, T=1.0,
+                                           seed=33)
+    assert chk.exact_accept >= 16
 
 
 def test_free_running_text_equals_the_oracles_fp32():

@@ -1,0 +1,95 @@
+"""The lookahead rule: the oracle's version (oracle/decode.py) pinned against simulation and special
+cases, and the library's host-side controller against the oracle's on random traces (no GPU)."""
+import math
+import random
+
+import pytest
+
+from oracle.decode import LookaheadRule
+from paper_2411_00853_amd import binding as sv
+
+
+def simulate_round(rng, alpha, K):
+    a = 0
+    while a < K and rng.random() < alpha:
+        a += 1
+    return a
+
+
+def test_expected_tokens_matches_simulation():
+    rng = random.Random(1)
+    for alpha in (0.2, 0.6, 0.9):
+        for K in (1, 4, 9):
+            rule = LookaheadRule(1, 1.0, 5.0, 0.1, 1, 10, prior_accept=alpha, prior_weight=1e9)
+            n = 40000
+            mean = sum(simulate_round(rng, alpha, K) + 1 for _ in range(n)) / n
+            assert abs(rule.expected_tokens(K) - mean) < 4 * math.sqrt(K * K / n) + 1e-9
+
+
+def test_estimate_converges_and_choice_is_the_simulated_optimum():
+    rng = random.Random(2)
+    cost = (1.2, 4.9, 0.15)
+    for alpha in (0.15, 0.5, 0.85):
+        rule = LookaheadRule(4, *cost, 1, 10, forget=0.98, prior_accept=0.5, prior_weight=2.0)
+        K = 5
+        for _ in range(600):
+            rule.update([simulate_round(rng, alpha, K) for _ in range(4)], K)
+            K = rule.next()
+        assert all(abs(rule.accept(b) - alpha) < 0.08 for b in range(4))
+        # throughput of every K by simulation; the rule's K must be within 2 % of the best
+        rates = {}
+        for k in range(1, 11):
+            n = 20000
+            tok = sum(simulate_round(rng, alpha, k) + 1 for _ in range(n)) / n
+            rates[k] = tok / (k * cost[0] + cost[1] + k * cost[2])
+        assert rates[K] >= 0.98 * max(rates.values()), (alpha, K, rates)
+
+
+def test_special_cases():
+    always = LookaheadRule(2, 1.0, 5.0, 0.1, 1, 8, prior_accept=1.0, prior_weight=1e9)
+    assert always.next() == 8 and always.expected_tokens(3) == 8.0            # alpha = 1: K+1 tokens each
+    never = LookaheadRule(2, 1.0, 5.0, 0.1, 2, 8, prior_accept=0.0, prior_weight=1e9)
+    assert never.next() == 2                                                    # proposals are pure cost
+    free = LookaheadRule(1, 0.0, 5.0, 0.0, 1, 8, prior_accept=0.3, prior_weight=1e9)
+    assert free.next() == 8                                                     # drafting costs nothing
+    skip = LookaheadRule(2, 1.0, 5.0, 0.1, 1, 8)
+    skip.update([-1, 3], 5)
+    assert skip.tested == [0.0, 4.0] and skip.kept == [0.0, 3.0]
+    skip.update([5, 0], 5)                                                      # all kept: K tested, not K+1
+    assert skip.tested == [5.0, 0.9 * 4.0 + 1.0] and skip.kept == [5.0, 0.9 * 3.0]
+
+
+def test_library_controller_equals_the_oracle_rule():
+    rng = random.Random(3)
+    for trial in range(20):
+        B = rng.randint(1, 16)
+        args = dict(draft_ms=rng.uniform(0.1, 3.0), verify_ms=rng.uniform(1.0, 9.0),
+                    verify_ms_per_token=rng.uniform(0.0, 0.5), k_min=rng.randint(1, 3), k_max=rng.randint(3, 15),
+                    forget=rng.uniform(0.5, 1.0), prior_accept=rng.uniform(0.0, 1.0), prior_weight=rng.uniform(0.5, 8.0))
+        lib_c = sv.Lookahead(B, **args)
+        ref = LookaheadRule(B, **args)
+        alphas = [rng.random() for _ in range(B)]
+        K = lib_c.next()
+        assert K == ref.next()
+        for _ in range(60):
+            na = [(-1 if rng.random() < 0.05 else simulate_round(rng, alphas[b], K)) for b in range(B)]
+            lib_c.update(na, K)
+            ref.update(na, K)
+            K = lib_c.next()
+            assert K == ref.next()
+            for b in range(B):
+                assert lib_c.accept(b) == ref.accept(b)
+        lib_c.close()
+
+
+def test_library_controller_rejects_bad_arguments():
+    with pytest.raises(sv.SpecError):
+        sv.Lookahead(4, 1.0, 5.0, 0.1, 0, 5)
+    with pytest.raises(sv.SpecError):
+        sv.Lookahead(4, 1.0, 5.0, 0.1, 2, 16)
+    with pytest.raises(sv.SpecError):
+        sv.Lookahead(4, 1.0, 5.0, 0.1, 1, 5, forget=0.0)
+    c = sv.Lookahead(2, 1.0, 5.0, 0.1, 1, 5)
+    with pytest.raises(sv.SpecError):
+        c.update([6, 0], 5)
+    c.close()
