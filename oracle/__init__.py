@@ -188,6 +188,21 @@ def sample(target_logits: torch.Tensor, draft_logits: torch.Tensor, draft_tokens
     return int(na.value), list(out), diag
 
 
+def greedy(target_logits: torch.Tensor, draft_tokens: Sequence[int]):
+    """Temperature-0 verification of one sequence: (n_accepted, out_tokens [K+1], smallest deciding gap)."""
+    K = len(draft_tokens)
+    V = target_logits.shape[-1]
+    assert target_logits.shape == (K + 1, V) and target_logits.dtype == torch.float32
+    toks = (C.c_int32 * max(K, 1))(*[int(t) for t in draft_tokens])
+    na = C.c_int32(0)
+    out = (C.c_int32 * (K + 1))()
+    gap = C.c_float(0.0)
+    rc = lib().oracle_greedy(C.c_int32(V), C.c_int32(K), _fptr(target_logits), toks, C.byref(na), out, C.byref(gap))
+    if rc:
+        raise ValueError("oracle_greedy rejected its arguments")
+    return int(na.value), list(out), float(gap.value)
+
+
 def tree_sample(parent: Sequence[int], tokens: Sequence[int], target_logits: torch.Tensor,
                 draft_logits: torch.Tensor, uniforms: Sequence[float], temperature: float):
     """One sequence's token tree.  target_logits, draft_logits [N+1,V] fp32 (row 0: the root, row i+1:

@@ -413,6 +413,34 @@ int32_t oracle_inverse_cdf(int32_t V, const double* r, double target, double* lo
     return last_pos;
 }
 
+int oracle_greedy(int32_t V, int32_t K, const float* target_logits, const int32_t* draft_tokens,
+                  int32_t* n_accepted, int32_t* out_tokens, float* min_gap)
+{
+    if (V <= 0 || K < 0) return -1;
+    int a = 0;
+    float gap_min = INFINITY;
+    for (int i = 0; i <= K; ++i) {
+        const float* row = target_logits + (size_t)i * V;
+        int best = 0;
+        for (int v = 1; v < V; ++v)
+            if (row[v] > row[best]) best = v;
+        float second = -INFINITY;
+        for (int v = 0; v < V; ++v)
+            if (v != best && row[v] > second) second = row[v];
+        if (V > 1 && row[best] - second < gap_min) gap_min = row[best] - second;
+        if (i < K && draft_tokens[i] == best) {
+            out_tokens[a++] = best;
+            continue;
+        }
+        out_tokens[a] = best;
+        break;
+    }
+    for (int i = a + 1; i <= K; ++i) out_tokens[i] = -1;
+    *n_accepted = a;
+    if (min_gap) *min_gap = gap_min;
+    return 0;
+}
+
 int oracle_tree_sample(int32_t V, int32_t N, const int32_t* parent, const int32_t* tokens,
                        const float* target_logits, const float* draft_logits, const float* uniforms, float T,
                        int32_t* n_accepted, int32_t* path, int32_t* out_tokens, oracle_tree_diag* diag)

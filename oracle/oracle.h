@@ -106,6 +106,13 @@ int oracle_sample(int32_t vocab, int32_t K, const float* target_logits, const fl
                   const int32_t* draft_tokens, const float* uniforms, float temperature,
                   int32_t* n_accepted, int32_t* out_tokens, oracle_sample_diag* diag);
 
+/* Greedy verification (temperature 0: both models put all mass on their most likely token, and the
+ * rejection rule collapses): draft i is kept iff it equals argmax of target row i; the final token
+ * is argmax of row a (first mismatch) or of row K.  argmax takes the lowest id among equal maxima.
+ * min_gap (may be NULL) receives the smallest top-1/top-2 logit gap over the rows that decided. */
+int oracle_greedy(int32_t vocab, int32_t K, const float* target_logits, const int32_t* draft_tokens,
+                  int32_t* n_accepted, int32_t* out_tokens, float* min_gap);
+
 /* Diagnostics of one sequence's tree verification. */
 typedef struct {
     double accept_ratio[16];  /* per node i < 16: min(1, r(x_i)/q(x_i)) if the node was tested, else -1 */

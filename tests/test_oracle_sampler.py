@@ -17,6 +17,7 @@ import scipy.special
 import torch
 
 import oracle
+from paper_2411_00853_amd import workload as wl
 
 
 def logits_of(probs):
@@ -276,3 +277,38 @@ def test_bad_arguments_are_rejected():
         oracle.sample(l, l[:1].clone(), [4], [0.1, 0.1], 1.0)     # token id out of range
     with pytest.raises(ValueError):
         oracle.sample(l, l[:1].clone(), [0], [0.1, 0.1], 0.0)     # temperature must be positive
+
+
+def test_greedy_rule_is_the_zero_temperature_limit_and_plain_argmax():
+    """oracle_greedy against (a) torch.argmax row by row and (b) oracle_sample at a temperature so low
+    that all mass sits on the argmax (whatever the draft distribution and the uniforms are)."""
+    rng = wl.Rng(77)
+    V, K = 200, 5
+    hits = set()
+    for case in range(60):
+        tl = rng.normal(500 + case, (K + 1, V), 2.0)
+        best = torch.argmax(tl, dim=1).tolist()
+        toks = list(best[:K])
+        cut = case % (K + 2)                      # first mismatching position (K+1: none)
+        if cut < K:
+            toks[cut] = (toks[cut] + 1 + case) % V
+            if toks[cut] == best[cut]:
+                toks[cut] = (toks[cut] + 1) % V
+        a, out, gap = oracle.greedy(tl, toks)
+        want_a = min(cut, K)
+        assert a == want_a and out[:a] == best[:a] and out[a] == best[a] and out[a + 1:] == [-1] * (K - a)
+        hits.add(a)
+        # the limit of the stochastic rule: a draft that proposes its own most likely token (q(x) -> 1),
+        # so that u q(x) < p(x) holds iff p(x) -> 1, i.e. iff x is the target's most likely token too
+        dl = rng.normal(900 + case, (K, V), 2.0)
+        for i in range(K):
+            dl[i, toks[i]] = dl[i].max() + 1.0
+        us = [max(u, 1e-3) for u in rng.uniform(1300 + case, (K + 1,)).tolist()]
+        assert gap > 1e-3
+        T = min(gap, 1.0) / 60.0                  # every runner-up has relative mass <= e^-60
+        a2, out2, _ = oracle.sample(tl, dl, toks, us, T)
+        assert (a2, out2) == (a, out)
+    assert hits == set(range(K + 1))
+    ties = torch.zeros((1, 7))
+    ties[0, 3] = ties[0, 5] = 2.0
+    assert oracle.greedy(ties, [])[1] == [3]      # lowest id among equal maxima
