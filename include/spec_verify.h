@@ -145,7 +145,11 @@ typedef struct {
     const float* draft_logits;     /* device fp32[B][Kmax][V]; q_i = softmax(draft_logits[b][i]/T) */
     const float* uniforms;         /* device fp32[B][Kmax+1] in [0,1): [b][i], i < K_b decides draft
                                       i (kept iff u*q(x) < p(x)); [b][K_b] drives the final draw */
-    float temperature;             /* > 0; applied to target and draft logits alike */
+    float temperature;             /* > 0: applied to target and draft logits alike.  0: the greedy rule --
+                                      draft i is kept iff it is the most likely token of target row i
+                                      (lowest id among equal maxima), the final token is the most likely
+                                      token of the first mismatching row or of row K_b; draft_logits and
+                                      uniforms are not read */
     const float* target_logits_in; /* optional device fp32[M][V], M = sum(K_b+1), rows ordered by
                                       (sequence, window offset): if non-NULL the decoder pass is
                                       skipped and only the sampling part runs */

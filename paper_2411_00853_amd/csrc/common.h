@@ -83,11 +83,18 @@ struct SamplerWorkspace {
     int32_t* accepted;    // [B] a_b
     double* row_inv_z;    // [B][2] 1/Z of the two rows the final draw reads (p, q)
     float* row_max;       // [B][2] their maxima
+    int32_t* part_idx;    // [stat rows][stat chunks] greedy rule: lowest id holding the chunk maximum
 };
 
 int launch_prepare(const StepTables& t, const LookaheadPack& ks, int B, int Kmax, int V, int max_batch,
                    int max_kv_len, bool has_cache, const int32_t* seq_slot, const int32_t* last_token,
                    const int32_t* draft_tokens, const int32_t* kv_len, int32_t* flag, hipStream_t s);
+
+// Temperature 0: keep a proposal iff it is the target row's most likely token (lowest id among equal
+// maxima); the final token is the most likely token of the first mismatching row, or of row K_b.
+int launch_greedy(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax, int V,
+                  int M, const float* target_logits, const int32_t* draft_tokens, int auto_rollback, int32_t* kv_len,
+                  int32_t* n_accepted, int32_t* out_tokens, Profiler* prof, hipStream_t s);
 
 // Where a plain draw (every K_b = 0: one token from each sequence's row) puts its results when the
 // sampler serves a proposing model instead of a verification.  tokens == NULL: verification mode.

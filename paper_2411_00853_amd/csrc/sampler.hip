@@ -425,6 +425,92 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
 }
 
 // ---------------------------------------------------------------------------------------------
+// Temperature 0.  Pass 1: per (target row, chunk) the maximum and the lowest id that holds it.
+// Pass 2 (one wavefront per sequence): combine the chunks of each window row in ascending order,
+// compare with the proposals, emit.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(TPB) argmax_kernel(int V, int n_chunks, const float* __restrict__ target,
+                                                     float* __restrict__ part_max, int32_t* __restrict__ part_idx)
+{
+    __shared__ float sv[TPB / 64];
+    __shared__ int si[TPB / 64];
+    const int row = blockIdx.x / n_chunks, chunk = blockIdx.x % n_chunks;
+    const float* p = target + (size_t)row * V;
+    const int base = chunk * STAT_CHUNK;
+    const int lim = min(STAT_CHUNK, V - base);
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < lim; i += TPB) {   // ascending ids per thread: '>' keeps the first maximum
+        const float x = p[base + i];
+        if (x > best || bi == 0x7fffffff) {
+            best = x;
+            bi = base + i;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ob = __shfl_xor(best, o);
+        const int oi = __shfl_xor(bi, o);
+        if (ob > best || (ob == best && oi < bi)) {
+            best = ob;
+            bi = oi;
+        }
+    }
+    if ((threadIdx.x & 63) == 0) {
+        sv[threadIdx.x >> 6] = best;
+        si[threadIdx.x >> 6] = bi;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < TPB / 64; ++w)
+            if (sv[w] > best || (sv[w] == best && si[w] < bi)) {
+                best = sv[w];
+                bi = si[w];
+            }
+        part_max[(size_t)row * n_chunks + chunk] = best;
+        part_idx[(size_t)row * n_chunks + chunk] = bi;
+    }
+}
+
+__global__ void __launch_bounds__(64) greedy_emit_kernel(StepTables t, LookaheadPack ks, int Kmax, int n_chunks,
+                                                         const float* __restrict__ part_max,
+                                                         const int32_t* __restrict__ part_idx,
+                                                         const int32_t* __restrict__ draft_tokens, int auto_rollback,
+                                                         int32_t* kv_len, int32_t* __restrict__ n_accepted,
+                                                         int32_t* __restrict__ out_tokens)
+{
+    const int b = blockIdx.x;
+    if (threadIdx.x != 0) return;
+    int32_t* o = out_tokens + b * (Kmax + 1);
+    if (!t.seq_ok[b]) {
+        n_accepted[b] = -1;
+        for (int i = 0; i <= Kmax; ++i) o[i] = -1;
+        return;
+    }
+    const int K = ks.k[b];
+    int a = 0;
+    for (int j = 0; j <= K; ++j) {
+        const size_t r = (size_t)(t.seq_row0[b] + j) * n_chunks;
+        float best = part_max[r];
+        int bi = part_idx[r];
+        for (int c = 1; c < n_chunks; ++c)
+            if (part_max[r + c] > best) {   // chunks ascend in id: a later equal maximum does not win
+                best = part_max[r + c];
+                bi = part_idx[r + c];
+            }
+        if (j < K && draft_tokens[b * Kmax + j] == bi) {
+            o[a++] = bi;
+            continue;
+        }
+        o[a] = bi;
+        break;
+    }
+    for (int i = a + 1; i <= Kmax; ++i) o[i] = -1;
+    n_accepted[b] = a;
+    if (kv_len) kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : K) + 1;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Token trees.  Window slot 0 is the sequence's last token (the root), slot i+1 is node i; the
 // nodes come in topological order with parent[i] = -1 (child of the root) or an index < i.
 // ---------------------------------------------------------------------------------------------
@@ -752,6 +838,24 @@ int launch_prepare(const StepTables& t, const LookaheadPack& ks, int B, int Kmax
     hipLaunchKernelGGL(prepare_kernel, dim3(1), dim3(TPB), 0, s, t, ks, B, Kmax, V, max_batch, max_kv_len,
                        has_cache ? 1 : 0, seq_slot, last_token, draft_tokens, kv_len, flag);
     SPECV_LAUNCH_CHECK("prepare_kernel");
+    return SPEC_OK;
+}
+
+int launch_greedy(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax, int V,
+                  int M, const float* target_logits, const int32_t* draft_tokens, int auto_rollback, int32_t* kv_len,
+                  int32_t* n_accepted, int32_t* out_tokens, Profiler* prof, hipStream_t s)
+{
+    const int n_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
+    {
+        ProfScope ps(prof, SPEC_PROF_SAMPLER_STATS, s);
+        hipLaunchKernelGGL(argmax_kernel, dim3((unsigned)M * n_chunks), dim3(TPB), 0, s, V, n_chunks, target_logits,
+                           w.part_max, w.part_idx);
+        SPECV_LAUNCH_CHECK("argmax_kernel");
+    }
+    ProfScope ps(prof, SPEC_PROF_SAMPLER_DRAW, s);
+    hipLaunchKernelGGL(greedy_emit_kernel, dim3(B), dim3(64), 0, s, t, ks, Kmax, n_chunks, w.part_max, w.part_idx,
+                       draft_tokens, auto_rollback, kv_len, n_accepted, out_tokens);
+    SPECV_LAUNCH_CHECK("greedy_emit_kernel");
     return SPEC_OK;
 }
 

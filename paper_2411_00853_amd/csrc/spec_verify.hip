@@ -186,6 +186,7 @@ extern "C" int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* w
     A(&h->sampler.accepted, B);
     A(&h->sampler.row_inv_z, 2 * (size_t)B);
     A(&h->sampler.row_max, 2 * (size_t)B);
+    A(&h->sampler.part_idx, (size_t)max_stat * n_stat_chunks);
     if (rc == SPEC_OK && hipMemset(h->flag, 0, 16) != hipSuccess) rc = fail(SPEC_ERR_DEVICE, "hipMemset failed");
     if (rc == SPEC_OK && has_model) {
         h->layers.assign(weights->layers, weights->layers + cfg->n_layers);
@@ -273,8 +274,9 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     const int B = args->batch, Kmax = c.max_lookahead;
     if (B < 1 || B > c.max_batch) return fail(SPEC_ERR_INVALID_ARG, "batch %d outside 1..%d", B, c.max_batch);
     if (!args->lookahead) return fail(SPEC_ERR_INVALID_ARG, "lookahead is NULL");
-    if (!(args->temperature > 0.f)) return fail(SPEC_ERR_INVALID_ARG, "temperature must be > 0");
-    if (!args->uniforms) return fail(SPEC_ERR_INVALID_ARG, "uniforms is NULL");
+    if (!(args->temperature >= 0.f)) return fail(SPEC_ERR_INVALID_ARG, "temperature must be >= 0");
+    const bool greedy = args->temperature == 0.f;
+    if (!greedy && !args->uniforms) return fail(SPEC_ERR_INVALID_ARG, "uniforms is NULL");
     if (!out->n_accepted || !out->out_tokens) return fail(SPEC_ERR_INVALID_ARG, "n_accepted or out_tokens is NULL");
     LookaheadPack ks;
     memset(&ks, 0, sizeof(ks));
@@ -287,7 +289,7 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
         n_stat += 2 * k + 1;
         any_draft |= k;
     }
-    if (any_draft && (!args->draft_tokens || !args->draft_logits))
+    if (any_draft && (!args->draft_tokens || (!greedy && !args->draft_logits)))
         return fail(SPEC_ERR_INVALID_ARG, "draft_tokens or draft_logits is NULL");
     const bool run_model = args->target_logits_in == nullptr;
     if (run_model) {
@@ -313,6 +315,10 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
         SPECV_HIP(hipMemcpyAsync(out->logits_out, logits, (size_t)M * c.vocab * sizeof(float),
                                  hipMemcpyDeviceToDevice, s));
     }
+    if (greedy)
+        return launch_greedy(h->tables, h->sampler, ks, B, Kmax, c.vocab, M, logits, args->draft_tokens,
+                             args->auto_rollback, run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens,
+                             &h->prof, s);
     return launch_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, n_stat, logits, args->draft_logits,
                           args->draft_tokens, args->uniforms, Kmax + 1, args->temperature, args->auto_rollback,
                           run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, nullptr, &h->prof, s);

@@ -7,6 +7,7 @@ a band is asserted to be small, so the comparison is not vacuous."""
 import pytest
 import torch
 
+import oracle
 from paper_2411_00853_amd import workload as wl
 
 pytestmark = pytest.mark.gpu
@@ -121,7 +122,7 @@ def test_stress_recipe_reduced_and_rejected_arguments():
     with pytest.raises(sv.SpecError):
         sv.spec_verify_step(h, [4, 0], u, 1.0, na, ot, target_logits_in=l)          # K above max_lookahead
     with pytest.raises(sv.SpecError):
-        sv.spec_verify_step(h, [0, 0], u, 0.0, na, ot, target_logits_in=l)          # temperature
+        sv.spec_verify_step(h, [0, 0], u, -1.0, na, ot, target_logits_in=l)         # temperature
     with pytest.raises(sv.SpecError):
         sv.spec_verify_step(h, [0, 0], u, 1.0, na, ot)                              # no model, no logits
     with pytest.raises(sv.SpecError):
@@ -134,3 +135,40 @@ def test_stress_recipe_reduced_and_rejected_arguments():
         sv.spec_verify_poll(h)
     assert e.value.status == -6 and na.tolist()[0] == -1 and na.tolist()[1] >= 0
     sv.spec_verify_poll(h)   # flag cleared
+
+
+@pytest.mark.parametrize("V", [1000, 32003, 128256])
+def test_greedy_rule_at_temperature_zero(V):
+    """temperature 0: kept prefix = proposals equal to the row's argmax; exact against the oracle
+    (both sides compare the same fp32 logits), ties resolved to the lowest id."""
+    from paper_2411_00853_amd import binding as sv
+    B, Kmax = 9, 6
+    rng = wl.Rng(21, "cpu")
+    look = [Kmax, 0, 3, 6, 1, 5, 2, 6, 4]
+    M = sum(k + 1 for k in look)
+    tl = rng.normal(1, (M, V), 2.0)
+    best = torch.argmax(tl, dim=1)
+    toks = torch.zeros((B, Kmax), dtype=torch.int32)
+    r0 = 0
+    for b, k in enumerate(look):
+        toks[b, :k] = best[r0:r0 + k].to(torch.int32)
+        if k and b % 3 != 0:
+            toks[b, b % k] = (toks[b, b % k] + 7) % V       # a mismatch somewhere in the window
+        r0 += k + 1
+    # a tie across two chunks in one row: the lower id must win
+    tl[0, 5] = tl[0, V - 3] = tl[0].max() + 1.0
+    toks[0, 0] = 5
+    h = sv.spec_verify_init(sv.sampler_cfg(V, B, Kmax), None, None, None)
+    na = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    ot = torch.full((B, Kmax + 1), -7, dtype=torch.int32, device="cuda")
+    sv.spec_verify_step(h, look, None, 0.0, na, ot, draft_tokens=toks.cuda(), target_logits_in=tl.cuda().contiguous())
+    torch.cuda.synchronize()
+    sv.spec_verify_poll(h)
+    h.close()
+    r0, seen = 0, set()
+    for b, k in enumerate(look):
+        a, out, _ = oracle.greedy(tl[r0:r0 + k + 1].contiguous(), toks[b, :k].tolist())
+        assert int(na[b]) == a and ot[b, :k + 1].tolist() == out and (ot[b, k + 1:] == -1).all()
+        seen.add(a)
+        r0 += k + 1
+    assert len(seen) >= 4
