@@ -587,6 +587,8 @@ __global__ void __launch_bounds__(TPB) prepare_tree_kernel(StepTables t, Lookahe
     }
 }
 
+constexpr int TREE_TPB = 1024;   // the walk is one workgroup per sequence: make it a big one
+
 struct TreeOut {
     int32_t* n_accepted;   // [B]
     int32_t* out_tokens;   // [B][Kmax+1]
@@ -597,7 +599,7 @@ struct TreeOut {
 // distribution p; a child with token x is kept iff u * q(x) < r(x); every rejection replaces r by
 // max(0, r - q) renormalised.  r is never materialised: r_k(v) is recomputed from p(v), q(v) and the
 // masses S_1..S_k of the earlier levels, so a rejection costs one pass over the two logits rows.
-__global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadPack ks, int Kmax, int V,
+__global__ void __launch_bounds__(TREE_TPB) tree_walk_kernel(StepTables t, LookaheadPack ks, int Kmax, int V,
                                                         int n_stat_chunks, const float* __restrict__ target,
                                                         const float* __restrict__ draft,
                                                         const int32_t* __restrict__ parent,
@@ -611,7 +613,7 @@ __global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadP
     __shared__ float row_m[2 * MAXN + 2];
     __shared__ double row_z[2 * MAXN + 2];
     __shared__ double level_S[MAXN + 1];     // level_S[k]: mass of the unnormalised r_k, k >= 1
-    __shared__ double wsum[TPB / 64];
+    __shared__ double wsum[TREE_TPB / 64];
     __shared__ double r[RES_CHUNK];
     __shared__ int s_flag, s_tok, s_chunk;
     __shared__ double s_val, s_before, s_target;
@@ -619,8 +621,8 @@ __global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadP
     const int N = ks.k[b];
     if (!t.seq_ok[b]) {
         if (threadIdx.x == 0) out.n_accepted[b] = -1;
-        for (int i = threadIdx.x; i <= Kmax; i += TPB) out.out_tokens[b * (Kmax + 1) + i] = -1;
-        for (int i = threadIdx.x; i < Kmax; i += TPB) out.path[b * Kmax + i] = -1;
+        for (int i = threadIdx.x; i <= Kmax; i += TREE_TPB) out.out_tokens[b * (Kmax + 1) + i] = -1;
+        for (int i = threadIdx.x; i < Kmax; i += TREE_TPB) out.path[b * Kmax + i] = -1;
         return;
     }
     const double inv_T = (double)inv_T_f;
@@ -658,7 +660,10 @@ __global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadP
         __syncthreads();
         if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = v;
         __syncthreads();
-        return (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+        double tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < TREE_TPB / 64; ++w) tot += wsum[w];   // fixed order
+        return tot;
     };
 
     for (int c = 0; c < N; ++c) {
@@ -705,7 +710,7 @@ __global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadP
         // rejected: mass of max(0, r/S - q)
         double acc = 0.0;
         const double div = level > 0 ? level_S[level] : 1.0;
-        for (int v = threadIdx.x; v < V; v += TPB) {
+        for (int v = threadIdx.x; v < V; v += TREE_TPB) {
             const float lq = qrow[v];
             double pv = resid(prow[v], lq, level);
             if (level > 0) pv = pv / div;
@@ -722,7 +727,7 @@ __global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadP
 
     // final draw from r_level of the current node: chunk masses, then a scan inside one chunk
     const int n_res_chunks = (V + RES_CHUNK - 1) / RES_CHUNK;
-    constexpr int PER = RES_CHUNK / TPB;
+    constexpr int PER = RES_CHUNK / TREE_TPB;
     double total = 0.0;   // meaningful in thread 0
     __shared__ double mass[64];
     for (int c0 = 0; c0 < n_res_chunks; c0 += 64) {
@@ -730,7 +735,7 @@ __global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadP
             const int base = cc * RES_CHUNK;
             const int lim = min(RES_CHUNK, V - base);
             double acc = 0.0;
-            for (int i = threadIdx.x; i < lim; i += TPB) acc += resid(prow[base + i], qrow[base + i], level);
+            for (int i = threadIdx.x; i < lim; i += TREE_TPB) acc += resid(prow[base + i], qrow[base + i], level);
             const double m = block_sum(acc);
             if (threadIdx.x == 0) mass[cc - c0] = m;
         }
@@ -762,7 +767,7 @@ __global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadP
         const int base = s_chunk * RES_CHUNK;
         const int lim = min(RES_CHUNK, V - base);
         const double before = s_before, target_mass = s_target;
-        for (int i = threadIdx.x; i < RES_CHUNK; i += TPB)
+        for (int i = threadIdx.x; i < RES_CHUNK; i += TREE_TPB)
             r[i] = i < lim ? resid(prow[base + i], qrow[base + i], level) : 0.0;
         __syncthreads();
         double loc = 0.0;
@@ -805,7 +810,8 @@ __global__ void __launch_bounds__(TPB) tree_walk_kernel(StepTables t, LookaheadP
         __syncthreads();
         if (threadIdx.x == 0) {
             int y = s_tok;
-            if (y < 0) y = max(max(scratch[0], scratch[1]), max(scratch[2], scratch[3]));
+            if (y < 0)
+                for (int w = 0; w < TREE_TPB / 64; ++w) y = max(y, scratch[w]);
             if (y < 0) y = 0;
             out.n_accepted[b] = a;
             int32_t* o = out.out_tokens + b * (Kmax + 1);
@@ -895,7 +901,7 @@ int launch_tree_sampler(const StepTables& t, const SamplerWorkspace& w, const Lo
     }
     ProfScope ps(prof, SPEC_PROF_SAMPLER_DRAW, s);
     TreeOut o{n_accepted, out_tokens, path};
-    hipLaunchKernelGGL(tree_walk_kernel, dim3(B), dim3(TPB), 0, s, t, ks, Kmax, V, n_stat_chunks, target_logits,
+    hipLaunchKernelGGL(tree_walk_kernel, dim3(B), dim3(TREE_TPB), 0, s, t, ks, Kmax, V, n_stat_chunks, target_logits,
                        draft_logits, parent, tokens, uniforms, inv_T, w.part_max, w.part_sum, auto_rollback, kv_len, o);
     SPECV_LAUNCH_CHECK("tree_walk_kernel");
     return SPEC_OK;
