@@ -131,6 +131,21 @@ int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* weights, voi
 
 void spec_verify_destroy(spec_handle* h);
 
+/* Paged cache (bf16 models): instead of one contiguous run per slot, the 32-position blocks of all
+ * sequences live in pages of a shared pool; a page holds one block of every layer and kv head
+ * (spec_kv_page_bytes).  The library keeps the block table and the list of free pages on the
+ * device: a step takes pages for the positions it appends, and whatever lowers a cache length
+ * (auto_rollback, spec_kv_rollback, the decoding round) hands pages that hold no valid position
+ * back, so rejected proposals cost no memory and the pool may be smaller than
+ * max_batch * max_kv_len positions.  A sequence whose step finds the pool empty is skipped
+ * (SPEC_ERR_KV_OVERFLOW from spec_verify_poll).  Everything else behaves as with spec_verify_init;
+ * results are bit-identical.  kv_pool: device buffer of kv_pool_bytes (>= one page), caller-owned. */
+size_t spec_kv_page_bytes(const spec_model_cfg* cfg);
+int spec_verify_init_paged(const spec_model_cfg* cfg, const spec_weights* weights, void* kv_pool,
+                           size_t kv_pool_bytes, int32_t* kv_len, spec_handle** out);
+/* Free and total pages (host ints); synchronises the stream. */
+int spec_kv_pages(spec_handle* h, int32_t* free_pages, int32_t* total_pages, void* stream);
+
 /* Inputs of one step.  B = batch; Kmax = cfg.max_lookahead; V = cfg.vocab.
  * Sequence b scores the window [last_token[b], draft_tokens[b][0..K_b-1]] at positions
  * n_b .. n_b+K_b where n_b = kv_len[seq_slot[b]].  Target row j of a sequence gives the

@@ -102,6 +102,10 @@ def lib():
         L.spec_verify_destroy.argtypes = [C.c_void_p]
         L.spec_verify_init.argtypes = [C.POINTER(spec_model_cfg), C.POINTER(spec_weights), C.c_void_p, C.c_size_t,
                                        C.c_void_p, C.POINTER(C.c_void_p)]
+        L.spec_verify_init_paged.argtypes = L.spec_verify_init.argtypes
+        L.spec_kv_page_bytes.restype = C.c_size_t
+        L.spec_kv_page_bytes.argtypes = [C.POINTER(spec_model_cfg)]
+        L.spec_kv_pages.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
         L.spec_verify_step.argtypes = [C.c_void_p, C.POINTER(spec_step_args), C.POINTER(spec_step_out), C.c_void_p]
         L.spec_verify_tree_step.argtypes = [C.c_void_p, C.POINTER(spec_tree_args), C.POINTER(spec_tree_out), C.c_void_p]
         L.spec_kv_rollback.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.c_void_p]
@@ -215,8 +219,23 @@ class Handle:
             self.ptr = None
 
 
+def spec_kv_page_bytes(cfg: spec_model_cfg) -> int:
+    return int(lib().spec_kv_page_bytes(C.byref(cfg)))
+
+
+def spec_kv_pages(h: Handle, stream=None):
+    """(free pages, total pages) of a paged handle."""
+    f, t = C.c_int32(0), C.c_int32(0)
+    _check(lib().spec_kv_pages(h.ptr, C.byref(f), C.byref(t), _stream(stream)))
+    return int(f.value), int(t.value)
+
+
+def spec_verify_init_paged(cfg: spec_model_cfg, weights: dict, kv_pool: torch.Tensor, kv_len: torch.Tensor) -> Handle:
+    return spec_verify_init(cfg, weights, kv_pool, kv_len, paged=True)
+
+
 def spec_verify_init(cfg: spec_model_cfg, weights: Optional[dict], kv_cache: Optional[torch.Tensor],
-                     kv_len: Optional[torch.Tensor]) -> Handle:
+                     kv_len: Optional[torch.Tensor], paged: bool = False) -> Handle:
     """weights: {"tok_embed", "final_norm", "lm_head", "layers": [{"attn_norm", "w_qkv", "w_o", "ffn_norm",
     "w_gate_up", "w_down"}]} of device tensors already in the layout the header prescribes (bf16
     projection matrices packed with spec_pack_weight), or None for a sampler-only handle."""
@@ -234,7 +253,8 @@ def spec_verify_init(cfg: spec_model_cfg, weights: Optional[dict], kv_cache: Opt
         keep.append(arr)
         wp = C.byref(w)
     nbytes = kv_cache.numel() * kv_cache.element_size() if kv_cache is not None else 0
-    _check(lib().spec_verify_init(C.byref(cfg), wp, _ptr(kv_cache), nbytes, _ptr(kv_len, torch.int32), C.byref(out)))
+    init = lib().spec_verify_init_paged if paged else lib().spec_verify_init
+    _check(init(C.byref(cfg), wp, _ptr(kv_cache), nbytes, _ptr(kv_len, torch.int32), C.byref(out)))
     return Handle(out.value, cfg, keep)
 
 

@@ -35,7 +35,10 @@ __device__ __forceinline__ void split_frag(const float (&x)[8], Frag& hi, Frag& 
     }
 }
 
-template <int HD, int RT>
+// PAGED: the blocks of a slot are looked up in the page table.  A wavefront keeps the page numbers
+// of its chunk's (at most 64) blocks one per lane and broadcasts the one it needs, so the address
+// of a prefetch never waits for memory.
+template <int HD, int RT, bool PAGED>
 __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadPack ks, CacheGeom g, int n_q_heads,
                                                         int layer, const uint4* __restrict__ cache,
                                                         const float* __restrict__ q, int chunk_keys, int max_chunks,
@@ -93,14 +96,27 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
         for (int d = 0; d < DT; ++d) acc[rt][d] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const uint4* head = cache + cache_head_base(g, layer, t.seq_slot[b], hkv) / 8;
     const int blk0 = key0 >> 5, blk1 = (key1 + 31) >> 5;
+    const uint4* head;
+    int my_page = 0;
+    if constexpr (PAGED) {
+        head = cache + ((size_t)layer * g.n_kv_heads + hkv) * (64 * HD) / 8;   // offset inside a page
+        const int p = g.table[(size_t)t.seq_slot[b] * g.blocks_per_slot + min(blk0 + lane, blk1 - 1)];
+        my_page = p < 0 ? 0 : p;
+    } else {
+        head = cache + cache_head_base(g, layer, t.seq_slot[b], hkv) / 8;
+    }
 
     uint4 ka[2][STEPS], va[DT], kb[2][STEPS], vb[DT];
     // unconditional loads (a block index past the chunk re-reads the chunk's last block): with no
     // branch around them the compiler counts outstanding loads exactly and the prefetch stays in flight
     auto load_block = [&](int blk, uint4(&kk)[2][STEPS], uint4(&vv)[DT]) {
-        const uint4* p = head + (size_t)min(blk, blk1 - 1) * BLK_U4 + lane;
+        const int bb = min(blk, blk1 - 1);
+        const uint4* p;
+        if constexpr (PAGED)
+            p = head + (size_t)__builtin_amdgcn_readlane(my_page, bb - blk0) * (g.page_stride / 8) + lane;
+        else
+            p = head + (size_t)bb * BLK_U4 + lane;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -319,7 +335,7 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(StepTables t, CacheGeom g
 static int g_items_per_cu = 0;   // wavefront work items per compute unit to aim for; 0 = default
 void set_attn_items_per_cu(int n) { g_items_per_cu = n; }
 
-AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count)
+AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count, bool paged)
 {
     // One wavefront per (sequence, kv head, position chunk).  Measured on MI355X: a few long
     // streams beat many short ones (each wavefront keeps 32 KiB in flight and HBM likes long
@@ -330,6 +346,7 @@ AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count)
     const long per = (long)batch * n_kv_heads;
     long chunks = want_items / per;
     if (chunks < 1) chunks = 1;
+    if (paged && chunks < (max_kv_len + 2047) / 2048) chunks = (max_kv_len + 2047) / 2048;   // 64 blocks per wavefront
     if (chunks > 16) chunks = 16;   // the merge walks a row's chunks one after the other
     long keys = (max_kv_len + chunks - 1) / chunks;
     keys = (keys + 31) / 32 * 32;
@@ -339,11 +356,11 @@ AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count)
 }
 
 size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
-                           int cu_count)
+                           int cu_count, bool paged)
 {
     size_t worst = 0;
     for (int b = 1; b <= max_batch; ++b) {
-        const AttnPlan p = plan_attention(max_kv_len, b, n_kv_heads, cu_count);
+        const AttnPlan p = plan_attention(max_kv_len, b, n_kv_heads, cu_count, paged);
         const size_t e = (size_t)b * n_kv_heads * p.max_chunks * group * max_window * hd;
         if (e > worst) worst = e;
     }
@@ -356,8 +373,16 @@ static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, 
                          const AttnPlan& p, int r_cap, float sl2, float* part_o, float* part_ml)
 {
 #define SPECV_ATTN(RT)                                                                                           \
-    hipLaunchKernelGGL((attn_chunk_kernel<HD, RT>), grid, dim3(64), 0, s, t, ks, g, n_q_heads, layer,            \
-                       (const uint4*)cache, q, p.chunk_keys, p.max_chunks, r_cap, sl2, part_o, part_ml)
+    do {                                                                                                         \
+        if (g.table)                                                                                             \
+            hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, true>), grid, dim3(64), 0, s, t, ks, g, n_q_heads,     \
+                               layer, (const uint4*)cache, q, p.chunk_keys, p.max_chunks, r_cap, sl2, part_o,    \
+                               part_ml);                                                                         \
+        else                                                                                                     \
+            hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, false>), grid, dim3(64), 0, s, t, ks, g, n_q_heads,    \
+                               layer, (const uint4*)cache, q, p.chunk_keys, p.max_chunks, r_cap, sl2, part_o,    \
+                               part_ml);                                                                         \
+    } while (0)
     switch (rt) {
     case 1: SPECV_ATTN(1); break;
     case 2: SPECV_ATTN(2); break;
@@ -387,7 +412,9 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
         return SPEC_OK;
     }
     (void)p_unused;
-    const AttnPlan p = plan_attention(max_kv_len, B, g.n_kv_heads, cu_count);
+    const AttnPlan p = plan_attention(max_kv_len, B, g.n_kv_heads, cu_count, g.table != nullptr);
+    if (g.table && p.chunk_keys > 2048)
+        return fail(SPEC_ERR_SHAPE, "paged attention handles chunks of up to 2048 positions (max_kv_len up to 32768)");
     const int group = n_q_heads / g.n_kv_heads;
     const int r_cap = group * max_window;
     int kmax = 0;

@@ -54,6 +54,16 @@ struct ProfScope {
     }
 };
 
+// The page pool of a paged cache: a stack of free page numbers.  Pages are taken only by the row
+// bookkeeping kernels (before a window is appended) and by imports, and returned only where a cache
+// length shrinks -- never both in one kernel, so plain atomic counters suffice.
+struct PagePool {
+    int32_t* table;        // NULL: contiguous cache, everything below is a no-op
+    int32_t* free_stack;   // [n_pages]
+    int32_t* free_top;     // number of entries in free_stack
+    int blocks_per_slot;
+};
+
 // ---- per-step row bookkeeping built on the device by the prepare kernel ------------------------
 struct LookaheadPack {
     uint8_t k[SPEC_MAX_BATCH];
@@ -70,6 +80,7 @@ struct StepTables {
     int32_t* row_tok;    // [M] token id fed at this row
     int32_t* row_rope;   // [M] position the rotary embedding uses: n_b + depth of the row in its window
     uint32_t* row_mask;  // [M] bit i set: the row attends to window slot i (position n_b + i)
+    PagePool pool;       // the cache's page pool (table == NULL: contiguous cache)
 };
 
 // ---- sampler (sampler.hip) ---------------------------------------------------------------------
@@ -130,7 +141,10 @@ struct RollbackPack {
     int32_t slot[SPEC_MAX_BATCH];
     int32_t len[SPEC_MAX_BATCH];
 };
-int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len, int32_t* flag, hipStream_t s);
+int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len, int32_t* flag, const PagePool& pool,
+                    hipStream_t s);
+// paged caches: make sure positions [pos0, pos1) of a slot have pages (flags SPEC_ERR_KV_OVERFLOW if not)
+int launch_pool_cover(const PagePool& pool, int slot, int pos0, int pos1, int32_t* flag, hipStream_t s);
 
 // ---- decoder pass (elementwise.hip, gemm.hip, attention.hip) -----------------------------------
 struct RopeTable {
@@ -146,7 +160,13 @@ struct CacheGeom {
     size_t layer_stride;  // elements
     size_t slot_stride;
     size_t head_stride;   // bf16: keys and values of one head (2*t_pad*hd); fp32: one plane (t_pad*hd)
+    // paged mode (bf16 only): the 32-position blocks of a slot live in pages of a shared pool,
+    // [page][layer][kv head][block]; table[slot * blocks_per_slot + blk] names the page (-1: none)
+    const int32_t* table; // NULL: contiguous mode
+    int blocks_per_slot;
+    size_t page_stride;   // elements of one page: n_layers * n_kv_heads * 64 * head_dim
 };
+
 CacheGeom make_cache_geom(const spec_model_cfg& c);
 
 // Row-wise sums of squares travel as SSQ_CHUNK-column partial sums ([M][n_ssq]).  RMSNorm is split
@@ -213,10 +233,10 @@ struct AttnPlan {
     int chunk_keys;   // keys per wavefront work item (multiple of 32)
     int max_chunks;   // chunks per (sequence, kv head) at max_kv_len
 };
-AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count);
+AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count, bool paged = false);
 void set_attn_items_per_cu(int n);
 size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
-                           int cu_count);
+                           int cu_count, bool paged = false);
 int launch_attention(const AttnPlan& p, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M,
                      const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
                      float* part_o, float* part_ml, const XOut& xo, int max_window, Profiler* prof, hipStream_t s);

@@ -4,6 +4,7 @@
 // the cache layout are those of the verify step.
 #include <cstring>
 
+#include "cache_layout.h"
 #include "handle.h"
 #include "../../include/spec_decode.h"
 
@@ -88,7 +89,7 @@ __global__ void __launch_bounds__(TPB) advance_kernel(int B, int Kt, int Kd, int
                                                       const int32_t* __restrict__ target_seq_slot,
                                                       int32_t* prev_tok, int32_t* last_tok, int32_t* win,
                                                       int32_t* out_tokens, int32_t* n_out, int32_t* draft_len,
-                                                      int64_t* counters)
+                                                      PagePool draft_pool, int64_t* counters)
 {
     __shared__ int s_kept[TPB], s_emit[TPB], s_run[TPB];
     const int b = threadIdx.x;
@@ -106,7 +107,10 @@ __global__ void __launch_bounds__(TPB) advance_kernel(int B, int Kt, int Kd, int
             last_tok[b] = o[a];
             if (win) win[b * Kd] = o[a];
             // the text grew to L + a + 1 tokens; the draft has valid entries for all but its last two
-            if (draft_len) draft_len[target_seq_slot[b]] = target_seq_n[b] + a;
+            if (draft_len) {
+                draft_len[target_seq_slot[b]] = target_seq_n[b] + a;
+                pool_trim(draft_pool, target_seq_slot[b], target_seq_n[b] + a);
+            }
             kept = a;
             emitted = a + 1;
             ran = 1;
@@ -209,6 +213,7 @@ extern "C" int spec_decode_init(spec_handle* target, spec_handle* draft, const s
             t->row_tok = draft->tables.row_tok;
             t->row_rope = draft->tables.row_rope;
             t->row_mask = draft->tables.row_mask;
+            t->pool = draft->tables.pool;
         }
     }
     if (rc != SPEC_OK) {
@@ -312,7 +317,7 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
     d->last_rows = M;
     hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(TPB), 0, s, B, Kt, d->Kd, d->cap, d->n_accepted, d->round_out,
                        d->draft_tokens, tg->tables.seq_n, tg->tables.seq_slot, d->prev_tok, d->last_tok, d->win,
-                       d->out_tokens, d->n_out, dr ? dr->kv_len : nullptr, d->counters);
+                       d->out_tokens, d->n_out, dr ? dr->kv_len : nullptr, dr ? dr->tables.pool : PagePool{}, d->counters);
     SPECV_LAUNCH_CHECK("advance_kernel");
     return SPEC_OK;
 }

@@ -203,12 +203,13 @@ __global__ void __launch_bounds__(64) rope_append_kernel(const float* __restrict
                 q_out[(size_t)m * dq + head * hd + i] = ra;
                 q_out[(size_t)m * dq + head * hd + i + half] = rb;
             } else {
-                const size_t base = cache_head_base(g, layer, slot, head - n_q_heads);
                 if constexpr (BF16) {
                     __bf16* c16 = static_cast<__bf16*>(cache);
-                    c16[base + tiled_k_offset(hd, pos, i)] = static_cast<__bf16>(ra);
-                    c16[base + tiled_k_offset(hd, pos, i + half)] = static_cast<__bf16>(rb);
+                    const size_t blk = cache_block_base(g, layer, slot, head - n_q_heads, pos >> 5);
+                    c16[blk + tiled_k_within(hd, pos & 31, i)] = static_cast<__bf16>(ra);
+                    c16[blk + tiled_k_within(hd, pos & 31, i + half)] = static_cast<__bf16>(rb);
                 } else {
+                    const size_t base = cache_head_base(g, layer, slot, head - n_q_heads);
                     float* c32 = static_cast<float*>(cache);
                     c32[base + plain_offset(g, 0, pos, i)] = ra;
                     c32[base + plain_offset(g, 0, pos, i + half)] = rb;
@@ -216,11 +217,12 @@ __global__ void __launch_bounds__(64) rope_append_kernel(const float* __restrict
             }
         }
     } else {
-        const size_t base = cache_head_base(g, layer, slot, head - n_q_heads - g.n_kv_heads);
+        const int hv = head - n_q_heads - g.n_kv_heads;
+        const size_t base = BF16 ? cache_block_base(g, layer, slot, hv, pos >> 5) : cache_head_base(g, layer, slot, hv);
         for (int i = threadIdx.x; i < hd; i += 64) {
             const float v = sum_splits(row + i, n_split, split_stride) * rs;
             if constexpr (BF16)
-                static_cast<__bf16*>(cache)[base + tiled_v_offset(hd, pos, i)] = static_cast<__bf16>(v);
+                static_cast<__bf16*>(cache)[base + tiled_v_within(hd, pos & 31, i)] = static_cast<__bf16>(v);
             else
                 static_cast<float*>(cache)[base + plain_offset(g, 1, pos, i)] = v;
         }
@@ -252,12 +254,12 @@ __global__ void __launch_bounds__(TPB) kv_copy_kernel(CacheGeom g, void* cache, 
         const int head = (int)(r % g.n_kv_heads); r /= g.n_kv_heads;
         const int kv = (int)(r % 2);
         const int layer = (int)(r / 2);
-        const size_t base = cache_head_base(g, layer, slot, head);
         size_t off;
         if constexpr (BF16)
-            off = base + (kv ? tiled_v_offset(hd, pos0 + p, dim) : tiled_k_offset(hd, pos0 + p, dim));
+            off = cache_block_base(g, layer, slot, head, (pos0 + p) >> 5)
+                  + (kv ? tiled_v_within(hd, (pos0 + p) & 31, dim) : tiled_k_within(hd, (pos0 + p) & 31, dim));
         else
-            off = base + plain_offset(g, kv, pos0 + p, dim);
+            off = cache_head_base(g, layer, slot, head) + plain_offset(g, kv, pos0 + p, dim);
         if constexpr (BF16) {
             uint16_t* c = static_cast<uint16_t*>(cache);
             uint16_t* q = static_cast<uint16_t*>(plain);
@@ -382,7 +384,8 @@ __global__ void __launch_bounds__(64) kv_compact_kernel(CacheGeom g, void* cache
     const int a = n_accepted[b];
     const int n = t.seq_n[b], hd = g.head_dim;
     const int layer = blockIdx.y / g.n_kv_heads, head = blockIdx.y % g.n_kv_heads;
-    const size_t base = cache_head_base(g, layer, t.seq_slot[b], head);
+    const int slot = t.seq_slot[b];
+    const size_t base = cache_head_base(g, layer, slot, head);   // fp32 only
     for (int k = 1; k <= a; ++k) {
         const int node = path[b * Kmax + k - 1];
         if (node < 0 || node >= Kmax) return;   // cannot happen: the walk writes a valid indices first
@@ -391,8 +394,10 @@ __global__ void __launch_bounds__(64) kv_compact_kernel(CacheGeom g, void* cache
         for (int i = threadIdx.x; i < hd; i += 64) {
             if constexpr (BF16) {
                 uint16_t* c = static_cast<uint16_t*>(cache);
-                c[base + tiled_k_offset(hd, dst, i)] = c[base + tiled_k_offset(hd, src, i)];
-                c[base + tiled_v_offset(hd, dst, i)] = c[base + tiled_v_offset(hd, src, i)];
+                const size_t sb = cache_block_base(g, layer, slot, head, src >> 5);
+                const size_t db = cache_block_base(g, layer, slot, head, dst >> 5);
+                c[db + tiled_k_within(hd, dst & 31, i)] = c[sb + tiled_k_within(hd, src & 31, i)];
+                c[db + tiled_v_within(hd, dst & 31, i)] = c[sb + tiled_v_within(hd, src & 31, i)];
             } else {
                 float* c = static_cast<float*>(cache);
                 c[base + plain_offset(g, 0, dst, i)] = c[base + plain_offset(g, 0, src, i)];

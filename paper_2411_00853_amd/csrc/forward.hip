@@ -33,7 +33,7 @@ int forward_init(spec_handle* h, int max_rows)
     const spec_model_cfg& c = h->cfg;
     const Dims z = dims_of(c);
     h->max_rows = max_rows;
-    h->geom = make_cache_geom(c);
+    if (!h->geom.table) h->geom = make_cache_geom(c);   // a paged handle set its geometry already
     if (c.dtype == SPEC_DTYPE_BF16 && max_rows > 352)
         return fail(SPEC_ERR_SHAPE, "max_batch*(max_lookahead+1) = %d rows exceeds the 352 the bf16 GEMM supports",
                     max_rows);
@@ -67,10 +67,10 @@ int forward_init(spec_handle* h, int max_rows)
                 const size_t e = gemm_partial_elems(plan_gemm(rows, Ns[i], Ks[i], h->cu_count, true), rows);
                 if (e > part) part = e;
             }
-        h->attn_plan = plan_attention(c.max_kv_len, c.max_batch, c.n_kv_heads, h->cu_count);
+        h->attn_plan = plan_attention(c.max_kv_len, c.max_batch, c.n_kv_heads, h->cu_count, h->geom.table != nullptr);
         const int group = c.n_q_heads / c.n_kv_heads;
         const size_t po = attn_partial_floats(c.max_kv_len, c.max_batch, c.n_kv_heads, group, c.max_lookahead + 1,
-                                              c.head_dim, h->cu_count);
+                                              c.head_dim, h->cu_count, h->geom.table != nullptr);
         A(&h->attn_part_o, po);
         A(&h->attn_part_ml, po / c.head_dim * 2);
     } else {

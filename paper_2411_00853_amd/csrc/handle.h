@@ -37,6 +37,7 @@ struct spec_handle {
     const float* final_norm = nullptr;
     const void* lm_head = nullptr;
     specv::CacheGeom geom{};
+    int n_pages = 0;           // paged cache: pages in the caller's pool (0: contiguous cache)
     specv::AttnPlan attn_plan{};
     bool split_act = true;     // feed activations to the matrix cores as bf16 head + remainder
     float* x = nullptr;        // [rows][d_model] residual stream

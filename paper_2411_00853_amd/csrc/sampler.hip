@@ -11,6 +11,7 @@
 // by the statistics pass (float4 per lane, 32 values per lane in flight); only the one or two
 // rows that the final draw needs are read again.  Sums are kept in fp64 and every reduction has a
 // fixed order (no floating-point atomics), so results are reproducible bit for bit.
+#include "cache_layout.h"
 #include "common.h"
 
 namespace specv {
@@ -75,6 +76,7 @@ __global__ void __launch_bounds__(TPB) prepare_kernel(StepTables t, LookaheadPac
                 if (seq_slot[i] == slot) { ok = 0; err = SPEC_ERR_INVALID_ARG; }
             n = kv_len[slot];
             if (n < 0 || n + K + 1 > max_kv_len) { ok = 0; err = SPEC_ERR_KV_OVERFLOW; }
+            else if (ok && !pool_cover(t.pool, slot, n, n + K + 1)) { ok = 0; err = SPEC_ERR_KV_OVERFLOW; }
         }
     }
     int t0 = last_token ? last_token[b] : 0;
@@ -420,7 +422,10 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
         for (int i = 0; i < a; ++i) o[i] = draft_tokens[b * Kmax + i];
         o[a] = y;
         for (int i = a + 1; i <= Kmax; ++i) o[i] = -1;
-        if (kv_len) kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : K) + 1;
+        if (kv_len) {
+            kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : K) + 1;
+            pool_trim(t.pool, t.seq_slot[b], t.seq_n[b] + (auto_rollback ? a : K) + 1);
+        }
     }
 }
 
@@ -507,7 +512,10 @@ __global__ void __launch_bounds__(64) greedy_emit_kernel(StepTables t, Lookahead
     }
     for (int i = a + 1; i <= Kmax; ++i) o[i] = -1;
     n_accepted[b] = a;
-    if (kv_len) kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : K) + 1;
+    if (kv_len) {
+        kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : K) + 1;
+        pool_trim(t.pool, t.seq_slot[b], t.seq_n[b] + (auto_rollback ? a : K) + 1);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -553,6 +561,7 @@ __global__ void __launch_bounds__(TPB) prepare_tree_kernel(StepTables t, Lookahe
                 if (seq_slot[i] == slot) { ok = 0; err = SPEC_ERR_INVALID_ARG; }
             n = kv_len[slot];
             if (n < 0 || n + N + 1 > max_kv_len) { ok = 0; err = SPEC_ERR_KV_OVERFLOW; }
+            else if (ok && !pool_cover(t.pool, slot, n, n + N + 1)) { ok = 0; err = SPEC_ERR_KV_OVERFLOW; }
         }
     }
     const int t0 = last_token ? last_token[b] : 0;
@@ -818,14 +827,17 @@ __global__ void __launch_bounds__(TREE_TPB) tree_walk_kernel(StepTables t, Looka
             o[a] = y;
             for (int i = a + 1; i <= Kmax; ++i) o[i] = -1;
             for (int i = a; i < Kmax; ++i) out.path[b * Kmax + i] = -1;
-            if (kv_len) kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : N) + 1;
+            if (kv_len) {
+                kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : N) + 1;
+                pool_trim(t.pool, t.seq_slot[b], t.seq_n[b] + (auto_rollback ? a : N) + 1);
+            }
         }
     }
 }
 
 // kv_len[slot] = len where 0 <= len <= kv_len[slot]; anything else leaves the slot alone and flags.
 __global__ void __launch_bounds__(TPB) rollback_kernel(RollbackPack p, int n, int max_batch, int32_t* kv_len,
-                                                       int32_t* flag)
+                                                       int32_t* flag, PagePool pool)
 {
     const int i = threadIdx.x;
     if (i >= n) return;
@@ -833,6 +845,12 @@ __global__ void __launch_bounds__(TPB) rollback_kernel(RollbackPack p, int n, in
     if (slot < 0 || slot >= max_batch) { atomicCAS(flag, 0, (int)SPEC_ERR_INVALID_ARG); return; }
     if (len < 0 || len > kv_len[slot]) { atomicCAS(flag, 0, (int)SPEC_ERR_ROLLBACK); return; }
     kv_len[slot] = len;
+    pool_trim(pool, slot, len);
+}
+
+__global__ void pool_cover_kernel(PagePool pool, int slot, int pos0, int pos1, int32_t* flag)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0 && !pool_cover(pool, slot, pos0, pos1)) atomicCAS(flag, 0, (int)SPEC_ERR_KV_OVERFLOW);
 }
 
 }  // namespace
@@ -907,10 +925,19 @@ int launch_tree_sampler(const StepTables& t, const SamplerWorkspace& w, const Lo
     return SPEC_OK;
 }
 
-int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len, int32_t* flag, hipStream_t s)
+int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len, int32_t* flag, const PagePool& pool,
+                    hipStream_t s)
 {
-    hipLaunchKernelGGL(rollback_kernel, dim3(1), dim3(TPB), 0, s, p, n, max_batch, kv_len, flag);
+    hipLaunchKernelGGL(rollback_kernel, dim3(1), dim3(TPB), 0, s, p, n, max_batch, kv_len, flag, pool);
     SPECV_LAUNCH_CHECK("rollback_kernel");
+    return SPEC_OK;
+}
+
+int launch_pool_cover(const PagePool& pool, int slot, int pos0, int pos1, int32_t* flag, hipStream_t s)
+{
+    if (!pool.table) return SPEC_OK;
+    hipLaunchKernelGGL(pool_cover_kernel, dim3(1), dim3(64), 0, s, pool, slot, pos0, pos1, flag);
+    SPECV_LAUNCH_CHECK("pool_cover_kernel");
     return SPEC_OK;
 }
 

@@ -2,6 +2,8 @@
 // Every step of the path runs in the kernels of this library; this file only validates, sizes and
 // enqueues.
 #include "common.h"
+#include <vector>
+
 #include "handle.h"
 
 #include <cstdarg>
@@ -120,8 +122,30 @@ extern "C" size_t spec_kv_cache_bytes(const spec_model_cfg* c)
     return g.layer_stride * (size_t)c->n_layers * (c->dtype == SPEC_DTYPE_BF16 ? 2 : 4);
 }
 
+extern "C" size_t spec_kv_page_bytes(const spec_model_cfg* c)
+{
+    if (check_cfg(c, true) != SPEC_OK || c->dtype != SPEC_DTYPE_BF16) return 0;
+    return (size_t)c->n_layers * c->n_kv_heads * 64 * c->head_dim * 2;
+}
+
+static int init_common(const spec_model_cfg* cfg, const spec_weights* weights, void* kv_cache, size_t kv_cache_bytes,
+                       int32_t* kv_len, bool paged, spec_handle** out);
+
 extern "C" int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* weights, void* kv_cache,
                                 size_t kv_cache_bytes, int32_t* kv_len, spec_handle** out)
+{
+    return init_common(cfg, weights, kv_cache, kv_cache_bytes, kv_len, false, out);
+}
+
+extern "C" int spec_verify_init_paged(const spec_model_cfg* cfg, const spec_weights* weights, void* kv_pool,
+                                      size_t kv_pool_bytes, int32_t* kv_len, spec_handle** out)
+{
+    if (!weights) return fail(SPEC_ERR_INVALID_ARG, "a paged handle needs a model");
+    return init_common(cfg, weights, kv_pool, kv_pool_bytes, kv_len, true, out);
+}
+
+static int init_common(const spec_model_cfg* cfg, const spec_weights* weights, void* kv_cache, size_t kv_cache_bytes,
+                       int32_t* kv_len, bool paged, spec_handle** out)
 {
     if (!out) return fail(SPEC_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
@@ -137,9 +161,14 @@ extern "C" int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* w
             if (!w.attn_norm || !w.w_qkv || !w.w_o || !w.ffn_norm || !w.w_gate_up || !w.w_down)
                 return fail(SPEC_ERR_INVALID_ARG, "layer %d has a NULL weight", l);
         }
-        const size_t need = spec_kv_cache_bytes(cfg);
-        if (kv_cache_bytes < need)
-            return fail(SPEC_ERR_INVALID_ARG, "kv_cache_bytes %zu is below the required %zu", kv_cache_bytes, need);
+        if (paged) {
+            if (cfg->dtype != SPEC_DTYPE_BF16) return fail(SPEC_ERR_SHAPE, "a paged cache needs the bf16 storage type");
+            if (kv_cache_bytes < spec_kv_page_bytes(cfg)) return fail(SPEC_ERR_INVALID_ARG, "the pool holds no whole page");
+        } else {
+            const size_t need = spec_kv_cache_bytes(cfg);
+            if (kv_cache_bytes < need)
+                return fail(SPEC_ERR_INVALID_ARG, "kv_cache_bytes %zu is below the required %zu", kv_cache_bytes, need);
+        }
     } else if (kv_cache) {
         return fail(SPEC_ERR_INVALID_ARG, "kv_cache given without weights");
     }
@@ -188,6 +217,31 @@ extern "C" int spec_verify_init(const spec_model_cfg* cfg, const spec_weights* w
     A(&h->sampler.row_max, 2 * (size_t)B);
     A(&h->sampler.part_idx, (size_t)max_stat * n_stat_chunks);
     if (rc == SPEC_OK && hipMemset(h->flag, 0, 16) != hipSuccess) rc = fail(SPEC_ERR_DEVICE, "hipMemset failed");
+    if (rc == SPEC_OK && paged) {
+        // page table (all -1), stack of free pages (all of them), geometry of the pool
+        const int bps = (cfg->max_kv_len + 31) / 32;
+        const size_t page_elems = (size_t)cfg->n_layers * cfg->n_kv_heads * 64 * cfg->head_dim;
+        const size_t n_pages = kv_cache_bytes / (page_elems * 2);
+        h->n_pages = (int)(n_pages > 0x7fffffff ? 0x7fffffff : n_pages);
+        PagePool& pp = h->tables.pool;
+        pp.blocks_per_slot = bps;
+        A(&pp.table, (size_t)B * bps);
+        A(&pp.free_stack, (size_t)h->n_pages);
+        A(&pp.free_top, 4);
+        if (rc == SPEC_OK) {
+            std::vector<int32_t> init((size_t)B * bps, -1), stack((size_t)h->n_pages);
+            for (int i = 0; i < h->n_pages; ++i) stack[i] = h->n_pages - 1 - i;   // page 0 is handed out first
+            const int32_t top = h->n_pages;
+            if (hipMemcpy(pp.table, init.data(), init.size() * 4, hipMemcpyHostToDevice) != hipSuccess
+                || hipMemcpy(pp.free_stack, stack.data(), stack.size() * 4, hipMemcpyHostToDevice) != hipSuccess
+                || hipMemcpy(pp.free_top, &top, 4, hipMemcpyHostToDevice) != hipSuccess)
+                rc = fail(SPEC_ERR_DEVICE, "hipMemcpy failed");
+        }
+        h->geom = make_cache_geom(*cfg);
+        h->geom.table = pp.table;
+        h->geom.blocks_per_slot = bps;
+        h->geom.page_stride = page_elems;
+    }
     if (rc == SPEC_OK && has_model) {
         h->layers.assign(weights->layers, weights->layers + cfg->n_layers);
         h->tok_embed = weights->tok_embed;
@@ -403,7 +457,7 @@ extern "C" int spec_kv_rollback(spec_handle* h, const int32_t* seq_slot, const i
         p.slot[i] = seq_slot[i];
         p.len[i] = new_len[i];
     }
-    return launch_rollback(p, n, h->cfg.max_batch, h->kv_len, h->flag, (hipStream_t)stream);
+    return launch_rollback(p, n, h->cfg.max_batch, h->kv_len, h->flag, h->tables.pool, (hipStream_t)stream);
 }
 
 static int kv_copy_common(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, void* plain, bool to_cache,
@@ -415,6 +469,11 @@ static int kv_copy_common(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_
     if (pos0 < 0 || n_pos < 0 || pos0 + n_pos > h->cfg.max_kv_len)
         return fail(SPEC_ERR_INVALID_ARG, "positions [%d, %d) outside the slot", pos0, pos0 + n_pos);
     if (n_pos == 0) return SPEC_OK;
+    if (to_cache) {
+        // pages are always taken from a slot's first block on, so that a slot's table has no holes
+        const int rc = launch_pool_cover(h->tables.pool, slot, 0, pos0 + n_pos, h->flag, (hipStream_t)stream);
+        if (rc) return rc;
+    }
     return launch_kv_copy(h->geom, h->kv_cache, slot, pos0, n_pos, plain, to_cache, (hipStream_t)stream);
 }
 
@@ -426,6 +485,16 @@ extern "C" int spec_kv_import(spec_handle* h, int32_t slot, int32_t pos0, int32_
 extern "C" int spec_kv_export(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, void* dst, void* stream)
 {
     return kv_copy_common(h, slot, pos0, n_pos, dst, false, stream);
+}
+
+extern "C" int spec_kv_pages(spec_handle* h, int32_t* free_pages, int32_t* total_pages, void* stream)
+{
+    if (!h || !free_pages || !total_pages) return fail(SPEC_ERR_INVALID_ARG, "NULL argument");
+    if (!h->tables.pool.table) return fail(SPEC_ERR_INVALID_ARG, "the handle's cache is not paged");
+    SPECV_HIP(hipStreamSynchronize((hipStream_t)stream));
+    SPECV_HIP(hipMemcpy(free_pages, h->tables.pool.free_top, 4, hipMemcpyDeviceToHost));
+    *total_pages = h->n_pages;
+    return SPEC_OK;
 }
 
 extern "C" int spec_verify_poll(spec_handle* h, void* stream)
