@@ -34,6 +34,7 @@ def parse():
     ap.add_argument("--temperature", type=float, default=0.0, help="decode workload: sampling temperature (0 = default 4.0)")
     ap.add_argument("--lookahead", type=int, default=5, help="decode workload: proposals per round")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--paged", action="store_true", help="7b/1b/dyn workloads: keep the KV cache in a page pool")
     ap.add_argument("--layers", type=int, default=0,
                     help="build only this many decoder layers (for hardware-counter runs, where every dispatch is slow; "
                          "per-launch figures are unchanged, whole-step figures are not those of the workload)")
@@ -422,9 +423,14 @@ def main():
     sv.spec_k_set_gemm_wg_target(args.gemm_wg_target)
     weights, w_cpu = build_device_model(sv, wl, w, torch, want_cpu)
     cfg = sv.make_cfg(shape, B, w.max_kv_len, Kmax)
-    kv = torch.empty(sv.spec_kv_cache_bytes(cfg), dtype=torch.uint8, device="cuda")
     kv_len = torch.zeros(B, dtype=torch.int32, device="cuda")
-    h = sv.spec_verify_init(cfg, weights, kv, kv_len)
+    if args.paged:
+        n_pages = sum((n + Kmax + 1 + 31) // 32 for n in w.kv_lens)     # exactly what the step can touch
+        kv = torch.empty(n_pages * sv.spec_kv_page_bytes(cfg), dtype=torch.uint8, device="cuda")
+        h = sv.spec_verify_init_paged(cfg, weights, kv, kv_len)
+    else:
+        kv = torch.empty(sv.spec_kv_cache_bytes(cfg), dtype=torch.uint8, device="cuda")
+        h = sv.spec_verify_init(cfg, weights, kv, kv_len)
 
     # synthetic cache contents: N(0,1) keys and values, one sequence at a time
     cpu_caches = []
@@ -532,7 +538,8 @@ def main():
         "config": {"workload": f"{w.name}-shape: L{s.n_layers} d{s.d_model} {s.n_q_heads}q/{s.n_kv_heads}kv x{s.head_dim} "
                                f"FFN{s.d_ffn} V{V}; batch {B}, KV {min(w.kv_lens)}..{max(w.kv_lens)} tokens, "
                                f"K {min(look)}..{max(look)}, T {w.temperature}",
-                   "rows_per_step": w.rows, "drafts": "independent N(0,1.28^2) draft logits, tokens ~ q"},
+                   "rows_per_step": w.rows, "drafts": "independent N(0,1.28^2) draft logits, tokens ~ q",
+                   "kv_cache": "paged" if args.paged else "contiguous"},
         "scored_positions_per_s": w.rows / (ms_per_step * 1e-3),
         "acceptance_rate": accepted / max(drafted, 1),
         "emitted_tokens_per_step": emitted,
