@@ -18,12 +18,16 @@ from typing import List, Sequence
 
 import torch
 
-from . import Model, SampleDiag, sample
+from . import Model, SampleDiag, greedy, sample
 
 
 def draw(logits: torch.Tensor, temperature: float, u: float):
     """One token from softmax(logits / T) by inverse CDF in ascending token id (the K = 0 case of
-    `oracle.sample`: a single draw from the row's distribution).  Returns (token, SampleDiag)."""
+    `oracle.sample`: a single draw from the row's distribution); at temperature 0 the most likely
+    token (the K = 0 case of `oracle.greedy`).  Returns (token, diagnostics)."""
+    if temperature == 0:
+        _, out, gap = greedy(logits.reshape(1, -1), [])
+        return int(out[0]), gap
     _, out, diag = sample(logits.reshape(1, -1), torch.zeros((0, logits.numel())), [], [u], temperature)
     return int(out[0]), diag
 
@@ -79,7 +83,10 @@ def speculative_round(target: Model, draft: Model, st: SequenceState, K: int, te
     # proposals[:i], i.e. the one proposal i is tested against, row K the extra token's
     p_logits = target.verify_sequential(st.target_cache, L - 1, [st.tokens[-1]] + proposals)
     ql = torch.stack(q_logits) if K else torch.zeros((0, p_logits.shape[1]))
-    a, out, diag = sample(p_logits, ql, proposals, list(verify_uniforms[:K + 1]), temperature)
+    if temperature == 0:
+        a, out, diag = greedy(p_logits, proposals)      # diag: the smallest deciding logit gap
+    else:
+        a, out, diag = sample(p_logits, ql, proposals, list(verify_uniforms[:K + 1]), temperature)
     emitted = [int(t) for t in out[:a + 1]]
     st.tokens.extend(emitted)
     # caches: the target appended the whole window, of which last token + a proposals remain valid;

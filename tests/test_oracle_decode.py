@@ -181,3 +181,24 @@ def test_autoregressive_decode_feeds_positions_in_order():
         lg = tgt.decode_one(cache, len(seq) - 1, seq[-1])
         assert od.draw(lg, 0.8, us[i])[0] == y
         seq.append(y)
+
+
+def test_temperature_zero_rounds_emit_the_targets_greedy_text_exactly():
+    """Greedy speculative decoding: whatever the draft proposes, the text is the target's greedy
+    continuation, token for token; a draft equal to the target has every proposal kept."""
+    tgt, drf = model(SMALL, 61), model(SMALL_DRAFT, 62)
+    R, K = 6, 4
+    zeros_d, zeros_v = [[0.0] * K] * R, [[0.0] * (K + 1)] * R
+    st = fresh_state(tgt, drf, CONTEXT)
+    trace = od.speculative_decode(tgt, drf, st, R, K, 0.0, zeros_d, zeros_v)
+    new = st.tokens[len(CONTEXT):]
+    cache = tgt.new_cache()
+    seq = list(CONTEXT)
+    od.feed(tgt, cache, 0, seq, len(seq) - 1)
+    for _ in range(max(len(new), 3 * (K + 1))):
+        seq.append(int(torch.argmax(tgt.decode_one(cache, len(seq) - 1, seq[-1]))))
+    assert seq[len(CONTEXT):len(CONTEXT) + len(new)] == new and len(new) == sum(t.n_accepted + 1 for t in trace)
+    same = model(SMALL, 61)
+    st2 = fresh_state(tgt, same, CONTEXT)
+    trace2 = od.speculative_decode(tgt, same, st2, 3, K, 0.0, zeros_d, zeros_v)
+    assert [t.n_accepted for t in trace2] == [K] * 3 and st2.tokens == seq[:len(CONTEXT) + 3 * (K + 1)]
