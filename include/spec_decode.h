@@ -62,7 +62,10 @@ typedef struct {
                                        draft, 0 without */
     const float* draft_uniforms;    /* fp32 [batch][Kt], Kt = target max_lookahead; NULL when K = 0 */
     const float* verify_uniforms;   /* fp32 [batch][Kt+1] */
-    float temperature;              /* > 0, used by both models */
+    float temperature;              /* > 0: used by both models.  0: greedy decoding -- every proposal is
+                                       the draft's most likely token, the verification is the greedy rule of
+                                       spec_verify_step, and neither uniforms array is read (the emitted
+                                       text is then the target's greedy text whatever the draft proposes) */
 } spec_round_args;
 
 /* Queue one round.  Launches only; reads nothing back. */

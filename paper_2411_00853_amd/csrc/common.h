@@ -103,9 +103,11 @@ int launch_prepare(const StepTables& t, const LookaheadPack& ks, int B, int Kmax
 
 // Temperature 0: keep a proposal iff it is the target row's most likely token (lowest id among equal
 // maxima); the final token is the most likely token of the first mismatching row, or of row K_b.
+struct DrawEmit;
+// emit != NULL: every K_b = 0 and M rows = all rows of the step; the token of sequence b comes from row seq_row0[b]
 int launch_greedy(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax, int V,
                   int M, const float* target_logits, const int32_t* draft_tokens, int auto_rollback, int32_t* kv_len,
-                  int32_t* n_accepted, int32_t* out_tokens, Profiler* prof, hipStream_t s);
+                  int32_t* n_accepted, int32_t* out_tokens, const DrawEmit* emit, Profiler* prof, hipStream_t s);
 
 // Where a plain draw (every K_b = 0: one token from each sequence's row) puts its results when the
 // sampler serves a proposing model instead of a verification.  tokens == NULL: verification mode.

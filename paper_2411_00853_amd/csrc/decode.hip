@@ -258,12 +258,14 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
     const int B = d->B, K = args->lookahead, Kt = d->Kt, V = d->V;
     if (d->draft) {
         if (K < 1 || K > Kt) return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: lookahead %d outside 1..%d", K, Kt);
-        if (!args->draft_uniforms) return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: draft_uniforms is NULL");
+        if (!args->draft_uniforms && args->temperature != 0.f)
+            return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: draft_uniforms is NULL");
     } else if (K != 0) {
         return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: a decoder without a draft model runs lookahead 0 only");
     }
-    if (!args->verify_uniforms) return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: verify_uniforms is NULL");
-    if (!(args->temperature > 0.f)) return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: temperature must be > 0");
+    if (!(args->temperature >= 0.f)) return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: temperature must be >= 0");
+    const bool greedy = args->temperature == 0.f;
+    if (!greedy && !args->verify_uniforms) return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: verify_uniforms is NULL");
     hipStream_t s = (hipStream_t)stream;
     spec_handle* tg = d->target;
     spec_handle* dr = d->draft;
@@ -295,9 +297,13 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
             em.kv_add = i == 0 ? 2 : 1;
             em.logits_copy = d->draft_logits + (size_t)i * V;
             em.copy_stride = (size_t)Kt * V;
-            rc = launch_sampler(i == 0 ? d->draw_first : d->draw_next, dr->sampler, zero, B, 0, V, B, dr->logits,
-                                nullptr, nullptr, args->draft_uniforms + i, Kt, args->temperature, 0, nullptr,
-                                nullptr, nullptr, &em, &dr->prof, s);
+            if (greedy)
+                rc = launch_greedy(i == 0 ? d->draw_first : d->draw_next, dr->sampler, zero, B, 0, V, rows, dr->logits,
+                                   nullptr, 0, nullptr, nullptr, nullptr, &em, &dr->prof, s);
+            else
+                rc = launch_sampler(i == 0 ? d->draw_first : d->draw_next, dr->sampler, zero, B, 0, V, B, dr->logits,
+                                    nullptr, nullptr, args->draft_uniforms + i, Kt, args->temperature, 0, nullptr,
+                                    nullptr, nullptr, &em, &dr->prof, s);
             if (rc) return rc;
         }
     }
@@ -310,9 +316,13 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
     if (rc) return rc;
     rc = forward_run(tg, ks, B, M, tg->logits, s);
     if (rc) return rc;
-    rc = launch_sampler(tg->tables, tg->sampler, ks, B, Kt, V, B * (2 * K + 1), tg->logits, d->draft_logits,
-                        d->draft_tokens, args->verify_uniforms, Kt + 1, args->temperature, 1, tg->kv_len,
-                        d->n_accepted, d->round_out, nullptr, &tg->prof, s);
+    if (greedy)
+        rc = launch_greedy(tg->tables, tg->sampler, ks, B, Kt, V, M, tg->logits, d->draft_tokens, 1, tg->kv_len,
+                           d->n_accepted, d->round_out, nullptr, &tg->prof, s);
+    else
+        rc = launch_sampler(tg->tables, tg->sampler, ks, B, Kt, V, B * (2 * K + 1), tg->logits, d->draft_logits,
+                            d->draft_tokens, args->verify_uniforms, Kt + 1, args->temperature, 1, tg->kv_len,
+                            d->n_accepted, d->round_out, nullptr, &tg->prof, s);
     if (rc) return rc;
     d->last_rows = M;
     hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(TPB), 0, s, B, Kt, d->Kd, d->cap, d->n_accepted, d->round_out,

@@ -482,10 +482,27 @@ __global__ void __launch_bounds__(64) greedy_emit_kernel(StepTables t, Lookahead
                                                          const int32_t* __restrict__ part_idx,
                                                          const int32_t* __restrict__ draft_tokens, int auto_rollback,
                                                          int32_t* kv_len, int32_t* __restrict__ n_accepted,
-                                                         int32_t* __restrict__ out_tokens)
+                                                         int32_t* __restrict__ out_tokens, DrawEmit emit)
 {
     const int b = blockIdx.x;
     if (threadIdx.x != 0) return;
+    if (emit.tokens) {   // a proposing model's step (every K_b = 0): the most likely token of the sequence's row
+        int y = -1;
+        if (t.seq_ok[b]) {
+            const size_t r = (size_t)t.seq_row0[b] * n_chunks;
+            float best = part_max[r];
+            y = part_idx[r];
+            for (int c = 1; c < n_chunks; ++c)
+                if (part_max[r + c] > best) {
+                    best = part_max[r + c];
+                    y = part_idx[r + c];
+                }
+            if (emit.kv_len) emit.kv_len[t.seq_slot[b]] = t.seq_n[b] + emit.kv_add;
+        }
+        emit.tokens[b * emit.stride + emit.offset] = y;
+        emit.next_token[b] = y;
+        return;
+    }
     int32_t* o = out_tokens + b * (Kmax + 1);
     if (!t.seq_ok[b]) {
         n_accepted[b] = -1;
@@ -867,8 +884,10 @@ int launch_prepare(const StepTables& t, const LookaheadPack& ks, int B, int Kmax
 
 int launch_greedy(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax, int V,
                   int M, const float* target_logits, const int32_t* draft_tokens, int auto_rollback, int32_t* kv_len,
-                  int32_t* n_accepted, int32_t* out_tokens, Profiler* prof, hipStream_t s)
+                  int32_t* n_accepted, int32_t* out_tokens, const DrawEmit* emit, Profiler* prof, hipStream_t s)
 {
+    DrawEmit em{};
+    if (emit) em = *emit;
     const int n_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
     {
         ProfScope ps(prof, SPEC_PROF_SAMPLER_STATS, s);
@@ -878,7 +897,7 @@ int launch_greedy(const StepTables& t, const SamplerWorkspace& w, const Lookahea
     }
     ProfScope ps(prof, SPEC_PROF_SAMPLER_DRAW, s);
     hipLaunchKernelGGL(greedy_emit_kernel, dim3(B), dim3(64), 0, s, t, ks, Kmax, n_chunks, w.part_max, w.part_idx,
-                       draft_tokens, auto_rollback, kv_len, n_accepted, out_tokens);
+                       draft_tokens, auto_rollback, kv_len, n_accepted, out_tokens, em);
     SPECV_LAUNCH_CHECK("greedy_emit_kernel");
     return SPEC_OK;
 }

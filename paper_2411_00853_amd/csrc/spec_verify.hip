@@ -372,7 +372,7 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     if (greedy)
         return launch_greedy(h->tables, h->sampler, ks, B, Kmax, c.vocab, M, logits, args->draft_tokens,
                              args->auto_rollback, run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens,
-                             &h->prof, s);
+                             nullptr, &h->prof, s);
     return launch_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, n_stat, logits, args->draft_logits,
                           args->draft_tokens, args->uniforms, Kmax + 1, args->temperature, args->auto_rollback,
                           run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, nullptr, &h->prof, s);

@@ -214,6 +214,42 @@ def test_free_running_text_equals_the_oracles_fp32():
     assert compared >= 20, "too few tokens compared for the test to mean anything"
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_greedy_rounds_at_temperature_zero(dtype):
+    """T = 0: proposals are the draft's most likely tokens, the verification is the greedy rule, and
+    the text is the target's greedy continuation.  Compared with the oracle's run for as long as
+    every deciding logit gap of the oracle's run is far above the logit tolerance."""
+    t_shape = wl.ModelShape(2, 256, 4, 4, 64, 512, 300, dtype=dtype)
+    d_shape = wl.ModelShape(1, 128, 2, 2, 64, 256, 300, dtype=dtype)
+    K, R = 3, 6
+    pair = Pair(t_shape, d_shape, CONTEXTS, 96, K, 64, seed=51, std=0.3)   # large weights: clear logit gaps
+    B = len(CONTEXTS)
+    accepted = []
+    for r in range(R):
+        pair.sv.spec_decode_round(pair.dec, K, None, None, 0.0)
+        torch.cuda.synchronize()
+        accepted.append(pair.view(K)["n_accepted"].tolist())
+    pair.sv.spec_verify_poll(pair.tg.h)
+    pair.sv.spec_verify_poll(pair.dr.h)
+    g = pair.view(K)
+    tol = 5 * LOGIT_TOL[dtype] if dtype == "fp32" else LOGIT_TOL[dtype]   # a gap that the logit error cannot close
+    compared = 0
+    for b, st in enumerate(pair.states):
+        trace = od.speculative_decode(pair.tg.om, pair.dr.om, st, R, K, 0.0, [[0.0] * K] * R, [[0.0] * (K + 1)] * R)
+        safe_rounds = 0
+        for t in trace:
+            draft_gaps = [float(torch.topk(row, 2).values[0] - torch.topk(row, 2).values[1]) for row in t.draft_logits]
+            if min(draft_gaps + [t.diag]) < tol:
+                break
+            safe_rounds += 1
+        safe = sum(len(t.emitted) for t in trace[:safe_rounds])
+        n = int(g["n_tokens"][b])
+        assert g["tokens"][b, :n].tolist()[:safe] == st.tokens[len(CONTEXTS[b]):][:safe]
+        assert [accepted[r][b] for r in range(safe_rounds)] == [t.n_accepted for t in trace[:safe_rounds]]
+        compared += safe
+    assert compared >= (12 if dtype == "fp32" else 4), compared
+
+
 def test_plain_sampling_rounds_without_a_draft():
     """lookahead 0, no draft model: one token per round drawn from the target -- the baseline loop."""
     from test_gpu_forward import Rig
