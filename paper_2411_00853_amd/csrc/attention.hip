@@ -75,7 +75,7 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
         const bool real = r < rows;
         const int j = real ? r / group : 0, hl = real ? r % group : 0;
         n_vis[rt] = real ? n : 0;
-        wmask[rt] = real ? t.row_mask[row0 + j] : 0u;
+        wmask[rt] = !real ? 0u : (t.tree ? t.row_mask[row0 + j] : (2u << j) - 1u);
         const float4* src = reinterpret_cast<const float4*>(q + (size_t)(row0 + j) * dq + (hkv * group + hl) * HD + 8 * gq);
         const float sc = real ? scale_log2e : 0.f;   // rows past the window contribute zeros
 #pragma unroll
@@ -288,7 +288,7 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(StepTables t, CacheGeom g
     }
     const int n_keys = pos + 1;
     const int n_cached = t.seq_n[t.row_seq[m]];
-    const uint32_t wmask = t.row_mask[m];
+    const uint32_t wmask = t.tree ? t.row_mask[m] : 0xffffffffu;   // chains: n_keys = pos + 1 is the whole rule
     const int slot = t.seq_slot[t.row_seq[m]];
     const int hkv = hq / (n_q_heads / g.n_kv_heads);
     const float* kbase = cache + cache_head_base(g, layer, slot, hkv) + plain_offset(g, 0, 0, 0);

@@ -81,6 +81,8 @@ struct StepTables {
     int32_t* row_rope;   // [M] position the rotary embedding uses: n_b + depth of the row in its window
     uint32_t* row_mask;  // [M] bit i set: the row attends to window slot i (position n_b + i)
     PagePool pool;       // the cache's page pool (table == NULL: contiguous cache)
+    int tree;            // set by the host: 0 = the windows are chains (row_rope = row_pos, row_mask = slots
+                         // 0..j, so the kernels need not load them), 1 = token trees
 };
 
 // ---- sampler (sampler.hip) ---------------------------------------------------------------------

@@ -269,6 +269,8 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
     hipStream_t s = (hipStream_t)stream;
     spec_handle* tg = d->target;
     spec_handle* dr = d->draft;
+    tg->tables.tree = 0;
+    if (dr) dr->tables.tree = 0;
     int rc;
     LookaheadPack ks;
 

@@ -182,6 +182,7 @@ __global__ void __launch_bounds__(64) rope_append_kernel(const float* __restrict
 {
     const int m = blockIdx.x, head = blockIdx.y;
     const int pos = t.row_pos[m];
+    const int rope_pos = t.tree ? t.row_rope[m] : pos;   // loaded alongside pos, not after the branch below
     const int hd = g.head_dim, half = hd >> 1;
     const int dq = n_q_heads * hd;
     const float* row = partial + (size_t)m * ld + head * hd;
@@ -193,7 +194,7 @@ __global__ void __launch_bounds__(64) rope_append_kernel(const float* __restrict
     const int slot = t.seq_slot[t.row_seq[m]];
     const float rs = row_inv_rms(ns.ssq, ns.n_ssq, m, ns.d, ns.eps);   // the attention norm's row scale
     if (head < n_q_heads + g.n_kv_heads) {
-        const float* cs = cos_sin + (size_t)t.row_rope[m] * hd;   // [half][2]; depth in the window, not the slot
+        const float* cs = cos_sin + (size_t)rope_pos * hd;   // [half][2]; depth in the window, not the slot
         for (int i = threadIdx.x; i < half; i += 64) {
             const float a = sum_splits(row + i, n_split, split_stride) * rs;
             const float b = sum_splits(row + i + half, n_split, split_stride) * rs;

@@ -353,6 +353,7 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     hipStream_t s = (hipStream_t)stream;
     // draft_tokens may be NULL when every K_b is 0; the kernels then never read it
     int rc;
+    h->tables.tree = 0;
     {
         ProfScope ps(&h->prof, SPEC_PROF_PREPARE, s);
         rc = launch_prepare(h->tables, ks, B, Kmax, c.vocab, c.max_batch, c.max_kv_len, run_model, args->seq_slot,
@@ -409,6 +410,7 @@ extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args,
     }
     hipStream_t s = (hipStream_t)stream;
     int rc;
+    h->tables.tree = 1;
     {
         ProfScope ps(&h->prof, SPEC_PROF_PREPARE, s);
         rc = launch_prepare_tree(h->tables, ks, B, Kmax, c.vocab, c.max_batch, c.max_kv_len, run_model, args->seq_slot,
