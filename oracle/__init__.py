@@ -225,6 +225,24 @@ def tree_sample(parent: Sequence[int], tokens: Sequence[int], target_logits: tor
     return int(na.value), list(path)[:int(na.value)], list(out), diag
 
 
+def tree_greedy(parent: Sequence[int], tokens: Sequence[int], target_logits: torch.Tensor):
+    """Temperature-0 verification of one sequence's tree: (n_accepted, path, out_tokens [N+1], smallest gap)."""
+    N = len(tokens)
+    V = target_logits.shape[-1]
+    assert len(parent) == N and target_logits.shape == (N + 1, V) and target_logits.dtype == torch.float32
+    par = (C.c_int32 * max(N, 1))(*[int(v) for v in parent])
+    tok = (C.c_int32 * max(N, 1))(*[int(v) for v in tokens])
+    na = C.c_int32(0)
+    path = (C.c_int32 * max(N, 1))()
+    out = (C.c_int32 * (N + 1))()
+    gap = C.c_float(0.0)
+    rc = lib().oracle_tree_greedy(C.c_int32(V), C.c_int32(N), par, tok, _fptr(target_logits), C.byref(na), path, out,
+                                  C.byref(gap))
+    if rc:
+        raise ValueError("oracle_tree_greedy rejected its arguments")
+    return int(na.value), list(path)[:int(na.value)], list(out), float(gap.value)
+
+
 def tree_paths(parent: Sequence[int]):
     """For every node its path from the root (list of node indices ending in the node itself)."""
     paths = []

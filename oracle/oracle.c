@@ -441,6 +441,43 @@ int oracle_greedy(int32_t V, int32_t K, const float* target_logits, const int32_
     return 0;
 }
 
+int oracle_tree_greedy(int32_t V, int32_t N, const int32_t* parent, const int32_t* tokens,
+                       const float* target_logits, int32_t* n_accepted, int32_t* path, int32_t* out_tokens,
+                       float* min_gap)
+{
+    if (V <= 0 || N < 0) return -1;
+    for (int i = 0; i < N; ++i)
+        if (parent[i] < -1 || parent[i] >= i || tokens[i] < 0 || tokens[i] >= V) return -1;
+    int cur = -1, a = 0;
+    float gap_min = INFINITY;
+    for (;;) {
+        const float* row = target_logits + (size_t)(cur + 1) * V;
+        int best = 0;
+        for (int v = 1; v < V; ++v)
+            if (row[v] > row[best]) best = v;
+        float second = -INFINITY;
+        for (int v = 0; v < V; ++v)
+            if (v != best && row[v] > second) second = row[v];
+        if (V > 1 && row[best] - second < gap_min) gap_min = row[best] - second;
+        int next = -1;
+        for (int c = cur + 1; c < N; ++c)
+            if (parent[c] == cur && tokens[c] == best) { next = c; break; }
+        if (next < 0) {
+            out_tokens[a] = best;
+            break;
+        }
+        path[a] = next;
+        out_tokens[a] = best;
+        ++a;
+        cur = next;
+    }
+    for (int i = a + 1; i <= N; ++i) out_tokens[i] = -1;
+    for (int i = a; i < N; ++i) path[i] = -1;
+    *n_accepted = a;
+    if (min_gap) *min_gap = gap_min;
+    return 0;
+}
+
 int oracle_tree_sample(int32_t V, int32_t N, const int32_t* parent, const int32_t* tokens,
                        const float* target_logits, const float* draft_logits, const float* uniforms, float T,
                        int32_t* n_accepted, int32_t* path, int32_t* out_tokens, oracle_tree_diag* diag)

@@ -113,6 +113,14 @@ int oracle_sample(int32_t vocab, int32_t K, const float* target_logits, const fl
 int oracle_greedy(int32_t vocab, int32_t K, const float* target_logits, const int32_t* draft_tokens,
                   int32_t* n_accepted, int32_t* out_tokens, float* min_gap);
 
+/* Greedy verification of a token tree (temperature 0): from the root, move to the first child (in
+ * index order) whose token is the most likely token of the current node's target row; when there is
+ * none, that most likely token is the final token.  target_logits [N+1][vocab] (row 0: the root).
+ * path [N], out_tokens [N+1] as in oracle_tree_sample. */
+int oracle_tree_greedy(int32_t vocab, int32_t N, const int32_t* parent, const int32_t* tokens,
+                       const float* target_logits, int32_t* n_accepted, int32_t* path, int32_t* out_tokens,
+                       float* min_gap);
+
 /* Diagnostics of one sequence's tree verification. */
 typedef struct {
     double accept_ratio[16];  /* per node i < 16: min(1, r(x_i)/q(x_i)) if the node was tested, else -1 */

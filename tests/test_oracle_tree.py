@@ -137,3 +137,54 @@ def test_tree_logits_rows_depend_on_their_own_path_only():
     assert torch.equal(rows[4], chain[2]) and torch.equal(rows[6], chain[3])
     # siblings see the same prefix: rows of nodes 2 and 3 differ only through their own token
     assert not torch.equal(rows[3], rows[4])
+
+
+def test_greedy_tree_walk_follows_the_argmax_path_and_is_the_cold_limit():
+    """oracle_tree_greedy: (a) a chain is oracle_greedy; (b) on a tree the kept path is the unique
+    root-down path whose tokens are the row-wise argmaxes, found with plain torch; (c) it is what
+    oracle_tree_sample gives at a temperature so low that all mass sits on the argmax, for a draft
+    that proposes its own most likely token."""
+    rng = wl.Rng(31)
+    V, N = 50, 9
+    parent = [-1, -1, -1, 0, 0, 1, 3, 3, 4]
+    depths = set()
+    for case in range(80):
+        tl = rng.normal(100 + case, (N + 1, V), 2.0)
+        best = torch.argmax(tl, dim=1).tolist()
+        toks = rng.randint(300 + case, (N,), V).tolist()
+        # plant the argmax along a path of random depth
+        want_path, cur = [], -1
+        for d in range(case % 5):
+            kids = [c for c in range(N) if parent[c] == cur]
+            if not kids:
+                break
+            c = kids[(case + d) % len(kids)]
+            toks[c] = best[cur + 1]
+            want_path.append(c)
+            cur = c
+        for c in range(N):                      # no accidental matches elsewhere
+            if c not in want_path and toks[c] == best[parent[c] + 1]:
+                toks[c] = (toks[c] + 1) % V
+                if toks[c] == best[parent[c] + 1]:
+                    toks[c] = (toks[c] + 1) % V
+        a, path, out, gap = oracle.tree_greedy(parent, toks, tl)
+        assert path == want_path and a == len(want_path)
+        assert out[:a] == [toks[c] for c in path] and out[a] == best[cur + 1] and out[a + 1:] == [-1] * (N - a)
+        depths.add(a)
+        # (c) on the kept path taken as a chain, with a draft whose most likely token is the proposal
+        T = min(gap, 1.0) / 60.0
+        ctoks = [toks[c] for c in want_path]
+        rows = [0] + [c + 1 for c in want_path]
+        ctl = tl[rows].contiguous()
+        cdl = torch.zeros((len(rows), V))
+        for i, c in enumerate(want_path):
+            cdl[i] = rng.normal(700 + case, (V,), 1.0)
+            cdl[i, toks[c]] = cdl[i].max() + 1.0
+        us = [max(u, 1e-3) for u in rng.uniform(900 + case, (len(rows),)).tolist()]
+        a2, path2, out2, _ = oracle.tree_sample(list(range(-1, len(want_path) - 1)), ctoks, ctl, cdl, us, T)
+        assert a2 == a and out2[:a + 1] == out[:a + 1]
+    assert depths == {0, 1, 2, 3, 4} or depths == {0, 1, 2, 3}
+    tl = rng.normal(1, (4, V), 2.0)
+    chain_toks = torch.argmax(tl[:3], dim=1).tolist()
+    chain_toks[2] = (chain_toks[2] + 1) % V
+    assert oracle.tree_greedy([-1, 0, 1], chain_toks, tl)[::2] == oracle.greedy(tl, chain_toks)[:2]
