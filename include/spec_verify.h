@@ -196,7 +196,9 @@ int spec_verify_step(spec_handle* h, const spec_step_args* args, const spec_step
  * uniforms[b][c] * q(x) < r(x), and then becomes the current node; every rejection replaces r by
  * max(0, r - q) renormalised.  When the current node has no child left, the final token is drawn
  * from r by inverse CDF (as in spec_verify_step) with uniforms[b][N_b].
- * A chain (parent[i] = i-1) gives exactly spec_verify_step.
+ * A chain (parent[i] = i-1) gives exactly spec_verify_step.  temperature 0 selects the greedy walk:
+ * move to the first child whose token is the most likely token of the current node's target row,
+ * otherwise emit that token (draft_logits and uniforms are not read).
  * With auto_rollback the kept nodes' keys and values are moved to positions n_b+1..n_b+a and
  * kv_len[slot] = n_b + a + 1; without it the window stays as scored and kv_len = n_b + N_b + 1. */
 typedef struct {

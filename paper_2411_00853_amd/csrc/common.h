@@ -208,6 +208,10 @@ int launch_reduce_splits(const float* partial, int n_split, size_t split_stride,
                          const float* ssq, int n_ssq, int d, float eps, float* out, hipStream_t s);
 int launch_kv_copy(const CacheGeom& g, void* cache, int slot, int pos0, int n_pos, void* plain, bool to_cache,
                    hipStream_t s);
+int launch_tree_greedy(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax, int V,
+                       int M, const float* target_logits, const int32_t* parent, const int32_t* tokens,
+                       int auto_rollback, int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens, int32_t* path,
+                       Profiler* prof, hipStream_t s);
 // keys/values of the kept path (slot path[k]+1 of the window) moved to positions n+1..n+a, all layers
 int launch_kv_compact(const CacheGeom& g, void* cache, const StepTables& t, int B, int Kmax, const int32_t* n_accepted,
                       const int32_t* path, hipStream_t s);

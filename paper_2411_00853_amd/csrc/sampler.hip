@@ -535,6 +535,54 @@ __global__ void __launch_bounds__(64) greedy_emit_kernel(StepTables t, Lookahead
     }
 }
 
+// Temperature 0 on a tree: from the root, move to the first child (index order) whose token is the
+// most likely token of the current node's row; otherwise that token ends the step.
+__global__ void __launch_bounds__(64) tree_greedy_kernel(StepTables t, LookaheadPack ks, int Kmax, int n_chunks,
+                                                         const float* __restrict__ part_max,
+                                                         const int32_t* __restrict__ part_idx,
+                                                         const int32_t* __restrict__ parent,
+                                                         const int32_t* __restrict__ tokens, int auto_rollback,
+                                                         int32_t* kv_len, int32_t* __restrict__ n_accepted,
+                                                         int32_t* __restrict__ out_tokens, int32_t* __restrict__ path)
+{
+    const int b = blockIdx.x;
+    if (threadIdx.x != 0) return;
+    int32_t* o = out_tokens + b * (Kmax + 1);
+    int32_t* pth = path + b * Kmax;
+    if (!t.seq_ok[b]) {
+        n_accepted[b] = -1;
+        for (int i = 0; i <= Kmax; ++i) o[i] = -1;
+        for (int i = 0; i < Kmax; ++i) pth[i] = -1;
+        return;
+    }
+    const int N = ks.k[b];
+    int cur = -1, a = 0;
+    for (;;) {
+        const size_t r = (size_t)(t.seq_row0[b] + cur + 1) * n_chunks;
+        float best = part_max[r];
+        int bi = part_idx[r];
+        for (int c = 1; c < n_chunks; ++c)
+            if (part_max[r + c] > best) {
+                best = part_max[r + c];
+                bi = part_idx[r + c];
+            }
+        int next = -1;
+        for (int c = cur + 1; c < N; ++c)
+            if (parent[b * Kmax + c] == cur && tokens[b * Kmax + c] == bi) { next = c; break; }
+        o[a] = bi;
+        if (next < 0) break;
+        pth[a++] = next;
+        cur = next;
+    }
+    for (int i = a + 1; i <= Kmax; ++i) o[i] = -1;
+    for (int i = a; i < Kmax; ++i) pth[i] = -1;
+    n_accepted[b] = a;
+    if (kv_len) {
+        kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : N) + 1;
+        pool_trim(t.pool, t.seq_slot[b], t.seq_n[b] + (auto_rollback ? a : N) + 1);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Token trees.  Window slot 0 is the sequence's last token (the root), slot i+1 is node i; the
 // nodes come in topological order with parent[i] = -1 (child of the root) or an index < i.
@@ -899,6 +947,25 @@ int launch_greedy(const StepTables& t, const SamplerWorkspace& w, const Lookahea
     hipLaunchKernelGGL(greedy_emit_kernel, dim3(B), dim3(64), 0, s, t, ks, Kmax, n_chunks, w.part_max, w.part_idx,
                        draft_tokens, auto_rollback, kv_len, n_accepted, out_tokens, em);
     SPECV_LAUNCH_CHECK("greedy_emit_kernel");
+    return SPEC_OK;
+}
+
+int launch_tree_greedy(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax, int V,
+                       int M, const float* target_logits, const int32_t* parent, const int32_t* tokens,
+                       int auto_rollback, int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens, int32_t* path,
+                       Profiler* prof, hipStream_t s)
+{
+    const int n_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
+    {
+        ProfScope ps(prof, SPEC_PROF_SAMPLER_STATS, s);
+        hipLaunchKernelGGL(argmax_kernel, dim3((unsigned)M * n_chunks), dim3(TPB), 0, s, V, n_chunks, target_logits,
+                           w.part_max, w.part_idx);
+        SPECV_LAUNCH_CHECK("argmax_kernel");
+    }
+    ProfScope ps(prof, SPEC_PROF_SAMPLER_DRAW, s);
+    hipLaunchKernelGGL(tree_greedy_kernel, dim3(B), dim3(64), 0, s, t, ks, Kmax, n_chunks, w.part_max, w.part_idx,
+                       parent, tokens, auto_rollback, kv_len, n_accepted, out_tokens, path);
+    SPECV_LAUNCH_CHECK("tree_greedy_kernel");
     return SPEC_OK;
 }
 

@@ -386,8 +386,9 @@ extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args,
     const int B = args->batch, Kmax = c.max_lookahead;
     if (B < 1 || B > c.max_batch) return fail(SPEC_ERR_INVALID_ARG, "batch %d outside 1..%d", B, c.max_batch);
     if (!args->n_nodes) return fail(SPEC_ERR_INVALID_ARG, "n_nodes is NULL");
-    if (!(args->temperature > 0.f)) return fail(SPEC_ERR_INVALID_ARG, "temperature must be > 0");
-    if (!args->uniforms) return fail(SPEC_ERR_INVALID_ARG, "uniforms is NULL");
+    if (!(args->temperature >= 0.f)) return fail(SPEC_ERR_INVALID_ARG, "temperature must be >= 0");
+    const bool greedy = args->temperature == 0.f;
+    if (!greedy && !args->uniforms) return fail(SPEC_ERR_INVALID_ARG, "uniforms is NULL");
     if (!out->n_accepted || !out->out_tokens || !out->path)
         return fail(SPEC_ERR_INVALID_ARG, "n_accepted, out_tokens or path is NULL");
     LookaheadPack ks;
@@ -400,7 +401,7 @@ extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args,
         M += k + 1;
         any |= k;
     }
-    if (!args->draft_logits) return fail(SPEC_ERR_INVALID_ARG, "draft_logits is NULL");
+    if (!greedy && !args->draft_logits) return fail(SPEC_ERR_INVALID_ARG, "draft_logits is NULL");
     if (any && (!args->draft_tokens || !args->parent))
         return fail(SPEC_ERR_INVALID_ARG, "draft_tokens or parent is NULL");
     const bool run_model = args->target_logits_in == nullptr;
@@ -428,6 +429,11 @@ extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args,
         SPECV_HIP(hipMemcpyAsync(out->logits_out, logits, (size_t)M * c.vocab * sizeof(float),
                                  hipMemcpyDeviceToDevice, s));
     }
+    if (greedy)
+        rc = launch_tree_greedy(h->tables, h->sampler, ks, B, Kmax, c.vocab, M, logits, args->parent, args->draft_tokens,
+                                args->auto_rollback, run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens,
+                                out->path, &h->prof, s);
+    else
     rc = launch_tree_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, 2 * M, logits, args->draft_logits,
                              args->parent, args->draft_tokens, args->uniforms, args->temperature,
                              args->auto_rollback, run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens,

@@ -220,3 +220,34 @@ def test_bad_parent_is_flagged_and_skipped():
         sv.spec_verify_poll(h)
     assert int(na[0]) == -1 and int(na[1]) >= 0
     h.close()
+
+
+def test_greedy_tree_walk_at_temperature_zero():
+    from paper_2411_00853_amd import binding as sv
+    B, Kmax, V = 10, 9, 32003
+    n_nodes, parent, toks, tl, dl, us = make_tree_inputs(91, B, Kmax, V, 1.0)
+    # plant argmax tokens on some children so that walks of several depths occur
+    r0 = 0
+    for b, n in enumerate(n_nodes):
+        best = torch.argmax(tl[r0:r0 + n + 1], dim=1)
+        for i in range(n):
+            if (b + i) % 2 == 0:
+                toks[b, i] = int(best[int(parent[b, i]) + 1])
+        r0 += n + 1
+    h = sv.spec_verify_init(sv.sampler_cfg(V, B, Kmax), None, None, None)
+    na = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    ot = torch.full((B, Kmax + 1), -7, dtype=torch.int32, device="cuda")
+    pt = torch.full((B, Kmax), -7, dtype=torch.int32, device="cuda")
+    sv.spec_verify_tree_step(h, n_nodes, parent.cuda(), toks.cuda(), None, None, 0.0, na, ot, pt,
+                             target_logits_in=tl.cuda().contiguous())
+    torch.cuda.synchronize()
+    sv.spec_verify_poll(h)
+    h.close()
+    r0, seen = 0, set()
+    for b, n in enumerate(n_nodes):
+        a, path, out, _ = oracle.tree_greedy(parent[b, :n].tolist(), toks[b, :n].tolist(), tl[r0:r0 + n + 1].contiguous())
+        assert int(na[b]) == a and pt[b, :a].tolist() == path and (pt[b, a:] == -1).all()
+        assert ot[b, :n + 1].tolist() == out and (ot[b, n + 1:] == -1).all()
+        seen.add(a)
+        r0 += n + 1
+    assert len(seen) >= 3
