@@ -204,6 +204,12 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
         }
 }
 
+// zero a fragment buffer (a kernel rather than a memset node, so that the call can be captured in a graph)
+__global__ void __launch_bounds__(256) zero_kernel(uint4* __restrict__ p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = make_uint4(0, 0, 0, 0);
+}
+
 // fp32 row-major X[M][K] (optionally times gain[K]) -> fragment buffer
 __global__ void __launch_bounds__(256) pack_x_kernel(const float* __restrict__ X, const float* __restrict__ gain, int M,
                                                      int K, int mt_count, int planes, uint4* __restrict__ xf)
@@ -442,7 +448,10 @@ extern "C" int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, 
     GemmPlan p = plan_gemm(M, N, K, 256, split_x != 0);
     float* partial = (float*)workspace;
     char* xf = (char*)workspace + (((size_t)16 * M * p.n_pad * sizeof(float) + 255) & ~(size_t)255);
-    SPECV_HIP(hipMemsetAsync(xf, 0, xfrag_uint4s(p.mt, p.planes, K) * sizeof(uint4), (hipStream_t)stream));
+    const size_t n_xf = xfrag_uint4s(p.mt, p.planes, K);
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n_xf + 255) / 256 < 2048 ? (n_xf + 255) / 256 : 2048)), dim3(256), 0,
+                       (hipStream_t)stream, (uint4*)xf, n_xf);
+    SPECV_LAUNCH_CHECK("zero_kernel");
     int rc = launch_pack_x(x, nullptr, M, K, p.mt, p.planes, xf, (hipStream_t)stream);
     if (rc) return rc;
     rc = launch_gemm_bf16(p, xf, w_packed, M, N, K, partial, (hipStream_t)stream);

@@ -434,10 +434,10 @@ extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args,
                                 args->auto_rollback, run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens,
                                 out->path, &h->prof, s);
     else
-    rc = launch_tree_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, 2 * M, logits, args->draft_logits,
-                             args->parent, args->draft_tokens, args->uniforms, args->temperature,
-                             args->auto_rollback, run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens,
-                             out->path, &h->prof, s);
+        rc = launch_tree_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, 2 * M, logits, args->draft_logits,
+                                 args->parent, args->draft_tokens, args->uniforms, args->temperature,
+                                 args->auto_rollback, run_model ? h->kv_len : nullptr, out->n_accepted,
+                                 out->out_tokens, out->path, &h->prof, s);
     if (rc) return rc;
     if (run_model && args->auto_rollback) {
         ProfScope ps(&h->prof, SPEC_PROF_GLUE, s);
