@@ -21,6 +21,7 @@
 #include "cache_layout.h"
 #include "common.h"
 #include "frag.h"
+#include "splits.h"
 
 namespace specv {
 namespace {
@@ -38,12 +39,17 @@ __device__ __forceinline__ void split_frag(const float (&x)[8], Frag& hi, Frag& 
 // PAGED: the blocks of a slot are looked up in the page table.  A wavefront keeps the page numbers
 // of its chunk's (at most 64) blocks one per lane and broadcasts the one it needs, so the address
 // of a prefetch never waits for memory.
-template <int HD, int RT, bool PAGED>
+// FUSED: the kernel takes the QKV projection's partial sums instead of finished queries: every
+// wavefront adds up, scales and rotates the queries it needs, and the wavefront whose chunk holds
+// window positions does the same for the window's keys and values of its kv head, stores them in
+// the cache (for later steps) and only then starts to stream -- so no separate rotary/append kernel
+// runs between the projection and the attention.
+template <int HD, int RT, bool PAGED, bool FUSED>
 __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadPack ks, CacheGeom g, int n_q_heads,
-                                                        int layer, const uint4* __restrict__ cache,
+                                                        int layer, const uint4* cache,
                                                         const float* __restrict__ q, int chunk_keys, int max_chunks,
                                                         int r_cap, float scale_log2e, float* __restrict__ part_o,
-                                                        float* __restrict__ part_ml)
+                                                        float* __restrict__ part_ml, QkvSrc src, uint16_t* cache_w)
 {
     constexpr int STEPS = HD / 32;     // 32-dim steps of the score product
     constexpr int DT = HD / 16;        // 16-dim tiles of the output
@@ -64,37 +70,6 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
     const int rows = (K + 1) * group;
     const int dq = n_q_heads * HD;
     const int row0 = t.seq_row0[b];
-
-    // queries, pre-scaled by log2(e)/sqrt(hd), as bf16 head + remainder operand fragments
-    Frag qh[RT][STEPS], ql[RT][STEPS];
-    int n_vis[RT];           // cached positions below this are visible to the query (0 for padding rows)
-    uint32_t wmask[RT];      // window slots (positions n + i) the query attends to
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        const int r = rt * 16 + c16;
-        const bool real = r < rows;
-        const int j = real ? r / group : 0, hl = real ? r % group : 0;
-        n_vis[rt] = real ? n : 0;
-        wmask[rt] = !real ? 0u : (t.tree ? t.row_mask[row0 + j] : (2u << j) - 1u);
-        const float4* src = reinterpret_cast<const float4*>(q + (size_t)(row0 + j) * dq + (hkv * group + hl) * HD + 8 * gq);
-        const float sc = real ? scale_log2e : 0.f;   // rows past the window contribute zeros
-#pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            const float4 a = src[8 * s], b = src[8 * s + 1];
-            const float x[8] = {a.x * sc, a.y * sc, a.z * sc, a.w * sc, b.x * sc, b.y * sc, b.z * sc, b.w * sc};
-            split_frag(x, qh[rt][s], ql[rt][s]);
-        }
-    }
-
-    floatx4 acc[RT][DT];
-    float m_run[RT], l_run[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        m_run[rt] = -INFINITY;
-        l_run[rt] = 0.f;
-#pragma unroll
-        for (int d = 0; d < DT; ++d) acc[rt][d] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
 
     const int blk0 = key0 >> 5, blk1 = (key1 + 31) >> 5;
     const uint4* head;
@@ -124,6 +99,116 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
 #pragma unroll
         for (int d = 0; d < DT; ++d) vv[d] = p[4 * HD + d * 64];
     };
+    load_block(blk0, ka, va);   // the stream starts before anything else is fetched
+
+    // queries, pre-scaled by log2(e)/sqrt(hd), as bf16 head + remainder operand fragments
+    Frag qh[RT][STEPS], ql[RT][STEPS];
+    int n_vis[RT];           // cached positions below this are visible to the query (0 for padding rows)
+    uint32_t wmask[RT];      // window slots (positions n + i) the query attends to
+    // Where this lane's share of a row tile's queries starts in the partial sums: 8 dims of every
+    // 32-dim step, i.e. 2 * STEPS float4 columns.
+    auto q_columns = [&](int rt, const float** cols, float& rs) {
+        const int r = rt * 16 + c16;
+        const bool real = r < rows;
+        const int j = real ? r / group : 0, hl = real ? r % group : 0;
+        const int m = row0 + j;
+        rs = row_inv_rms(src.ns.ssq, src.ns.n_ssq, m, src.ns.d, src.ns.eps);
+        const float* pq = src.partial + (size_t)m * src.ld + (hkv * group + hl) * HD + 8 * gq;
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            cols[2 * s] = pq + 32 * s;
+            cols[2 * s + 1] = pq + 32 * s + 4;
+        }
+    };
+    // Scale, rotate and split them: dims d and d + HD/2 (a rotary pair) sit in steps s and
+    // s + STEPS/2 of the same lane.
+    auto q_finish = [&](int rt, const float4* sums, float rs, int j, float sc) {
+        float raw[STEPS][8];
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const float4 a = sums[2 * s], b = sums[2 * s + 1];
+            raw[s][0] = a.x * rs; raw[s][1] = a.y * rs; raw[s][2] = a.z * rs; raw[s][3] = a.w * rs;
+            raw[s][4] = b.x * rs; raw[s][5] = b.y * rs; raw[s][6] = b.z * rs; raw[s][7] = b.w * rs;
+        }
+        const int rpos = t.tree ? t.row_rope[row0 + j] : n + j;
+        const float* cs = src.cos_sin + (size_t)rpos * HD + 2 * (8 * gq);   // [HD/2][2] per position
+#pragma unroll
+        for (int s = 0; s < STEPS / 2; ++s) {
+            float x0[8], x1[8];
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const float4 c2 = *reinterpret_cast<const float4*>(cs + 2 * (32 * s) + 4 * e4);   // cos,sin of 2 dims
+                const float ca[2] = {c2.x, c2.z}, sa[2] = {c2.y, c2.w};
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const int e = 2 * e4 + h2;
+                    const float a = raw[s][e], bq = raw[s + STEPS / 2][e];
+                    x0[e] = (a * ca[h2] - bq * sa[h2]) * sc;
+                    x1[e] = (a * sa[h2] + bq * ca[h2]) * sc;
+                }
+            }
+            split_frag(x0, qh[rt][s], ql[rt][s]);
+            split_frag(x1, qh[rt][s + STEPS / 2], ql[rt][s + STEPS / 2]);
+        }
+    };
+    // 64-dim heads: the partial sums of two row tiles are requested together (the same number of
+    // loads in flight as one tile of a 128-dim head)
+    constexpr int RB = (FUSED && HD == 64 && RT >= 2) ? 2 : 1;
+    float4 pre[RB > 1 ? RT + 1 : 1][2 * STEPS];   // sums fetched ahead (batched variant only)
+    float pre_rs[RB > 1 ? RT + 1 : 1];
+    if constexpr (RB > 1) {
+#pragma unroll
+        for (int rt0 = 0; rt0 < RT; rt0 += 2) {
+            const float* cols[2][2 * STEPS];
+            q_columns(rt0, cols[0], pre_rs[rt0]);
+            q_columns(min(rt0 + 1, RT - 1), cols[1], pre_rs[rt0 + 1]);
+            const float* flat[4 * STEPS];
+            float4 fsum[4 * STEPS];
+#pragma unroll
+            for (int x = 0; x < 4 * STEPS; ++x) flat[x] = cols[x / (2 * STEPS)][x % (2 * STEPS)];
+            sum_splits4_many(flat, src.n_split, src.stride, fsum);
+#pragma unroll
+            for (int x = 0; x < 4 * STEPS; ++x) pre[rt0 + x / (2 * STEPS)][x % (2 * STEPS)] = fsum[x];
+        }
+    }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int r = rt * 16 + c16;
+        const bool real = r < rows;
+        const int j = real ? r / group : 0, hl = real ? r % group : 0;
+        n_vis[rt] = real ? n : 0;
+        wmask[rt] = !real ? 0u : (t.tree ? t.row_mask[row0 + j] : (2u << j) - 1u);
+        const float sc = real ? scale_log2e : 0.f;   // rows past the window contribute zeros
+        if constexpr (FUSED && RB > 1) {
+            q_finish(rt, pre[rt], pre_rs[rt], j, sc);
+        } else if constexpr (FUSED) {
+            const float* cols[2 * STEPS];
+            float rs;
+            q_columns(rt, cols, rs);
+            float4 sums[2 * STEPS];
+            sum_splits4_many(cols, src.n_split, src.stride, sums);
+            q_finish(rt, sums, rs, j, sc);
+        } else {
+            const float4* qsrc = reinterpret_cast<const float4*>(q + (size_t)(row0 + j) * dq + (hkv * group + hl) * HD + 8 * gq);
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const float4 a = qsrc[8 * s], b = qsrc[8 * s + 1];
+                const float x[8] = {a.x * sc, a.y * sc, a.z * sc, a.w * sc, b.x * sc, b.y * sc, b.z * sc, b.w * sc};
+                split_frag(x, qh[rt][s], ql[rt][s]);
+            }
+        }
+    }
+
+    floatx4 acc[RT][DT];
+    float m_run[RT], l_run[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        m_run[rt] = -INFINITY;
+        l_run[rt] = 0.f;
+#pragma unroll
+        for (int d = 0; d < DT; ++d) acc[rt][d] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
     auto process = [&](int blk, const uint4(&kk)[2][STEPS], uint4(&vv)[DT]) {
         const int kbase = blk * 32;
         const bool tail = kbase + 32 > n || kbase >= key1;   // reaches the window / the end: mask per element
@@ -201,7 +286,73 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
     // Two blocks per trip, no branch inside: a block index past the chunk holds only positions
     // >= total, which the tail masking turns into zero weight, so an odd block count just ends with
     // one idle half trip.
-    load_block(blk0, ka, va);
+    if constexpr (FUSED) {
+        // The window's keys (rotated) and values of this kv head that fall into this chunk.  HD/8
+        // lanes share a position (each 4 rotary pairs of the key and 8 dims of the value), so a
+        // wavefront covers 8 positions per trip in rounds of 64 / (HD/8); each round's loads are issued
+        // together.  (Putting both rounds of a 128-dim head in flight at once costs registers the main
+        // loop needs: measured slower.)
+        const int w0 = max(key0, n), w1 = key1;   // positions [w0, w1) are window slots of this chunk
+        if (w0 < w1) {
+            constexpr int HALF = HD / 2, LP = HD / 8, PPR = 64 / LP, NR = 8 / PPR;
+            const int u = lane / LP, tq = lane % LP;
+            const int slot = t.seq_slot[b];
+            const int kcol = n_q_heads * HD + hkv * HD, vcol = (n_q_heads + g.n_kv_heads) * HD + hkv * HD;
+            for (int p0 = w0; p0 < w1; p0 += 8) {
+                float kr[NR][8], vr[NR][8];
+                int posr[NR];
+#pragma unroll
+                for (int h = 0; h < NR; ++h) {
+                    const int pc = min(p0 + PPR * h + u, w1 - 1);   // clamped: the loads are unconditional
+                    posr[h] = pc;
+                    const int m = row0 + (pc - n);
+                    const float rs = row_inv_rms(src.ns.ssq, src.ns.n_ssq, m, src.ns.d, src.ns.eps);
+                    const float* prow = src.partial + (size_t)m * src.ld;
+                    const int rpos = t.tree ? t.row_rope[m] : pc;
+                    const float* cols[4] = {prow + kcol + 4 * tq, prow + kcol + HALF + 4 * tq, prow + vcol + 8 * tq,
+                                            prow + vcol + 8 * tq + 4};
+                    float4 kv4[4];
+                    sum_splits4_many(cols, src.n_split, src.stride, kv4);
+                    const float a[4] = {kv4[0].x, kv4[0].y, kv4[0].z, kv4[0].w};
+                    const float bk[4] = {kv4[1].x, kv4[1].y, kv4[1].z, kv4[1].w};
+                    const float* cs = src.cos_sin + (size_t)rpos * HD + 2 * (4 * tq);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float c = cs[2 * e], sn = cs[2 * e + 1];
+                        const float x = a[e] * rs, y = bk[e] * rs;
+                        kr[h][e] = x * c - y * sn;
+                        kr[h][4 + e] = x * sn + y * c;
+                    }
+                    const float4 A = kv4[2], B = kv4[3];
+                    vr[h][0] = A.x * rs; vr[h][1] = A.y * rs; vr[h][2] = A.z * rs; vr[h][3] = A.w * rs;
+                    vr[h][4] = B.x * rs; vr[h][5] = B.y * rs; vr[h][6] = B.z * rs; vr[h][7] = B.w * rs;
+                }
+#pragma unroll
+                for (int h = 0; h < NR; ++h) {
+                    if (p0 + PPR * h + u < w1) {
+                        const size_t blk = cache_block_base(g, layer, slot, hkv, posr[h] >> 5);
+                        const int t32 = posr[h] & 31;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            cache_w[blk + tiled_k_within(HD, t32, 4 * tq + e)] =
+                                __builtin_bit_cast(uint16_t, static_cast<__bf16>(kr[h][e]));
+                            cache_w[blk + tiled_k_within(HD, t32, 4 * tq + e + HALF)] =
+                                __builtin_bit_cast(uint16_t, static_cast<__bf16>(kr[h][4 + e]));
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            cache_w[blk + tiled_v_within(HD, t32, 8 * tq + e)] =
+                                __builtin_bit_cast(uint16_t, static_cast<__bf16>(vr[h][e]));
+                    }
+                }
+            }
+            // the stores must have landed before this wavefront reads the blocks they belong to; only
+            // the first block was requested before them
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);
+            if (blk0 >= (w0 >> 5)) load_block(blk0, ka, va);
+        }
+    }
     for (int blk = blk0; blk < blk1; blk += 2) {
         load_block(blk + 1, kb, vb);
         process(blk, ka, va);
@@ -367,21 +518,31 @@ size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int gr
     return worst;
 }
 
+// The variants with 128-dim heads and three or four row tiles have no registers left for the fused
+// prologue (they would spill); those shapes keep the separate rotary/append kernel.
+constexpr bool fused_fits(int hd, int rt) { return !(hd == 128 && rt >= 3); }
+
 template <int HD>
 static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, const LookaheadPack& ks,
                          const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
-                         const AttnPlan& p, int r_cap, float sl2, float* part_o, float* part_ml)
+                         const AttnPlan& p, int r_cap, float sl2, float* part_o, float* part_ml, const QkvSrc& src,
+                         void* cache_w)
 {
+#define SPECV_ATTN_GO(RT, PG, FU)                                                                              \
+    hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, PG, FU>), grid, dim3(64), 0, s, t, ks, g, n_q_heads, layer,    \
+                       (const uint4*)cache, q, p.chunk_keys, p.max_chunks, r_cap, sl2, part_o, part_ml, src,     \
+                       (uint16_t*)cache_w)
 #define SPECV_ATTN(RT)                                                                                           \
     do {                                                                                                         \
-        if (g.table)                                                                                             \
-            hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, true>), grid, dim3(64), 0, s, t, ks, g, n_q_heads,     \
-                               layer, (const uint4*)cache, q, p.chunk_keys, p.max_chunks, r_cap, sl2, part_o,    \
-                               part_ml);                                                                         \
-        else                                                                                                     \
-            hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, false>), grid, dim3(64), 0, s, t, ks, g, n_q_heads,    \
-                               layer, (const uint4*)cache, q, p.chunk_keys, p.max_chunks, r_cap, sl2, part_o,    \
-                               part_ml);                                                                         \
+        if (src.partial) {                                                                                       \
+            if constexpr (fused_fits(HD, RT)) {                                                                  \
+                if (g.table) SPECV_ATTN_GO(RT, true, true);                                                      \
+                else SPECV_ATTN_GO(RT, false, true);                                                             \
+            } else {                                                                                             \
+                return fail(SPEC_ERR_SHAPE, "attention variant cannot take unfinished queries");                 \
+            }                                                                                                    \
+        } else if (g.table) SPECV_ATTN_GO(RT, true, false);                                                      \
+        else SPECV_ATTN_GO(RT, false, false);                                                                    \
     } while (0)
     switch (rt) {
     case 1: SPECV_ATTN(1); break;
@@ -391,14 +552,26 @@ static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, 
     default: return fail(SPEC_ERR_SHAPE, "attention supports at most 64 query rows per kv head");
     }
 #undef SPECV_ATTN
+#undef SPECV_ATTN_GO
     SPECV_LAUNCH_CHECK("attn_chunk_kernel");
     return SPEC_OK;
 }
 
+bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack& ks, int B)
+{
+    if (g.dtype != SPEC_DTYPE_BF16) return false;
+    int kmax = 0;
+    for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
+    const int rt = ((kmax + 1) * (n_q_heads / g.n_kv_heads) + 15) / 16;
+    return fused_fits(g.head_dim, rt);
+}
+
 int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,
                      int n_q_heads, int layer, const void* cache, const float* q, float* part_o, float* part_ml,
-                     const XOut& xo, int max_window, Profiler* prof, hipStream_t s)
+                     const XOut& xo, int max_window, Profiler* prof, hipStream_t s, const QkvSrc* qkv, void* cache_w)
 {
+    QkvSrc src{};
+    if (qkv) src = *qkv;
     const int hd = g.head_dim;
     const float scale = 1.0f / sqrtf((float)hd);
     if (g.dtype != SPEC_DTYPE_BF16) {
@@ -426,9 +599,9 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
     {
         ProfScope ps(prof, SPEC_PROF_ATTENTION, s);
         if (hd == 128)
-            rc = launch_chunks<128>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml);
+            rc = launch_chunks<128>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml, src, cache_w);
         else if (hd == 64)
-            rc = launch_chunks<64>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml);
+            rc = launch_chunks<64>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml, src, cache_w);
         else
             return fail(SPEC_ERR_SHAPE, "bf16 attention needs head_dim 64 or 128");
     }

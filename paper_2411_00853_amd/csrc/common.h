@@ -237,6 +237,19 @@ int launch_pack_x(const float* x, const float* gain, int M, int K, int mt_count,
 void set_gemm_wg_target(int workgroups);
 int launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* y, hipStream_t s);
 
+// The QKV projection's result as the attention kernel can take it directly (bf16 path): K-range
+// partial sums [n_split][M][ld] with columns q heads | k heads | v heads, the row scale of the
+// attention norm, and the rotary table.  partial == NULL: queries come rotated from `q`, and the
+// window's keys and values are already in the cache.
+struct QkvSrc {
+    const float* partial;
+    int n_split;
+    size_t stride;
+    int ld;
+    NormScale ns;
+    const float* cos_sin;
+};
+
 struct AttnPlan {
     int chunk_keys;   // keys per wavefront work item (multiple of 32)
     int max_chunks;   // chunks per (sequence, kv head) at max_kv_len
@@ -245,8 +258,12 @@ AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count,
 void set_attn_items_per_cu(int n);
 size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
                            int cu_count, bool paged = false);
+// Whether the bf16 attention kernel can take the QKV projection's partial sums itself (QkvSrc) for
+// this step's shapes; if not, launch_rope_append has to run first.
+bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack& ks, int B);
 int launch_attention(const AttnPlan& p, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M,
                      const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
-                     float* part_o, float* part_ml, const XOut& xo, int max_window, Profiler* prof, hipStream_t s);
+                     float* part_o, float* part_ml, const XOut& xo, int max_window, Profiler* prof, hipStream_t s,
+                     const QkvSrc* qkv = nullptr, void* cache_w = nullptr);
 
 }  // namespace specv

@@ -150,14 +150,23 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
 
     RUN(SPEC_PROF_GLUE, launch_embed(c.dtype, h->tok_embed, t.row_tok, M, z.d, h->x, h->ssq, h->layers[0].attn_norm, to_xf, s));
     Out o;
+    const bool fuse = h->fuse_rope && attention_takes_qkv(h->geom, c.n_q_heads, ks, B);
     for (int l = 0; l < c.n_layers; ++l) {
         const spec_layer_weights& w = h->layers[l];
         rc = gemm(h->x, w.attn_norm, w.w_qkv, z.nqkv, z.d, &o);
         if (rc) return rc;
-        RUN(SPEC_PROF_GLUE, launch_rope_append(h->partial, o.n_split, o.stride, o.ld, t, M, h->geom, c.n_q_heads, l, h->cos_sin,
-                               scaled, h->kv_cache, h->q, s));
-        rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache, h->q, h->attn_part_o,
-                              h->attn_part_ml, to_att, c.max_lookahead + 1, &h->prof, s);
+        if (fuse) {
+            // the attention kernel adds up, scales and rotates q, k, v itself and appends k, v
+            const QkvSrc qkv{h->partial, o.n_split, o.stride, o.ld, scaled, h->cos_sin};
+            rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache,
+                                  h->q, h->attn_part_o, h->attn_part_ml, to_att, c.max_lookahead + 1, &h->prof, s, &qkv,
+                                  h->kv_cache);
+        } else {
+            RUN(SPEC_PROF_GLUE, launch_rope_append(h->partial, o.n_split, o.stride, o.ld, t, M, h->geom, c.n_q_heads, l,
+                                                   h->cos_sin, scaled, h->kv_cache, h->q, s));
+            rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache,
+                                  h->q, h->attn_part_o, h->attn_part_ml, to_att, c.max_lookahead + 1, &h->prof, s);
+        }
         if (rc) return rc;
         rc = gemm(h->att, nullptr, w.w_o, z.d, z.dq, &o);
         if (rc) return rc;

@@ -57,11 +57,21 @@ __host__ __device__ inline size_t xfrag_uint4s(int mt_count, int planes, int K)
 }
 
 // 1 / rms of a row from its partial sums of squares (eps inside the root); ssq == NULL -> 1
+// The partial sums are fetched eight at a time with clamped indices (surplus values dropped), so that
+// all loads of a batch are in flight together: a plain loop over a run-time count waits for every
+// load in turn, and this sits on the critical path of kernels that are nothing but latency.
 __device__ __forceinline__ float row_inv_rms(const float* ssq, int n_ssq, int m, int d, float eps)
 {
     if (!ssq) return 1.f;
     float ss = 0.f;
-    for (int i = 0; i < n_ssq; ++i) ss += ssq[(size_t)m * n_ssq + i];
+    const float* p = ssq + (size_t)m * n_ssq;
+    for (int i0 = 0; i0 < n_ssq; i0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = p[min(i0 + i, n_ssq - 1)];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ss += (i0 + i < n_ssq) ? v[i] : 0.f;
+    }
     return 1.0f / sqrtf(ss / (float)d + eps);
 }
 
