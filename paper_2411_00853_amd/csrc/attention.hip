@@ -401,19 +401,55 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(StepTables t, LookaheadP
         const int total = t.seq_n[b] + ks.k[b] + 1;
         const int n_chunks = (total + chunk_keys - 1) / chunk_keys;
         const size_t item0 = ((size_t)b * n_kv_heads + hq / group) * max_chunks;
+        // Chunks are taken eight at a time, every load of a batch issued before the first use
+        // (indices past the end clamped, their terms dropped), so that a batch costs one memory round
+        // trip; a loop that loads, tests and then loads again per chunk pays two per chunk.  The
+        // arithmetic is the plain definition: global max first, then the weighted sums in chunk order.
+        constexpr int MB = 8;
+        auto ml_at = [&](int c) {
+            return *reinterpret_cast<const float2*>(part_ml + ((item0 + min(c, n_chunks - 1)) * r_cap + r) * 2);
+        };
+        float2 ml0[MB];
+        float4 oa[MB], ob[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            ml0[i] = ml_at(i);
+            const float* po = part_o + ((item0 + min(i, n_chunks - 1)) * r_cap + r) * hd + d8 * 8;
+            oa[i] = *reinterpret_cast<const float4*>(po);
+            ob[i] = *reinterpret_cast<const float4*>(po + 4);
+        }
         float mx = -INFINITY;
-        for (int c = 0; c < n_chunks; ++c) mx = fmaxf(mx, part_ml[((item0 + c) * r_cap + r) * 2]);
+#pragma unroll
+        for (int i = 0; i < MB; ++i) mx = fmaxf(mx, i < n_chunks ? ml0[i].x : -INFINITY);
+        for (int c0 = MB; c0 < n_chunks; c0 += MB) {
+            float2 t2[MB];
+#pragma unroll
+            for (int i = 0; i < MB; ++i) t2[i] = ml_at(c0 + i);
+#pragma unroll
+            for (int i = 0; i < MB; ++i) mx = fmaxf(mx, c0 + i < n_chunks ? t2[i].x : -INFINITY);
+        }
         float den = 0.f;
-        for (int c = 0; c < n_chunks; ++c) {
-            const size_t idx = (item0 + c) * r_cap + r;
-            const float mc = part_ml[idx * 2];
-            if (mc == -INFINITY) continue;   // chunk entirely after this query's position
-            const float w = exp2f(mc - mx);
-            den += w * part_ml[idx * 2 + 1];
-            const float4 a = *reinterpret_cast<const float4*>(part_o + idx * hd + d8 * 8);
-            const float4 bq = *reinterpret_cast<const float4*>(part_o + idx * hd + d8 * 8 + 4);
-            v[0] += w * a.x; v[1] += w * a.y; v[2] += w * a.z; v[3] += w * a.w;
-            v[4] += w * bq.x; v[5] += w * bq.y; v[6] += w * bq.z; v[7] += w * bq.w;
+        auto add = [&](bool use, float2 ml, const float4& a, const float4& bq) {
+            // a chunk entirely after this query's position has max -inf and takes no part
+            const bool on = use && ml.x != -INFINITY;
+            const float w = on ? exp2f(ml.x - mx) : 0.f;
+            den += on ? w * ml.y : 0.f;
+            v[0] += on ? w * a.x : 0.f; v[1] += on ? w * a.y : 0.f; v[2] += on ? w * a.z : 0.f; v[3] += on ? w * a.w : 0.f;
+            v[4] += on ? w * bq.x : 0.f; v[5] += on ? w * bq.y : 0.f; v[6] += on ? w * bq.z : 0.f; v[7] += on ? w * bq.w : 0.f;
+        };
+#pragma unroll
+        for (int i = 0; i < MB; ++i) add(i < n_chunks, ml0[i], oa[i], ob[i]);
+        for (int c0 = MB; c0 < n_chunks; c0 += MB) {
+            float2 t2[MB];
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                t2[i] = ml_at(c0 + i);
+                const float* po = part_o + ((item0 + min(c0 + i, n_chunks - 1)) * r_cap + r) * hd + d8 * 8;
+                oa[i] = *reinterpret_cast<const float4*>(po);
+                ob[i] = *reinterpret_cast<const float4*>(po + 4);
+            }
+#pragma unroll
+            for (int i = 0; i < MB; ++i) add(c0 + i < n_chunks, t2[i], oa[i], ob[i]);
         }
         const float inv = 1.0f / den;
 #pragma unroll

@@ -108,8 +108,10 @@ __global__ void __launch_bounds__(TPB) silu_mul_kernel(const float* __restrict__
         const float r = row_inv_rms(ns.ssq, ns.n_ssq, m, ns.d, ns.eps);
         const float* pg = partial + (size_t)m * ld + cg;
         const float* pu = partial + (size_t)m * ld + cu;
-        const float4 g0 = sum_splits4(pg, n_split, split_stride), g1 = sum_splits4(pg + 4, n_split, split_stride);
-        const float4 u0 = sum_splits4(pu, n_split, split_stride), u1 = sum_splits4(pu + 4, n_split, split_stride);
+        const float* cols[4] = {pg, pg + 4, pu, pu + 4};
+        float4 sums[4];
+        sum_splits4_many(cols, n_split, split_stride, sums);   // one memory round trip for all four
+        const float4 g0 = sums[0], g1 = sums[1], u0 = sums[2], u1 = sums[3];
         const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
         const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
         float v[8];
