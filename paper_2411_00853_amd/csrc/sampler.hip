@@ -183,10 +183,29 @@ __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack 
 __device__ __forceinline__ void combine_row(const float* pm, const double* ps, int n_chunks, double inv_T, float* m_out,
                                             double* z_out)
 {
+    // chunks eight at a time, the loads of a batch issued together (indices past the end clamped,
+    // their terms dropped): a plain loop over a run-time count waits for every load in turn
     float m = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, pm[c]);
+    for (int c0 = 0; c0 < n_chunks; c0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = pm[min(c0 + i, n_chunks - 1)];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) m = fmaxf(m, v[i]);   // a repeated value does not change the maximum
+    }
     double z = 0.0;
-    for (int c = 0; c < n_chunks; ++c) z += ps[c] * exp((double)(pm[c] - m) * inv_T);
+    for (int c0 = 0; c0 < n_chunks; c0 += 8) {
+        float v[8];
+        double sv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            v[i] = pm[min(c0 + i, n_chunks - 1)];
+            sv[i] = ps[min(c0 + i, n_chunks - 1)];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (c0 + i < n_chunks) z += sv[i] * exp((double)(v[i] - m) * inv_T);
+    }
     *m_out = m;
     *z_out = z;
 }
@@ -220,9 +239,12 @@ __global__ void __launch_bounds__(TPB) accept_mass_kernel(StepTables t, Lookahea
     __syncthreads();
     const float* trow0 = target + (size_t)t.seq_row0[b] * V;
     const float* drow0 = draft + (size_t)b * Kmax * V;
-    if (threadIdx.x == 0) {
-        int a = K;
-        for (int i = 0; i < K; ++i) {
+    if (threadIdx.x < 64) {
+        // lane i tests proposal i (all positions at once: the tests are independent, only the first
+        // failure matters); padding lanes repeat the last proposal and are masked out
+        const int i = min((int)threadIdx.x, max(K - 1, 0));
+        bool keep = true;
+        if (K > 0) {
             const int x = draft_tokens[b * Kmax + i];
             const bool xin = x >= 0 && x < V;   // out-of-range ids were flagged by prepare; stay in bounds
             const float lp = xin ? trow0[(size_t)i * V + x] : 0.f;
@@ -231,9 +253,10 @@ __global__ void __launch_bounds__(TPB) accept_mass_kernel(StepTables t, Lookahea
             const double eq = exp((double)(lq - row_m[K + 1 + i]) * inv_T);
             // keep iff u * q(x) < p(x)  <=>  u * eq * Zp < ep * Zq
             const double u = (double)uniforms[b * u_stride + i];
-            if (!(u * eq * row_z[i] < ep * row_z[K + 1 + i])) { a = i; break; }
+            keep = u * eq * row_z[i] < ep * row_z[K + 1 + i];
         }
-        s_a = a;
+        const unsigned long long failed = __ballot(!keep && (int)threadIdx.x < K);
+        if (threadIdx.x == 0) s_a = failed ? __builtin_ctzll(failed) : K;
     }
     __syncthreads();
     const int a = s_a;
@@ -303,7 +326,14 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
     }
     const int a = w.accepted[b];
     bool residual = a < K;
+    // the chunk masses, fetched by as many lanes at once and then walked by one from LDS
+    __shared__ double s_mass[TPB];
     const double* mass = w.chunk_mass + (size_t)b * n_res_chunks;
+    if (n_res_chunks <= TPB) {
+        if ((int)threadIdx.x < n_res_chunks) s_mass[threadIdx.x] = mass[threadIdx.x];
+        __syncthreads();
+        mass = s_mass;
+    }
     if (threadIdx.x == 0) {
         double S = 0.0;
         for (int c = 0; c < n_res_chunks; ++c) S += mass[c];
