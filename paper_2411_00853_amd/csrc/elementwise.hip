@@ -64,7 +64,10 @@ __global__ void __launch_bounds__(UNIT_TPB) resid_kernel(const T* __restrict__ E
         } else {
             const float4 a = *reinterpret_cast<const float4*>(xp), b = *reinterpret_cast<const float4*>(xp + 4);
             const float* pp = partial + (size_t)m * ld + k8 * 8;
-            const float4 pa = sum_splits4(pp, n_split, split_stride), pb = sum_splits4(pp + 4, n_split, split_stride);
+            const float* cols[2] = {pp, pp + 4};
+            float4 sums[2];
+            sum_splits4_many<2, 8>(cols, n_split, split_stride, sums);   // up to 8 ranges in one round trip
+            const float4 pa = sums[0], pb = sums[1];
             v[0] = a.x + pa.x; v[1] = a.y + pa.y; v[2] = a.z + pa.z; v[3] = a.w + pa.w;
             v[4] = b.x + pb.x; v[5] = b.y + pb.y; v[6] = b.z + pb.z; v[7] = b.w + pb.w;
         }

@@ -270,14 +270,25 @@ __global__ void __launch_bounds__(TPB) accept_mass_kernel(StepTables t, Lookahea
 
     const int base = chunk * RES_CHUNK;
     const int lim = min(RES_CHUNK, V - base);
+    // all of a lane's logits are requested before the first is used (indices past the end clamped,
+    // their terms dropped): one memory round trip instead of one per element
+    constexpr int PER = RES_CHUNK / TPB;
+    float lp[PER], lq[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) lp[k] = prow[base + min((int)threadIdx.x + k * TPB, lim - 1)];
+    if (residual) {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) lq[k] = qrow[base + min((int)threadIdx.x + k * TPB, lim - 1)];
+    }
     double acc = 0.0;
-    for (int i = threadIdx.x; i < lim; i += TPB) {
-        double pv = (double)__expf((prow[base + i] - mp) * inv_T_f) * izp;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        double pv = (double)__expf((lp[k] - mp) * inv_T_f) * izp;
         if (residual) {
-            double qv = (double)__expf((qrow[base + i] - mq) * inv_T_f) * izq;
+            double qv = (double)__expf((lq[k] - mq) * inv_T_f) * izq;
             pv = pv > qv ? pv - qv : 0.0;
         }
-        acc += pv;
+        if ((int)threadIdx.x + k * TPB < lim) acc += pv;
     }
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) ssum[threadIdx.x >> 6] = acc;
@@ -378,16 +389,25 @@ __global__ void __launch_bounds__(TPB) final_draw_kernel(StepTables t, Lookahead
         const int base = c * RES_CHUNK;
         const int lim = min(RES_CHUNK, V - base);
         __syncthreads();
-        for (int i = threadIdx.x; i < RES_CHUNK; i += TPB) {
-            double pv = 0.0;
-            if (i < lim) {
-                pv = (double)__expf((prow[base + i] - mp) * inv_T_f) * izp;
+        {
+            // all loads first (clamped), then the arithmetic: one memory round trip per chunk
+            float lp[PER], lq[PER];
+#pragma unroll
+            for (int k = 0; k < PER; ++k) lp[k] = prow[base + min((int)threadIdx.x + k * TPB, lim - 1)];
+            if (residual) {
+#pragma unroll
+                for (int k = 0; k < PER; ++k) lq[k] = qrow[base + min((int)threadIdx.x + k * TPB, lim - 1)];
+            }
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const int i = threadIdx.x + k * TPB;
+                double pv = (double)__expf((lp[k] - mp) * inv_T_f) * izp;
                 if (residual) {
-                    double qv = (double)__expf((qrow[base + i] - mq) * inv_T_f) * izq;
+                    double qv = (double)__expf((lq[k] - mq) * inv_T_f) * izq;
                     pv = pv > qv ? pv - qv : 0.0;
                 }
+                r[i] = i < lim ? pv : 0.0;
             }
-            r[i] = pv;
         }
         __syncthreads();
         // lane-local sums of 16 consecutive ids, then an inclusive scan over the 256 lanes

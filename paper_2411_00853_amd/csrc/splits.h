@@ -56,25 +56,25 @@ __device__ __forceinline__ float sum_splits(const float* p, int n_split, size_t 
     return sum_splits_w<8>(p, n_split, stride);
 }
 
-// Many sums at once: N float4 columns of one row, all loads of a batch of (up to) four ranges issued
+// Many sums at once: N float4 columns of one row, all loads of a batch of (up to) W ranges issued
 // before the first addition (calling sum_splits4 N times makes N dependent round trips: the
 // compiler keeps each call's loads next to its additions).  Ranges are added in index order.
-template <int N>
+template <int N, int W = 4>
 __device__ __forceinline__ void sum_splits4_many(const float* const (&p)[N], int n_split, size_t stride, float4 (&out)[N])
 {
 #pragma unroll
     for (int x = 0; x < N; ++x) out[x] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s0 = 0; s0 < n_split; s0 += 4) {
-        float4 a[N][4];
+    for (int s0 = 0; s0 < n_split; s0 += W) {
+        float4 a[N][W];
 #pragma unroll
         for (int x = 0; x < N; ++x)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < W; ++i)
                 a[x][i] = *reinterpret_cast<const float4*>(p[x] + (size_t)min(s0 + i, n_split - 1) * stride);
 #pragma unroll
         for (int x = 0; x < N; ++x)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < W; ++i) {
                 const bool ok = s0 + i < n_split;
                 out[x].x += ok ? a[x][i].x : 0.f; out[x].y += ok ? a[x][i].y : 0.f;
                 out[x].z += ok ? a[x][i].z : 0.f; out[x].w += ok ? a[x][i].w : 0.f;
