@@ -36,6 +36,15 @@ __device__ __forceinline__ void split_frag(const float (&x)[8], Frag& hi, Frag& 
     }
 }
 
+// A sequence's positions are cut into max_chunks equal runs of whole 32-position blocks (at least
+// 128 positions each), from its own current length: the launch is sized for the longest sequence
+// the cache can hold, but a shorter one still spreads over all of its wavefronts.
+__device__ __forceinline__ int seq_chunk_keys(int total, int max_chunks)
+{
+    const int per = (total + max_chunks - 1) / max_chunks;
+    return max((per + 31) & ~31, 128);
+}
+
 // PAGED: the blocks of a slot are looked up in the page table.  A wavefront keeps the page numbers
 // of its chunk's (at most 64) blocks one per lane and broadcasts the one it needs, so the address
 // of a prefetch never waits for memory.
@@ -47,7 +56,7 @@ __device__ __forceinline__ void split_frag(const float (&x)[8], Frag& hi, Frag& 
 template <int HD, int RT, bool PAGED, bool FUSED>
 __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadPack ks, CacheGeom g, int n_q_heads,
                                                         int layer, const uint4* cache,
-                                                        const float* __restrict__ q, int chunk_keys, int max_chunks,
+                                                        const float* __restrict__ q, int max_chunks,
                                                         int r_cap, float scale_log2e, float* __restrict__ part_o,
                                                         float* __restrict__ part_ml, QkvSrc src, uint16_t* cache_w)
 {
@@ -63,9 +72,10 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
     const int K = ks.k[b];
     const int n = t.seq_n[b];
     const int total = n + K + 1;
-    const int key0 = chunk * chunk_keys;
+    const int ck = seq_chunk_keys(total, max_chunks);
+    const int key0 = chunk * ck;
     if (key0 >= total) return;
-    const int key1 = min(key0 + chunk_keys, total);
+    const int key1 = min(key0 + ck, total);
     const int group = n_q_heads / g.n_kv_heads;
     const int rows = (K + 1) * group;
     const int dq = n_q_heads * HD;
@@ -383,7 +393,7 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
 // One thread per 8 consecutive dims of a (row, query head); the result goes out as the output
 // projection's operand fragments.
 __global__ void __launch_bounds__(64) attn_merge_kernel(StepTables t, LookaheadPack ks, int n_kv_heads, int n_q_heads,
-                                                        int hd, int chunk_keys, int max_chunks, int r_cap,
+                                                        int hd, int max_chunks, int r_cap,
                                                         const float* __restrict__ part_o,
                                                         const float* __restrict__ part_ml, XOut xo)
 {
@@ -399,7 +409,8 @@ __global__ void __launch_bounds__(64) attn_merge_kernel(StepTables t, LookaheadP
         const int j = m - t.seq_row0[b];
         const int r = j * group + hq % group;
         const int total = t.seq_n[b] + ks.k[b] + 1;
-        const int n_chunks = (total + chunk_keys - 1) / chunk_keys;
+        const int ck = seq_chunk_keys(total, max_chunks);
+        const int n_chunks = (total + ck - 1) / ck;
         const size_t item0 = ((size_t)b * n_kv_heads + hq / group) * max_chunks;
         // Chunks are taken eight at a time, every load of a batch issued before the first use
         // (indices past the end clamped, their terms dropped), so that a batch costs one memory round
@@ -566,7 +577,7 @@ static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, 
 {
 #define SPECV_ATTN_GO(RT, PG, FU)                                                                              \
     hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, PG, FU>), grid, dim3(64), 0, s, t, ks, g, n_q_heads, layer,    \
-                       (const uint4*)cache, q, p.chunk_keys, p.max_chunks, r_cap, sl2, part_o, part_ml, src,     \
+                       (const uint4*)cache, q, p.max_chunks, r_cap, sl2, part_o, part_ml, src,                   \
                        (uint16_t*)cache_w)
 #define SPECV_ATTN(RT)                                                                                           \
     do {                                                                                                         \
@@ -644,7 +655,7 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
     if (rc) return rc;
     ProfScope ps(prof, SPEC_PROF_ATTN_MERGE, s);
     hipLaunchKernelGGL(attn_merge_kernel, dim3(M, (n_q_heads * hd / 8 + 63) / 64), dim3(64), 0, s, t, ks, g.n_kv_heads,
-                       n_q_heads, hd, p.chunk_keys, p.max_chunks, r_cap, part_o, part_ml, xo);
+                       n_q_heads, hd, p.max_chunks, r_cap, part_o, part_ml, xo);
     SPECV_LAUNCH_CHECK("attn_merge_kernel");
     return SPEC_OK;
 }
