@@ -739,7 +739,7 @@ __global__ void __launch_bounds__(TREE_TPB) tree_walk_kernel(StepTables t, Looka
     __shared__ double level_S[MAXN + 1];     // level_S[k]: mass of the unnormalised r_k, k >= 1
     __shared__ double wsum[TREE_TPB / 64];
     __shared__ double r[RES_CHUNK];
-    __shared__ int s_flag, s_tok, s_chunk;
+    __shared__ int s_tok, s_chunk;
     __shared__ double s_val, s_before, s_target;
     const int b = blockIdx.x;
     const int N = ks.k[b];
@@ -790,14 +790,28 @@ __global__ void __launch_bounds__(TREE_TPB) tree_walk_kernel(StepTables t, Looka
         return tot;
     };
 
+    // What the test of node c needs from memory does not depend on the walk (a node is always tested
+    // against its parent's rows): lane c fetches it for all nodes at once, and every thread then
+    // takes the same decisions from LDS -- no load and no barrier per tested node.
+    __shared__ int s_par[MAXN], s_ntok[MAXN];
+    __shared__ double s_ep[MAXN], s_eq[MAXN], s_u[MAXN];
+    if ((int)threadIdx.x < N) {
+        const int c = threadIdx.x;
+        const int pr = par[c] + 1;                 // row of the parent (0: the root)
+        const int x = tok[c];
+        s_par[c] = par[c];
+        s_ntok[c] = x;
+        s_u[c] = (double)uniforms[b * (Kmax + 1) + c];
+        s_ep[c] = exp((double)(trow0[(size_t)pr * V + x] - row_m[pr]) * inv_T);
+        s_eq[c] = exp((double)(drow0[(size_t)pr * V + x] - row_m[N + 1 + pr]) * inv_T);
+    }
+    __syncthreads();
+
     for (int c = 0; c < N; ++c) {
-        if (par[c] != cur) continue;
-        if (threadIdx.x == 0) {
-            const int x = tok[c];
-            const double u = (double)uniforms[b * (Kmax + 1) + c];
-            const double ep = exp((double)(prow[x] - mp) * inv_T);
-            const double eq = exp((double)(qrow[x] - mq) * inv_T);
-            bool keep;
+        if (s_par[c] != cur) continue;
+        bool keep;
+        {
+            const double u = s_u[c], ep = s_ep[c], eq = s_eq[c];
             if (level == 0) {
                 keep = u * eq * row_z[cur + 1] < ep * row_z[N + 1 + cur + 1];   // u q(x) < p(x), division-free
             } else {
@@ -810,15 +824,11 @@ __global__ void __launch_bounds__(TREE_TPB) tree_walk_kernel(StepTables t, Looka
                 }
                 keep = u * qx * level_S[level] < rx;   // u q(x) < r(x) / S
             }
-            s_flag = keep ? 1 : 0;
         }
-        __syncthreads();
-        const bool keep = s_flag != 0;
-        __syncthreads();
         if (keep) {
             if (threadIdx.x == 0) {
                 out.path[b * Kmax + a] = c;
-                out.out_tokens[b * (Kmax + 1) + a] = tok[c];
+                out.out_tokens[b * (Kmax + 1) + a] = s_ntok[c];
             }
             ++a;
             cur = c;
@@ -834,12 +844,22 @@ __global__ void __launch_bounds__(TREE_TPB) tree_walk_kernel(StepTables t, Looka
         // rejected: mass of max(0, r/S - q)
         double acc = 0.0;
         const double div = level > 0 ? level_S[level] : 1.0;
-        for (int v = threadIdx.x; v < V; v += TREE_TPB) {
-            const float lq = qrow[v];
-            double pv = resid(prow[v], lq, level);
-            if (level > 0) pv = pv / div;
-            const double qv = (double)__expf((lq - mq) * inv_T_f) * izq;
-            acc += pv > qv ? pv - qv : 0.0;
+        for (int v0 = threadIdx.x; v0 < V; v0 += 8 * TREE_TPB) {
+            // eight elements per trip, loads first (indices past the end clamped, their terms dropped)
+            float lpv[8], lqv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int v = min(v0 + k * TREE_TPB, V - 1);
+                lpv[k] = prow[v];
+                lqv[k] = qrow[v];
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                double pv = resid(lpv[k], lqv[k], level);
+                if (level > 0) pv = pv / div;
+                const double qv = (double)__expf((lqv[k] - mq) * inv_T_f) * izq;
+                if (v0 + k * TREE_TPB < V) acc += pv > qv ? pv - qv : 0.0;
+            }
         }
         const double S_new = block_sum(acc);
         if (S_new > 0.0) {   // <= 0 cannot happen in exact arithmetic; then r stays as it is
@@ -859,7 +879,18 @@ __global__ void __launch_bounds__(TREE_TPB) tree_walk_kernel(StepTables t, Looka
             const int base = cc * RES_CHUNK;
             const int lim = min(RES_CHUNK, V - base);
             double acc = 0.0;
-            for (int i = threadIdx.x; i < lim; i += TREE_TPB) acc += resid(prow[base + i], qrow[base + i], level);
+            {
+                float lpv[PER], lqv[PER];
+#pragma unroll
+                for (int k = 0; k < PER; ++k) {
+                    const int i = min((int)threadIdx.x + k * TREE_TPB, lim - 1);
+                    lpv[k] = prow[base + i];
+                    lqv[k] = qrow[base + i];
+                }
+#pragma unroll
+                for (int k = 0; k < PER; ++k)
+                    if ((int)threadIdx.x + k * TREE_TPB < lim) acc += resid(lpv[k], lqv[k], level);
+            }
             const double m = block_sum(acc);
             if (threadIdx.x == 0) mass[cc - c0] = m;
         }
@@ -891,8 +922,20 @@ __global__ void __launch_bounds__(TREE_TPB) tree_walk_kernel(StepTables t, Looka
         const int base = s_chunk * RES_CHUNK;
         const int lim = min(RES_CHUNK, V - base);
         const double before = s_before, target_mass = s_target;
-        for (int i = threadIdx.x; i < RES_CHUNK; i += TREE_TPB)
-            r[i] = i < lim ? resid(prow[base + i], qrow[base + i], level) : 0.0;
+        {
+            float lpv[PER], lqv[PER];
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const int i = min((int)threadIdx.x + k * TREE_TPB, lim - 1);
+                lpv[k] = prow[base + i];
+                lqv[k] = qrow[base + i];
+            }
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const int i = threadIdx.x + k * TREE_TPB;
+                r[i] = i < lim ? resid(lpv[k], lqv[k], level) : 0.0;
+            }
+        }
         __syncthreads();
         double loc = 0.0;
         int my_last = -1;
