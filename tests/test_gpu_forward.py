@@ -140,6 +140,43 @@ def test_small_bf16_models_ragged_batch(shape):
     assert err < 5e-3     # head + remainder operands keep the error far below the bf16 bound
 
 
+@pytest.mark.parametrize("shape,kmax,look", [
+    # 8 query heads per kv head: (K+1)*8 query rows per kv head
+    (wl.ModelShape(2, 512, 8, 1, 128, 512, 1000), 5, [5, 0, 3, 2]),   # 48 rows, 128-dim heads: separate rotary kernel
+    (wl.ModelShape(2, 512, 8, 1, 128, 512, 1000), 7, [7, 1, 4, 0]),   # 64 rows, 128-dim heads
+    (wl.ModelShape(2, 512, 8, 1, 64, 512, 1000), 7, [7, 1, 4, 0]),    # 64 rows, 64-dim heads: merged kernel
+])
+def test_wide_query_groups(shape, kmax, look):
+    rig = Rig(shape, 4, 200, kmax, seed=4, std=0.05)
+    rng = wl.Rng(9, "cpu")
+    lens = {0: 61, 1: 35, 2: 0, 3: 140}
+    for s, n in lens.items():
+        rig.prefill(s, rng.randint(30 + s, (n,), shape.vocab).tolist())
+    slots = [3, 0, 2, 1]
+    err, chk, na, ot, logits, want = _check_step(rig, slots, [5, 6, 7, 8], look, 0.9, 13)
+    assert err < 5e-3
+    # the window's keys and values are where the oracle put them (whichever kernel wrote them)
+    for s, k in zip(slots, look):
+        n = lens[s]
+        got = torch.empty((shape.n_layers, 2, shape.n_kv_heads, k + 1, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+        rig.sv.spec_kv_export(rig.h, s, n, got)
+        torch.cuda.synchronize()
+        ref = rig.caches[s][:, :, :, n:n + k + 1, :]
+        assert (got.cpu().float() - ref.float()).abs().max().item() < 2e-2
+
+
+def test_sequences_far_below_the_cache_capacity():
+    """The launch is sized for max_kv_len; every sequence cuts its own length into the chunks."""
+    shape = wl.ModelShape(2, 256, 4, 2, 64, 256, 512)
+    rig = Rig(shape, 3, 4000, 4, seed=6, std=0.05)
+    rng = wl.Rng(10, "cpu")
+    lens = {0: 700, 1: 130, 2: 3}
+    for s, n in lens.items():
+        rig.prefill(s, rng.randint(40 + s, (n,), shape.vocab).tolist())
+    err, chk, na, ot, logits, want = _check_step(rig, [0, 1, 2], [5, 6, 7], [4, 2, 3], 0.9, 14)
+    assert err < 5e-3
+
+
 def test_step_rollback_step_reproduces_bits_and_ignores_stale_slots():
     shape = wl.ModelShape(2, 256, 4, 2, 64, 256, 512)
     rig = Rig(shape, 2, 96, 4, seed=5, std=0.05)
