@@ -114,14 +114,49 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
 #pragma unroll
         for (int u = 0; u < UPT; ++u) xs[buf][xoff[u]] = xr[u];
     };
+    auto x_frag = [&](int buf, int c, int plane, int a) {
+        return __builtin_bit_cast(bf16x8, xs[buf][((c * PLANES + plane) * MT + a) * 64 + lane]);
+    };
     auto compute = [&](const u32x4(&w)[KC][NT], int buf) {
+        if constexpr (MT >= 3) {
+            // One wavefront per SIMD: nothing else fills the matrix pipeline while this wave waits
+            // for an LDS read, so the fragments of row tile t+1 are requested before the products of
+            // tile t are issued, and the instruction order is pinned (2 LDS reads, then the 2*NT
+            // products of the previous reads); left to itself the scheduler reads, waits, multiplies.
+            bf16x8 xh = x_frag(buf, 0, 0, 0), xl = xh;
+            if constexpr (PLANES == 2) xl = x_frag(buf, 0, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, PLANES, 0);            // LDS reads of tile 0
+#pragma unroll
+            for (int t = 0; t < KC * MT; ++t) {
+                const int c = t / MT, a = t % MT;
+                bf16x8 nh = xh, nl = xl;
+                if (t + 1 < KC * MT) {
+                    nh = x_frag(buf, (t + 1) / MT, 0, (t + 1) % MT);
+                    nl = nh;
+                    if constexpr (PLANES == 2) nl = x_frag(buf, (t + 1) / MT, 1, (t + 1) % MT);
+                }
+#pragma unroll
+                for (int i = 0; i < NT; ++i)
+                    acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xh, __builtin_bit_cast(bf16x8, w[c][i]), acc[a][i], 0, 0, 0);
+                if constexpr (PLANES == 2) {
+#pragma unroll
+                    for (int i = 0; i < NT; ++i)
+                        acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xl, __builtin_bit_cast(bf16x8, w[c][i]), acc[a][i], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, PLANES, 0);        // LDS reads of tile t+1
+                __builtin_amdgcn_sched_group_barrier(0x008, PLANES * NT, 0);   // products of tile t
+                xh = nh;
+                xl = nl;
+            }
+            return;
+        }
 #pragma unroll
         for (int c = 0; c < KC; ++c)
 #pragma unroll
             for (int a = 0; a < MT; ++a) {
-                const bf16x8 xh = __builtin_bit_cast(bf16x8, xs[buf][((c * PLANES + 0) * MT + a) * 64 + lane]);
+                const bf16x8 xh = x_frag(buf, c, 0, a);
                 bf16x8 xl = xh;
-                if constexpr (PLANES == 2) xl = __builtin_bit_cast(bf16x8, xs[buf][((c * PLANES + 1) * MT + a) * 64 + lane]);
+                if constexpr (PLANES == 2) xl = x_frag(buf, c, 1, a);
 #pragma unroll
                 for (int i = 0; i < NT; ++i) {
                     const bf16x8 wf = __builtin_bit_cast(bf16x8, w[c][i]);
@@ -132,6 +167,57 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
             }
     };
 
+    if constexpr (MT >= 6) {
+        // Many row tiles: a chunk's products take about as long as a memory round trip, and with two W
+        // buffers the loads of chunk j+2 can only be issued after the products of chunk j (they reuse
+        // its registers), so products and waiting alternate instead of overlapping.  A third W buffer
+        // lets the loads of chunk j+2 go out BEFORE the products of chunk j, and three X register
+        // sets keep the fragments of chunks j+2..j+4 in flight (X is the larger of the two streams
+        // here and misses L2 as often as not).  One K block per chunk (KC == 1): no chunk is partial,
+        // nothing needs masking; loads past the range are redirected to its last block and their
+        // chunks never multiplied.
+        static_assert(MT < 6 || KC == 1, "the three-buffer pipeline takes one K block per chunk");
+        u32x4 wc[KC][NT];
+        u32x4 x0[UPT], x1[UPT], x2[UPT];
+        auto load_xs = [&](int kbase, u32x4(&dst)[UPT]) {
+            const u32x4* src = Xf + (size_t)min(kbase, kb1 - 1) * (PLANES * MT * 64);
+#pragma unroll
+            for (int u = 0; u < UPT; ++u) dst[u] = src[xoff[u]];
+        };
+        auto store_xs = [&](int buf, const u32x4(&from)[UPT]) {
+#pragma unroll
+            for (int u = 0; u < UPT; ++u) xs[buf][xoff[u]] = from[u];
+        };
+        const int n_chunks = kb1 - kb0;
+        // step j: W of chunk j+2 requested, chunk j multiplied, chunk j+1's X (set xn, fetched three
+        // steps ago) put into the other LDS buffer, chunk j+4's X requested into the same set
+        auto step = [&](int j, const u32x4(&cur)[KC][NT], u32x4(&ahead)[KC][NT], u32x4(&xn)[UPT]) {
+            load_w(kb0 + j + 2, ahead);
+            compute(cur, j & 1);
+            store_xs((j + 1) & 1, xn);
+            load_xs(kb0 + j + 4, xn);
+            __syncthreads();
+        };
+        load_w(kb0, wa);
+        __builtin_amdgcn_sched_barrier(0);
+        load_xs(kb0, x0);
+        load_xs(kb0 + 1, x1);
+        load_xs(kb0 + 2, x2);
+        load_w(kb0 + 1, wb);
+        store_xs(0, x0);
+        load_xs(kb0 + 3, x0);
+        __syncthreads();
+        int j = 0;
+        for (; j + 3 <= n_chunks; j += 3) {
+            step(j, wa, wc, x1);
+            step(j + 1, wb, wa, x2);
+            step(j + 2, wc, wb, x0);
+        }
+        if (j < n_chunks) {
+            step(j, wa, wc, x1);
+            if (j + 1 < n_chunks) step(j + 1, wb, wa, x2);
+        }
+    } else {
     // The W stream starts first; afterwards X loads are always issued before the W loads of the same
     // step, so that waiting for X (older) leaves the W loads (younger) in flight.
     load_w(kb0, wa);
@@ -185,6 +271,7 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
             compute(wa, 0);
         }
     }
+    }   // MT < 6
 
     const int n_pad = n_tiles * 16;
     float* out = partial + (size_t)split * M * n_pad;
@@ -290,7 +377,7 @@ int launch_variant(const GemmPlan& p, const void* xf, const void* w, int M, int 
 }
 
 struct Variant {
-    int mt, nt, kc;
+    int mt, nt, kc;   // row tiles, column tiles per wave, K blocks per LDS chunk
 };
 // row tiles -> (column tiles per wave, K blocks per LDS chunk); LDS = 2 buffers * planes * mt * kc KiB.
 // Up to 3 row tiles there is a second, wider variant (4 column tiles per wave, 2 K blocks per
@@ -360,26 +447,23 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     if (M < 1 || M > 352) return fail(SPEC_ERR_SHAPE, "GEMM supports 1..352 rows, got %d", M);
     if (K % 32) return fail(SPEC_ERR_SHAPE, "GEMM needs K %% 32 == 0, got %d", K);
     const int n_tiles = (N + 15) / 16;
-    if (p.nt == 4) {
-        switch (p.mt) {
-        case 1: return launch_variant<1, 4, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-        case 2: return launch_variant<2, 4, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-        case 3: return launch_variant<3, 4, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-        case 6: return launch_variant<6, 4, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-        case 8: return launch_variant<8, 4, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-        case 11: return launch_variant<11, 4, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-        default: return fail(SPEC_ERR_SHAPE, "no wide GEMM variant for %d rows", M);
-        }
-    }
-    switch (p.mt) {
-    case 1: return launch_variant<1, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 2: return launch_variant<2, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 3: return launch_variant<3, 2, 4>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 4: return launch_variant<4, 2, 2>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 16: return launch_variant<16, 2, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    case 22: return launch_variant<22, 2, 1>(p, x_frags, w_packed, M, K, n_tiles, partial, s);
-    default: return fail(SPEC_ERR_SHAPE, "no GEMM variant for %d rows", M);
-    }
+#define SPECV_GEMM(MT_, NT_, KC_)                                                                       \
+    if (p.mt == MT_ && p.nt == NT_)                                                                      \
+        return launch_variant<MT_, NT_, KC_>(p, x_frags, w_packed, M, K, n_tiles, partial, s)
+    SPECV_GEMM(1, 4, 2);
+    SPECV_GEMM(2, 4, 2);
+    SPECV_GEMM(3, 4, 2);
+    SPECV_GEMM(1, 2, 4);
+    SPECV_GEMM(2, 2, 4);
+    SPECV_GEMM(3, 2, 4);
+    SPECV_GEMM(4, 2, 2);
+    SPECV_GEMM(6, 4, 1);
+    SPECV_GEMM(8, 4, 1);
+    SPECV_GEMM(11, 4, 1);
+    SPECV_GEMM(16, 2, 1);
+    SPECV_GEMM(22, 2, 1);
+#undef SPECV_GEMM
+    return fail(SPEC_ERR_SHAPE, "no GEMM variant for %d rows (%d row tiles, %d column tiles per wave)", M, p.mt, p.nt);
 }
 
 int launch_pack_x(const float* x, const float* gain, int M, int K, int mt_count, int planes, void* x_frags, hipStream_t s)
