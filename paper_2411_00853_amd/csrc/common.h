@@ -251,7 +251,7 @@ struct QkvSrc {
 };
 
 struct AttnPlan {
-    int chunk_keys;   // keys per wavefront work item (multiple of 32)
+    int chunk_keys;   // most keys a wavefront work item can get (multiple of 32): a sequence at max_kv_len
     int max_chunks;   // chunks per (sequence, kv head) at max_kv_len
 };
 AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count, bool paged = false);
