@@ -47,26 +47,34 @@ constexpr int WPACK_KG = 4;   // K blocks per group of the packed weight order
 // All global loads below are unconditional (addresses clamped into range, W zeroed by selects past
 // the K range): with no branch around a load the compiler can count outstanding loads exactly, so
 // a wait for X never turns into a wait for the whole W stream.
-template <int MT, int NT, int KC, int PLANES>
-__global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restrict__ Xf, const u32x4* __restrict__ Wp,
+// RS = 2 (many row tiles): eight wavefronts per workgroup, two row halves x four column groups.
+// A wavefront then holds the accumulators of MTW = ceil(MT/2) row tiles only, which fits two
+// wavefronts per SIMD: the matrix instruction issues faster with a second wavefront to alternate
+// with (measured: one 16x16x32 product per 19-20 cycles and SIMD instead of 22-26), and the
+// other wavefront's products cover this one's waits.
+template <int MT, int NT, int KC, int PLANES, int RS = 1>
+__global__ void __launch_bounds__(256 * RS) gemm_skinny_kernel(const u32x4* __restrict__ Xf, const u32x4* __restrict__ Wp,
                                                           float* __restrict__ partial, int M, int n_tiles,
                                                           int kb_total, int kb_per_split, int n_split, int n_blocks)
 {
     constexpr int CHUNK_U4 = KC * PLANES * MT * 64;     // 16-byte units per X chunk (contiguous in Xf)
-    constexpr int UPT = (CHUNK_U4 + 255) / 256;         // per thread
+    constexpr int TPBK = 256 * RS;                        // threads per workgroup
+    constexpr int UPT = (CHUNK_U4 + TPBK - 1) / TPBK;     // per thread
     __shared__ u32x4 xs[2][CHUNK_U4];                   // two chunk buffers
 
     int split, nblk;
     map_block(blockIdx.x, n_split, &split, &nblk);
     if (nblk >= n_blocks) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tile0 = (nblk * 4 + wave) * NT;
+    constexpr int MTW = (MT + RS - 1) / RS;               // row tiles of one wavefront
+    const int a0 = RS == 1 ? 0 : (wave & 1) * MTW;          // its first row tile
+    const int tile0 = (nblk * 4 + (RS == 1 ? wave : wave >> 1)) * NT;
     const int kb0 = split * kb_per_split;
     const int kb1 = min(kb0 + kb_per_split, kb_total);
 
-    floatx4 acc[MT][NT];
+    floatx4 acc[MTW][NT];
 #pragma unroll
-    for (int a = 0; a < MT; ++a)
+    for (int a = 0; a < MTW; ++a)
 #pragma unroll
         for (int i = 0; i < NT; ++i) acc[a][i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
@@ -74,7 +82,7 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
     u32x4 xr[UPT];
     int xoff[UPT];
 #pragma unroll
-    for (int u = 0; u < UPT; ++u) xoff[u] = min(u * 256 + (int)threadIdx.x, CHUNK_U4 - 1);   // surplus threads repeat
+    for (int u = 0; u < UPT; ++u) xoff[u] = min(u * TPBK + (int)threadIdx.x, CHUNK_U4 - 1);   // surplus threads repeat
 
     // W tile order: [K group of 4 blocks][column tile][block in group][lane] -- the chunk a workgroup
     // reads in one step (its 4*NT tiles, KC blocks) is one contiguous run, and workgroups of
@@ -114,8 +122,11 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
 #pragma unroll
         for (int u = 0; u < UPT; ++u) xs[buf][xoff[u]] = xr[u];
     };
+    // fragment of the wavefront's a-th row tile (RS = 2 and odd MT: the second half's last tile does
+    // not exist; it re-reads the tile before it and its results are dropped)
     auto x_frag = [&](int buf, int c, int plane, int a) {
-        return __builtin_bit_cast(bf16x8, xs[buf][((c * PLANES + plane) * MT + a) * 64 + lane]);
+        const int row_tile = RS == 1 ? a : min(a0 + a, MT - 1);
+        return __builtin_bit_cast(bf16x8, xs[buf][((c * PLANES + plane) * MT + row_tile) * 64 + lane]);
     };
     auto compute = [&](const u32x4(&w)[KC][NT], int buf) {
         if constexpr (MT >= 3) {
@@ -127,13 +138,13 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
             if constexpr (PLANES == 2) xl = x_frag(buf, 0, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, PLANES, 0);            // LDS reads of tile 0
 #pragma unroll
-            for (int t = 0; t < KC * MT; ++t) {
-                const int c = t / MT, a = t % MT;
+            for (int t = 0; t < KC * MTW; ++t) {
+                const int c = t / MTW, a = t % MTW;
                 bf16x8 nh = xh, nl = xl;
-                if (t + 1 < KC * MT) {
-                    nh = x_frag(buf, (t + 1) / MT, 0, (t + 1) % MT);
+                if (t + 1 < KC * MTW) {
+                    nh = x_frag(buf, (t + 1) / MTW, 0, (t + 1) % MTW);
                     nl = nh;
-                    if constexpr (PLANES == 2) nl = x_frag(buf, (t + 1) / MT, 1, (t + 1) % MT);
+                    if constexpr (PLANES == 2) nl = x_frag(buf, (t + 1) / MTW, 1, (t + 1) % MTW);
                 }
 #pragma unroll
                 for (int i = 0; i < NT; ++i)
@@ -277,14 +288,14 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const u32x4* __restric
     float* out = partial + (size_t)split * M * n_pad;
     const int g = lane >> 4, c = lane & 15;
 #pragma unroll
-    for (int a = 0; a < MT; ++a)
+    for (int a = 0; a < MTW; ++a)
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
             const int tile = tile0 + i;
-            if (tile < n_tiles) {
+            if (tile < n_tiles && a0 + a < MT) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int m = a * 16 + 4 * g + r;
+                    const int m = (a0 + a) * 16 + 4 * g + r;
                     if (m < M) out[(size_t)m * n_pad + tile * 16 + c] = acc[a][i][r];
                 }
             }
@@ -359,7 +370,7 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const uint16_t* __rest
     }
 }
 
-template <int MT, int NT, int KC>
+template <int MT, int NT, int KC, int RS = 1>
 int launch_variant(const GemmPlan& p, const void* xf, const void* w, int M, int K, int n_tiles, float* partial,
                    hipStream_t s)
 {
@@ -367,10 +378,10 @@ int launch_variant(const GemmPlan& p, const void* xf, const void* w, int M, int 
     int grid = n_blocks * p.n_split;
     if (p.n_split < 8) grid = (n_blocks + (8 / p.n_split) - 1) / (8 / p.n_split) * 8;
     if (p.planes == 2)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 2>), dim3(grid), dim3(256), 0, s, (const u32x4*)xf,
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 2, RS>), dim3(grid), dim3(256 * RS), 0, s, (const u32x4*)xf,
                            (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks);
     else
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 1>), dim3(grid), dim3(256), 0, s, (const u32x4*)xf,
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 1, RS>), dim3(grid), dim3(256 * RS), 0, s, (const u32x4*)xf,
                            (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks);
     SPECV_LAUNCH_CHECK("gemm_skinny_kernel");
     return SPEC_OK;
@@ -384,6 +395,8 @@ struct Variant {
 // chunk) for matrices with many columns.
 // From 6 row tiles on the matrix cores and the LDS reads of X start to matter: several column tiles
 // per wave (each X fragment read from LDS feeds that many products) keep LDS traffic per W byte down.
+// From 8 row tiles on the workgroup has eight wavefronts (two row halves, see the kernel): measured
+// slower at 6 row tiles (88 rows), faster from 8 on (120 rows -6 %, 160 -7 %, 250 and 320 -20 %).
 constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {6, 4, 1},
                                  {8, 4, 1}, {11, 4, 1}, {16, 2, 1}, {22, 2, 1}};
 constexpr int kWideMaxMt = 3;
@@ -447,9 +460,9 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     if (M < 1 || M > 352) return fail(SPEC_ERR_SHAPE, "GEMM supports 1..352 rows, got %d", M);
     if (K % 32) return fail(SPEC_ERR_SHAPE, "GEMM needs K %% 32 == 0, got %d", K);
     const int n_tiles = (N + 15) / 16;
-#define SPECV_GEMM(MT_, NT_, KC_)                                                                       \
+#define SPECV_GEMM(MT_, NT_, KC_, ...)                                                                  \
     if (p.mt == MT_ && p.nt == NT_)                                                                      \
-        return launch_variant<MT_, NT_, KC_>(p, x_frags, w_packed, M, K, n_tiles, partial, s)
+        return launch_variant<MT_, NT_, KC_, ##__VA_ARGS__>(p, x_frags, w_packed, M, K, n_tiles, partial, s)
     SPECV_GEMM(1, 4, 2);
     SPECV_GEMM(2, 4, 2);
     SPECV_GEMM(3, 4, 2);
@@ -458,10 +471,10 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     SPECV_GEMM(3, 2, 4);
     SPECV_GEMM(4, 2, 2);
     SPECV_GEMM(6, 4, 1);
-    SPECV_GEMM(8, 4, 1);
-    SPECV_GEMM(11, 4, 1);
-    SPECV_GEMM(16, 2, 1);
-    SPECV_GEMM(22, 2, 1);
+    SPECV_GEMM(8, 4, 1, 2);
+    SPECV_GEMM(11, 4, 1, 2);
+    SPECV_GEMM(16, 2, 1, 2);
+    SPECV_GEMM(22, 2, 1, 2);
 #undef SPECV_GEMM
     return fail(SPEC_ERR_SHAPE, "no GEMM variant for %d rows (%d row tiles, %d column tiles per wave)", M, p.mt, p.nt);
 }
