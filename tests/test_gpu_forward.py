@@ -177,6 +177,45 @@ def test_sequences_far_below_the_cache_capacity():
     assert err < 5e-3
 
 
+def _random_case(seed):
+    """A seeded small model and batch: shapes, lengths and lookaheads drawn from the ranges the
+    library accepts (bf16: 64- or 128-dim heads, widths multiples of 32)."""
+    import random
+    r = random.Random(seed)
+    hd = r.choice([64, 128])
+    n_kv = r.choice([1, 2, 4])
+    group = r.choice([1, 2, 3, 4, 8])
+    n_q = n_kv * group
+    d = r.choice([128, 224, 384])
+    ffn = r.choice([160, 352, 736])
+    vocab = r.choice([257, 1000, 4099])
+    dtype = r.choice(["bf16", "bf16", "fp32"])
+    kmax = r.choice([1, 3, 6, 9, 15])
+    if (kmax + 1) * group > 64:          # the attention kernels take at most 64 query rows per kv head
+        kmax = 64 // group - 1
+    shape = wl.ModelShape(r.choice([1, 2]), d, n_q, n_kv, hd, ffn, vocab, dtype=dtype)
+    n_slots = r.choice([1, 2, 3, 5])
+    cap = r.choice([96, 300, 1500])
+    lens = [r.choice([0, 1, 31, 32, 33, r.randrange(2, cap - kmax - 1), cap - kmax - 1]) for _ in range(n_slots)]
+    look = [r.randrange(0, kmax + 1) for _ in range(n_slots)]
+    look[r.randrange(n_slots)] = kmax
+    order = list(range(n_slots))
+    r.shuffle(order)
+    return shape, n_slots, cap, kmax, lens, look, order, r.choice([0.6, 1.0, 1.7])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_small_models(seed):
+    shape, n_slots, cap, kmax, lens, look, order, T = _random_case(1000 + seed)
+    rig = Rig(shape, n_slots, cap, kmax, seed=20 + seed, std=0.05)
+    rng = wl.Rng(300 + seed, "cpu")
+    for s, n in enumerate(lens):
+        rig.prefill(s, rng.randint(70 + s, (n,), shape.vocab).tolist())
+    t0 = rng.randint(90, (n_slots,), shape.vocab).tolist()
+    err, chk, na, ot, logits, want = _check_step(rig, order, t0, [look[s] for s in order], T, 40 + seed)
+    assert err <= (1e-4 if shape.dtype == "fp32" else 5e-3), (err, shape, lens, look)
+
+
 def test_step_rollback_step_reproduces_bits_and_ignores_stale_slots():
     shape = wl.ModelShape(2, 256, 4, 2, 64, 256, 512)
     rig = Rig(shape, 2, 96, 4, seed=5, std=0.05)
