@@ -106,6 +106,38 @@ def test_paged_cache_gives_the_same_results_and_returns_pages():
     assert paged.free() == 9
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 5, 7, 9, 11, 12, 13])
+def test_random_small_models_on_a_page_pool(seed):
+    """The seeded random cases of test_gpu_forward (bf16 ones) give the same logits, tokens and
+    lengths on a page pool as on the contiguous cache."""
+    from test_gpu_forward import Rig, _random_case
+    shape, n_slots, cap, kmax, lens, look, order, T = _random_case(1000 + seed)
+    if shape.dtype != "bf16":
+        pytest.skip("a page pool holds bf16 caches only")
+    base = Rig(shape, n_slots, cap, kmax, seed=20 + seed, std=0.05)
+    rng = wl.Rng(300 + seed, "cpu")
+    for s, n in enumerate(lens):
+        base.prefill(s, rng.randint(70 + s, (n,), shape.vocab).tolist())
+    n_pages = sum((n + kmax + 1 + 31) // 32 for n in lens)          # exactly what the step can touch
+    paged = PagedRig(base, n_slots, cap, kmax, n_pages=n_pages)
+    for s in range(n_slots):
+        paged.load(base, s)
+    V = shape.vocab
+    t0 = rng.randint(90, (n_slots,), V).tolist()
+    lk = [look[s] for s in order]
+    toks = rng.randint(91, (n_slots, max(kmax, 1)), V)[:, :kmax].contiguous()
+    dl = rng.normal(92, (n_slots, max(kmax, 1), V), 1.0)[:, :kmax].contiguous()
+    us = rng.uniform(93, (n_slots, kmax + 1))
+    want = _linear(base, base.sv, order, t0, lk, toks, dl, us, T, kmax, V)
+    got = _linear(paged, paged.sv, order, t0, lk, toks, dl, us, T, kmax, V)
+    paged.sv.spec_verify_poll(paged.h)
+    assert torch.equal(want[1], got[1]) and torch.equal(want[2], got[2])
+    assert (want[0] - got[0]).abs().max().item() <= 1e-5      # same arithmetic unless the chunk plans differ
+    kl = paged.kv_len.cpu().tolist()
+    assert kl == base.kv_len.cpu().tolist()
+    assert paged.free() == n_pages - sum((n + 31) // 32 for n in kl)
+
+
 def test_pool_exhaustion_skips_the_sequence_and_is_reported():
     from test_gpu_forward import Rig
     Kmax, T, V = 4, 1.0, SHAPE.vocab
