@@ -178,7 +178,7 @@ __global__ void __launch_bounds__(256 * RS) gemm_skinny_kernel(const u32x4* __re
             }
     };
 
-    if constexpr (MT >= 6) {
+    if constexpr (MT >= 8) {
         // Many row tiles: a chunk's products take about as long as a memory round trip, and with two W
         // buffers the loads of chunk j+2 can only be issued after the products of chunk j (they reuse
         // its registers), so products and waiting alternate instead of overlapping.  A third W buffer
@@ -187,7 +187,7 @@ __global__ void __launch_bounds__(256 * RS) gemm_skinny_kernel(const u32x4* __re
         // here and misses L2 as often as not).  One K block per chunk (KC == 1): no chunk is partial,
         // nothing needs masking; loads past the range are redirected to its last block and their
         // chunks never multiplied.
-        static_assert(MT < 6 || KC == 1, "the three-buffer pipeline takes one K block per chunk");
+        static_assert(MT < 8 || KC == 1, "the three-buffer pipeline takes one K block per chunk");
         u32x4 wc[KC][NT];
         u32x4 x0[UPT], x1[UPT], x2[UPT];
         auto load_xs = [&](int kbase, u32x4(&dst)[UPT]) {
@@ -282,7 +282,7 @@ __global__ void __launch_bounds__(256 * RS) gemm_skinny_kernel(const u32x4* __re
             compute(wa, 0);
         }
     }
-    }   // MT < 6
+    }   // MT < 8
 
     const int n_pad = n_tiles * 16;
     float* out = partial + (size_t)split * M * n_pad;
@@ -395,9 +395,10 @@ struct Variant {
 // chunk) for matrices with many columns.
 // From 6 row tiles on the matrix cores and the LDS reads of X start to matter: several column tiles
 // per wave (each X fragment read from LDS feeds that many products) keep LDS traffic per W byte down.
-// From 8 row tiles on the workgroup has eight wavefronts (two row halves, see the kernel): measured
-// slower at 6 row tiles (88 rows), faster from 8 on (120 rows -6 %, 160 -7 %, 250 and 320 -20 %).
-constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {6, 4, 1},
+// From 8 row tiles on the workgroup has eight wavefronts (two row halves) and the three-buffer
+// pipeline of one K block per chunk (see the kernel): both measured slower at 6 row tiles (88
+// rows), faster from 8 on (120 rows -6 %, 160 -7 %, 250 and 320 -20 %).
+constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {6, 4, 2},
                                  {8, 4, 1}, {11, 4, 1}, {16, 2, 1}, {22, 2, 1}};
 constexpr int kWideMaxMt = 3;
 constexpr int kWideMinTiles = 340;   // column tiles from which the wide variant still fills the chip
@@ -470,7 +471,7 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     SPECV_GEMM(2, 2, 4);
     SPECV_GEMM(3, 2, 4);
     SPECV_GEMM(4, 2, 2);
-    SPECV_GEMM(6, 4, 1);
+    SPECV_GEMM(6, 4, 2);
     SPECV_GEMM(8, 4, 1, 2);
     SPECV_GEMM(11, 4, 1, 2);
     SPECV_GEMM(16, 2, 1, 2);
