@@ -391,7 +391,7 @@ struct Variant {
     int mt, nt, kc;   // row tiles, column tiles per wave, K blocks per LDS chunk
 };
 // row tiles -> (column tiles per wave, K blocks per LDS chunk); LDS = 2 buffers * planes * mt * kc KiB.
-// Up to 3 row tiles there is a second, wider variant (4 column tiles per wave, 2 K blocks per
+// Up to 4 row tiles there is a second, wider variant (4 column tiles per wave, 2 K blocks per
 // chunk) for matrices with many columns.
 // From 6 row tiles on the matrix cores and the LDS reads of X start to matter: several column tiles
 // per wave (each X fragment read from LDS feeds that many products) keep LDS traffic per W byte down.
@@ -400,7 +400,7 @@ struct Variant {
 // rows), faster from 8 on (120 rows -6 %, 160 -7 %, 250 and 320 -20 %).
 constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {6, 4, 2},
                                  {8, 4, 1}, {11, 4, 1}, {16, 2, 1}, {22, 2, 1}};
-constexpr int kWideMaxMt = 3;
+constexpr int kWideMaxMt = 4;
 constexpr int kWideMinTiles = 340;   // column tiles from which the wide variant still fills the chip
 
 const Variant* pick_variant(int M)
@@ -467,6 +467,7 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     SPECV_GEMM(1, 4, 2);
     SPECV_GEMM(2, 4, 2);
     SPECV_GEMM(3, 4, 2);
+    SPECV_GEMM(4, 4, 2);
     SPECV_GEMM(1, 2, 4);
     SPECV_GEMM(2, 2, 4);
     SPECV_GEMM(3, 2, 4);
