@@ -398,8 +398,9 @@ struct Variant {
 // From 8 row tiles on the workgroup has eight wavefronts (two row halves) and the three-buffer
 // pipeline of one K block per chunk (see the kernel): both measured slower at 6 row tiles (88
 // rows), faster from 8 on (120 rows -6 %, 160 -7 %, 250 and 320 -20 %).
-constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {6, 4, 2},
-                                 {8, 4, 1}, {11, 4, 1}, {12, 4, 1}, {16, 2, 1}, {22, 2, 1}};
+constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {5, 4, 2}, {6, 4, 2},
+                                 {8, 4, 1}, {9, 4, 1}, {11, 4, 1}, {12, 4, 1}, {14, 2, 1}, {16, 2, 1},
+                                 {19, 2, 1}, {22, 2, 1}};
 constexpr int kWideMaxMt = 4;
 constexpr int kWideMinTiles = 340;   // column tiles from which the wide variant still fills the chip
 
@@ -472,11 +473,15 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     SPECV_GEMM(2, 2, 4);
     SPECV_GEMM(3, 2, 4);
     SPECV_GEMM(4, 2, 2);
+    SPECV_GEMM(5, 4, 2);
     SPECV_GEMM(6, 4, 2);
     SPECV_GEMM(8, 4, 1, 2);
+    SPECV_GEMM(9, 4, 1, 2);
     SPECV_GEMM(11, 4, 1, 2);
     SPECV_GEMM(12, 4, 1, 2);
+    SPECV_GEMM(14, 2, 1, 2);
     SPECV_GEMM(16, 2, 1, 2);
+    SPECV_GEMM(19, 2, 1, 2);
     SPECV_GEMM(22, 2, 1, 2);
 #undef SPECV_GEMM
     return fail(SPEC_ERR_SHAPE, "no GEMM variant for %d rows (%d row tiles, %d column tiles per wave)", M, p.mt, p.nt);
