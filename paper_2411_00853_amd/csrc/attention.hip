@@ -604,13 +604,18 @@ static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, 
     return SPEC_OK;
 }
 
-bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack& ks, int B)
+bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack& ks, int B, int max_kv_len, int cu_count)
 {
     if (g.dtype != SPEC_DTYPE_BF16) return false;
     int kmax = 0;
     for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
     const int rt = ((kmax + 1) * (n_q_heads / g.n_kv_heads) + 15) / 16;
-    return fused_fits(g.head_dim, rt);
+    if (!fused_fits(g.head_dim, rt)) return false;
+    // Every wavefront of a (sequence, kv head) puts the queries together again: with short chunks
+    // (few sequences, many chunks each) that costs more than the separate kernel it replaces
+    // (measured: batch 1 at 1B-shape, 128-position chunks, 2 % slower; 256-position chunks faster).
+    const AttnPlan p = plan_attention(max_kv_len, B, g.n_kv_heads, cu_count, g.table != nullptr);
+    return p.chunk_keys >= 192;
 }
 
 int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,

@@ -150,7 +150,7 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
 
     RUN(SPEC_PROF_GLUE, launch_embed(c.dtype, h->tok_embed, t.row_tok, M, z.d, h->x, h->ssq, h->layers[0].attn_norm, to_xf, s));
     Out o;
-    const bool fuse = h->fuse_rope && attention_takes_qkv(h->geom, c.n_q_heads, ks, B);
+    const bool fuse = h->fuse_rope && attention_takes_qkv(h->geom, c.n_q_heads, ks, B, c.max_kv_len, h->cu_count);
     for (int l = 0; l < c.n_layers; ++l) {
         const spec_layer_weights& w = h->layers[l];
         rc = gemm(h->x, w.attn_norm, w.w_qkv, z.nqkv, z.d, &o);
