@@ -40,6 +40,7 @@ def parse():
                          "per-launch figures are unchanged, whole-step figures are not those of the workload)")
     ap.add_argument("--attn-items-per-cu", type=int, default=0, help="tuning: attention work items per compute unit")
     ap.add_argument("--gemm-wg-target", type=int, default=0, help="tuning: workgroups per GEMM launch")
+    ap.add_argument("--swiglu-min-wgs", type=int, default=0, help="tuning: fewest workgroups for SwiGLU inside the gate/up GEMM")
     return ap.parse_args()
 
 
@@ -401,6 +402,9 @@ def main():
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU: there is no CPU fallback for the HIP path")
+    sv.spec_k_set_attn_items_per_cu(args.attn_items_per_cu)
+    sv.spec_k_set_gemm_wg_target(args.gemm_wg_target)
+    sv.spec_k_set_swiglu_min_wgs(args.swiglu_min_wgs)
     if args.workload == "stress":
         return bench_stress(args, torch, sv, wl)
     if args.workload == "copy":
@@ -419,8 +423,6 @@ def main():
     t_setup = time.time()
     log(f"[bench] workload {w.name}: B={B} rows={w.rows} layers={shape.n_layers} d={shape.d_model} V={V}")
 
-    sv.spec_k_set_attn_items_per_cu(args.attn_items_per_cu)
-    sv.spec_k_set_gemm_wg_target(args.gemm_wg_target)
     weights, w_cpu = build_device_model(sv, wl, w, torch, want_cpu)
     cfg = sv.make_cfg(shape, B, w.max_kv_len, Kmax)
     kv_len = torch.zeros(B, dtype=torch.int32, device="cuda")

@@ -39,6 +39,11 @@ int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, int32_t M, 
  * (0 = default, two per compute unit).  Process-wide; affects launches made after the call. */
 void spec_k_set_gemm_wg_target(int32_t workgroups);
 
+/* Tuning knob: the gate/up projection finishes SwiGLU inside the GEMM (one K range, 128-column
+ * workgroups, up to 64 rows) when that launch has at least this many workgroups; 0 = default
+ * (a third of the compute units).  1 forces it wherever the shape allows. */
+void spec_k_set_swiglu_min_wgs(int32_t workgroups);
+
 /* Tuning knob: wavefront work items (sequence, kv head, position chunk) per compute unit that the
  * attention kernel's position split aims for (0 = default).  Set before spec_verify_init: the
  * workspace for chunk results is sized with it.  Process-wide. */

@@ -121,6 +121,8 @@ def lib():
         L.spec_k_gemm_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
         L.spec_k_set_gemm_wg_target.restype = None
         L.spec_k_set_gemm_wg_target.argtypes = [C.c_int32]
+        L.spec_k_set_swiglu_min_wgs.restype = None
+        L.spec_k_set_swiglu_min_wgs.argtypes = [C.c_int32]
         L.spec_k_set_attn_items_per_cu.restype = None
         L.spec_k_set_attn_items_per_cu.argtypes = [C.c_int32]
         L.spec_verify_profile_begin.argtypes = [C.c_void_p]
@@ -445,6 +447,10 @@ def spec_k_gemm_bf16(x: torch.Tensor, w_packed: torch.Tensor, n_out: int, split_
 
 def spec_k_set_gemm_wg_target(workgroups: int):
     lib().spec_k_set_gemm_wg_target(int(workgroups))
+
+
+def spec_k_set_swiglu_min_wgs(workgroups: int):
+    lib().spec_k_set_swiglu_min_wgs(int(workgroups))
 
 
 def spec_k_set_attn_items_per_cu(items: int):

@@ -58,6 +58,11 @@ int forward_init(spec_handle* h, int max_rows)
         const size_t xf_bytes = xfrag_uint4s(gemm_row_tiles(max_rows), 2, kmax) * sizeof(uint4);
         if (rc == SPEC_OK) rc = a.alloc(&h->xf, xf_bytes);
         if (rc == SPEC_OK && hipMemset(h->xf, 0, xf_bytes) != hipSuccess) rc = fail(SPEC_ERR_DEVICE, "hipMemset failed");
+        // the gate/up GEMM reads h->xf while its early workgroups already write the down projection's
+        // operand, which therefore has a buffer of its own (rows up to the 4 row tiles that path serves)
+        const size_t xa_bytes = xfrag_uint4s(gemm_row_tiles(std::min(max_rows, 64)), 2, z.F) * sizeof(uint4);
+        if (rc == SPEC_OK) rc = a.alloc(&h->xf_act, xa_bytes);
+        if (rc == SPEC_OK && hipMemset(h->xf_act, 0, xa_bytes) != hipSuccess) rc = fail(SPEC_ERR_DEVICE, "hipMemset failed");
         // partial-sum space for the largest GEMM at any row count
         const int Ns[G_COUNT] = {z.nqkv, z.d, 2 * z.F, z.d, z.V};
         const int Ks[G_COUNT] = {z.d, z.dq, z.d, z.F, z.d};
@@ -126,14 +131,15 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
     const XOut to_act{bf16 ? h->xf : nullptr, mt, planes, bf16 ? nullptr : h->act};
     const NormScale scaled{bf16 ? h->ssq : nullptr, n_ssq, z.d, c.rms_eps};
     const NormScale unscaled{nullptr, 0, 0, 0.f};
-    auto gemm = [&](const float* plain_in, const float* gain, const void* w, int N, int K, Out* o) -> int {
+    auto gemm = [&](const float* plain_in, const float* gain, const void* w, int N, int K, Out* o,
+                    const void* in_frags = nullptr) -> int {
         if (bf16) {
             const GemmPlan p = plan_gemm(M, N, K, h->cu_count, h->split_act);
             o->n_split = p.n_split;
             o->ld = p.n_pad;
             o->stride = (size_t)M * p.n_pad;
             ProfScope ps_(&h->prof, SPEC_PROF_GEMM, s);
-            return launch_gemm_bf16(p, h->xf, w, M, N, K, h->partial, s);
+            return launch_gemm_bf16(p, in_frags ? in_frags : h->xf, w, M, N, K, h->partial, s);
         }
         o->n_split = 1;
         o->ld = N;
@@ -150,6 +156,7 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
 
     RUN(SPEC_PROF_GLUE, launch_embed(c.dtype, h->tok_embed, t.row_tok, M, z.d, h->x, h->ssq, h->layers[0].attn_norm, to_xf, s));
     Out o;
+    const bool swiglu_in_gemm = bf16 && gemm_swiglu_fits(M, z.F, h->cu_count);
     const bool fuse = h->fuse_rope && attention_takes_qkv(h->geom, c.n_q_heads, ks, B, c.max_kv_len, h->cu_count);
     for (int l = 0; l < c.n_layers; ++l) {
         const spec_layer_weights& w = h->layers[l];
@@ -171,10 +178,18 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
         rc = gemm(h->att, nullptr, w.w_o, z.d, z.dq, &o);
         if (rc) return rc;
         RUN(SPEC_PROF_GLUE, launch_resid(h->partial, o.n_split, o.stride, o.ld, M, z.d, h->x, h->ssq, w.ffn_norm, to_xf, s));
-        rc = gemm(h->x, w.ffn_norm, w.w_gate_up, 2 * z.F, z.d, &o);
-        if (rc) return rc;
-        RUN(SPEC_PROF_GLUE, launch_silu_mul(h->partial, o.n_split, o.stride, o.ld, M, z.F, bf16, scaled, to_act, s));
-        rc = gemm(h->act, nullptr, w.w_down, z.d, z.F, &o);
+        if (swiglu_in_gemm) {
+            // the gate/up GEMM applies the norm's row scale and SwiGLU itself and writes the down
+            // projection's operand (into the second fragment buffer: it is still reading the first)
+            RUN(SPEC_PROF_GEMM, launch_gemm_swiglu(h->xf, planes, w.w_gate_up, M, z.F, z.d, h->ssq, n_ssq, z.d, c.rms_eps,
+                                                   h->xf_act, mt, planes, s));
+            rc = gemm(h->act, nullptr, w.w_down, z.d, z.F, &o, h->xf_act);
+        } else {
+            rc = gemm(h->x, w.ffn_norm, w.w_gate_up, 2 * z.F, z.d, &o);
+            if (rc) return rc;
+            RUN(SPEC_PROF_GLUE, launch_silu_mul(h->partial, o.n_split, o.stride, o.ld, M, z.F, bf16, scaled, to_act, s));
+            rc = gemm(h->act, nullptr, w.w_down, z.d, z.F, &o);
+        }
         if (rc) return rc;
         const float* next_gain = (l + 1 < c.n_layers) ? h->layers[l + 1].attn_norm : h->final_norm;
         RUN(SPEC_PROF_GLUE, launch_resid(h->partial, o.n_split, o.stride, o.ld, M, z.d, h->x, h->ssq, next_gain, to_xf, s));

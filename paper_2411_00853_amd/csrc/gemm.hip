@@ -52,10 +52,23 @@ constexpr int WPACK_KG = 4;   // K blocks per group of the packed weight order
 // wavefronts per SIMD: the matrix instruction issues faster with a second wavefront to alternate
 // with (measured: one 16x16x32 product per 19-20 cycles and SIMD instead of 22-26), and the
 // other wavefront's products cover this one's waits.
-template <int MT, int NT, int KC, int PLANES, int RS = 1>
+// EPI = 1 (gate/up projection with a single K range, NT == 2, columns packed so that a gate tile and
+// its up tile are neighbours): instead of leaving sums for another kernel, the workgroup applies the
+// row scale of the preceding norm, computes silu(gate) * up and writes the result as operand
+// fragments of the down projection.  One kernel and one round of partial sums less per layer.
+struct SwigluOut {
+    const float* ssq;   // NormScale of the rows (sums of squares in n_ssq chunks)
+    int n_ssq, d;
+    float eps;
+    uint4* frags;       // fragment buffer of the down projection's operand
+    int mt, planes;
+};
+
+template <int MT, int NT, int KC, int PLANES, int RS = 1, int EPI = 0>
 __global__ void __launch_bounds__(256 * RS) gemm_skinny_kernel(const u32x4* __restrict__ Xf, const u32x4* __restrict__ Wp,
                                                           float* __restrict__ partial, int M, int n_tiles,
-                                                          int kb_total, int kb_per_split, int n_split, int n_blocks)
+                                                          int kb_total, int kb_per_split, int n_split, int n_blocks,
+                                                          SwigluOut so)
 {
     constexpr int CHUNK_U4 = KC * PLANES * MT * 64;     // 16-byte units per X chunk (contiguous in Xf)
     constexpr int TPBK = 256 * RS;                        // threads per workgroup
@@ -284,9 +297,42 @@ __global__ void __launch_bounds__(256 * RS) gemm_skinny_kernel(const u32x4* __re
     }
     }   // MT < 8
 
+    const int g = lane >> 4, c = lane & 15;
+    if constexpr (EPI == 1) {
+        static_assert(EPI == 0 || (NT == 2 && RS == 1), "the SwiGLU epilogue pairs the two column tiles of a wavefront");
+        static_assert(EPI == 0 || sizeof(xs) >= 4 * MT * 256 * sizeof(float), "tile staging fits the X chunk buffers");
+        __shared__ float rsv[MT * 16];
+        __syncthreads();                                      // everyone is done with the X chunk buffers
+        float* tw = reinterpret_cast<float*>(&xs[0][0]) + wave * (MT * 256);   // [MT*16 rows][16 units]
+        for (int m = threadIdx.x; m < MT * 16; m += 256)
+            rsv[m] = m < M ? row_inv_rms(so.ssq, so.n_ssq, m, so.d, so.eps) : 0.f;
+        __syncthreads();
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int ml = a * 16 + 4 * g + r;
+                const float rs = rsv[ml];
+                const float ge = acc[a][0][r] * rs, ue = acc[a][1][r] * rs;
+                tw[ml * 16 + c] = ge / (1.f + expf(-ge)) * ue;
+            }
+        __syncthreads();
+        if (tile0 + 1 < n_tiles) {
+            const int f0 = (tile0 >> 1) * 16;                 // first FFN unit of this tile pair
+            for (int u = lane; u < MT * 32; u += 64) {
+                const int row = u >> 1, oct = u & 1;
+                if (row < M) {
+                    const float4 lo4 = *reinterpret_cast<const float4*>(tw + row * 16 + oct * 8);
+                    const float4 hi4 = *reinterpret_cast<const float4*>(tw + row * 16 + oct * 8 + 4);
+                    const float v[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+                    store_x_unit(so.frags, so.mt, so.planes, row, (f0 >> 3) + oct, v);
+                }
+            }
+        }
+        return;
+    }
     const int n_pad = n_tiles * 16;
     float* out = partial + (size_t)split * M * n_pad;
-    const int g = lane >> 4, c = lane & 15;
 #pragma unroll
     for (int a = 0; a < MTW; ++a)
 #pragma unroll
@@ -379,10 +425,10 @@ int launch_variant(const GemmPlan& p, const void* xf, const void* w, int M, int 
     if (p.n_split < 8) grid = (n_blocks + (8 / p.n_split) - 1) / (8 / p.n_split) * 8;
     if (p.planes == 2)
         hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 2, RS>), dim3(grid), dim3(256 * RS), 0, s, (const u32x4*)xf,
-                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks);
+                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
     else
         hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 1, RS>), dim3(grid), dim3(256 * RS), 0, s, (const u32x4*)xf,
-                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks);
+                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
     SPECV_LAUNCH_CHECK("gemm_skinny_kernel");
     return SPEC_OK;
 }
@@ -487,6 +533,54 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     return fail(SPEC_ERR_SHAPE, "no GEMM variant for %d rows (%d row tiles, %d column tiles per wave)", M, p.mt, p.nt);
 }
 
+namespace {
+int g_swiglu_min_wgs = 0;   // 0: a third of the compute units
+}
+void set_swiglu_min_wgs(int n) { g_swiglu_min_wgs = n; }
+
+// The gate/up projection can finish SwiGLU itself when it runs as ONE K range of 128-column
+// workgroups (narrow variants, up to 4 row tiles) and that still gives enough workgroups.
+bool gemm_swiglu_fits(int M, int F, int cu_count)
+{
+    const int mt = gemm_row_tiles(M);
+    if (mt < 1 || mt > 4 || F % 16) return false;
+    const int wgs = (2 * F / 16 + 7) / 8;
+    // measured: 172 workgroups (F = 11008) step -1.9 %, 128 workgroups (F = 8192) -3.5 %
+    return wgs >= (g_swiglu_min_wgs > 0 ? g_swiglu_min_wgs : cu_count / 3);
+}
+
+template <int MT, int KC>
+static int launch_swiglu_variant(int planes, const void* xf, const void* w, int M, int K, int n_tiles, const SwigluOut& so,
+                                 hipStream_t s)
+{
+    const int n_blocks = (n_tiles + 7) / 8;
+    const int grid = (n_blocks + 7) / 8 * 8;       // map_block deals workgroups to the 8 XCDs
+    const int kb = K / 32;
+    if (planes == 2)
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, 2, KC, 2, 1, 1>), dim3(grid), dim3(256), 0, s, (const u32x4*)xf,
+                           (const u32x4*)w, nullptr, M, n_tiles, kb, (kb + WPACK_KG - 1) / WPACK_KG * WPACK_KG, 1, n_blocks, so);
+    else
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, 2, KC, 1, 1, 1>), dim3(grid), dim3(256), 0, s, (const u32x4*)xf,
+                           (const u32x4*)w, nullptr, M, n_tiles, kb, (kb + WPACK_KG - 1) / WPACK_KG * WPACK_KG, 1, n_blocks, so);
+    SPECV_LAUNCH_CHECK("gemm_skinny_kernel (SwiGLU)");
+    return SPEC_OK;
+}
+
+int launch_gemm_swiglu(const void* x_frags, int planes, const void* w_gate_up, int M, int F, int K, const float* ssq,
+                       int n_ssq, int d, float eps, void* act_frags, int act_mt, int act_planes, hipStream_t s)
+{
+    if (K % 32 || F % 16) return fail(SPEC_ERR_SHAPE, "SwiGLU GEMM needs K %% 32 == 0 and F %% 16 == 0");
+    const SwigluOut so{ssq, n_ssq, d, eps, static_cast<uint4*>(act_frags), act_mt, act_planes};
+    const int n_tiles = 2 * F / 16;
+    switch (gemm_row_tiles(M)) {
+    case 1: return launch_swiglu_variant<1, 4>(planes, x_frags, w_gate_up, M, K, n_tiles, so, s);
+    case 2: return launch_swiglu_variant<2, 4>(planes, x_frags, w_gate_up, M, K, n_tiles, so, s);
+    case 3: return launch_swiglu_variant<3, 4>(planes, x_frags, w_gate_up, M, K, n_tiles, so, s);
+    case 4: return launch_swiglu_variant<4, 2>(planes, x_frags, w_gate_up, M, K, n_tiles, so, s);
+    default: return fail(SPEC_ERR_SHAPE, "no SwiGLU GEMM variant for %d rows", M);
+    }
+}
+
 int launch_pack_x(const float* x, const float* gain, int M, int K, int mt_count, int planes, void* x_frags, hipStream_t s)
 {
     const int total = M * (K / 8);
@@ -534,6 +628,7 @@ extern "C" int spec_pack_weight(const void* src, void* dst, int32_t n_out, int32
 }
 
 extern "C" void spec_k_set_gemm_wg_target(int32_t workgroups) { set_gemm_wg_target(workgroups); }
+extern "C" void spec_k_set_swiglu_min_wgs(int32_t workgroups) { set_swiglu_min_wgs(workgroups); }
 extern "C" void spec_k_set_attn_items_per_cu(int32_t items) { set_attn_items_per_cu(items); }
 
 extern "C" size_t spec_k_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K)

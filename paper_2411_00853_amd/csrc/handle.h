@@ -44,6 +44,7 @@ struct spec_handle {
     float* x = nullptr;        // [rows][d_model] residual stream
     float* hn = nullptr;       // [rows][d_model] normalised activations (fp32 path only)
     void* xf = nullptr;        // operand fragments of the current GEMM's input (bf16 path)
+    void* xf_act = nullptr;    // second fragment buffer: the down projection's operand when the gate/up GEMM writes it
     float* ssq = nullptr;      // [rows][ssq chunks] partial sums of squares of x
     float* q = nullptr;        // [rows][n_q_heads*head_dim] rotated queries
     float* att = nullptr;      // [rows][n_q_heads*head_dim] attention output
