@@ -543,7 +543,7 @@ void set_swiglu_min_wgs(int n) { g_swiglu_min_wgs = n; }
 bool gemm_swiglu_fits(int M, int F, int cu_count)
 {
     const int mt = gemm_row_tiles(M);
-    if (mt < 1 || mt > 4 || F % 16) return false;
+    if (mt < 1 || mt > 4 || F % 16) return false;   // (6 row tiles measured: the narrow GEMM loses more than the kernel saved)
     const int wgs = (2 * F / 16 + 7) / 8;
     // measured: 172 workgroups (F = 11008) step -1.9 %, 128 workgroups (F = 8192) -3.5 %
     return wgs >= (g_swiglu_min_wgs > 0 ? g_swiglu_min_wgs : cu_count / 3);
