@@ -49,6 +49,15 @@ void spec_k_set_swiglu_min_wgs(int32_t workgroups);
  * workspace for chunk results is sized with it.  Process-wide. */
 void spec_k_set_attn_items_per_cu(int32_t items);
 
+/* Tuning knob: the attention workgroups merge the chunk results of a (sequence, kv head) themselves
+ * (one workgroup of up to 8 wavefronts per pair, no merge kernel) when the launch has at least this
+ * many pairs; 0 = default (half the compute units).  1 forces it wherever the shape allows. */
+void spec_k_set_attn_merge_min_pairs(int32_t pairs);
+
+/* Tuning knob: most position chunks per (sequence, kv head), 1..16 (anything else restores the
+ * default 16).  Set before spec_verify_init, like spec_k_set_attn_items_per_cu. */
+void spec_k_set_attn_max_chunks(int32_t chunks);
+
 /* Same product for a plain fp32 W[N][K]. */
 int spec_k_gemm_f32(const float* x, const float* w, float* y, int32_t M, int32_t N, int32_t K, void* stream);
 

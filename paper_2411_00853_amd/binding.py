@@ -125,6 +125,10 @@ def lib():
         L.spec_k_set_swiglu_min_wgs.argtypes = [C.c_int32]
         L.spec_k_set_attn_items_per_cu.restype = None
         L.spec_k_set_attn_items_per_cu.argtypes = [C.c_int32]
+        L.spec_k_set_attn_merge_min_pairs.restype = None
+        L.spec_k_set_attn_merge_min_pairs.argtypes = [C.c_int32]
+        L.spec_k_set_attn_max_chunks.restype = None
+        L.spec_k_set_attn_max_chunks.argtypes = [C.c_int32]
         L.spec_verify_profile_begin.argtypes = [C.c_void_p]
         L.spec_verify_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32),
                                               C.POINTER(C.c_double)]
@@ -455,6 +459,14 @@ def spec_k_set_swiglu_min_wgs(workgroups: int):
 
 def spec_k_set_attn_items_per_cu(items: int):
     lib().spec_k_set_attn_items_per_cu(int(items))
+
+
+def spec_k_set_attn_merge_min_pairs(pairs: int):
+    lib().spec_k_set_attn_merge_min_pairs(int(pairs))
+
+
+def spec_k_set_attn_max_chunks(chunks: int):
+    lib().spec_k_set_attn_max_chunks(int(chunks))
 
 
 def spec_k_gemm_f32(x: torch.Tensor, w: torch.Tensor, stream=None):

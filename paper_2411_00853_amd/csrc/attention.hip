@@ -53,33 +53,60 @@ __device__ __forceinline__ int seq_chunk_keys(int total, int max_chunks)
 // window positions does the same for the window's keys and values of its kv head, stores them in
 // the cache (for later steps) and only then starts to stream -- so no separate rotary/append kernel
 // runs between the projection and the attention.
-template <int HD, int RT, bool PAGED, bool FUSED>
-__global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadPack ks, CacheGeom g, int n_q_heads,
-                                                        int layer, const uint4* cache,
-                                                        const float* __restrict__ q, int max_chunks,
-                                                        int r_cap, float scale_log2e, float* __restrict__ part_o,
-                                                        float* __restrict__ part_ml, QkvSrc src, uint16_t* cache_w)
+// CW > 0: one workgroup of CW wavefronts per (sequence, kv head), wavefront c taking chunk c; the
+// chunk results meet in LDS and the workgroup itself writes the merged, normalised output as the
+// output projection's operand fragments (same arithmetic and order as attn_merge_kernel): no second
+// kernel, no round trip of the chunk results through memory.  CW == 0: one wavefront per workgroup,
+// chunk results to part_o / part_ml for attn_merge_kernel (more chunks than a workgroup can hold).
+template <int HD, int RT, bool PAGED, bool FUSED, int CW>
+__global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
+    attn_chunk_kernel(StepTables t, LookaheadPack ks, CacheGeom g, int n_q_heads, int layer, const uint4* cache,
+                      const float* __restrict__ q, int max_chunks, int r_cap, float scale_log2e,
+                      float* __restrict__ part_o, float* __restrict__ part_ml, QkvSrc src, uint16_t* cache_w, XOut xo)
 {
     constexpr int STEPS = HD / 32;     // 32-dim steps of the score product
     constexpr int DT = HD / 16;        // 16-dim tiles of the output
     constexpr int BLK_U4 = 8 * HD;     // uint4 per 32-position block (keys then values)
-    const int lane = threadIdx.x, c16 = lane & 15, gq = lane >> 4;
-    const int item = blockIdx.x;
-    const int chunk = item % max_chunks;
-    const int hkv = (item / max_chunks) % g.n_kv_heads;
-    const int b = item / (max_chunks * g.n_kv_heads);
-    if (!t.seq_ok[b]) return;
+    const int lane = threadIdx.x & 63, c16 = lane & 15, gq = lane >> 4;
+    const int item = CW > 0 ? blockIdx.x * max_chunks + (threadIdx.x >> 6) : blockIdx.x;   // ((b, hkv), chunk)
+    const int chunk = CW > 0 ? (int)(threadIdx.x >> 6) : item % max_chunks;
+    const int hkv = (CW > 0 ? blockIdx.x : item / max_chunks) % g.n_kv_heads;
+    const int b = (CW > 0 ? blockIdx.x : item / max_chunks) / g.n_kv_heads;
     const int K = ks.k[b];
+    const int group = n_q_heads / g.n_kv_heads;
+    const int rows = (K + 1) * group;
+    const int row0 = t.seq_row0[b];
+    if (!t.seq_ok[b]) {
+        if constexpr (CW > 0) {   // rows of a skipped sequence: zero operand rows, as the merge kernel writes them
+            const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int u = threadIdx.x; u < rows * (HD / 8); u += 64 * CW) {
+                const int r = u / (HD / 8), d8 = u % (HD / 8);
+                store_x_unit(static_cast<uint4*>(xo.frags), xo.mt, xo.planes, row0 + r / group,
+                             (hkv * group + r % group) * (HD / 8) + d8, z);
+            }
+        }
+        return;
+    }
     const int n = t.seq_n[b];
     const int total = n + K + 1;
     const int ck = seq_chunk_keys(total, max_chunks);
     const int key0 = chunk * ck;
-    if (key0 >= total) return;
-    const int key1 = min(key0 + ck, total);
-    const int group = n_q_heads / g.n_kv_heads;
-    const int rows = (K + 1) * group;
+    const bool active = chunk < max_chunks && key0 < total;
+    if constexpr (CW == 0) {
+        if (!active) return;
+    }
     const int dq = n_q_heads * HD;
-    const int row0 = t.seq_row0[b];
+    floatx4 acc[RT][DT];
+    float m_run[RT], l_run[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        m_run[rt] = -INFINITY;
+        l_run[rt] = 0.f;
+#pragma unroll
+        for (int d = 0; d < DT; ++d) acc[rt][d] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    if (active) {
+    const int key1 = min(key0 + ck, total);
 
     const int blk0 = key0 >> 5, blk1 = (key1 + 31) >> 5;
     const uint4* head;
@@ -207,16 +234,6 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
                 split_frag(x, qh[rt][s], ql[rt][s]);
             }
         }
-    }
-
-    floatx4 acc[RT][DT];
-    float m_run[RT], l_run[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        m_run[rt] = -INFINITY;
-        l_run[rt] = 0.f;
-#pragma unroll
-        for (int d = 0; d < DT; ++d) acc[rt][d] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
     auto process = [&](int blk, const uint4(&kk)[2][STEPS], uint4(&vv)[DT]) {
@@ -369,22 +386,71 @@ __global__ void __launch_bounds__(64) attn_chunk_kernel(StepTables t, LookaheadP
         load_block(blk + 2, ka, va);
         process(blk + 1, kb, vb);
     }
+    }   // active
 
+    if constexpr (CW == 0) {
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-        float l = l_run[rt];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        const int r = rt * 16 + c16;
-        if (r < rows) {
-            float* o = part_o + ((size_t)item * r_cap + r) * HD + 4 * gq;
+        for (int rt = 0; rt < RT; ++rt) {
+            float l = l_run[rt];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            const int r = rt * 16 + c16;
+            if (r < rows) {
+                float* o = part_o + ((size_t)item * r_cap + r) * HD + 4 * gq;
+#pragma unroll
+                for (int d = 0; d < DT; ++d)
+                    *reinterpret_cast<float4*>(o + 16 * d) = make_float4(acc[rt][d][0], acc[rt][d][1], acc[rt][d][2], acc[rt][d][3]);
+                if (gq == 0) {
+                    part_ml[((size_t)item * r_cap + r) * 2 + 0] = m_run[rt];
+                    part_ml[((size_t)item * r_cap + r) * 2 + 1] = l;
+                }
+            }
+        }
+    } else {
+        // chunk results of the CW wavefronts -> LDS -> merged rows as operand fragments
+        __shared__ float s_o[CW][RT * 16][HD];
+        __shared__ float s_m[CW][RT * 16], s_l[CW][RT * 16];
+        static_assert(CW == 0 || sizeof(float) * CW * RT * 16 * (HD + 2) <= 64 * 1024, "chunk results fit in LDS");
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            float l = l_run[rt];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            const int r = rt * 16 + c16;
 #pragma unroll
             for (int d = 0; d < DT; ++d)
-                *reinterpret_cast<float4*>(o + 16 * d) = make_float4(acc[rt][d][0], acc[rt][d][1], acc[rt][d][2], acc[rt][d][3]);
+                *reinterpret_cast<float4*>(&s_o[chunk][r][16 * d + 4 * gq]) =
+                    make_float4(acc[rt][d][0], acc[rt][d][1], acc[rt][d][2], acc[rt][d][3]);
             if (gq == 0) {
-                part_ml[((size_t)item * r_cap + r) * 2 + 0] = m_run[rt];
-                part_ml[((size_t)item * r_cap + r) * 2 + 1] = l;
+                s_m[chunk][r] = m_run[rt];
+                s_l[chunk][r] = l;
             }
+        }
+        __syncthreads();
+        // out = sum_c w_c o_c / sum_c w_c l_c with w_c = 2^(m_c - max m), chunks in index order
+        for (int u = threadIdx.x; u < rows * (HD / 8); u += 64 * CW) {
+            const int r = u / (HD / 8), d8 = u % (HD / 8);
+            float mx = -INFINITY;
+#pragma unroll
+            for (int c = 0; c < CW; ++c) mx = fmaxf(mx, s_m[c][r]);
+            float den = 0.f;
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < CW; ++c) {
+                const float mc = s_m[c][r];
+                const bool on = mc != -INFINITY;   // a chunk entirely after this query's position (or empty)
+                const float w = on ? exp2f(mc - mx) : 0.f;
+                den += on ? w * s_l[c][r] : 0.f;
+                const float4 a = *reinterpret_cast<const float4*>(&s_o[c][r][8 * d8]);
+                const float4 bq = *reinterpret_cast<const float4*>(&s_o[c][r][8 * d8 + 4]);
+                v[0] += on ? w * a.x : 0.f; v[1] += on ? w * a.y : 0.f; v[2] += on ? w * a.z : 0.f; v[3] += on ? w * a.w : 0.f;
+                v[4] += on ? w * bq.x : 0.f; v[5] += on ? w * bq.y : 0.f; v[6] += on ? w * bq.z : 0.f; v[7] += on ? w * bq.w : 0.f;
+            }
+            const float inv = 1.0f / den;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= inv;
+            store_x_unit(static_cast<uint4*>(xo.frags), xo.mt, xo.planes, row0 + r / group,
+                         (hkv * group + r % group) * (HD / 8) + d8, v);
         }
     }
 }
@@ -532,6 +598,10 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(StepTables t, CacheGeom g
 
 static int g_items_per_cu = 0;   // wavefront work items per compute unit to aim for; 0 = default
 void set_attn_items_per_cu(int n) { g_items_per_cu = n; }
+static int g_max_chunks = 16;   // most chunks per (sequence, kv head)
+void set_attn_max_chunks(int n) { g_max_chunks = n >= 1 && n <= 16 ? n : 16; }
+static int g_merge_min_pairs = 0;   // fewest (sequence, kv head) pairs for merging inside the workgroup; 0 = default
+void set_attn_merge_min_pairs(int n) { g_merge_min_pairs = n; }
 
 AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count, bool paged)
 {
@@ -545,7 +615,7 @@ AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count,
     long chunks = want_items / per;
     if (chunks < 1) chunks = 1;
     if (paged && chunks < (max_kv_len + 2047) / 2048) chunks = (max_kv_len + 2047) / 2048;   // 64 blocks per wavefront
-    if (chunks > 16) chunks = 16;   // the merge walks a row's chunks one after the other
+    if (chunks > g_max_chunks) chunks = g_max_chunks;   // (16 unless set: the merge walks a row's chunks one after the other)
     long keys = (max_kv_len + chunks - 1) / chunks;
     keys = (keys + 31) / 32 * 32;
     p.chunk_keys = (int)keys;
@@ -569,16 +639,43 @@ size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int gr
 // prologue (they would spill); those shapes keep the separate rotary/append kernel.
 constexpr bool fused_fits(int hd, int rt) { return !(hd == 128 && rt >= 3); }
 
+// Workgroups of cw wavefronts can merge their chunk results themselves when those fit in 64 KiB of
+// LDS, and with 8 wavefronts only where two of them fit on a SIMD (64-dim heads, one row tile).
+constexpr bool merge_fits(int hd, int rt, int cw)
+{
+    return cw * rt * 16 * (hd + 2) * 4 <= 64 * 1024 && (cw < 8 || (hd == 64 && rt == 1));
+}
+
+// wavefronts per workgroup for a launch with max_chunks chunks per (sequence, kv head): 1, 2, 4 or 8,
+// or 0 when the chunks go to memory and attn_merge_kernel merges them
+// (a workgroup sits on ONE compute unit: with few (sequence, kv head) pairs and many chunks each,
+// merging inside the workgroup would leave most of the chip idle -- measured slower for the draft
+// model's 64 pairs x 8 chunks -- so it needs at least half as many workgroups as compute units)
+static int merge_width(int hd, int rt, int max_chunks, int n_pairs, int cu_count)
+{
+    const int cw = max_chunks <= 1 ? 1 : max_chunks <= 2 ? 2 : max_chunks <= 4 ? 4 : max_chunks <= 8 ? 8 : 0;
+    const int need = g_merge_min_pairs > 0 ? g_merge_min_pairs : cu_count / 2;
+    return cw > 0 && merge_fits(hd, rt, cw) && n_pairs >= need ? cw : 0;
+}
+
 template <int HD>
-static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, const LookaheadPack& ks,
+static int launch_chunks(int rt, int cw, dim3 grid, dim3 wg_grid, hipStream_t s, const StepTables& t, const LookaheadPack& ks,
                          const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
                          const AttnPlan& p, int r_cap, float sl2, float* part_o, float* part_ml, const QkvSrc& src,
-                         void* cache_w)
+                         void* cache_w, const XOut& xo)
 {
+#define SPECV_ATTN_CW(RT, PG, FU, CW_)                                                                         \
+    hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, PG, FU, CW_>), CW_ > 0 ? wg_grid : grid, dim3(CW_ > 0 ? 64 * CW_ : 64), \
+                       0, s, t, ks, g, n_q_heads, layer, (const uint4*)cache, q, p.max_chunks, r_cap, sl2, part_o,   \
+                       part_ml, src, (uint16_t*)cache_w, xo)
 #define SPECV_ATTN_GO(RT, PG, FU)                                                                              \
-    hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, PG, FU>), grid, dim3(64), 0, s, t, ks, g, n_q_heads, layer,    \
-                       (const uint4*)cache, q, p.max_chunks, r_cap, sl2, part_o, part_ml, src,                   \
-                       (uint16_t*)cache_w)
+    do {                                                                                                         \
+        if (cw == 1) SPECV_ATTN_CW(RT, PG, FU, 1);                                                               \
+        else if (cw == 2) { if constexpr (merge_fits(HD, RT, 2)) SPECV_ATTN_CW(RT, PG, FU, 2); }                 \
+        else if (cw == 4) { if constexpr (merge_fits(HD, RT, 4)) SPECV_ATTN_CW(RT, PG, FU, 4); }                 \
+        else if (cw == 8) { if constexpr (merge_fits(HD, RT, 8)) SPECV_ATTN_CW(RT, PG, FU, 8); }                 \
+        else SPECV_ATTN_CW(RT, PG, FU, 0);                                                                       \
+    } while (0)
 #define SPECV_ATTN(RT)                                                                                           \
     do {                                                                                                         \
         if (src.partial) {                                                                                       \
@@ -600,6 +697,7 @@ static int launch_chunks(int rt, dim3 grid, hipStream_t s, const StepTables& t, 
     }
 #undef SPECV_ATTN
 #undef SPECV_ATTN_GO
+#undef SPECV_ATTN_CW
     SPECV_LAUNCH_CHECK("attn_chunk_kernel");
     return SPEC_OK;
 }
@@ -645,19 +743,22 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
     int kmax = 0;
     for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
     const int rt = ((kmax + 1) * group + 15) / 16;
-    const dim3 grid((unsigned)B * g.n_kv_heads * p.max_chunks);
+    const dim3 grid((unsigned)B * g.n_kv_heads * p.max_chunks), wg_grid((unsigned)B * g.n_kv_heads);
     const float sl2 = scale * 1.4426950408889634f;
+    if (hd != 64 && hd != 128) return fail(SPEC_ERR_SHAPE, "bf16 attention needs head_dim 64 or 128");
+    const int cw = rt >= 1 && rt <= 4 ? merge_width(hd, rt, p.max_chunks, B * g.n_kv_heads, cu_count) : 0;
     int rc;
     {
         ProfScope ps(prof, SPEC_PROF_ATTENTION, s);
         if (hd == 128)
-            rc = launch_chunks<128>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml, src, cache_w);
-        else if (hd == 64)
-            rc = launch_chunks<64>(rt, grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o, part_ml, src, cache_w);
+            rc = launch_chunks<128>(rt, cw, grid, wg_grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o,
+                                    part_ml, src, cache_w, xo);
         else
-            return fail(SPEC_ERR_SHAPE, "bf16 attention needs head_dim 64 or 128");
+            rc = launch_chunks<64>(rt, cw, grid, wg_grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o,
+                                   part_ml, src, cache_w, xo);
     }
     if (rc) return rc;
+    if (cw > 0) return SPEC_OK;   // the workgroups merged their chunks themselves
     ProfScope ps(prof, SPEC_PROF_ATTN_MERGE, s);
     hipLaunchKernelGGL(attn_merge_kernel, dim3(M, (n_q_heads * hd / 8 + 63) / 64), dim3(64), 0, s, t, ks, g.n_kv_heads,
                        n_q_heads, hd, p.max_chunks, r_cap, part_o, part_ml, xo);

@@ -262,6 +262,8 @@ struct AttnPlan {
 };
 AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count, bool paged = false);
 void set_attn_items_per_cu(int n);
+void set_attn_merge_min_pairs(int n);
+void set_attn_max_chunks(int n);
 size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
                            int cu_count, bool paged = false);
 // Whether the bf16 attention kernel can take the QKV projection's partial sums itself (QkvSrc) for

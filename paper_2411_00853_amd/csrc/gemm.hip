@@ -630,6 +630,8 @@ extern "C" int spec_pack_weight(const void* src, void* dst, int32_t n_out, int32
 extern "C" void spec_k_set_gemm_wg_target(int32_t workgroups) { set_gemm_wg_target(workgroups); }
 extern "C" void spec_k_set_swiglu_min_wgs(int32_t workgroups) { set_swiglu_min_wgs(workgroups); }
 extern "C" void spec_k_set_attn_items_per_cu(int32_t items) { set_attn_items_per_cu(items); }
+extern "C" void spec_k_set_attn_merge_min_pairs(int32_t pairs) { set_attn_merge_min_pairs(pairs); }
+extern "C" void spec_k_set_attn_max_chunks(int32_t chunks) { set_attn_max_chunks(chunks); }
 
 extern "C" size_t spec_k_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K)
 {

@@ -237,6 +237,31 @@ def test_random_small_models_with_swiglu_inside_the_gemm(seed):
         sv.spec_k_set_swiglu_min_wgs(0)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 5, 7, 9, 11, 12, 13, 14, 15, 16, 18, 20, 22])
+@pytest.mark.parametrize("max_chunks", [1, 2, 3, 8])
+def test_random_small_models_with_chunks_merged_in_the_workgroup(seed, max_chunks):
+    """The same seeded cases with the attention workgroups forced to merge their chunks themselves
+    (by default only launches with enough (sequence, kv head) pairs do), at 1, 2, 4 (for 3 chunks) and
+    8 wavefronts per workgroup; shapes whose chunk results do not fit fall back to the merge kernel."""
+    from paper_2411_00853_amd import binding as sv
+    shape, n_slots, cap, kmax, lens, look, order, T = _random_case(1000 + seed)
+    if shape.dtype != "bf16":
+        pytest.skip("bf16 path only")
+    sv.spec_k_set_attn_merge_min_pairs(1)
+    sv.spec_k_set_attn_max_chunks(max_chunks)
+    try:
+        rig = Rig(shape, n_slots, cap, kmax, seed=20 + seed, std=0.05)
+        rng = wl.Rng(300 + seed, "cpu")
+        for s, n in enumerate(lens):
+            rig.prefill(s, rng.randint(70 + s, (n,), shape.vocab).tolist())
+        t0 = rng.randint(90, (n_slots,), shape.vocab).tolist()
+        err, chk, na, ot, logits, want = _check_step(rig, order, t0, [look[s] for s in order], T, 40 + seed)
+        assert err <= 5e-3, (err, shape, lens, look)
+    finally:
+        sv.spec_k_set_attn_merge_min_pairs(0)
+        sv.spec_k_set_attn_max_chunks(0)
+
+
 def test_step_rollback_step_reproduces_bits_and_ignores_stale_slots():
     shape = wl.ModelShape(2, 256, 4, 2, 64, 256, 512)
     rig = Rig(shape, 2, 96, 4, seed=5, std=0.05)
