@@ -290,7 +290,17 @@ def test_step_rollback_step_reproduces_bits_and_ignores_stale_slots():
     assert e.value.status == -7
 
 
-def test_kv_overflow_skips_the_sequence():
+@pytest.mark.parametrize("merge_in_workgroup", [False, True])
+def test_kv_overflow_skips_the_sequence(merge_in_workgroup):
+    from paper_2411_00853_amd import binding as sv
+    sv.spec_k_set_attn_merge_min_pairs(1 if merge_in_workgroup else 0)   # both ways of writing a skipped row
+    try:
+        _kv_overflow_case()
+    finally:
+        sv.spec_k_set_attn_merge_min_pairs(0)
+
+
+def _kv_overflow_case():
     shape = wl.ModelShape(1, 128, 2, 2, 64, 128, 300)
     rig = Rig(shape, 2, 40, 4, seed=6)
     rng = wl.Rng(4, "cpu")
@@ -310,3 +320,7 @@ def test_kv_overflow_skips_the_sequence():
     assert e.value.status == -3
     assert na.cpu().tolist()[0] == -1 and na.cpu().tolist()[1] >= 0
     assert rig.kv_len.cpu().tolist()[0] == 38                        # untouched
+    # the healthy neighbour is unaffected: a second step on it alone matches the oracle
+    rig.kv_len[1] = 10
+    err, chk, na2, ot2, logits, want = _check_step(rig, [1], [2], [4], 1.0, 77)
+    assert err < 5e-3
