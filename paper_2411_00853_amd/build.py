@@ -4,6 +4,7 @@ from __future__ import annotations
 import os
 import shutil
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -11,8 +12,14 @@ LIB = os.path.join(HERE, "libspecverify.so")
 SOURCES = ["spec_verify.hip", "forward.hip", "sampler.hip", "gemm.hip", "attention.hip", "elementwise.hip",
            "probe.hip", "decode.hip", "lookahead.hip"]
 # packed-fp32 instructions are disabled for all device code
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# Per-source additions.  attention.hip: matrix instructions take their accumulators in ordinary vector
+# registers; left to its default the compiler parks them in the accumulation registers and copies all
+# 32 of them out and back around every block's products (the rare rescaling is vector arithmetic).
+# The GEMM kernels keep the default: several of their variants measured slower with this option.
+SOURCE_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+OBJ_DIR = os.path.join(HERE, "_build")
 
 
 def _hipcc() -> str:
@@ -34,13 +41,30 @@ def sources_newer_than_lib() -> bool:
 def build_library(force: bool = False, verbose: bool = False) -> str:
     if not force and not sources_newer_than_lib():
         return LIB
-    cmd = [_hipcc()] + FLAGS + ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if verbose or r.returncode:
-        noise = "packed-fp32-ops"
-        print("\n".join(l for l in (r.stdout + r.stderr).splitlines() if noise not in l))
-    if r.returncode:
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    hipcc = _hipcc()
+    noise = "packed-fp32-ops"
+
+    def report(r):
+        if verbose or r.returncode:
+            print("\n".join(l for l in (r.stdout + r.stderr).splitlines() if noise not in l and l.strip()))
+
+    def compile_one(src):
+        obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+        cmd = [hipcc] + FLAGS + SOURCE_FLAGS.get(src, []) + ["-c", "-o", obj, os.path.join(CSRC, src)]
+        return obj, subprocess.run(cmd, capture_output=True, text=True)
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:   # one hipcc process per source
+        done = list(pool.map(compile_one, SOURCES))
+    for _, r in done:
+        report(r)
+    if any(r.returncode for _, r in done):
         raise RuntimeError("hipcc failed building libspecverify.so")
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [o for o, _ in done],
+                       capture_output=True, text=True)
+    report(r)
+    if r.returncode:
+        raise RuntimeError("hipcc failed linking libspecverify.so")
     return LIB
 
 

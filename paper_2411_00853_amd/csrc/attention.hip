@@ -284,17 +284,32 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
             for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[rt], mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = exp2f(m_run[rt] - m_use);
-            m_run[rt] = m_new;
+            // The reference exponent m_run of a row only moves when a score exceeds it by more than
+            // 8 (weights stay below 2^8, far inside fp32 and the two-plane split): after the first
+            // blocks that is rare, and a trip in which no row of the wavefront moves skips the
+            // rescaling of the accumulators -- 32 multiplications and as many register moves each way,
+            // about as many issue cycles as the block's matrix products.  Sums and outputs stay
+            // relative to m_run, which is all the merge needs.
+            const bool move = mx > m_run[rt] + 8.f;
+            if (__builtin_amdgcn_ballot_w64(move) != 0) {
+                const float m_to = move ? mx : m_run[rt];
+                const float m_fin = (m_to == -INFINITY) ? 0.f : m_to;
+                const float alpha = move ? __builtin_amdgcn_exp2f(m_run[rt] - m_fin) : 1.f;
+                m_run[rt] = m_to;
+                l_run[rt] *= alpha;
+#pragma unroll
+                for (int d = 0; d < DT; ++d) {
+                    acc[rt][d][0] *= alpha; acc[rt][d][1] *= alpha; acc[rt][d][2] *= alpha; acc[rt][d][3] *= alpha;
+                }
+            }
+            const float m_use = (m_run[rt] == -INFINITY) ? 0.f : m_run[rt];
             float ps = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                sv[e] = exp2f(sv[e] - m_use);
+                sv[e] = __builtin_amdgcn_exp2f(sv[e] - m_use);   // arguments <= 8; far below -126 the result is 0
                 ps += sv[e];
             }
-            l_run[rt] = l_run[rt] * alpha + ps;
+            l_run[rt] += ps;
             Frag ph, pl;
             split_frag(sv, ph, pl);
 #pragma unroll
@@ -302,7 +317,6 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
                 Frag vf;
                 vf.u = vv[d];
                 floatx4 a = acc[rt][d];
-                a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
                 a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, ph.v, a, 0, 0, 0);
                 a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pl.v, a, 0, 0, 0);
                 acc[rt][d] = a;

@@ -177,6 +177,30 @@ def test_sequences_far_below_the_cache_capacity():
     assert err < 5e-3
 
 
+@pytest.mark.parametrize("hd,merge_in_workgroup", [(64, False), (64, True), (128, False), (128, True)])
+def test_peaked_attention_scores(hd, merge_in_workgroup):
+    """Query and key projections scaled up so that the scores spread over tens of units: in some
+    blocks a row's running reference exponent jumps, in others a new maximum stays within the
+    margin and the reference lags behind it; both must agree with the plain softmax."""
+    from paper_2411_00853_amd import binding as sv
+    shape = wl.ModelShape(2, 256, 256 // hd, 128 // hd, hd, 256, 512)
+    w = wl.make_weights(shape, 21, "cpu", std=0.05)
+    for lay in w["layers"]:
+        rows = shape.d_q + shape.d_kv                      # the query and key rows of q|k|v
+        lay["w_qkv"][:rows] = (lay["w_qkv"][:rows].float() * 4.0).to(lay["w_qkv"].dtype)
+    sv.spec_k_set_attn_merge_min_pairs(1 if merge_in_workgroup else 0)
+    try:
+        rig = Rig(shape, 2, 700, 4, w_cpu=w)
+        rng = wl.Rng(33, "cpu")
+        for s, n in {0: 610, 1: 150}.items():
+            rig.prefill(s, rng.randint(70 + s, (n,), shape.vocab).tolist())
+        # the scores really are spread out: the oracle's attention is far from uniform
+        err, chk, na, ot, logits, want = _check_step(rig, [0, 1], [9, 11], [4, 3], 1.0, 15)
+        assert err < 1e-2
+    finally:
+        sv.spec_k_set_attn_merge_min_pairs(0)
+
+
 def _random_case(seed):
     """A seeded small model and batch: shapes, lengths and lookaheads drawn from the ranges the
     library accepts (bf16: 64- or 128-dim heads, widths multiples of 32)."""
