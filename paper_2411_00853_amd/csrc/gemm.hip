@@ -443,10 +443,12 @@ struct Variant {
 // per wave (each X fragment read from LDS feeds that many products) keep LDS traffic per W byte down.
 // From 8 row tiles on the workgroup has eight wavefronts (two row halves) and the three-buffer
 // pipeline of one K block per chunk (see the kernel): both measured slower at 6 row tiles (88
-// rows), faster from 8 on (120 rows -6 %, 160 -7 %, 250 and 320 -20 %).
+// rows), faster from 8 on (120 rows -6 %, 160 -7 %, 250 and 320 -20 %).  Those variants come in
+// even row-tile counts only: the two row halves of a workgroup take ceil(mt/2) tiles each, so an
+// odd count costs what the next even one does.
 constexpr Variant kVariants[] = {{1, 2, 4}, {2, 2, 4}, {3, 2, 4}, {4, 2, 2}, {5, 4, 2}, {6, 4, 2},
-                                 {8, 4, 1}, {9, 4, 1}, {11, 4, 1}, {12, 4, 1}, {14, 2, 1}, {16, 2, 1},
-                                 {19, 2, 1}, {22, 2, 1}};
+                                 {8, 4, 1}, {10, 4, 1}, {12, 4, 1}, {14, 2, 1}, {16, 2, 1}, {18, 2, 1},
+                                 {20, 2, 1}, {22, 2, 1}};
 constexpr int kWideMaxMt = 4;
 constexpr int kWideMinTiles = 340;   // column tiles from which the wide variant still fills the chip
 
@@ -522,12 +524,12 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     SPECV_GEMM(5, 4, 2);
     SPECV_GEMM(6, 4, 2);
     SPECV_GEMM(8, 4, 1, 2);
-    SPECV_GEMM(9, 4, 1, 2);
-    SPECV_GEMM(11, 4, 1, 2);
+    SPECV_GEMM(10, 4, 1, 2);
     SPECV_GEMM(12, 4, 1, 2);
     SPECV_GEMM(14, 2, 1, 2);
     SPECV_GEMM(16, 2, 1, 2);
-    SPECV_GEMM(19, 2, 1, 2);
+    SPECV_GEMM(18, 2, 1, 2);
+    SPECV_GEMM(20, 2, 1, 2);
     SPECV_GEMM(22, 2, 1, 2);
 #undef SPECV_GEMM
     return fail(SPEC_ERR_SHAPE, "no GEMM variant for %d rows (%d row tiles, %d column tiles per wave)", M, p.mt, p.nt);
