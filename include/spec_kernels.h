@@ -44,6 +44,11 @@ void spec_k_set_gemm_wg_target(int32_t workgroups);
  * (a third of the compute units).  1 forces it wherever the shape allows. */
 void spec_k_set_swiglu_min_wgs(int32_t workgroups);
 
+/* Tuning knob: wavefronts per workgroup of that SwiGLU GEMM (each takes a gate tile and its up
+ * tile): 2, 3 or 4; 0 = default (as few as still give no more workgroups than compute units).
+ * Process-wide; affects launches made after the call. */
+void spec_k_set_swiglu_column_groups(int32_t groups);
+
 /* Tuning knob: wavefront work items (sequence, kv head, position chunk) per compute unit that the
  * attention kernel's position split aims for (0 = default).  Set before spec_verify_init: the
  * workspace for chunk results is sized with it.  Process-wide. */

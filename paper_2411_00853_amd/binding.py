@@ -123,6 +123,8 @@ def lib():
         L.spec_k_set_gemm_wg_target.argtypes = [C.c_int32]
         L.spec_k_set_swiglu_min_wgs.restype = None
         L.spec_k_set_swiglu_min_wgs.argtypes = [C.c_int32]
+        L.spec_k_set_swiglu_column_groups.restype = None
+        L.spec_k_set_swiglu_column_groups.argtypes = [C.c_int32]
         L.spec_k_set_attn_items_per_cu.restype = None
         L.spec_k_set_attn_items_per_cu.argtypes = [C.c_int32]
         L.spec_k_set_attn_merge_min_pairs.restype = None
@@ -455,6 +457,10 @@ def spec_k_set_gemm_wg_target(workgroups: int):
 
 def spec_k_set_swiglu_min_wgs(workgroups: int):
     lib().spec_k_set_swiglu_min_wgs(int(workgroups))
+
+
+def spec_k_set_swiglu_column_groups(groups: int):
+    lib().spec_k_set_swiglu_column_groups(int(groups))
 
 
 def spec_k_set_attn_items_per_cu(items: int):

@@ -239,8 +239,9 @@ void set_gemm_wg_target(int workgroups);
 // (see gemm.hip); `fits` says whether the shape allows it.
 bool gemm_swiglu_fits(int M, int F, int cu_count);
 void set_swiglu_min_wgs(int workgroups);
+void set_swiglu_column_groups(int groups);
 int launch_gemm_swiglu(const void* x_frags, int planes, const void* w_gate_up, int M, int F, int K, const float* ssq,
-                       int n_ssq, int d, float eps, void* act_frags, int act_mt, int act_planes, hipStream_t s);
+                       int n_ssq, int d, float eps, void* act_frags, int act_mt, int act_planes, int cu_count, hipStream_t s);
 int launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* y, hipStream_t s);
 
 // The QKV projection's result as the attention kernel can take it directly (bf16 path): K-range

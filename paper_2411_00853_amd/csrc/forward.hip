@@ -182,7 +182,7 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
             // the gate/up GEMM applies the norm's row scale and SwiGLU itself and writes the down
             // projection's operand (into the second fragment buffer: it is still reading the first)
             RUN(SPEC_PROF_GEMM, launch_gemm_swiglu(h->xf, planes, w.w_gate_up, M, z.F, z.d, h->ssq, n_ssq, z.d, c.rms_eps,
-                                                   h->xf_act, mt, planes, s));
+                                                   h->xf_act, mt, planes, h->cu_count, s));
             rc = gemm(h->act, nullptr, w.w_down, z.d, z.F, &o, h->xf_act);
         } else {
             rc = gemm(h->x, w.ffn_norm, w.w_gate_up, 2 * z.F, z.d, &o);

@@ -56,6 +56,12 @@ constexpr int WPACK_KG = 4;   // K blocks per group of the packed weight order
 // its up tile are neighbours): instead of leaving sums for another kernel, the workgroup applies the
 // row scale of the preceding norm, computes silu(gate) * up and writes the result as operand
 // fragments of the down projection.  One kernel and one round of partial sums less per layer.
+// CG: wavefronts (column groups of NT tiles) per workgroup, 4 unless the launch picks fewer.  With a
+// single K range every workgroup streams all of X through its compute unit next to its share of W;
+// three wavefronts per workgroup put the 7B-shape gate/up projection on 230 compute units instead of
+// 172, and the same stream ran in 32.5 instead of 37.8 us (stand-alone, epilogue removed; without
+// any X traffic both take 30 us): what a compute unit can pull from L2 per unit of time, X included,
+// is the limit there, not HBM.
 struct SwigluOut {
     const float* ssq;   // NormScale of the rows (sums of squares in n_ssq chunks)
     int n_ssq, d;
@@ -64,14 +70,15 @@ struct SwigluOut {
     int mt, planes;
 };
 
-template <int MT, int NT, int KC, int PLANES, int RS = 1, int EPI = 0>
-__global__ void __launch_bounds__(256 * RS) gemm_skinny_kernel(const u32x4* __restrict__ Xf, const u32x4* __restrict__ Wp,
+template <int MT, int NT, int KC, int PLANES, int RS = 1, int EPI = 0, int CG = 4>
+__global__ void __launch_bounds__(64 * CG * RS) gemm_skinny_kernel(const u32x4* __restrict__ Xf, const u32x4* __restrict__ Wp,
                                                           float* __restrict__ partial, int M, int n_tiles,
                                                           int kb_total, int kb_per_split, int n_split, int n_blocks,
                                                           SwigluOut so)
 {
     constexpr int CHUNK_U4 = KC * PLANES * MT * 64;     // 16-byte units per X chunk (contiguous in Xf)
-    constexpr int TPBK = 256 * RS;                        // threads per workgroup
+    static_assert(RS == 1 || CG == 4, "two row halves come with four column groups");
+    constexpr int TPBK = 64 * CG * RS;                    // threads per workgroup: CG column groups x RS row halves
     constexpr int UPT = (CHUNK_U4 + TPBK - 1) / TPBK;     // per thread
     __shared__ u32x4 xs[2][CHUNK_U4];                   // two chunk buffers
 
@@ -81,7 +88,7 @@ __global__ void __launch_bounds__(256 * RS) gemm_skinny_kernel(const u32x4* __re
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     constexpr int MTW = (MT + RS - 1) / RS;               // row tiles of one wavefront
     const int a0 = RS == 1 ? 0 : (wave & 1) * MTW;          // its first row tile
-    const int tile0 = (nblk * 4 + (RS == 1 ? wave : wave >> 1)) * NT;
+    const int tile0 = (nblk * CG + (RS == 1 ? wave : wave >> 1)) * NT;
     const int kb0 = split * kb_per_split;
     const int kb1 = min(kb0 + kb_per_split, kb_total);
 
@@ -300,11 +307,11 @@ __global__ void __launch_bounds__(256 * RS) gemm_skinny_kernel(const u32x4* __re
     const int g = lane >> 4, c = lane & 15;
     if constexpr (EPI == 1) {
         static_assert(EPI == 0 || (NT == 2 && RS == 1), "the SwiGLU epilogue pairs the two column tiles of a wavefront");
-        static_assert(EPI == 0 || sizeof(xs) >= 4 * MT * 256 * sizeof(float), "tile staging fits the X chunk buffers");
+        static_assert(EPI == 0 || sizeof(xs) >= CG * MT * 256 * sizeof(float), "tile staging fits the X chunk buffers");
         __shared__ float rsv[MT * 16];
         __syncthreads();                                      // everyone is done with the X chunk buffers
         float* tw = reinterpret_cast<float*>(&xs[0][0]) + wave * (MT * 256);   // [MT*16 rows][16 units]
-        for (int m = threadIdx.x; m < MT * 16; m += 256)
+        for (int m = threadIdx.x; m < MT * 16; m += TPBK)
             rsv[m] = m < M ? row_inv_rms(so.ssq, so.n_ssq, m, so.d, so.eps) : 0.f;
         __syncthreads();
 #pragma unroll
@@ -537,48 +544,71 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
 
 namespace {
 int g_swiglu_min_wgs = 0;   // 0: a third of the compute units
+int g_swiglu_cg = 0;        // 0: chosen by swiglu_column_groups; 2, 3, 4: forced (tests)
 }
 void set_swiglu_min_wgs(int n) { g_swiglu_min_wgs = n; }
+void set_swiglu_column_groups(int n) { g_swiglu_cg = n >= 2 && n <= 4 ? n : 0; }
 
 // The gate/up projection can finish SwiGLU itself when it runs as ONE K range of 128-column
 // workgroups (narrow variants, up to 4 row tiles) and that still gives enough workgroups.
 bool gemm_swiglu_fits(int M, int F, int cu_count)
 {
     const int mt = gemm_row_tiles(M);
-    if (mt < 1 || mt > 4 || F % 16) return false;   // (6 row tiles measured: the narrow GEMM loses more than the kernel saved)
+    if (mt < 1 || mt > 4 || F % 16) return false;   // (6 row tiles measured, with four and with three wavefronts per workgroup: the narrow GEMM loses more than the kernel saved)
     const int wgs = (2 * F / 16 + 7) / 8;
     // measured: 172 workgroups (F = 11008) step -1.9 %, 128 workgroups (F = 8192) -3.5 %
     return wgs >= (g_swiglu_min_wgs > 0 ? g_swiglu_min_wgs : cu_count / 3);
 }
 
-template <int MT, int KC>
-static int launch_swiglu_variant(int planes, const void* xf, const void* w, int M, int K, int n_tiles, const SwigluOut& so,
-                                 hipStream_t s)
+template <int MT, int KC, int CG>
+static int launch_swiglu_cg(int planes, const void* xf, const void* w, int M, int K, int n_tiles, const SwigluOut& so,
+                            hipStream_t s)
 {
-    const int n_blocks = (n_tiles + 7) / 8;
+    const int n_blocks = (n_tiles + 2 * CG - 1) / (2 * CG);
     const int grid = (n_blocks + 7) / 8 * 8;       // map_block deals workgroups to the 8 XCDs
     const int kb = K / 32;
     if (planes == 2)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, 2, KC, 2, 1, 1>), dim3(grid), dim3(256), 0, s, (const u32x4*)xf,
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, 2, KC, 2, 1, 1, CG>), dim3(grid), dim3(64 * CG), 0, s, (const u32x4*)xf,
                            (const u32x4*)w, nullptr, M, n_tiles, kb, (kb + WPACK_KG - 1) / WPACK_KG * WPACK_KG, 1, n_blocks, so);
     else
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, 2, KC, 1, 1, 1>), dim3(grid), dim3(256), 0, s, (const u32x4*)xf,
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, 2, KC, 1, 1, 1, CG>), dim3(grid), dim3(64 * CG), 0, s, (const u32x4*)xf,
                            (const u32x4*)w, nullptr, M, n_tiles, kb, (kb + WPACK_KG - 1) / WPACK_KG * WPACK_KG, 1, n_blocks, so);
     SPECV_LAUNCH_CHECK("gemm_skinny_kernel (SwiGLU)");
     return SPEC_OK;
 }
 
+// wavefronts per workgroup of the SwiGLU GEMM: as few as still give no more workgroups than compute
+// units (the number of wavefronts in the launch is the same either way, one per pair of column tiles;
+// fewer per workgroup spread them, and the X traffic, over more compute units)
+static int swiglu_column_groups(int n_tiles, int cu_count)
+{
+    for (int cg = 2; cg < 4; ++cg)
+        if ((n_tiles + 2 * cg - 1) / (2 * cg) <= cu_count) return cg;
+    return 4;
+}
+
+template <int MT, int KC>
+static int launch_swiglu_variant(int planes, const void* xf, const void* w, int M, int K, int n_tiles, const SwigluOut& so,
+                                 int cu_count, hipStream_t s)
+{
+    switch (g_swiglu_cg > 0 ? g_swiglu_cg : swiglu_column_groups(n_tiles, cu_count)) {
+    case 2: return launch_swiglu_cg<MT, KC, 2>(planes, xf, w, M, K, n_tiles, so, s);
+    case 3: return launch_swiglu_cg<MT, KC, 3>(planes, xf, w, M, K, n_tiles, so, s);
+    default: return launch_swiglu_cg<MT, KC, 4>(planes, xf, w, M, K, n_tiles, so, s);
+    }
+}
+
 int launch_gemm_swiglu(const void* x_frags, int planes, const void* w_gate_up, int M, int F, int K, const float* ssq,
-                       int n_ssq, int d, float eps, void* act_frags, int act_mt, int act_planes, hipStream_t s)
+                       int n_ssq, int d, float eps, void* act_frags, int act_mt, int act_planes, int cu_count, hipStream_t s)
 {
     if (K % 32 || F % 16) return fail(SPEC_ERR_SHAPE, "SwiGLU GEMM needs K %% 32 == 0 and F %% 16 == 0");
     const SwigluOut so{ssq, n_ssq, d, eps, static_cast<uint4*>(act_frags), act_mt, act_planes};
     const int n_tiles = 2 * F / 16;
     switch (gemm_row_tiles(M)) {
-    case 1: return launch_swiglu_variant<1, 4>(planes, x_frags, w_gate_up, M, K, n_tiles, so, s);
-    case 2: return launch_swiglu_variant<2, 4>(planes, x_frags, w_gate_up, M, K, n_tiles, so, s);
-    case 3: return launch_swiglu_variant<3, 4>(planes, x_frags, w_gate_up, M, K, n_tiles, so, s);
-    case 4: return launch_swiglu_variant<4, 2>(planes, x_frags, w_gate_up, M, K, n_tiles, so, s);
+    case 1: return launch_swiglu_variant<1, 4>(planes, x_frags, w_gate_up, M, K, n_tiles, so, cu_count, s);
+    case 2: return launch_swiglu_variant<2, 4>(planes, x_frags, w_gate_up, M, K, n_tiles, so, cu_count, s);
+    case 3: return launch_swiglu_variant<3, 4>(planes, x_frags, w_gate_up, M, K, n_tiles, so, cu_count, s);
+    case 4: return launch_swiglu_variant<4, 2>(planes, x_frags, w_gate_up, M, K, n_tiles, so, cu_count, s);
     default: return fail(SPEC_ERR_SHAPE, "no SwiGLU GEMM variant for %d rows", M);
     }
 }
@@ -631,6 +661,7 @@ extern "C" int spec_pack_weight(const void* src, void* dst, int32_t n_out, int32
 
 extern "C" void spec_k_set_gemm_wg_target(int32_t workgroups) { set_gemm_wg_target(workgroups); }
 extern "C" void spec_k_set_swiglu_min_wgs(int32_t workgroups) { set_swiglu_min_wgs(workgroups); }
+extern "C" void spec_k_set_swiglu_column_groups(int32_t groups) { set_swiglu_column_groups(groups); }
 extern "C" void spec_k_set_attn_items_per_cu(int32_t items) { set_attn_items_per_cu(items); }
 extern "C" void spec_k_set_attn_merge_min_pairs(int32_t pairs) { set_attn_merge_min_pairs(pairs); }
 extern "C" void spec_k_set_attn_max_chunks(int32_t chunks) { set_attn_max_chunks(chunks); }

@@ -243,12 +243,14 @@ def test_random_small_models(seed):
 @pytest.mark.parametrize("seed", [0, 1, 2, 3, 5, 7, 9, 11, 12, 13, 14, 15])
 def test_random_small_models_with_swiglu_inside_the_gemm(seed):
     """The same seeded cases with the gate/up projection forced to finish SwiGLU itself (by default
-    only launches with enough workgroups do, i.e. large models)."""
+    only launches with enough workgroups do, i.e. large models), with 2, 3 or 4 wavefronts per
+    workgroup in turn (left alone, a small model always gets 2)."""
     from paper_2411_00853_amd import binding as sv
     shape, n_slots, cap, kmax, lens, look, order, T = _random_case(1000 + seed)
     if shape.dtype != "bf16":
         pytest.skip("bf16 path only")
     sv.spec_k_set_swiglu_min_wgs(1)
+    sv.spec_k_set_swiglu_column_groups(2 + seed % 3)
     try:
         rig = Rig(shape, n_slots, cap, kmax, seed=20 + seed, std=0.05)
         rng = wl.Rng(300 + seed, "cpu")
@@ -259,6 +261,7 @@ def test_random_small_models_with_swiglu_inside_the_gemm(seed):
         assert err <= 5e-3, (err, shape, lens, look)
     finally:
         sv.spec_k_set_swiglu_min_wgs(0)
+        sv.spec_k_set_swiglu_column_groups(0)
 
 
 @pytest.mark.parametrize("seed", [0, 1, 2, 3, 5, 7, 9, 11, 12, 13, 14, 15, 16, 18, 20, 22])
