@@ -23,7 +23,7 @@ def _oracle_rows(w, x, rows):
     (1, 64, 32), (6, 3072, 2048), (5, 100, 64), (16, 48, 96), (17, 1000, 320),
     (48, 4096, 4096), (48, 1024, 11008), (33, 2064, 512), (64, 256, 4096),
     (80, 304, 512), (100, 512, 1024), (128, 384, 256), (140, 96, 640), (176, 272, 512), (192, 400, 512),
-    (220, 208, 384), (250, 128, 2048), (300, 64, 256), (352, 640, 1024),
+    (220, 208, 384), (250, 128, 2048), (280, 144, 320), (300, 64, 256), (352, 640, 1024), (157, 352, 1024),
     # many columns: the variants with four column tiles per wavefront
     (8, 6000, 64), (20, 5504, 128), (40, 5456, 96), (64, 5632, 256), (75, 5440, 96), (90, 5440, 64), (185, 5440, 64),
 ])
