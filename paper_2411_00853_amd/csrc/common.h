@@ -225,6 +225,7 @@ struct GemmPlan {
     int nt;           // 16-column tiles per wavefront
     int planes;       // 2: bf16 head + remainder; 1: bf16 head only
     int kb_per_split; // 32-wide K blocks per range
+    int cg;           // column groups (of nt tiles) per workgroup: 4, or 3 for many-row launches that then fill more compute units
 };
 GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x);
 int gemm_row_tiles(int M);   // row tiles (mt) of the variant that serves M rows; 0 if none

@@ -77,7 +77,6 @@ __global__ void __launch_bounds__(64 * CG * RS) gemm_skinny_kernel(const u32x4* 
                                                           SwigluOut so)
 {
     constexpr int CHUNK_U4 = KC * PLANES * MT * 64;     // 16-byte units per X chunk (contiguous in Xf)
-    static_assert(RS == 1 || CG == 4, "two row halves come with four column groups");
     constexpr int TPBK = 64 * CG * RS;                    // threads per workgroup: CG column groups x RS row halves
     constexpr int UPT = (CHUNK_U4 + TPBK - 1) / TPBK;     // per thread
     __shared__ u32x4 xs[2][CHUNK_U4];                   // two chunk buffers
@@ -427,6 +426,21 @@ template <int MT, int NT, int KC, int RS = 1>
 int launch_variant(const GemmPlan& p, const void* xf, const void* w, int M, int K, int n_tiles, float* partial,
                    hipStream_t s)
 {
+    if constexpr (RS == 2) {
+        if (p.cg == 3) {
+            const int n_blocks = (n_tiles + 3 * NT - 1) / (3 * NT);
+            int grid = n_blocks * p.n_split;
+            if (p.n_split < 8) grid = (n_blocks + (8 / p.n_split) - 1) / (8 / p.n_split) * 8;
+            if (p.planes == 2)
+                hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 2, RS, 0, 3>), dim3(grid), dim3(192 * RS), 0, s, (const u32x4*)xf,
+                                   (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
+            else
+                hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 1, RS, 0, 3>), dim3(grid), dim3(192 * RS), 0, s, (const u32x4*)xf,
+                                   (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
+            SPECV_LAUNCH_CHECK("gemm_skinny_kernel");
+            return SPEC_OK;
+        }
+    }
     const int n_blocks = (n_tiles + 4 * NT - 1) / (4 * NT);
     int grid = n_blocks * p.n_split;
     if (p.n_split < 8) grid = (n_blocks + (8 / p.n_split) - 1) / (8 / p.n_split) * 8;
@@ -504,6 +518,16 @@ GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
     int s = 1;
     while (s < 16 && wg_x * s < target && (kb_total + 2 * s - 1) / (2 * s) >= 2 * kc) s *= 2;
     p.n_split = s;
+    // Many rows (the eight-wavefront variants): the matrix instructions set the pace, so compute units
+    // without a workgroup are lost time; three column groups per workgroup instead of four when that
+    // brings the launch from under four fifths of the compute units to at most all of them
+    // (157 rows: QKV 192 -> 256 workgroups, gate/up 172 -> 230; GEMM time of that step -6 %).  With
+    // few rows, where HBM sets the pace, the same change gained nothing and is not made.
+    p.cg = 4;
+    if (p.mt >= 8) {
+        const int wg3 = (n_tiles + 3 * p.nt - 1) / (3 * p.nt) * s;
+        if (wg_x * s * 5 < cu_count * 4 && wg3 <= cu_count) p.cg = 3;
+    }
     // ranges start on a K group of the packed order so that every chunk is one contiguous run
     p.kb_per_split = ((kb_total + s - 1) / s + WPACK_KG - 1) / WPACK_KG * WPACK_KG;
     return p;
