@@ -59,3 +59,13 @@ def test_bad_configurations_are_rejected_before_any_device_work(lib):
     assert sv.spec_kv_cache_bytes(odd) == 0
     assert lib.spec_verify_step(None, None, None, None) == -1
     assert lib.spec_kv_rollback(None, None, None, 0, None) == -1
+
+
+def test_build_lists_name_existing_sources():
+    """Every source the build compiles exists, and per-source options refer to listed sources."""
+    import os
+    from paper_2411_00853_amd import build as b
+    for src in b.SOURCES:
+        assert os.path.exists(os.path.join(b.CSRC, src)), src
+    assert set(b.SOURCE_FLAGS) <= set(b.SOURCES)
+    assert "--offload-arch=gfx950" in b.FLAGS and "-packed-fp32-ops" in b.FLAGS
