@@ -86,7 +86,7 @@ struct StepTables {
 };
 
 // ---- sampler (sampler.hip) ---------------------------------------------------------------------
-constexpr int STAT_CHUNK = 8192;   // logits per workgroup in the statistics pass
+constexpr int STAT_CHUNK = 16384;   // logits per workgroup in the statistics pass
 constexpr int RES_CHUNK = 4096;    // logits per workgroup in the residual pass / final scan
 
 struct SamplerWorkspace {

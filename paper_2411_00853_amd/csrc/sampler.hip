@@ -8,7 +8,7 @@
 // resample from max(0, p - q).
 //
 // The vocabulary-wide work is pure streaming, so it is laid out for HBM: every logit is read once
-// by the statistics pass (float4 per lane, 32 values per lane in flight); only the one or two
+// by the statistics pass (float4 per lane, 64 values per lane in flight); only the one or two
 // rows that the final draw needs are read again.  Sums are kept in fp64 and every reduction has a
 // fixed order (no floating-point atomics), so results are reproducible bit for bit.
 #include "cache_layout.h"
@@ -132,7 +132,7 @@ __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack 
     const int base = chunk * STAT_CHUNK;
     const int lim = min(STAT_CHUNK, V - base);
 
-    constexpr int PER = STAT_CHUNK / TPB;   // 32 values per lane
+    constexpr int PER = STAT_CHUNK / TPB;   // 64 values per lane
     float v[PER];
     if constexpr (VEC4) {
         const float4* p4 = reinterpret_cast<const float4*>(row + base);
