@@ -147,6 +147,8 @@ struct RollbackPack {
 };
 int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len, int32_t* flag, const PagePool& pool,
                     hipStream_t s);
+// paged caches, after launch_kv_compact: return the pages beyond n + n_accepted + 1 of every sequence
+int launch_tree_trim(const StepTables& t, int B, const int32_t* n_accepted, hipStream_t s);
 // paged caches: make sure positions [pos0, pos1) of a slot have pages (flags SPEC_ERR_KV_OVERFLOW if not)
 int launch_pool_cover(const PagePool& pool, int slot, int pos0, int pos1, int32_t* flag, hipStream_t s);
 

@@ -628,8 +628,10 @@ __global__ void __launch_bounds__(64) tree_greedy_kernel(StepTables t, Lookahead
     for (int i = a; i < Kmax; ++i) pth[i] = -1;
     n_accepted[b] = a;
     if (kv_len) {
+        // with auto_rollback the kept path is still to be moved: its pages go back after that
+        // (tree_trim_kernel), never here
         kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : N) + 1;
-        pool_trim(t.pool, t.seq_slot[b], t.seq_n[b] + (auto_rollback ? a : N) + 1);
+        if (!auto_rollback) pool_trim(t.pool, t.seq_slot[b], t.seq_n[b] + N + 1);
     }
 }
 
@@ -986,8 +988,10 @@ __global__ void __launch_bounds__(TREE_TPB) tree_walk_kernel(StepTables t, Looka
             for (int i = a + 1; i <= Kmax; ++i) o[i] = -1;
             for (int i = a; i < Kmax; ++i) out.path[b * Kmax + i] = -1;
             if (kv_len) {
+                // with auto_rollback the kept path is still to be moved: its pages go back after
+                // that (tree_trim_kernel), never here
                 kv_len[t.seq_slot[b]] = t.seq_n[b] + (auto_rollback ? a : N) + 1;
-                pool_trim(t.pool, t.seq_slot[b], t.seq_n[b] + (auto_rollback ? a : N) + 1);
+                if (!auto_rollback) pool_trim(t.pool, t.seq_slot[b], t.seq_n[b] + N + 1);
             }
         }
     }
@@ -1004,6 +1008,18 @@ __global__ void __launch_bounds__(TPB) rollback_kernel(RollbackPack p, int n, in
     if (len < 0 || len > kv_len[slot]) { atomicCAS(flag, 0, (int)SPEC_ERR_ROLLBACK); return; }
     kv_len[slot] = len;
     pool_trim(pool, slot, len);
+}
+
+// Paged cache, after a tree step's compaction: hand back the pages beyond the new length.  The walk
+// cannot do it: a kept node's keys and values may still sit in a block above n + a + 1 until
+// kv_compact_kernel has moved them (n = 28, kept node in window slot 4: position 32 is in the
+// second block, the new length 30 needs the first only).
+__global__ void __launch_bounds__(TPB) tree_trim_kernel(StepTables t, int B, const int32_t* __restrict__ n_accepted)
+{
+    const int b = threadIdx.x;
+    if (b >= B || !t.seq_ok[b]) return;
+    const int a = n_accepted[b];
+    if (a >= 0) pool_trim(t.pool, t.seq_slot[b], t.seq_n[b] + a + 1);
 }
 
 __global__ void pool_cover_kernel(PagePool pool, int slot, int pos0, int pos1, int32_t* flag)
@@ -1109,6 +1125,14 @@ int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len
 {
     hipLaunchKernelGGL(rollback_kernel, dim3(1), dim3(TPB), 0, s, p, n, max_batch, kv_len, flag, pool);
     SPECV_LAUNCH_CHECK("rollback_kernel");
+    return SPEC_OK;
+}
+
+int launch_tree_trim(const StepTables& t, int B, const int32_t* n_accepted, hipStream_t s)
+{
+    if (!t.pool.table) return SPEC_OK;
+    hipLaunchKernelGGL(tree_trim_kernel, dim3(1), dim3(TPB), 0, s, t, B, n_accepted);
+    SPECV_LAUNCH_CHECK("tree_trim_kernel");
     return SPEC_OK;
 }
 

@@ -442,6 +442,7 @@ extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args,
     if (run_model && args->auto_rollback) {
         ProfScope ps(&h->prof, SPEC_PROF_GLUE, s);
         rc = launch_kv_compact(h->geom, h->kv_cache, h->tables, B, Kmax, out->n_accepted, out->path, s);
+        if (rc == SPEC_OK) rc = launch_tree_trim(h->tables, B, out->n_accepted, s);
     }
     return rc;
 }

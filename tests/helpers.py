@@ -119,12 +119,18 @@ class TreeCheck:
         margins = {i: abs(float(us[i]) - d.accept_ratio[i]) for i in tested}
         gp = [int(v) for v in path_gpu[:max(a_gpu, 0)]]
         if a_gpu != a or gp != path:
-            # the two walks may only part ways at a node whose test is inside the margin
+            # The two walks may only part ways at a node whose own test is inside the margin.  Both
+            # try the children of the current node in index order, so after the common prefix the
+            # first child on which they decide differently is the lower of the two nodes they keep
+            # next (a walk that keeps none tested every child); the oracle tested that node.
             k = 0
             while k < min(len(gp), len(path)) and gp[k] == path[k]:
                 k += 1
-            assert any(m <= ACCEPT_MARGIN for m in margins.values()), \
-                f"walk {gp} != oracle {path}, margins {margins}"
+            nxt = [w[k] for w in (gp, path) if k < len(w)]
+            assert nxt, f"walks {gp} and {path} differ in length only by a common prefix"
+            node = min(nxt)
+            assert node in margins and margins[node] <= ACCEPT_MARGIN, \
+                f"walk {gp} != oracle {path}: they part at node {node}, margins {margins}"
             self.margin_walk += 1
             return
         self.exact_walk += 1
@@ -134,9 +140,20 @@ class TreeCheck:
         hi_gap = d.final_cdf_hi - d.final_target
         # the mass scale of r at level k >= 1 is S_k, so compare gaps relative to it
         scale = d.final_S if d.final_S > 0 else 1.0
+        yg = int(out_gpu[a])
         if lo_gap > CDF_MARGIN * scale and hi_gap > CDF_MARGIN * scale:
-            assert int(out_gpu[a]) == out[a], f"final token {out_gpu[a]} != oracle {out[a]} (gaps {lo_gap:.3e}, {hi_gap:.3e})"
+            assert yg == out[a], f"final token {yg} != oracle {out[a]} (gaps {lo_gap:.3e}, {hi_gap:.3e})"
             self.exact_token += 1
-        else:
-            assert 0 <= int(out_gpu[a]) < tl.shape[1]
-            self.margin_token += 1
+            return
+        # inside the band: the GPU's token must still be a valid draw for a CDF moved by the margin.
+        # r at the final node after `final_level` rejections: r <- max(0, r/S - q), starting from p
+        row = d.final_node + 1
+        q = oracle.softmax(dl[row], T)
+        r, S = oracle.softmax(tl[row], T), 1.0
+        for _ in range(d.final_level):
+            r, S = oracle.residual(r / S, q)
+        assert 0 <= yg < r.numel() and r[yg] > 0
+        c = torch.cumsum(r, 0)
+        lo = float(c[yg - 1]) if yg > 0 else 0.0
+        assert lo - 2 * CDF_MARGIN * scale <= d.final_target <= float(c[yg]) + 2 * CDF_MARGIN * scale
+        self.margin_token += 1

@@ -24,8 +24,9 @@ LOGIT_TOL = {"fp32": 1e-4, "bf16": 3e-2}
 class Pair:
     """Target + draft on both sides, a batch of sequences with oracle-built caches."""
 
-    def __init__(self, t_shape, d_shape, contexts, max_kv_len, Kt, max_new, seed=5, std=0.05):
-        from test_gpu_forward import Rig
+    def __init__(self, t_shape, d_shape, contexts, max_kv_len, Kt, max_new, seed=5, std=0.05, paged=None):
+        """paged = (target pages, draft pages): both handles keep their caches in page pools."""
+        from test_gpu_forward import Rig, PagedRig
         from paper_2411_00853_amd import binding as sv
         self.sv = sv
         B = len(contexts)
@@ -40,6 +41,13 @@ class Pair:
             self.tg.set_cache(b, len(ctx) - 1)
             self.dr.set_cache(b, len(ctx) - 2)
             self.states.append(st)
+        if paged:
+            ptg = PagedRig(self.tg, B, max_kv_len, Kt, n_pages=paged[0])
+            pdr = PagedRig(self.dr, B, max_kv_len, 1, n_pages=paged[1])
+            for b in range(B):
+                ptg.load(self.tg, b)
+                pdr.load(self.dr, b)
+            self.tg, self.dr = ptg, pdr
         self.dec = sv.spec_decode_init(self.tg.h, self.dr.h, B, max_new)
         self.max_new = max_new
         dev = "cuda"
@@ -123,9 +131,9 @@ def follow_round(pair, g, K, du, vu, T, chk, tally):
         assert kt[b] == len(st.tokens) - 1 and kd[b] == len(st.tokens) - 2
 
 
-def run_following(t_shape, d_shape, contexts, K, Kt, rounds, T, seed):
+def run_following(t_shape, d_shape, contexts, K, Kt, rounds, T, seed, paged=None):
     from helpers import SamplerCheck
-    pair = Pair(t_shape, d_shape, contexts, 96, Kt, 64, seed=seed)
+    pair = Pair(t_shape, d_shape, contexts, 96, Kt, 64, seed=seed, paged=paged)
     chk = SamplerCheck()
     tally = {"draft_err": 0.0, "target_err": 0.0, "draws_exact": 0, "draws_margin": 0,
              "ctx_len": [len(c) for c in contexts]}

@@ -69,6 +69,32 @@ class Rig:
         return self.om.verify_rows(caches, [self.n[s] for s in slots], windows)
 
 
+class PagedRig:
+    """The same model and sequences as a Rig (it shares the Rig's oracle, weights and oracle-side
+    caches), but the library handle keeps its cache in a page pool of n_pages pages."""
+
+    def __init__(self, base, n_slots, max_kv_len, max_lookahead, n_pages):
+        sv = base.sv
+        self.sv, self.shape, self.Kmax = sv, base.shape, max_lookahead
+        self.om, self.caches, self.n, self.w_cpu, self.w_dev = base.om, base.caches, base.n, base.w_cpu, base.w_dev
+        self.cfg = sv.make_cfg(base.shape, n_slots, max_kv_len, max_lookahead)
+        self.kv = torch.zeros(n_pages * sv.spec_kv_page_bytes(self.cfg), dtype=torch.uint8, device="cuda")
+        self.kv_len = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
+        self.h = sv.spec_verify_init_paged(self.cfg, base.w_dev, self.kv, self.kv_len)
+
+    def load(self, base, slot):
+        n = base.n[slot]
+        if n:
+            self.sv.spec_kv_import(self.h, slot, 0, base.caches[slot][:, :, :, :n, :].contiguous().cuda())
+        self.kv_len[slot] = n
+
+    def free(self):
+        return self.sv.spec_kv_pages(self.h)[0]
+
+    step = Rig.step
+    oracle_logits = Rig.oracle_logits
+
+
 def _drafts(rng, B, Kmax, V, T):
     dl = rng.normal(50, (B, max(Kmax, 1), V), 1.0)[:, :Kmax].contiguous()
     toks = wl.pick_tokens(rng, dl, T, 51) if Kmax else torch.zeros((B, 0), dtype=torch.int32)
@@ -92,21 +118,18 @@ def _check_step(rig, slots, t0, lookahead, T, seed, perturb=0.3):
     logits, na, ot = rig.step(slots, t0, lookahead, toks, dl, us, T)
     err = (logits - want).abs().max().item()
     assert err <= LOGIT_TOL[rig.shape.dtype], f"logits max-abs error {err}"
+    # KV bookkeeping: kv_len = n + accepted + 1, fp32 and bf16 models alike
+    kl = rig.kv_len.cpu().tolist()
+    for b, s in enumerate(slots):
+        assert 0 <= int(na[b]) <= lookahead[b] and kl[s] == n_before[b] + int(na[b]) + 1, (b, s, kl, n_before, na)
     if rig.shape.dtype == "fp32":
         chk = check_sampler_against_oracle(want, dl, toks, us, lookahead, T, Kmax, na, ot)
     else:
-        # identical logits for the token comparison: replay the sampler on the oracle's logits
-        for s, n in zip(slots, n_before):
-            rig.kv_len[s] = n
+        # identical logits for the token comparison: replay the sampler on the oracle's logits (a
+        # sampler-only step neither reads nor writes the cache lengths)
         _, na2, ot2 = rig.step(slots, t0, lookahead, toks, dl, us, T, target_logits_in=want.cuda())
         chk = check_sampler_against_oracle(want, dl, toks, us, lookahead, T, Kmax, na2, ot2)
-        for s, n in zip(slots, n_before):   # the sampler-only replay leaves kv_len alone; restore the step's
-            pass
-    # KV bookkeeping: kv_len = n + accepted + 1
-    kl = rig.kv_len.cpu().tolist()
-    for b, s in enumerate(slots):
-        if rig.shape.dtype == "fp32":
-            assert kl[s] == n_before[b] + int(na[b]) + 1
+        assert rig.kv_len.cpu().tolist() == kl
     return err, chk, na, ot, logits, want
 
 

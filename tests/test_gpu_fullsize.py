@@ -1,9 +1,9 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
-1B-shape and 7B-shape: every window row's logits against the oracle (<= 3e-2), tokens on identical
-logits under the margin rules.  Dynamic lookahead (32 ragged sequences): a sample of sequences
-through the oracle (shortest and longest cache, smallest and largest lookahead), plus properties
-that hold at any size for all of them.  Sampler stress: every sequence against the oracle.
+1B-shape, 7B-shape (contiguous and paged cache), dynamic lookahead (32 ragged sequences, 157 rows)
+and the 7B-shape token tree: every window row of every sequence against the oracle (<= 3e-2), tokens
+on identical logits under the margin rules; the oracle takes the sequences a few at a time, their
+caches regenerated from the seed.  Sampler stress: every sequence against the oracle.
 Weights are made on the GPU by the seeded generator and copied to the host for the oracle; KV
 contents are synthetic N(0,1) (stated in the workload recipe)."""
 import sys
@@ -42,44 +42,57 @@ class BigWeights:
 
 
 class BigRig:
-    def __init__(self, weights, n_slots, max_kv_len, Kmax):
+    def __init__(self, weights, n_slots, max_kv_len, Kmax, paged_lens=None):
+        """paged_lens: the sequences' cached lengths -- the cache then lives in a page pool of exactly
+        the pages one step of those sequences can touch (the handle `bench.py --paged` builds)."""
         from paper_2411_00853_amd import binding as sv
         shape = weights.shape
         self.sv, self.shape, self.Kmax, self.max_kv_len = sv, shape, Kmax, max_kv_len
         self.om = oracle.Model(shape, weights.cpu, max_kv_len)
         self.cfg = sv.make_cfg(shape, n_slots, max_kv_len, Kmax)
-        self.kv = torch.empty(sv.spec_kv_cache_bytes(self.cfg), dtype=torch.uint8, device="cuda")
         self.kv_len = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
-        self.h = sv.spec_verify_init(self.cfg, weights.dev, self.kv, self.kv_len)
+        if paged_lens is None:
+            self.kv = torch.empty(sv.spec_kv_cache_bytes(self.cfg), dtype=torch.uint8, device="cuda")
+            self.h = sv.spec_verify_init(self.cfg, weights.dev, self.kv, self.kv_len)
+        else:
+            self.n_pages = sum((n + Kmax + 1 + 31) // 32 for n in paged_lens)
+            self.kv = torch.empty(self.n_pages * sv.spec_kv_page_bytes(self.cfg), dtype=torch.uint8, device="cuda")
+            self.h = sv.spec_verify_init_paged(self.cfg, weights.dev, self.kv, self.kv_len)
 
-    def fill_slot(self, w, slot, n, seq_index, keep_cpu):
-        """Synthetic N(0,1) cache for one slot; returns the oracle-side cache if asked."""
+    def synthetic(self, w, n, seq_index):
+        """The sequence's synthetic N(0,1) keys and values [layer][k|v][head][n][dim], on the GPU."""
         s = self.shape
         rng = wl.Rng(w.seed, "cuda")
         plain = torch.empty((s.n_layers, 2, s.n_kv_heads, n, s.head_dim), dtype=s.torch_dtype, device="cuda")
         for l in range(s.n_layers):
             plain[l] = rng.normal(wl.S_KV + seq_index * 4096 + l, (2, s.n_kv_heads, n, s.head_dim), 1.0, s.torch_dtype)
-        self.sv.spec_kv_import(self.h, slot, 0, plain)
+        return plain
+
+    def fill_slot(self, w, slot, n, seq_index):
+        self.sv.spec_kv_import(self.h, slot, 0, self.synthetic(w, n, seq_index))
         self.kv_len[slot] = n
-        if not keep_cpu:
-            return None
+
+    def oracle_cache(self, w, n, seq_index):
+        """The same contents as an oracle-side cache (regenerated from the seed: a cache is 1-2 GB on
+        the host at these sizes, so the oracle takes the sequences a few at a time)."""
+        s = self.shape
         c = torch.zeros((s.n_layers, 2, s.n_kv_heads, self.max_kv_len, s.head_dim), dtype=s.torch_dtype)
-        c[:, :, :, :n] = plain.cpu()
+        c[:, :, :, :n] = self.synthetic(w, n, seq_index).cpu()
         return c
 
     def close(self):
         self.h.close()
 
 
-def _run_and_check(rig, w, check_seqs, label):
-    """One step of workload w; sequences in check_seqs are verified against the oracle."""
+def _run_and_check(rig, w, label, group=8):
+    """One step of workload w; EVERY sequence is verified against the oracle, `group` at a time:
+    all window rows' logits (<= 3e-2) and the decisions on identical logits."""
     from helpers import SamplerCheck
     sv, shape = rig.sv, w.shape
     B, Kmax, V = w.batch, w.max_lookahead, shape.vocab
     look = list(w.lookahead)
-    caches = {}
     for b in range(B):
-        caches[b] = rig.fill_slot(w, b, w.kv_lens[b], b, b in check_seqs)
+        rig.fill_slot(w, b, w.kv_lens[b], b)
     t0, _ = wl.make_context(w, "cuda")
     toks, dl = wl.make_free_drafts(w, "cuda")
     us = wl.make_uniforms(w, "cuda")
@@ -94,7 +107,7 @@ def _run_and_check(rig, w, check_seqs, label):
     sv.spec_verify_poll(rig.h)
     na_c, ot_c, lo_c = na.cpu(), ot.cpu(), lo.cpu()
     t0_c, toks_c, dl_c, us_c = t0.cpu(), toks.cpu(), dl.cpu(), us.cpu()
-    # properties that hold for every sequence at any size
+    # bookkeeping of every sequence
     kl = rig.kv_len.cpu().tolist()
     row0 = [0]
     for k in look:
@@ -105,37 +118,45 @@ def _run_and_check(rig, w, check_seqs, label):
         assert ot_c[b, :a].tolist() == toks_c[b, :a].tolist() and 0 <= int(ot_c[b, a]) < V
         assert (ot_c[b, a + 1:] == -1).all()
     assert torch.isfinite(lo_c).all()
-    # the oracle on the chosen sequences
-    seqs = sorted(check_seqs)
-    t = time.time()
-    want = rig.om.verify_rows([caches[b] for b in seqs], [w.kv_lens[b] for b in seqs],
-                              [[int(t0_c[b])] + toks_c[b, :look[b]].tolist() for b in seqs])
-    say(f"  [{label}] oracle: {want.shape[0]} rows in {time.time() - t:.1f}s")
-    worst, r = 0.0, 0
-    for b in seqs:
-        got = lo_c[row0[b]:row0[b + 1]]
-        worst = max(worst, (got - want[r:r + look[b] + 1]).abs().max().item())
-        r += look[b] + 1
-    say(f"  [{label}] logits max-abs error {worst:.3e} (logit std {want.std().item():.3f})")
-    assert worst <= 3e-2
-    # token parity on identical logits: replay the sampler on the oracle's logits for those sequences
-    sub_look = [look[b] for b in seqs]
-    Bs = len(seqs)
-    na2 = torch.zeros(Bs, dtype=torch.int32, device="cuda")
-    ot2 = torch.zeros((Bs, Kmax + 1), dtype=torch.int32, device="cuda")
-    idx = torch.tensor(seqs, device="cuda")
-    sv.spec_verify_step(rig.h, sub_look, us[idx].contiguous(), w.temperature, na2, ot2,
-                        draft_tokens=toks[idx].contiguous(), draft_logits=dl[idx].contiguous(),
-                        target_logits_in=want.cuda())
-    torch.cuda.synchronize()
+    # the oracle, a group of sequences at a time
+    worst, rows_checked, t_or = 0.0, 0, 0.0
     chk = SamplerCheck()
-    r = 0
-    for i, b in enumerate(seqs):
-        chk.compare(want[r:r + look[b] + 1], dl_c[b], toks_c[b, :look[b]].tolist(), us_c[b, :look[b] + 1].tolist(),
-                    w.temperature, int(na2[i]), ot2[i].cpu().tolist(), Kmax)
-        r += look[b] + 1
+    for g0 in range(0, B, group):
+        seqs = list(range(g0, min(g0 + group, B)))
+        caches = [rig.oracle_cache(w, w.kv_lens[b], b) for b in seqs]
+        t = time.time()
+        want = rig.om.verify_rows(caches, [w.kv_lens[b] for b in seqs],
+                                  [[int(t0_c[b])] + toks_c[b, :look[b]].tolist() for b in seqs])
+        t_or += time.time() - t
+        del caches
+        r = 0
+        for b in seqs:
+            got = lo_c[row0[b]:row0[b + 1]]
+            err = (got - want[r:r + look[b] + 1]).abs().max().item()
+            assert err <= 3e-2, f"[{label}] sequence {b} (n={w.kv_lens[b]}, K={look[b]}): logits max-abs error {err}"
+            worst = max(worst, err)
+            r += look[b] + 1
+        rows_checked += r
+        # token parity on identical logits: replay the sampler on the oracle's logits for this group
+        Bs = len(seqs)
+        na2 = torch.zeros(Bs, dtype=torch.int32, device="cuda")
+        ot2 = torch.zeros((Bs, Kmax + 1), dtype=torch.int32, device="cuda")
+        idx = torch.tensor(seqs, device="cuda")
+        sv.spec_verify_step(rig.h, [look[b] for b in seqs], us[idx].contiguous(), w.temperature, na2, ot2,
+                            draft_tokens=toks[idx].contiguous(), draft_logits=dl[idx].contiguous(),
+                            target_logits_in=want.cuda())
+        torch.cuda.synchronize()
+        r = 0
+        for i, b in enumerate(seqs):
+            chk.compare(want[r:r + look[b] + 1], dl_c[b], toks_c[b, :look[b]].tolist(), us_c[b, :look[b] + 1].tolist(),
+                        w.temperature, int(na2[i]), ot2[i].cpu().tolist(), Kmax)
+            r += look[b] + 1
+        say(f"  [{label}] sequences {seqs[0]}..{seqs[-1]} checked, worst logits error so far {worst:.3e}")
+    assert rows_checked == M
+    say(f"  [{label}] oracle: all {rows_checked} rows of {B} sequences in {t_or:.1f}s; logits max-abs error {worst:.3e}")
     say(f"  [{label}] sampler: exact accept {chk.exact_accept}, margin {chk.margin_accept}; "
         f"exact token {chk.exact_token}, margin {chk.margin_token}; accepted {na_c.tolist()}")
+    assert chk.exact_accept + chk.margin_accept == B
     return worst, chk
 
 
@@ -143,7 +164,7 @@ def test_1b_shape_full():
     w = wl.workload_1b()
     rig = BigRig(BigWeights(w.shape, w.seed), w.batch, w.max_kv_len, w.max_lookahead)
     try:
-        _run_and_check(rig, w, {0}, "1b")
+        _run_and_check(rig, w, "1b")
     finally:
         rig.close()
 
@@ -158,39 +179,48 @@ def test_7b_shape_full_all_rows(weights7b):
     w = wl.workload_7b()
     rig = BigRig(weights7b, w.batch, w.max_kv_len, w.max_lookahead)
     try:
-        _run_and_check(rig, w, set(range(8)), "7b")
+        _run_and_check(rig, w, "7b")
     finally:
         rig.close()
 
 
-def test_dynamic_lookahead_sampled_sequences(weights7b):
-    # same target weights as the 7B-shape case; 32 ragged sequences
+def test_7b_shape_paged_all_rows(weights7b):
+    """The handle `bench.py --paged` builds (a pool of exactly the pages the step can touch): all 48
+    rows against the oracle, decisions on identical logits, and the pages of rejected proposals back
+    in the pool afterwards."""
+    w = wl.workload_7b()
+    rig = BigRig(weights7b, w.batch, w.max_kv_len, w.max_lookahead, paged_lens=w.kv_lens)
+    try:
+        _run_and_check(rig, w, "7b-paged")
+        kl = rig.kv_len.cpu().tolist()
+        assert rig.sv.spec_kv_pages(rig.h)[0] == rig.n_pages - sum((n + 31) // 32 for n in kl)
+    finally:
+        rig.close()
+
+
+def test_dynamic_lookahead_all_sequences(weights7b):
+    # same target weights as the 7B-shape case; 32 ragged sequences, every one of them through the oracle
     w = wl.workload_dyn()
-    n, k = w.kv_lens, w.lookahead
-    pick = {min(range(32), key=lambda b: n[b]), max(range(32), key=lambda b: n[b]),
-            min(range(32), key=lambda b: k[b]), max(range(32), key=lambda b: k[b])}
-    say(f"  [dyn] rows {w.rows}, checking sequences {sorted(pick)}: n={[n[b] for b in sorted(pick)]} "
-        f"K={[k[b] for b in sorted(pick)]}")
+    say(f"  [dyn] rows {w.rows}, n={list(w.kv_lens)} K={list(w.lookahead)}")
     rig = BigRig(weights7b, w.batch, w.max_kv_len, w.max_lookahead)
     try:
-        _run_and_check(rig, w, pick, "dyn")
+        _run_and_check(rig, w, "dyn")
     finally:
         rig.close()
 
 
 def test_7b_shape_token_tree(weights7b):
-    """The 10-node tree per sequence at 7B-shape (88 window rows): logits of two sequences' nodes
-    against the oracle decoding along every root-to-leaf path, decisions on identical logits, and
-    for all sequences the bookkeeping and the compacted cache length."""
+    """The 10-node tree per sequence at 7B-shape (88 window rows): for every sequence the logits of all
+    nodes against the oracle decoding along every root-to-leaf path, decisions on identical logits,
+    the bookkeeping and the compacted cache length."""
     from helpers import TreeCheck
     w = wl.workload_tree()
-    sv = None
     rig = BigRig(weights7b, w.batch, w.max_kv_len, w.max_lookahead)
     try:
         sv, shape = rig.sv, w.shape
         B, N, V = w.batch, w.max_lookahead, shape.vocab
-        check = [0, 5]
-        caches = {b: rig.fill_slot(w, b, w.kv_lens[b], b, b in check) for b in range(B)}
+        for b in range(B):
+            rig.fill_slot(w, b, w.kv_lens[b], b)
         t0, _ = wl.make_context(w, "cuda")
         par, toks, dl = wl.make_tree_drafts(w, wl.TREE10_PARENT, "cuda")
         us = wl.make_uniforms(w, "cuda")
@@ -219,17 +249,27 @@ def test_7b_shape_token_tree(weights7b):
         leaves = [i for i in range(N) if i not in parent]
         worst = 0.0
         chk = TreeCheck()
-        t = time.time()
-        for b in check:
+        t_or = 0.0
+        for b in range(B):
+            # every root-to-leaf path is one ordinary window on a cache of its own (they share the prefix)
+            base = rig.oracle_cache(w, w.kv_lens[b], b)
+            caches = [base] + [base.clone() for _ in leaves[1:]]
+            t = time.time()
+            rows = rig.om.verify_rows(caches, [w.kv_lens[b]] * len(leaves),
+                                      [[int(t0_c[b])] + [int(toks_c[b, i]) for i in paths[leaf]] for leaf in leaves])
+            t_or += time.time() - t
+            del caches, base
             want = torch.zeros((N + 1, V))
+            r = 0
             for leaf in leaves:
-                rows = rig.om.verify_rows([caches[b]], [w.kv_lens[b]],
-                                          [[int(t0_c[b])] + [int(toks_c[b, i]) for i in paths[leaf]]])
-                want[0] = rows[0]
+                want[0] = rows[r]
                 for d, node in enumerate(paths[leaf]):
-                    want[node + 1] = rows[d + 1]
+                    want[node + 1] = rows[r + d + 1]
+                r += len(paths[leaf]) + 1
             got = lo_c[b * (N + 1):(b + 1) * (N + 1)]
-            worst = max(worst, (got - want).abs().max().item())
+            err = (got - want).abs().max().item()
+            assert err <= 3e-2, f"tree logits of sequence {b}: max-abs error {err}"
+            worst = max(worst, err)
             # decisions: replay the walk on the oracle's logits through the sampler-only entry
             na2 = torch.zeros(1, dtype=torch.int32, device="cuda")
             ot2 = torch.zeros((1, N + 1), dtype=torch.int32, device="cuda")
@@ -240,10 +280,11 @@ def test_7b_shape_token_tree(weights7b):
             torch.cuda.synchronize()
             chk.compare(parent, toks_c[b].tolist(), want, dl_c[b], us_c[b].tolist(), w.temperature, int(na2[0]),
                         pt2[0].cpu().tolist(), ot2[0].cpu().tolist(), N)
-        say(f"  [tree] oracle {time.time() - t:.1f}s; logits max-abs error {worst:.3e}; kept {na_c.tolist()}; "
-            f"exact walks {chk.exact_walk}, exact tokens {chk.exact_token}")
-        assert worst <= 3e-2
-        assert chk.exact_walk + chk.margin_walk == len(check)
+            say(f"  [tree] sequence {b} checked, worst logits error so far {worst:.3e}")
+        say(f"  [tree] oracle {t_or:.1f}s; logits max-abs error {worst:.3e}; kept {na_c.tolist()}; "
+            f"exact walks {chk.exact_walk}, margin walks {chk.margin_walk}; exact tokens {chk.exact_token}, "
+            f"margin tokens {chk.margin_token}")
+        assert chk.exact_walk + chk.margin_walk == B
     finally:
         rig.close()
 

@@ -123,6 +123,27 @@ def test_rows_at_once_is_bit_identical_to_one_token_at_a_time(shape):
         assert torch.equal(c1.view(torch.uint8), c2.view(torch.uint8))
 
 
+def test_rows_at_once_is_bit_identical_at_1b_shape():
+    """The same pin at the 1B-shape configuration itself (16 layers, d 2048, 32/8 heads of 64, FFN
+    8192, vocabulary 32000, bf16; one sequence, 1024 cached positions, window of 6): the full-size
+    GPU parity tests compare against the rows-at-once routine, so it is held to the one-token-at-a-
+    time definition at that size too, logits and appended cache entries bit for bit."""
+    w = wl.workload_1b()
+    s, n = w.shape, w.kv_lens[0]
+    m = oracle.Model(s, wl.make_weights(s, w.seed, "cpu"), w.max_kv_len)
+    rng = wl.Rng(w.seed, "cpu")
+    c1 = m.new_cache()
+    for l in range(s.n_layers):          # synthetic N(0,1) cache, as the workload's recipe has it
+        c1[l, :, :, :n] = rng.normal(wl.S_KV + l, (2, s.n_kv_heads, n, s.head_dim), 1.0, s.torch_dtype)
+    c2 = c1.clone()
+    window = rng.randint(77, (w.lookahead[0] + 1,), s.vocab).tolist()
+    want = m.verify_sequential(c1, n, window)
+    got = m.verify_rows([c2], [n], [window])
+    assert want.shape == (6, 32000) and torch.isfinite(want).all() and want.std().item() > 0.1
+    assert torch.equal(got, want)
+    assert torch.equal(c1.view(torch.uint8), c2.view(torch.uint8))
+
+
 def test_zero_lookahead_is_one_ordinary_decode():
     shape = SMALL
     w = _weights(shape)
