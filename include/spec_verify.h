@@ -183,6 +183,29 @@ typedef struct {
  * rejected position a, or r = p_K when all K drafts were kept. */
 int spec_verify_step(spec_handle* h, const spec_step_args* args, const spec_step_out* out, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the sampling part of spec_verify_step -- what that call
+ * does on a sampler-only handle when target_logits_in is given -- without a handle.  The row tables,
+ * chunk statistics, chunk masses and the error flag, which a handle keeps in its workspace, live in
+ * one fixed device array inside the library (about 0.55 MiB, held by every GPU the library runs on
+ * until the process ends), sized for
+ *     batch <= SPEC_NOALLOC_MAX_BATCH, max_lookahead <= SPEC_MAX_LOOKAHEAD, vocab <= SPEC_NOALLOC_MAX_VOCAB;
+ * anything larger is refused with SPEC_ERR_SHAPE before a kernel is launched.  The call allocates
+ * and frees nothing and synchronises nothing; the first call on a device also looks the array's
+ * address up (a host-side query), so make one call on a device before capturing any.
+ * args: as for spec_verify_step with target_logits_in REQUIRED (device fp32[M][vocab]); seq_slot,
+ * last_token and auto_rollback are ignored (no cache is touched); Kmax in the array shapes is the
+ * max_lookahead given here.  out: n_accepted and out_tokens as for spec_verify_step; results are
+ * bit-identical to that call's.  Device-side conditions (a draft token id outside [0, vocab)) write
+ * n_accepted[b] = -1 and out_tokens[b][*] = -1 for that sequence; there is no poll for this call.
+ * All calls on one GPU share the array, which keeps the previous call's contents (the call clears
+ * what must start at zero itself): calls that overlap in time on one GPU -- different streams or
+ * threads -- race and must be serialised by the caller. */
+#define SPEC_NOALLOC_MAX_BATCH 64
+#define SPEC_NOALLOC_MAX_VOCAB 262144
+int spec_sample_step_noalloc(int32_t vocab, int32_t max_lookahead, const spec_step_args* args,
+                             const spec_step_out* out, void* stream);
+
 /* Verification of a token TREE per sequence (the tree-structured candidates of the paper's
  * section on EAGLE-style decoding) instead of a chain.  Sequence b proposes N_b <= Kmax nodes in
  * topological order; parent[b][i] is -1 (child of the root = the sequence's last token) or the

@@ -107,6 +107,8 @@ def lib():
         L.spec_kv_page_bytes.argtypes = [C.POINTER(spec_model_cfg)]
         L.spec_kv_pages.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
         L.spec_verify_step.argtypes = [C.c_void_p, C.POINTER(spec_step_args), C.POINTER(spec_step_out), C.c_void_p]
+        L.spec_sample_step_noalloc.argtypes = [C.c_int32, C.c_int32, C.POINTER(spec_step_args), C.POINTER(spec_step_out),
+                                               C.c_void_p]
         L.spec_verify_tree_step.argtypes = [C.c_void_p, C.POINTER(spec_tree_args), C.POINTER(spec_tree_out), C.c_void_p]
         L.spec_kv_rollback.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.c_void_p]
         L.spec_kv_import.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
@@ -283,6 +285,19 @@ def spec_verify_step(h: Handle, lookahead: Sequence[int], uniforms: torch.Tensor
                           int(auto_rollback))
     out = spec_step_out(_ptr(n_accepted, torch.int32), _ptr(out_tokens, torch.int32), _ptr(logits_out, torch.float32))
     _check(lib().spec_verify_step(h.ptr, C.byref(args), C.byref(out), _stream(stream)))
+
+
+def spec_sample_step_noalloc(vocab: int, max_lookahead: int, lookahead: Sequence[int], uniforms: Optional[torch.Tensor],
+                             temperature: float, n_accepted: torch.Tensor, out_tokens: torch.Tensor,
+                             target_logits_in: torch.Tensor, draft_tokens: Optional[torch.Tensor] = None,
+                             draft_logits: Optional[torch.Tensor] = None, logits_out: Optional[torch.Tensor] = None,
+                             stream=None):
+    B = len(lookahead)
+    ks = (C.c_int32 * max(B, 1))(*[int(k) for k in lookahead])
+    args = spec_step_args(B, ks, None, None, _ptr(draft_tokens, torch.int32), _ptr(draft_logits, torch.float32),
+                          _ptr(uniforms, torch.float32), float(temperature), _ptr(target_logits_in, torch.float32), 0)
+    out = spec_step_out(_ptr(n_accepted, torch.int32), _ptr(out_tokens, torch.int32), _ptr(logits_out, torch.float32))
+    _check(lib().spec_sample_step_noalloc(int(vocab), int(max_lookahead), C.byref(args), C.byref(out), _stream(stream)))
 
 
 def spec_verify_tree_step(h: Handle, n_nodes: Sequence[int], parent: Optional[torch.Tensor],

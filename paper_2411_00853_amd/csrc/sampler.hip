@@ -14,6 +14,9 @@
 #include "cache_layout.h"
 #include "common.h"
 
+#include <cstring>
+#include <mutex>
+
 namespace specv {
 
 namespace {
@@ -1185,3 +1188,143 @@ int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const Lookahe
 }
 
 }  // namespace specv
+
+// ---------------------------------------------------------------------------------------------
+// The sampling part of the verify step for callers that cannot allocate: no handle, no hipMalloc.
+// The row tables and the sampler's workspace (chunk statistics, chunk masses, per-sequence
+// scalars, the error flag) live in one device array of fixed size instead of a handle's arena.
+// ---------------------------------------------------------------------------------------------
+namespace specv {
+namespace {
+
+constexpr int NA_MAX_BATCH = SPEC_NOALLOC_MAX_BATCH;
+constexpr int NA_MAX_VOCAB = SPEC_NOALLOC_MAX_VOCAB;
+constexpr int NA_MAX_ROWS = NA_MAX_BATCH * (SPEC_MAX_LOOKAHEAD + 1);
+constexpr int NA_MAX_STAT = NA_MAX_BATCH * (2 * SPEC_MAX_LOOKAHEAD + 1);
+constexpr int NA_STAT_CHUNKS = (NA_MAX_VOCAB + STAT_CHUNK - 1) / STAT_CHUNK;
+constexpr int NA_RES_CHUNKS = (NA_MAX_VOCAB + RES_CHUNK - 1) / RES_CHUNK;
+
+struct NoAllocScratch {
+    double part_sum[(size_t)NA_MAX_STAT * NA_STAT_CHUNKS];
+    double chunk_mass[(size_t)NA_MAX_BATCH * NA_RES_CHUNKS];
+    double row_inv_z[2 * NA_MAX_BATCH];
+    float part_max[(size_t)NA_MAX_STAT * NA_STAT_CHUNKS];
+    int32_t part_idx[(size_t)NA_MAX_STAT * NA_STAT_CHUNKS];
+    float row_max[2 * NA_MAX_BATCH];
+    int32_t accepted[NA_MAX_BATCH];
+    int32_t seq_row0[NA_MAX_BATCH + 1], seq_stat0[NA_MAX_BATCH + 1];
+    int32_t seq_n[NA_MAX_BATCH], seq_ok[NA_MAX_BATCH], seq_slot[NA_MAX_BATCH];
+    int32_t row_seq[NA_MAX_ROWS], row_pos[NA_MAX_ROWS], row_tok[NA_MAX_ROWS], row_rope[NA_MAX_ROWS];
+    uint32_t row_mask[NA_MAX_ROWS];
+    int32_t flag[4];
+};
+static_assert(sizeof(NoAllocScratch) <= (size_t)640 * 1024, "the fixed workspace is meant to stay modest");
+
+// Every GPU the library runs on holds its own copy of this array until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress: kernels get the address looked up below.
+static __device__ __align__(256) unsigned char scratch[sizeof(NoAllocScratch)];
+
+constexpr int NA_MAX_DEVICES = 64;
+NoAllocScratch* g_scratch_ptr[NA_MAX_DEVICES];   // per device; written once, under g_scratch_lock
+std::mutex g_scratch_lock;
+
+// Address of the current device's copy of the array (looked up on the first call on that device).
+int scratch_of_current_device(NoAllocScratch** out)
+{
+    int dev = -1;
+    SPECV_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= NA_MAX_DEVICES) return fail(SPEC_ERR_DEVICE, "device index %d is not supported", dev);
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        SPECV_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(SPEC_ERR_DEVICE, "hipGetSymbolAddress returned no address for the fixed workspace");
+        g_scratch_ptr[dev] = static_cast<NoAllocScratch*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SPEC_OK;
+}
+
+__global__ void fill_i32_kernel(int32_t* __restrict__ p, int n, int32_t v)
+{
+    if ((int)threadIdx.x < n) p[threadIdx.x] = v;
+}
+
+}  // namespace
+}  // namespace specv
+
+using namespace specv;
+
+extern "C" int spec_sample_step_noalloc(int32_t vocab, int32_t max_lookahead, const spec_step_args* args,
+                                        const spec_step_out* out, void* stream)
+{
+    if (!args || !out) return fail(SPEC_ERR_INVALID_ARG, "NULL args or out");
+    if (vocab < 1 || vocab > NA_MAX_VOCAB)
+        return fail(SPEC_ERR_SHAPE, "vocab %d outside 1..%d (the fixed workspace is sized for that)", vocab, NA_MAX_VOCAB);
+    if (max_lookahead < 0 || max_lookahead > SPEC_MAX_LOOKAHEAD)
+        return fail(SPEC_ERR_SHAPE, "max_lookahead %d outside 0..%d", max_lookahead, SPEC_MAX_LOOKAHEAD);
+    const int B = args->batch, Kmax = max_lookahead;
+    if (B < 1 || B > NA_MAX_BATCH)
+        return fail(SPEC_ERR_SHAPE, "batch %d outside 1..%d (the fixed workspace is sized for that)", B, NA_MAX_BATCH);
+    if (!args->target_logits_in) return fail(SPEC_ERR_INVALID_ARG, "target_logits_in is NULL: this entry point runs no decoder pass");
+    if (!args->lookahead) return fail(SPEC_ERR_INVALID_ARG, "lookahead is NULL");
+    if (!(args->temperature >= 0.f)) return fail(SPEC_ERR_INVALID_ARG, "temperature must be >= 0");
+    const bool greedy = args->temperature == 0.f;
+    if (!greedy && !args->uniforms) return fail(SPEC_ERR_INVALID_ARG, "uniforms is NULL");
+    if (!out->n_accepted || !out->out_tokens) return fail(SPEC_ERR_INVALID_ARG, "n_accepted or out_tokens is NULL");
+    LookaheadPack ks;
+    memset(&ks, 0, sizeof(ks));
+    int M = 0, n_stat = 0, any_draft = 0;
+    for (int b = 0; b < B; ++b) {
+        const int k = args->lookahead[b];
+        if (k < 0 || k > Kmax) return fail(SPEC_ERR_INVALID_ARG, "lookahead[%d] = %d outside 0..%d", b, k, Kmax);
+        ks.k[b] = (uint8_t)k;
+        M += k + 1;
+        n_stat += 2 * k + 1;
+        any_draft |= k;
+    }
+    if (any_draft && (!args->draft_tokens || (!greedy && !args->draft_logits)))
+        return fail(SPEC_ERR_INVALID_ARG, "draft_tokens or draft_logits is NULL");
+    NoAllocScratch* w = nullptr;
+    int rc = scratch_of_current_device(&w);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    // the array keeps the last call's contents: the flag must start at zero (a fill kernel, so that
+    // the call can be captured); every other entry that is read was written earlier in this call
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, s, w->flag, 4, 0);
+    SPECV_LAUNCH_CHECK("fill_i32_kernel");
+    StepTables t{};
+    t.seq_row0 = w->seq_row0;
+    t.seq_stat0 = w->seq_stat0;
+    t.seq_n = w->seq_n;
+    t.seq_ok = w->seq_ok;
+    t.seq_slot = w->seq_slot;
+    t.row_seq = w->row_seq;
+    t.row_pos = w->row_pos;
+    t.row_tok = w->row_tok;
+    t.row_rope = w->row_rope;
+    t.row_mask = w->row_mask;
+    t.tree = 0;
+    SamplerWorkspace sw{};
+    sw.part_max = w->part_max;
+    sw.part_sum = w->part_sum;
+    sw.chunk_mass = w->chunk_mass;
+    sw.accepted = w->accepted;
+    sw.row_inv_z = w->row_inv_z;
+    sw.row_max = w->row_max;
+    sw.part_idx = w->part_idx;
+    rc = launch_prepare(t, ks, B, Kmax, vocab, NA_MAX_BATCH, 0, false, nullptr, nullptr, args->draft_tokens, nullptr,
+                        w->flag, s);
+    if (rc) return rc;
+    if (out->logits_out) {
+        // a copy node, not an allocation; callers under capture simply pass logits_out = NULL
+        SPECV_HIP(hipMemcpyAsync(out->logits_out, args->target_logits_in, (size_t)M * vocab * sizeof(float),
+                                 hipMemcpyDeviceToDevice, s));
+    }
+    if (greedy)
+        return launch_greedy(t, sw, ks, B, Kmax, vocab, M, args->target_logits_in, args->draft_tokens, 0, nullptr,
+                             out->n_accepted, out->out_tokens, nullptr, nullptr, s);
+    return launch_sampler(t, sw, ks, B, Kmax, vocab, n_stat, args->target_logits_in, args->draft_logits,
+                          args->draft_tokens, args->uniforms, Kmax + 1, args->temperature, 0, nullptr, out->n_accepted,
+                          out->out_tokens, nullptr, nullptr, s);
+}

@@ -61,6 +61,20 @@ def test_bad_configurations_are_rejected_before_any_device_work(lib):
     assert lib.spec_kv_rollback(None, None, None, 0, None) == -1
 
 
+def test_noalloc_step_refuses_sizes_beyond_its_fixed_workspace(lib):
+    """Host-side checks of spec_sample_step_noalloc come before any device work."""
+    from paper_2411_00853_amd import binding as sv
+    ks = (C.c_int32 * 65)()
+    dummy = C.c_void_p(16)      # never dereferenced: the size checks come first
+    out = sv.spec_step_out(dummy, dummy, None)
+    for vocab, kmax, batch in ((1000, 4, 65), (262145, 4, 2), (1000, 16, 2), (0, 4, 2)):
+        args = sv.spec_step_args(batch, ks, None, None, dummy, dummy, dummy, 1.0, dummy, 0)
+        assert lib.spec_sample_step_noalloc(vocab, kmax, C.byref(args), C.byref(out), None) == -2
+        assert b"outside" in lib.spec_last_error()
+    args = sv.spec_step_args(2, ks, None, None, dummy, dummy, dummy, 1.0, None, 0)     # no target_logits_in
+    assert lib.spec_sample_step_noalloc(1000, 4, C.byref(args), C.byref(out), None) == -1
+
+
 def test_build_lists_name_existing_sources():
     """Every source the build compiles exists, and per-source options refer to listed sources."""
     import os

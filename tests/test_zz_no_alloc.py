@@ -1,0 +1,109 @@
+"""spec_sample_step_noalloc (the sampling step for callers that cannot allocate) against the existing
+entry point: spec_verify_step on a sampler-only handle.  Two calls in a row share the library's fixed
+device workspace, the second with a smaller input (fewer sequences, shorter windows, smaller
+vocabulary): outputs must be bit-identical to the handle's, and agree with the oracle under the
+margin rules.  Also the greedy rule, and the size limits (refused on the host)."""
+import pytest
+import torch
+
+from paper_2411_00853_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(seed, B, Kmax, V, T, look):
+    rng = wl.Rng(seed, "cpu")
+    M = sum(k + 1 for k in look)
+    tl = rng.normal(1, (M, V), 1.0)
+    dl = torch.zeros((B, max(Kmax, 1), V))
+    r0 = 0
+    for b, k in enumerate(look):
+        dl[b, :k] = tl[r0:r0 + k] + rng.normal(10 + b, (k, V), 0.4)
+        r0 += k + 1
+    dl = dl[:, :Kmax].contiguous()
+    toks = wl.pick_tokens(rng, dl, T if T > 0 else 1.0, 30) if Kmax else torch.zeros((B, 0), dtype=torch.int32)
+    us = rng.uniform(40, (B, Kmax + 1))
+    return tl, dl, toks, us
+
+
+def _both(V, Kmax, look, T, seed, poison):
+    """(n_accepted, out_tokens) of the handle's step and of the no-alloc step on the same inputs."""
+    from paper_2411_00853_amd import binding as sv
+    B = len(look)
+    tl, dl, toks, us = _inputs(seed, B, Kmax, V, T, look)
+    d = lambda t: t.cuda().contiguous()
+    tl_d, dl_d, toks_d, us_d = d(tl), d(dl), d(toks), d(us)
+    h = sv.spec_verify_init(sv.sampler_cfg(V, B, Kmax), None, None, None)
+    na1 = torch.full((B,), poison, dtype=torch.int32, device="cuda")
+    ot1 = torch.full((B, Kmax + 1), poison, dtype=torch.int32, device="cuda")
+    sv.spec_verify_step(h, look, us_d, T, na1, ot1, draft_tokens=toks_d if Kmax else None,
+                        draft_logits=dl_d if Kmax else None, target_logits_in=tl_d)
+    torch.cuda.synchronize()
+    sv.spec_verify_poll(h)
+    h.close()
+    na2 = torch.full((B,), poison, dtype=torch.int32, device="cuda")
+    ot2 = torch.full((B, Kmax + 1), poison, dtype=torch.int32, device="cuda")
+    sv.spec_sample_step_noalloc(V, Kmax, look, us_d, T, na2, ot2, tl_d, draft_tokens=toks_d if Kmax else None,
+                                draft_logits=dl_d if Kmax else None)
+    torch.cuda.synchronize()
+    return (tl, dl, toks, us), (na1.cpu(), ot1.cpu()), (na2.cpu(), ot2.cpu())
+
+
+def test_two_calls_in_a_row_the_second_smaller_match_the_handle_and_the_oracle():
+    from helpers import check_sampler_against_oracle
+    # first call: 12 sequences, windows up to 8, a vocabulary that is not a multiple of 4 and spans
+    # two statistics chunks and eight residual chunks with ragged tails
+    look_a = [8, 0, 3, 8, 1, 5, 2, 8, 4, 8, 7, 6]
+    inp_a, want_a, got_a = _both(32003, 8, look_a, 0.9, 101, -7)
+    # second call right behind it: 3 sequences, windows up to 4, vocabulary 1000 -- everything the
+    # first call left in the shared workspace is stale and larger than what this call writes
+    look_b = [4, 2, 0]
+    inp_b, want_b, got_b = _both(1000, 4, look_b, 1.3, 202, -5)
+    for want, got in ((want_a, got_a), (want_b, got_b)):
+        assert torch.equal(want[0], got[0]) and torch.equal(want[1], got[1])
+    assert len(set(got_a[0].tolist())) >= 3, "several accepted lengths should occur"
+    for (tl, dl, toks, us), look, Kmax, T, got in ((inp_a, look_a, 8, 0.9, got_a), (inp_b, look_b, 4, 1.3, got_b)):
+        chk = check_sampler_against_oracle(tl, dl, toks, us, look, T, Kmax, got[0], got[1])
+        assert chk.exact_accept + chk.margin_accept == len(look) and chk.exact_accept >= len(look) - 1
+
+
+def test_greedy_rule_and_a_bad_token_id():
+    import oracle
+    from paper_2411_00853_amd import binding as sv
+    look = [5, 3, 0, 5]
+    inp, want, got = _both(4099, 5, look, 0.0, 303, -3)
+    assert torch.equal(want[0], got[0]) and torch.equal(want[1], got[1])
+    tl, dl, toks, us = inp
+    r0 = 0
+    for b, k in enumerate(look):
+        a, out, _ = oracle.greedy(tl[r0:r0 + k + 1].contiguous(), toks[b, :k].tolist())
+        assert int(got[0][b]) == a and got[1][b, :k + 1].tolist() == out
+        r0 += k + 1
+    # a draft token outside the vocabulary: that sequence is skipped (n_accepted -1), its neighbour is not
+    V, K = 1000, 3
+    tl, dl, toks, us = _inputs(404, 2, K, V, 1.0, [K, K])
+    toks[0, 1] = V
+    na = torch.zeros(2, dtype=torch.int32, device="cuda")
+    ot = torch.zeros((2, K + 1), dtype=torch.int32, device="cuda")
+    sv.spec_sample_step_noalloc(V, K, [K, K], us.cuda(), 1.0, na, ot, tl.cuda(), draft_tokens=toks.cuda(),
+                                draft_logits=dl.cuda())
+    torch.cuda.synchronize()
+    assert int(na[0]) == -1 and (ot[0] == -1).all() and 0 <= int(na[1]) <= K
+    # the flag of that call does not leak into the next one
+    toks[0, 1] = 5
+    sv.spec_sample_step_noalloc(V, K, [K, K], us.cuda(), 1.0, na, ot, tl.cuda(), draft_tokens=toks.cuda(),
+                                draft_logits=dl.cuda())
+    torch.cuda.synchronize()
+    assert 0 <= int(na[0]) <= K
+
+
+def test_sizes_beyond_the_fixed_workspace_are_refused():
+    from paper_2411_00853_amd import binding as sv
+    na = torch.zeros(65, dtype=torch.int32, device="cuda")
+    ot = torch.zeros((65, 2), dtype=torch.int32, device="cuda")
+    tl = torch.zeros((65, 8), device="cuda")
+    us = torch.zeros((65, 2), device="cuda")
+    for vocab, kmax, look in ((8, 1, [0] * 65), (262145, 1, [0]), (8, 16, [0])):
+        with pytest.raises(sv.SpecError) as e:
+            sv.spec_sample_step_noalloc(vocab, kmax, look, us, 1.0, na, ot, tl)
+        assert e.value.status == -2
