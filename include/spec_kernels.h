@@ -36,7 +36,10 @@ int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, int32_t M, 
                      int32_t split_x, void* workspace, void* stream);
 
 /* Tuning knob: number of workgroups a GEMM launch aims for when it cuts K into ranges
- * (0 = default, two per compute unit).  Process-wide; affects launches made after the call. */
+ * (0 = default, two thirds of the compute units).  Process-wide; affects launches made after the
+ * call.  Set it before spec_verify_init: a handle's partial-sum workspace is sized for the plans in
+ * force at init, and a step whose plan needs more (a larger target set later) fails with
+ * SPEC_ERR_SHAPE instead of writing past the workspace. */
 void spec_k_set_gemm_wg_target(int32_t workgroups);
 
 /* Tuning knob: the gate/up projection finishes SwiGLU inside the GEMM (one K range, 128-column
@@ -51,7 +54,8 @@ void spec_k_set_swiglu_column_groups(int32_t groups);
 
 /* Tuning knob: wavefront work items (sequence, kv head, position chunk) per compute unit that the
  * attention kernel's position split aims for (0 = default).  Set before spec_verify_init: the
- * workspace for chunk results is sized with it.  Process-wide. */
+ * workspace for chunk results is sized with it, and a step whose plan needs more than the handle
+ * holds fails with SPEC_ERR_SHAPE.  Process-wide. */
 void spec_k_set_attn_items_per_cu(int32_t items);
 
 /* Tuning knob: the attention workgroups merge the chunk results of a (sequence, kv head) themselves

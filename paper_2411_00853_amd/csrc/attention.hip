@@ -736,7 +736,8 @@ bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack&
 
 int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,
                      int n_q_heads, int layer, const void* cache, const float* q, float* part_o, float* part_ml,
-                     const XOut& xo, int max_window, Profiler* prof, hipStream_t s, const QkvSrc* qkv, void* cache_w)
+                     size_t part_cap, const XOut& xo, int max_window, Profiler* prof, hipStream_t s, const QkvSrc* qkv,
+                     void* cache_w)
 {
     QkvSrc src{};
     if (qkv) src = *qkv;
@@ -758,6 +759,11 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
         return fail(SPEC_ERR_SHAPE, "paged attention handles chunks of up to 2048 positions (max_kv_len up to 32768)");
     const int group = n_q_heads / g.n_kv_heads;
     const int r_cap = group * max_window;
+    const size_t part_need = (size_t)B * g.n_kv_heads * p.max_chunks * r_cap * hd;
+    if (part_need > part_cap)
+        return fail(SPEC_ERR_SHAPE, "this step's attention plan (%d chunks per sequence and kv head) needs %zu floats of "
+                    "chunk results, the handle holds %zu: set the attention tuning knobs before spec_verify_init",
+                    p.max_chunks, part_need, part_cap);
     int kmax = 0;
     for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
     const int rt = ((kmax + 1) * group + 15) / 16;

@@ -270,12 +270,14 @@ void set_attn_merge_min_pairs(int n);
 void set_attn_max_chunks(int n);
 size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
                            int cu_count, bool paged = false);
+// part_cap: capacity of part_o in floats (part_ml holds 2/head_dim of that); a plan that needs more
+// (the tuning knobs changed after the buffers were sized) is refused with SPEC_ERR_SHAPE.
 // Whether the bf16 attention kernel can take the QKV projection's partial sums itself (QkvSrc) for
 // this step's shapes; if not, launch_rope_append has to run first.
 bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack& ks, int B, int max_kv_len, int cu_count);
 int launch_attention(const AttnPlan& p, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M,
                      const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
-                     float* part_o, float* part_ml, const XOut& xo, int max_window, Profiler* prof, hipStream_t s,
-                     const QkvSrc* qkv = nullptr, void* cache_w = nullptr);
+                     float* part_o, float* part_ml, size_t part_cap, const XOut& xo, int max_window, Profiler* prof,
+                     hipStream_t s, const QkvSrc* qkv = nullptr, void* cache_w = nullptr);
 
 }  // namespace specv

@@ -78,11 +78,13 @@ int forward_init(spec_handle* h, int max_rows)
                                               c.head_dim, h->cu_count, h->geom.table != nullptr);
         A(&h->attn_part_o, po);
         A(&h->attn_part_ml, po / c.head_dim * 2);
+        h->attn_part_cap = po;
     } else {
         // fp32 path: GEMM results are written whole; one buffer wide enough for any of them
         part = (size_t)max_rows * (size_t)std::max(std::max(z.nqkv, 2 * z.F), z.d);
     }
     A(&h->partial, part);
+    h->partial_cap = part;
     if (rc) return rc;
 
     // rotary table in fp64 on the host: cos, sin of pos * theta^(-2i/hd)
@@ -135,6 +137,11 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
                     const void* in_frags = nullptr) -> int {
         if (bf16) {
             const GemmPlan p = plan_gemm(M, N, K, h->cu_count, h->split_act);
+            // the plan follows process-wide tuning knobs; the buffer was sized with those in force at init
+            if (gemm_partial_elems(p, M) > h->partial_cap)
+                return fail(SPEC_ERR_SHAPE, "this step's GEMM plan (%d K ranges) needs %zu partial sums, the handle holds %zu: "
+                            "set the GEMM tuning knobs before spec_verify_init", p.n_split, gemm_partial_elems(p, M),
+                            h->partial_cap);
             o->n_split = p.n_split;
             o->ld = p.n_pad;
             o->stride = (size_t)M * p.n_pad;
@@ -166,13 +173,13 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
             // the attention kernel adds up, scales and rotates q, k, v itself and appends k, v
             const QkvSrc qkv{h->partial, o.n_split, o.stride, o.ld, scaled, h->cos_sin};
             rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache,
-                                  h->q, h->attn_part_o, h->attn_part_ml, to_att, c.max_lookahead + 1, &h->prof, s, &qkv,
+                                  h->q, h->attn_part_o, h->attn_part_ml, h->attn_part_cap, to_att, c.max_lookahead + 1, &h->prof, s, &qkv,
                                   h->kv_cache);
         } else {
             RUN(SPEC_PROF_GLUE, launch_rope_append(h->partial, o.n_split, o.stride, o.ld, t, M, h->geom, c.n_q_heads, l,
                                                    h->cos_sin, scaled, h->kv_cache, h->q, s));
             rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache,
-                                  h->q, h->attn_part_o, h->attn_part_ml, to_att, c.max_lookahead + 1, &h->prof, s);
+                                  h->q, h->attn_part_o, h->attn_part_ml, h->attn_part_cap, to_att, c.max_lookahead + 1, &h->prof, s);
         }
         if (rc) return rc;
         rc = gemm(h->att, nullptr, w.w_o, z.d, z.dq, &o);

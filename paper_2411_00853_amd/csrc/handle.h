@@ -50,10 +50,12 @@ struct spec_handle {
     float* att = nullptr;      // [rows][n_q_heads*head_dim] attention output
     float* act = nullptr;      // [rows][d_ffn]
     float* partial = nullptr;  // K-range partial sums of the current GEMM
+    size_t partial_cap = 0;    // its capacity in floats (sized at init from the plans of every row count)
     float* logits = nullptr;   // [rows][vocab] when the caller gives no logits_out
     float* cos_sin = nullptr;  // rotary table
     float* attn_part_o = nullptr;
     float* attn_part_ml = nullptr;
+    size_t attn_part_cap = 0;  // capacity of attn_part_o in floats (attn_part_ml holds 2/head_dim of that)
     int max_rows = 0;
 };
 

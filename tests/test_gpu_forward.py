@@ -374,3 +374,32 @@ def _kv_overflow_case():
     rig.kv_len[1] = 10
     err, chk, na2, ot2, logits, want = _check_step(rig, [1], [2], [4], 1.0, 77)
     assert err < 5e-3
+
+
+def test_tuning_knobs_raised_after_init_are_refused_not_overrun():
+    """The handle's partial-sum and chunk-result buffers are sized for the plans in force at init; a
+    knob raised afterwards makes the step fail on the host with SPEC_ERR_SHAPE (nothing is launched
+    past the buffers), and the step works again once the knob is back.  The shape is chosen so that the
+    defaults leave room to grow: an LM head wide enough for two K ranges by default (four when asked
+    for more workgroups), and 32 sequences x 8 kv heads, which get two position chunks each by default
+    (sixteen when asked for more work items)."""
+    from paper_2411_00853_amd import binding as sv
+    shape = wl.ModelShape(1, 512, 8, 8, 64, 512, 24000)
+    B = 32
+    rig = Rig(shape, B, 2048, 1, seed=3, std=0.05)
+    rng = wl.Rng(2, "cpu")
+    toks, dl = _drafts(rng, B, 1, shape.vocab, 1.0)
+    us = rng.uniform(3, (B, 2))
+    slots, t0, look = list(range(B)), rng.randint(4, (B,), shape.vocab).tolist(), [1] * B
+    for setter, value in ((sv.spec_k_set_gemm_wg_target, 4096), (sv.spec_k_set_attn_items_per_cu, 64)):
+        setter(value)
+        try:
+            with pytest.raises(sv.SpecError) as e:
+                rig.step(slots, t0, look, toks, dl, us, 1.0)
+            assert e.value.status == -2 and "before spec_verify_init" in str(e.value)
+        finally:
+            setter(0)
+        torch.cuda.synchronize()
+        rig.kv_len.zero_()                                  # the refused step's bookkeeping kernel had run
+    err, *_ = _check_step(rig, slots, t0, look, 1.0, 5)
+    assert err < 5e-3
