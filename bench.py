@@ -23,6 +23,41 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
+
+
+def event_timed(torch, step, iters):
+    """Per-step times (ms) of `iters` steps, each between two HIP events recorded on the stream the
+    steps are launched on (torch's current stream, which the binding passes to the library)."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in ev:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in ev)
+    pick = lambda q: t[min(len(t) - 1, int(q * len(t)))]
+    return {"iterations": iters, "median_ms": pick(0.5), "p10_ms": pick(0.1), "p90_ms": pick(0.9), "min_ms": t[0],
+            "max_ms": t[-1], "method": "HIP events around each step on the launch stream"}
+
+
+def expected_acceptance(torch, target_rows, draft_logits, look, T):
+    """Closed forms beside the measured acceptance rate.  Position i of a sequence keeps its proposal
+    with probability alpha_i = sum_v min(p_i(v), q_i(v)) (p_i, q_i: this step's target and draft
+    distributions; the proposal is a draw from q_i).  Returns (mean alpha over all tested positions,
+    expected kept proposals / proposals made = sum_b sum_i prod_{j<=i} alpha_bj / sum_b K_b)."""
+    r0, alphas, kept = 0, [], 0.0
+    for b, k in enumerate(look):
+        if k:
+            p = torch.softmax(target_rows[r0:r0 + k].double() / T, dim=-1)
+            q = torch.softmax(draft_logits[b, :k].double() / T, dim=-1)
+            a = torch.minimum(p, q).sum(dim=-1)
+            alphas.append(a)
+            kept += float(torch.cumprod(a, 0).sum())
+        r0 += k + 1
+    if not alphas:
+        return None, None
+    return float(torch.cat(alphas).mean()), kept / sum(look)
 
 
 def parse():
@@ -33,6 +68,11 @@ def parse():
     ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn", "stress", "copy", "decode", "tree"])
     ap.add_argument("--temperature", type=float, default=0.0, help="decode workload: sampling temperature (0 = default 4.0)")
     ap.add_argument("--lookahead", type=int, default=5, help="decode workload: proposals per round")
+    ap.add_argument("--draft", default="config", choices=["config", "1b"],
+                    help="decode workload: the draft model -- 'config' = the one the 7B-shape configuration names "
+                         "(4 layers, d_model 2048, 16 heads x 128, FFN 5504), '1b' = the 16-layer 1B-shape")
+    ap.add_argument("--timing-iters", type=int, default=100,
+                    help="per-step HIP-event timing: iterations behind the median / p10 / p90 figures")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--paged", action="store_true", help="7b/1b/dyn workloads: keep the KV cache in a page pool")
     ap.add_argument("--layers", type=int, default=0,
@@ -200,7 +240,10 @@ def bench_decode(args, torch, sv, wl):
     max_kv = n0 + (rounds_total + 2 * n_cal + 2) * (Kt + 1) + 8
     t_setup = time.time()
     tg, tg_len, keep_t = synthetic_model(sv, wl, torch, wl.SEVEN_B, wl.SEED_BASE + 2, B, max_kv, Kt, [n0] * B)
-    dr, dr_len, keep_d = synthetic_model(sv, wl, torch, wl.ONE_B, wl.SEED_BASE + 3, B, max_kv, 1, [n0 - 1] * B)
+    d_shape = wl.SEVEN_B_DRAFT if args.draft == "config" else wl.ONE_B
+    d_name = ("4 layers d_model 2048 (16 heads x 128, FFN 5504: the draft the 7B-shape configuration names)"
+              if args.draft == "config" else "1B-shape (16 layers d_model 2048)")
+    dr, dr_len, keep_d = synthetic_model(sv, wl, torch, d_shape, wl.SEED_BASE + 3, B, max_kv, 1, [n0 - 1] * B)
     log(f"[bench] decode setup {time.time() - t_setup:.1f}s")
     rng = wl.Rng(wl.SEED_BASE + 4, "cuda")
     V = wl.SEVEN_B.vocab
@@ -295,7 +338,7 @@ def bench_decode(args, torch, sv, wl):
         "metric": "emitted tokens/sec, speculative decoding loop", "value": spec_tps, "unit": "tokens/s", "n_gpus": 1,
         "steps": R, "warmup": W, "ms_per_step": t_spec / R * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"decode loop: target 7B-shape, draft 1B-shape (unrelated random weights), batch {B}, "
+        "config": {"workload": f"decode loop: target 7B-shape, draft {d_name} (unrelated random weights), batch {B}, "
                                f"{n0} cached tokens, K {K}, T {T}; a step is one round (K draft decodes + verification)"},
         "plain_sampling_tokens_per_s": base_tps, "plain_sampling_ms_per_token_step": t_base / R * 1e3,
         "speedup_over_plain_sampling": spec_tps / base_tps, "kept_fraction": kept / max(seq_rounds * K, 1),
@@ -485,6 +528,64 @@ def main():
     accepted = int(n_acc.sum().item())
     drafted = sum(look)
     log(f"[bench] {ms_per_step:.3f} ms/step, emitted {emitted} tokens/step")
+    timing = event_timed(torch, step, max(args.timing_iters, 1))
+    log(f"[bench] per-step events over {timing['iterations']} steps: median {timing['median_ms']:.3f} ms "
+        f"(p10 {timing['p10_ms']:.3f}, p90 {timing['p90_ms']:.3f})")
+
+    # closed-form acceptance of these inputs, from the step's own target rows
+    lo = torch.empty((w.rows, V), dtype=torch.float32, device="cuda")
+    sv.spec_kv_rollback(h, slot_list, len_list)
+    sv.spec_verify_step(h, look, uniforms, w.temperature, n_acc, out_tok, seq_slot=slots, last_token=t0,
+                        draft_tokens=draft_tokens, draft_logits=draft_logits, logits_out=lo, auto_rollback=True)
+    torch.cuda.synchronize()
+    alpha_mean, exp_kept = expected_acceptance(torch, lo, draft_logits, look, w.temperature)
+
+    # The same step with proposals that agree with the target about as a trained draft does: position
+    # by position, the draft's logits are the target's own row for the window so far plus N(0, 0.3^2),
+    # and the proposal is drawn from them.  The step's work is the same; what changes is how many of
+    # the scored positions end up as emitted tokens.
+    high = None
+    if Kmax > 0:
+        rng = wl.Rng(w.seed + 7, "cuda")
+        hi_tokens = torch.zeros_like(draft_tokens)
+        hi_logits = torch.zeros_like(draft_logits)
+        row0 = [0]
+        for k in look:
+            row0.append(row0[-1] + k + 1)
+        for i in range(Kmax):
+            sv.spec_kv_rollback(h, slot_list, len_list)
+            part = [min(k, i) for k in look]           # windows of the first i proposals
+            lo_i = torch.empty((sum(k + 1 for k in part), V), dtype=torch.float32, device="cuda")
+            sv.spec_verify_step(h, part, uniforms, w.temperature, n_acc, out_tok, seq_slot=slots, last_token=t0,
+                                draft_tokens=hi_tokens, draft_logits=hi_logits, logits_out=lo_i, auto_rollback=True)
+            r = 0
+            for b, k in enumerate(part):
+                if look[b] > i:
+                    hi_logits[b, i] = lo_i[r + i] + rng.normal(wl.S_DRAFT_NOISE + 64 + b * 16 + i, (V,), 0.3)
+                r += k + 1
+            hi_tokens[:, i] = wl.pick_tokens(rng, hi_logits[:, i], w.temperature, wl.S_DRAFT_PICK + 64 + i)
+        torch.cuda.synchronize()
+
+        def step_hi():
+            sv.spec_kv_rollback(h, slot_list, len_list)
+            sv.spec_verify_step(h, look, uniforms, w.temperature, n_acc, out_tok, seq_slot=slots, last_token=t0,
+                                draft_tokens=hi_tokens, draft_logits=hi_logits, logits_out=lo, auto_rollback=True)
+
+        for _ in range(3):
+            step_hi()
+        torch.cuda.synchronize()
+        tic = time.perf_counter()
+        for _ in range(args.steps):
+            step_hi()
+        torch.cuda.synchronize()
+        ms_hi = (time.perf_counter() - tic) / args.steps * 1e3
+        a_hi, e_hi = int(n_acc.sum().item()), int((n_acc + 1).sum().item())
+        am_hi, ek_hi = expected_acceptance(torch, lo, hi_logits, look, w.temperature)
+        high = {"drafts": "draft logits = the target's own row + N(0, 0.3^2), position by position; tokens ~ q",
+                "value": e_hi / (ms_hi * 1e-3), "unit": "tokens/s", "ms_per_step": ms_hi,
+                "acceptance_rate": a_hi / max(drafted, 1), "expected_acceptance": ek_hi,
+                "expected_acceptance_per_position": am_hi, "emitted_tokens_per_step": e_hi}
+        log(f"[bench] high-agreement drafts: {ms_hi:.3f} ms/step, kept {a_hi}/{drafted}, {high['value']:.0f} tokens/s")
 
     # the same steps again with per-kernel-class event timing (slower overall; kernel times unaffected)
     sv.spec_verify_profile_begin(h)
@@ -510,6 +611,15 @@ def main():
     attn_bytes = sum((n + k + 1) for n, k in zip(w.kv_lens, look)) * s.n_kv_heads * s.head_dim * 2 * 2 * s.n_layers
     stat_bytes = sum(2 * k + 1 for k in look) * V * 4
     alg = {"gemm": gemm_bytes, "attention": attn_bytes, "sampler_stats": stat_bytes}
+    # the projections one by one: (N, K, launches per step)
+    L = s.n_layers
+    gemm_shapes = {"gemm_qkv": (s.d_q + 2 * s.d_kv, s.d_model, L), "gemm_o": (s.d_model, s.d_q, L),
+                   "gemm_gate_up": (2 * s.d_ffn, s.d_model, L), "gemm_down": (s.d_model, s.d_ffn, L),
+                   "gemm_lm_head": (s.vocab, s.d_model, 1)}
+    M_rows = w.rows
+    for name, (N_, K_, cnt_) in gemm_shapes.items():
+        alg[name] = 2 * N_ * K_ * cnt_
+    attainable = min(MFMA_BF16_PEAK_TFLOPS, M_rows * HBM_PEAK_GBS / 1e3)   # intensity = 2MNK / 2NK = M flop/B
     kernels = {}
     for name, (ms_raw, cnt) in prof.items():
         # bracketed times are used as measured: the interval is the launch's whole slot on the stream
@@ -521,11 +631,31 @@ def main():
             e["algorithmic_MB_per_step"] = alg[name] / 1e6
             e["GBps"] = alg[name] * args.steps / (ms * 1e-3) / 1e9
             e["hbm_frac"] = e["GBps"] / HBM_PEAK_GBS
+        flops = None
+        if name in gemm_shapes and ms > 0:
+            N_, K_, cnt_ = gemm_shapes[name]
+            flops = 2.0 * M_rows * N_ * K_ * cnt_
+        elif name == "gemm" and ms > 0:
+            flops = sum(2.0 * M_rows * N_ * K_ * cnt_ for N_, K_, cnt_ in gemm_shapes.values())
+        if flops and s.dtype == "bf16":
+            tf = flops * args.steps / (ms * 1e-3) / 1e12
+            # every product is issued twice: activations enter as a bf16 head plus a bf16 remainder
+            e["mfma"] = {"useful_TFLOPs": tf, "issued_TFLOPs": 2 * tf, "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+                         "useful_frac_of_peak": tf / MFMA_BF16_PEAK_TFLOPS, "issued_frac_of_peak": 2 * tf / MFMA_BF16_PEAK_TFLOPS,
+                         "attainable_TFLOPs": attainable, "useful_frac_of_attainable": tf / attainable}
         kernels[name] = e
     g = kernels["gemm"]
     roofline = {"kernel": "gemm_skinny_kernel (QKV, O, gate/up, down, LM-head projections)",
                 "bound": "hbm", "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": hbm_traffic(w, args),
+                "frac": g["GBps"] / HBM_PEAK_GBS, "frac_basis": "hip-events",
+                "traffic": hbm_traffic(w, args),
+                "traffic_source": "replayed from profiles/hbm_traffic_7b.json (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of "
+                                  "this kernel source, hash-checked); not measured in this run",
+                "mfma": g.get("mfma"),
+                "mfma_note": f"the contraction runs on the matrix cores but at {M_rows} rows its intensity is {M_rows} flop/B "
+                             f"against a ridge of {MFMA_BF16_PEAK_TFLOPS / HBM_PEAK_GBS * 1e3:.0f}: the attainable rate is "
+                             f"min(peak, {M_rows} x 8 TB/s) = {attainable:.0f} TFLOP/s, so a 50 % share of the bf16 peak is out of "
+                             "reach whatever the kernel does; the HBM fraction is the binding figure",
                 "avg_launch_us": g["ms_per_step"] / g["launches_per_step"] * 1e3,
                 "algorithmic_bytes_per_launch": gemm_bytes / g["launches_per_step"],
                 "empty_event_pair_us": empty_pair_ms * 1e3,
@@ -543,8 +673,11 @@ def main():
                    "rows_per_step": w.rows, "drafts": "independent N(0,1.28^2) draft logits, tokens ~ q",
                    "kv_cache": "paged" if args.paged else "contiguous"},
         "scored_positions_per_s": w.rows / (ms_per_step * 1e-3),
+        "timing": timing,
         "acceptance_rate": accepted / max(drafted, 1),
+        "expected_acceptance": exp_kept, "expected_acceptance_per_position": alpha_mean,
         "emitted_tokens_per_step": emitted,
+        "high_agreement_drafts": high,
         "ms_per_step_K0": ms_k0, "ratio_step_K_over_K0": ms_per_step / ms_k0,
         "hbm_floor_ms": (gemm_bytes + attn_bytes + stat_bytes) / (HBM_PEAK_GBS * 1e9) * 1e3,
         "whole_step_hbm_frac": (gemm_bytes + attn_bytes + stat_bytes) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -101,7 +101,12 @@ int spec_decode_get_view(spec_decoder* d, spec_decode_view* out);
  * After a round with lookahead K in which sequence b kept a_b proposals, a_b + 1 proposals were
  * tested if a_b < K, else K:   tested_b <- forget * tested_b + min(a_b + 1, K),
  * kept_b <- forget * kept_b + a_b.  Sequences with a_b < 0 (skipped) are left alone.
- * All host-side, double precision, no device access: the caller copies n_accepted back itself. */
+ * All host-side, double precision, no device access: the caller copies n_accepted back itself.
+ * One K per round for the whole batch, not one per sequence: the draft steps and the verification
+ * are launched for the batch and their cost is set by the longest window, so a sequence gains
+ * nothing by proposing fewer tokens than its neighbours; the estimates are kept per sequence because
+ * tokens(K) is a sum over sequences with different alpha_b.  (spec_verify_step itself takes a
+ * lookahead per sequence; a caller that wants ragged windows passes them there.) */
 typedef struct {
     double draft_ms;             /* cost of one draft decode step for the batch */
     double verify_ms;            /* cost of a verification with an empty window (K = 0) */

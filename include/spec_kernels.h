@@ -87,7 +87,13 @@ enum {
     SPEC_PROF_SAMPLER_STATS = 4, /* softmax statistics over all target and draft rows */
     SPEC_PROF_SAMPLER_DRAW = 5,  /* accept scan, residual mass, final draw, KV length update */
     SPEC_PROF_PREPARE = 6,       /* row bookkeeping */
-    SPEC_PROF_COUNT = 7
+    /* the projection GEMMs one by one (each is also counted in SPEC_PROF_GEMM) */
+    SPEC_PROF_GEMM_QKV = 7,
+    SPEC_PROF_GEMM_O = 8,
+    SPEC_PROF_GEMM_GATE_UP = 9,  /* with SwiGLU where the GEMM finishes it itself */
+    SPEC_PROF_GEMM_DOWN = 10,
+    SPEC_PROF_GEMM_LM_HEAD = 11,
+    SPEC_PROF_COUNT = 12
 };
 struct spec_handle;
 int spec_verify_profile_begin(struct spec_handle* h);

@@ -121,7 +121,13 @@ int spec_pack_weight(const void* src_row_major, void* dst_packed, int32_t n_out,
 /* Bytes the caller must provide for the KV cache of cfg (all layers, max_batch slots). */
 size_t spec_kv_cache_bytes(const spec_model_cfg* cfg);
 
-/* Create a handle.  weights and kv_cache may both be NULL for a sampler-only handle (every step
+/* Create a handle for one target model and its KV cache.  The paper's description of the method
+ * (section "Speculative Sampling Results") speaks only of a target model that scores the proposals
+ * "in parallel"; it says nothing about a cache, so the state kept here is a reading: per cache slot
+ * the keys and values of every token the target has processed, in the storage type of the weights
+ * (bf16 models: bf16 cache; fp32 models: fp32 cache), entries rounded to that type before anything
+ * attends to them, and a length kv_len per slot that the step advances and rolls back.
+ * weights and kv_cache may both be NULL for a sampler-only handle (every step
  * must then supply target_logits_in).  kv_cache: device buffer of at least spec_kv_cache_bytes;
  * its internal tile order is private -- fill and read it with spec_kv_import / spec_kv_export.
  * kv_len: device int32[max_batch], number of valid cached positions per slot; read and updated
@@ -231,8 +237,10 @@ typedef struct {
     const int32_t* last_token;     /* device int32[B] */
     const int32_t* parent;         /* device int32[B][Kmax] */
     const int32_t* draft_tokens;   /* device int32[B][Kmax] */
-    const float* draft_logits;     /* device fp32[B][Kmax+1][V]: row 0 the root's, row i+1 node i's
-                                      (rows of nodes without children are never read) */
+    const float* draft_logits;     /* device fp32[B][Kmax+1][V]: row 0 the root's, row i+1 node i's.  All
+                                      N_b+1 rows of a sequence must be readable: the statistics pass
+                                      streams every one of them (the values of rows whose node has no
+                                      children do not influence the result) */
     const float* uniforms;         /* device fp32[B][Kmax+1]: [b][i] tests node i, [b][N_b] the final draw */
     float temperature;
     const float* target_logits_in; /* optional device fp32[M][V], M = sum(N_b+1): skip the decoder pass */
@@ -248,7 +256,14 @@ typedef struct {
 
 int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args, const spec_tree_out* out, void* stream);
 
-/* Set kv_len[seq_slot[i]] = new_len[i] for i < n (host arrays, n <= SPEC_MAX_BATCH).  The cache is
+/* Drop cached positions: the counterpart of the paper's "no more tokens are accepted" after the
+ * first rejection (section "Speculative Sampling Results") -- the rejected proposals were appended
+ * to the cache when the window was scored and must not be attended to again.  The paper does not
+ * describe a cache; the reading taken is that the valid prefix of a slot is [0, kv_len) and that a
+ * step leaves kv_len = n + a + 1 (last token and the a kept proposals; the final token is the next
+ * step's input).  spec_verify_step does this itself with auto_rollback; this call is for callers
+ * that roll back on their own (auto_rollback = 0, abandoning or rewinding a sequence).
+ * Set kv_len[seq_slot[i]] = new_len[i] for i < n (host arrays, n <= SPEC_MAX_BATCH).  The cache is
  * contiguous per slot, so dropping rejected positions moves no data; stale entries are never read
  * and are overwritten by the next append.  new_len must satisfy 0 <= new_len <= kv_len[slot]. */
 int spec_kv_rollback(spec_handle* h, const int32_t* seq_slot, const int32_t* new_len, int32_t n,

@@ -28,6 +28,20 @@ def build(force: bool = False) -> str:
     return _LIB_PATH
 
 
+def build_sanitized(out_dir: str) -> str:
+    """Compile oracle.c together with its driver (sanitize_main.c) under AddressSanitizer and
+    UndefinedBehaviorSanitizer into an executable in out_dir; returns its path.  Run it directly: it
+    exercises every exported routine on small seeded inputs and exits non-zero on a failed check,
+    the sanitizers abort on anything they find."""
+    exe = os.path.join(out_dir, "oracle_sanitized")
+    here = os.path.dirname(os.path.abspath(__file__))
+    cmd = ["gcc", "-O1", "-g", "-fopenmp", "-ffp-contract=off", "-Wall", "-Wextra",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+           "-o", exe, os.path.join(here, "sanitize_main.c"), _SRC[0], "-lm"]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 class _Model(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim",
                                          "d_ffn", "vocab", "dtype", "max_kv_len")] + \

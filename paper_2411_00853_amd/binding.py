@@ -498,7 +498,8 @@ def spec_k_gemm_f32(x: torch.Tensor, w: torch.Tensor, stream=None):
     return y
 
 
-PROF_CLASSES = ("gemm", "attention", "attn_merge", "glue", "sampler_stats", "sampler_draw", "prepare")
+PROF_CLASSES = ("gemm", "attention", "attn_merge", "glue", "sampler_stats", "sampler_draw", "prepare",
+                "gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head")
 
 
 def spec_verify_profile_begin(h: Handle):

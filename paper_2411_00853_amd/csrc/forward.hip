@@ -133,7 +133,7 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
     const XOut to_act{bf16 ? h->xf : nullptr, mt, planes, bf16 ? nullptr : h->act};
     const NormScale scaled{bf16 ? h->ssq : nullptr, n_ssq, z.d, c.rms_eps};
     const NormScale unscaled{nullptr, 0, 0, 0.f};
-    auto gemm = [&](const float* plain_in, const float* gain, const void* w, int N, int K, Out* o,
+    auto gemm = [&](int cls, const float* plain_in, const float* gain, const void* w, int N, int K, Out* o,
                     const void* in_frags = nullptr) -> int {
         if (bf16) {
             const GemmPlan p = plan_gemm(M, N, K, h->cu_count, h->split_act);
@@ -145,7 +145,7 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
             o->n_split = p.n_split;
             o->ld = p.n_pad;
             o->stride = (size_t)M * p.n_pad;
-            ProfScope ps_(&h->prof, SPEC_PROF_GEMM, s);
+            ProfScope ps_(&h->prof, cls, s);
             return launch_gemm_bf16(p, in_frags ? in_frags : h->xf, w, M, N, K, h->partial, s);
         }
         o->n_split = 1;
@@ -157,7 +157,7 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
             if (r) return r;
             plain_in = h->hn;
         }
-        ProfScope ps_(&h->prof, SPEC_PROF_GEMM, s);
+        ProfScope ps_(&h->prof, cls, s);
         return launch_gemm_f32(plain_in, (const float*)w, M, N, K, h->partial, s);
     };
 
@@ -167,7 +167,7 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
     const bool fuse = h->fuse_rope && attention_takes_qkv(h->geom, c.n_q_heads, ks, B, c.max_kv_len, h->cu_count);
     for (int l = 0; l < c.n_layers; ++l) {
         const spec_layer_weights& w = h->layers[l];
-        rc = gemm(h->x, w.attn_norm, w.w_qkv, z.nqkv, z.d, &o);
+        rc = gemm(SPEC_PROF_GEMM_QKV, h->x, w.attn_norm, w.w_qkv, z.nqkv, z.d, &o);
         if (rc) return rc;
         if (fuse) {
             // the attention kernel adds up, scales and rotates q, k, v itself and appends k, v
@@ -182,33 +182,33 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
                                   h->q, h->attn_part_o, h->attn_part_ml, h->attn_part_cap, to_att, c.max_lookahead + 1, &h->prof, s);
         }
         if (rc) return rc;
-        rc = gemm(h->att, nullptr, w.w_o, z.d, z.dq, &o);
+        rc = gemm(SPEC_PROF_GEMM_O, h->att, nullptr, w.w_o, z.d, z.dq, &o);
         if (rc) return rc;
         RUN(SPEC_PROF_GLUE, launch_resid(h->partial, o.n_split, o.stride, o.ld, M, z.d, h->x, h->ssq, w.ffn_norm, to_xf, s));
         if (swiglu_in_gemm) {
             // the gate/up GEMM applies the norm's row scale and SwiGLU itself and writes the down
             // projection's operand (into the second fragment buffer: it is still reading the first)
-            RUN(SPEC_PROF_GEMM, launch_gemm_swiglu(h->xf, planes, w.w_gate_up, M, z.F, z.d, h->ssq, n_ssq, z.d, c.rms_eps,
+            RUN(SPEC_PROF_GEMM_GATE_UP, launch_gemm_swiglu(h->xf, planes, w.w_gate_up, M, z.F, z.d, h->ssq, n_ssq, z.d, c.rms_eps,
                                                    h->xf_act, mt, planes, h->cu_count, s));
-            rc = gemm(h->act, nullptr, w.w_down, z.d, z.F, &o, h->xf_act);
+            rc = gemm(SPEC_PROF_GEMM_DOWN, h->act, nullptr, w.w_down, z.d, z.F, &o, h->xf_act);
         } else {
-            rc = gemm(h->x, w.ffn_norm, w.w_gate_up, 2 * z.F, z.d, &o);
+            rc = gemm(SPEC_PROF_GEMM_GATE_UP, h->x, w.ffn_norm, w.w_gate_up, 2 * z.F, z.d, &o);
             if (rc) return rc;
             RUN(SPEC_PROF_GLUE, launch_silu_mul(h->partial, o.n_split, o.stride, o.ld, M, z.F, bf16, scaled, to_act, s));
-            rc = gemm(h->act, nullptr, w.w_down, z.d, z.F, &o);
+            rc = gemm(SPEC_PROF_GEMM_DOWN, h->act, nullptr, w.w_down, z.d, z.F, &o);
         }
         if (rc) return rc;
         const float* next_gain = (l + 1 < c.n_layers) ? h->layers[l + 1].attn_norm : h->final_norm;
         RUN(SPEC_PROF_GLUE, launch_resid(h->partial, o.n_split, o.stride, o.ld, M, z.d, h->x, h->ssq, next_gain, to_xf, s));
     }
     if (bf16) {
-        rc = gemm(h->x, h->final_norm, h->lm_head, z.V, z.d, &o);
+        rc = gemm(SPEC_PROF_GEMM_LM_HEAD, h->x, h->final_norm, h->lm_head, z.V, z.d, &o);
         if (rc) return rc;
         RUN(SPEC_PROF_GLUE, launch_reduce_splits(h->partial, o.n_split, o.stride, M, z.V, o.ld, h->ssq, n_ssq, z.d, c.rms_eps,
                                  logits_out, s));
     } else {
         RUN(SPEC_PROF_GLUE, launch_rmsnorm_apply(h->x, h->ssq, h->final_norm, c.rms_eps, M, z.d, h->hn, s));
-        RUN(SPEC_PROF_GEMM, launch_gemm_f32(h->hn, (const float*)h->lm_head, M, z.V, z.d, logits_out, s));
+        RUN(SPEC_PROF_GEMM_LM_HEAD, launch_gemm_f32(h->hn, (const float*)h->lm_head, M, z.V, z.d, logits_out, s));
     }
     (void)unscaled;
 #undef RUN

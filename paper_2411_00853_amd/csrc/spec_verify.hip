@@ -280,8 +280,13 @@ extern "C" int spec_verify_profile_end(spec_handle* h, void* stream, double* ms,
     for (int i = 0; i < h->prof.used; ++i) {
         float t = 0.f;
         SPECV_HIP(hipEventElapsedTime(&t, h->prof.recs[i].start, h->prof.recs[i].stop));
-        ms[h->prof.recs[i].cls] += t;
-        launches[h->prof.recs[i].cls] += 1;
+        const int cls = h->prof.recs[i].cls;
+        ms[cls] += t;
+        launches[cls] += 1;
+        if (cls >= SPEC_PROF_GEMM_QKV && cls <= SPEC_PROF_GEMM_LM_HEAD) {   // every projection also counts as a GEMM
+            ms[SPEC_PROF_GEMM] += t;
+            launches[SPEC_PROF_GEMM] += 1;
+        }
     }
     if (empty_pair_ms) {
         // what a start/stop pair measures with nothing in between (median of 33): the part of every

@@ -187,6 +187,11 @@ S_WEIGHTS, S_KV, S_TOKENS, S_DRAFT_NOISE, S_DRAFT_PICK, S_UNIFORMS, S_K, S_N, S_
 TINY = ModelShape(2, 256, 4, 4, 64, 1024, 1024, dtype="fp32")
 ONE_B = ModelShape(16, 2048, 32, 8, 64, 8192, 32000)
 SEVEN_B = ModelShape(32, 4096, 32, 32, 128, 11008, 32000)
+# The draft models the configurations name ("draft 2 layers d_model 1024", "draft 4 layers d_model
+# 2048"); what they leave open is filled in like the target: same head_dim, same heads-to-width and
+# FFN-to-width ratios, same vocabulary.
+ONE_B_DRAFT = ModelShape(2, 1024, 16, 4, 64, 4096, 32000)
+SEVEN_B_DRAFT = ModelShape(4, 2048, 16, 16, 128, 5504, 32000)
 
 
 def workload_tiny() -> Workload:

@@ -303,3 +303,67 @@ def test_argument_errors():
     dec = sv.spec_decode_init(a.h, None, 2, 8)
     with pytest.raises(sv.SpecError):
         sv.spec_decode_round(dec, 0, None, torch.zeros(2, 3, device="cuda"), 1.0)   # no active batch
+
+
+@pytest.mark.parametrize("T,cost", [(1.0, (0.4, 5.0, 0.05)), (2.5, (0.4, 5.0, 0.05)), (2.5, (1.0, 4.0, 0.05))])
+def test_lookahead_controller_in_the_loop_fp32(T, cost):
+    """The lookahead follows the data inside the loop: every round's K is what the library's
+    controller (spec_lookahead_next) chooses from the kept counts the GPU reported so far.  The oracle
+    runs its own loop from the same start, its K chosen by its own rule (oracle.decode.LookaheadRule)
+    from its own results.  The sequence of K, the kept counts, the generated text and the acceptance
+    estimates must be the same, for as long as no decision of the oracle's run was closer to its
+    threshold than the margins a 1e-4 logit difference can move."""
+    from paper_2411_00853_amd import binding as sv
+    t_shape = wl.ModelShape(2, 256, 4, 4, 64, 512, 300, dtype="fp32")
+    d_shape = wl.ModelShape(1, 128, 2, 2, 64, 256, 300, dtype="fp32")
+    Kt, R, seed = 5, 10, 61
+    pair = Pair(t_shape, d_shape, CONTEXTS, 128, Kt, 96, seed=seed)
+    B = len(CONTEXTS)
+    kw = dict(draft_ms=cost[0], verify_ms=cost[1], verify_ms_per_token=cost[2], k_min=1, k_max=Kt)
+    ctl = sv.Lookahead(B, **kw)
+    rule = od.LookaheadRule(B, **kw)
+    rng = wl.Rng(seed, "cpu")
+    du = [rng.uniform(wl.S_UNIFORMS + 100 + r, (B, Kt)) for r in range(R)]
+    vu = [rng.uniform(wl.S_UNIFORMS + 200 + r, (B, Kt + 1)) for r in range(R)]
+    # ---- the GPU's loop, controller in it ----
+    ks_gpu, kept_gpu, est_gpu = [], [], []
+    for r in range(R):
+        k = ctl.next()
+        g = pair.round(k, du[r], vu[r], T)
+        a = g["n_accepted"].tolist()
+        ctl.update(a, k)
+        ks_gpu.append(k)
+        kept_gpu.append(a)
+        est_gpu.append([ctl.accept(b) for b in range(B)])
+    text_gpu = [g["tokens"][b, :int(g["n_tokens"][b])].tolist() for b in range(B)]
+    # ---- the oracle's loop, its own rule in it ----
+    # A round in which every decision of the oracle's run is clear of its threshold must agree in
+    # full.  A round with a decision too close to call may go either way: if the GPU took the same
+    # decisions the comparison goes on, otherwise the two runs have parted for good and it ends.
+    rounds_same, rounds_clear, pos = 0, 0, [0] * B
+    for r in range(R):
+        k = rule.next()
+        traces = [od.speculative_round(pair.tg.om, pair.dr.om, st, k, T, du[r][b].tolist(), vu[r][b].tolist())
+                  for b, st in enumerate(pair.states)]
+        rule.update([t.n_accepted for t in traces], k)
+        close = False
+        for b, t in enumerate(traces):
+            gaps = [min(d.final_target - d.final_cdf_lo, d.final_cdf_hi - d.final_target) for d in t.draft_diags]
+            gaps.append(min(t.diag.final_target - t.diag.final_cdf_lo, t.diag.final_cdf_hi - t.diag.final_target))
+            margins = [abs(float(vu[r][b, i]) - t.diag.accept_ratio[i]) for i in range(min(t.n_accepted + 1, k))]
+            close |= min(gaps) < 5e-5 or (bool(margins) and min(margins) < 1e-3)
+        same = ks_gpu[r] == k and kept_gpu[r] == [t.n_accepted for t in traces] and all(
+            text_gpu[b][pos[b]:pos[b] + len(t.emitted)] == t.emitted for b, t in enumerate(traces))
+        if not same:
+            assert close, (f"round {r}: K {ks_gpu[r]} vs {k}, kept {kept_gpu[r]} vs {[t.n_accepted for t in traces]} "
+                           "although every decision of the oracle's run was clear of its threshold")
+            break
+        for b, t in enumerate(traces):
+            assert abs(est_gpu[r][b] - rule.accept(b)) < 1e-12
+            pos[b] += len(t.emitted)
+        rounds_same += 1
+        rounds_clear += not close
+    assert rounds_same >= 5 and rounds_clear >= 2 and sum(pos) >= 20, (rounds_same, rounds_clear, pos)
+    if T > 1.0:
+        assert len(set(ks_gpu[:rounds_same])) >= 2, f"the lookahead should have moved with the data: {ks_gpu}"
+    ctl.close()
