@@ -65,7 +65,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn", "stress", "copy", "decode", "tree"])
+    ap.add_argument("--workload", default="7b", choices=["7b", "1b", "dyn", "rows352", "stress", "copy", "decode", "tree"])
     ap.add_argument("--temperature", type=float, default=0.0, help="decode workload: sampling temperature (0 = default 4.0)")
     ap.add_argument("--lookahead", type=int, default=5, help="decode workload: proposals per round")
     ap.add_argument("--draft", default="config", choices=["config", "1b"],
@@ -74,12 +74,16 @@ def parse():
     ap.add_argument("--timing-iters", type=int, default=100,
                     help="per-step HIP-event timing: iterations behind the median / p10 / p90 figures")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="only the timed steps and the per-class event timing (for hardware-counter runs, where every "
+                         "dispatch is slow): no per-step event statistics, no high-agreement leg, no K=0 ratio")
     ap.add_argument("--paged", action="store_true", help="7b/1b/dyn workloads: keep the KV cache in a page pool")
     ap.add_argument("--layers", type=int, default=0,
                     help="build only this many decoder layers (for hardware-counter runs, where every dispatch is slow; "
                          "per-launch figures are unchanged, whole-step figures are not those of the workload)")
     ap.add_argument("--attn-items-per-cu", type=int, default=0, help="tuning: attention work items per compute unit")
     ap.add_argument("--gemm-wg-target", type=int, default=0, help="tuning: workgroups per GEMM launch")
+    ap.add_argument("--gemm-balance-groups", type=int, default=1, help="tuning: many-row GEMMs as four column groups of three tiles")
     ap.add_argument("--swiglu-min-wgs", type=int, default=0, help="tuning: fewest workgroups for SwiGLU inside the gate/up GEMM")
     return ap.parse_args()
 
@@ -448,6 +452,7 @@ def main():
     sv.spec_k_set_attn_items_per_cu(args.attn_items_per_cu)
     sv.spec_k_set_gemm_wg_target(args.gemm_wg_target)
     sv.spec_k_set_swiglu_min_wgs(args.swiglu_min_wgs)
+    sv.spec_k_set_gemm_balance_groups(args.gemm_balance_groups)
     if args.workload == "stress":
         return bench_stress(args, torch, sv, wl)
     if args.workload == "copy":
@@ -456,7 +461,7 @@ def main():
         return bench_decode(args, torch, sv, wl)
     if args.workload == "tree":
         return bench_tree(args, torch, sv, wl)
-    w = {"7b": wl.workload_7b, "1b": wl.workload_1b, "dyn": wl.workload_dyn}[args.workload]()
+    w = {"7b": wl.workload_7b, "1b": wl.workload_1b, "dyn": wl.workload_dyn, "rows352": wl.workload_rows352}[args.workload]()
     if args.layers > 0:
         from dataclasses import replace
         w = replace(w, shape=replace(w.shape, n_layers=args.layers), name=f"{w.name}-{args.layers}layers")
@@ -528,7 +533,7 @@ def main():
     accepted = int(n_acc.sum().item())
     drafted = sum(look)
     log(f"[bench] {ms_per_step:.3f} ms/step, emitted {emitted} tokens/step")
-    timing = event_timed(torch, step, max(args.timing_iters, 1))
+    timing = event_timed(torch, step, 1 if args.skip_extras else max(args.timing_iters, 1))
     log(f"[bench] per-step events over {timing['iterations']} steps: median {timing['median_ms']:.3f} ms "
         f"(p10 {timing['p10_ms']:.3f}, p90 {timing['p90_ms']:.3f})")
 
@@ -545,7 +550,7 @@ def main():
     # and the proposal is drawn from them.  The step's work is the same; what changes is how many of
     # the scored positions end up as emitted tokens.
     high = None
-    if Kmax > 0:
+    if Kmax > 0 and not args.skip_extras:
         rng = wl.Rng(w.seed + 7, "cuda")
         hi_tokens = torch.zeros_like(draft_tokens)
         hi_logits = torch.zeros_like(draft_logits)
@@ -594,14 +599,15 @@ def main():
     prof, empty_pair_ms = sv.spec_verify_profile_end(h)
     # the paper's claim in measurable form: scoring K drafts costs about one ordinary decode
     zero = [0] * B
-    for _ in range(3):
+    n_k0 = 1 if args.skip_extras else max(5, args.steps // 5)
+    for _ in range(0 if args.skip_extras else 3):
         step(zero)
     torch.cuda.synchronize()
     tic = time.perf_counter()
-    for _ in range(max(5, args.steps // 5)):
+    for _ in range(n_k0):
         step(zero)
     torch.cuda.synchronize()
-    ms_k0 = (time.perf_counter() - tic) / max(5, args.steps // 5) * 1e3
+    ms_k0 = (time.perf_counter() - tic) / n_k0 * 1e3
     sv.spec_verify_poll(h)
 
     # algorithmic bytes per step (what must cross HBM once)

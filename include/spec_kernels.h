@@ -42,6 +42,11 @@ int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, int32_t M, 
  * SPEC_ERR_SHAPE instead of writing past the workspace. */
 void spec_k_set_gemm_wg_target(int32_t workgroups);
 
+/* Tuning knob: launches of more than 112 rows whose twelve column tiles per workgroup would run as
+ * three column groups of four tiles (six wavefronts) run as four groups of three tiles instead
+ * (eight wavefronts, two on every SIMD); 1 = on (default), 0 = off.  Process-wide. */
+void spec_k_set_gemm_balance_groups(int32_t on);
+
 /* Tuning knob: the gate/up projection finishes SwiGLU inside the GEMM (one K range, 128-column
  * workgroups, up to 64 rows) when that launch has at least this many workgroups; 0 = default
  * (a third of the compute units).  1 forces it wherever the shape allows. */

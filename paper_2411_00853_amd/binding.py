@@ -123,6 +123,8 @@ def lib():
         L.spec_k_gemm_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
         L.spec_k_set_gemm_wg_target.restype = None
         L.spec_k_set_gemm_wg_target.argtypes = [C.c_int32]
+        L.spec_k_set_gemm_balance_groups.restype = None
+        L.spec_k_set_gemm_balance_groups.argtypes = [C.c_int32]
         L.spec_k_set_swiglu_min_wgs.restype = None
         L.spec_k_set_swiglu_min_wgs.argtypes = [C.c_int32]
         L.spec_k_set_swiglu_column_groups.restype = None
@@ -468,6 +470,10 @@ def spec_k_gemm_bf16(x: torch.Tensor, w_packed: torch.Tensor, n_out: int, split_
 
 def spec_k_set_gemm_wg_target(workgroups: int):
     lib().spec_k_set_gemm_wg_target(int(workgroups))
+
+
+def spec_k_set_gemm_balance_groups(on: bool):
+    lib().spec_k_set_gemm_balance_groups(int(on))
 
 
 def spec_k_set_swiglu_min_wgs(workgroups: int):

@@ -227,6 +227,7 @@ struct GemmPlan {
     int nt;           // 16-column tiles per wavefront
     int planes;       // 2: bf16 head + remainder; 1: bf16 head only
     int kb_per_split; // 32-wide K blocks per range
+    int rs;           // row parts per workgroup: 1 (every wavefront takes all row tiles), 2 or 4
     int cg;           // column groups (of nt tiles) per workgroup: 4, or 3 for many-row launches that then fill more compute units
 };
 GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x);

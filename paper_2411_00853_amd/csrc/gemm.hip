@@ -86,8 +86,8 @@ __global__ void __launch_bounds__(64 * CG * RS) gemm_skinny_kernel(const u32x4* 
     if (nblk >= n_blocks) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     constexpr int MTW = (MT + RS - 1) / RS;               // row tiles of one wavefront
-    const int a0 = RS == 1 ? 0 : (wave & 1) * MTW;          // its first row tile
-    const int tile0 = (nblk * CG + (RS == 1 ? wave : wave >> 1)) * NT;
+    const int a0 = (wave % RS) * MTW;                       // its first row tile
+    const int tile0 = (nblk * CG + wave / RS) * NT;
     const int kb0 = split * kb_per_split;
     const int kb1 = min(kb0 + kb_per_split, kb_total);
 
@@ -422,36 +422,31 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const uint16_t* __rest
     }
 }
 
+template <int MT, int NT, int KC, int RS, int CG>
+int launch_groups(const GemmPlan& p, const void* xf, const void* w, int M, int K, int n_tiles, float* partial,
+                  hipStream_t s)
+{
+    const int n_blocks = (n_tiles + CG * NT - 1) / (CG * NT);
+    int grid = n_blocks * p.n_split;
+    if (p.n_split < 8) grid = (n_blocks + (8 / p.n_split) - 1) / (8 / p.n_split) * 8;
+    if (p.planes == 2)
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 2, RS, 0, CG>), dim3(grid), dim3(64 * CG * RS), 0, s, (const u32x4*)xf,
+                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
+    else
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 1, RS, 0, CG>), dim3(grid), dim3(64 * CG * RS), 0, s, (const u32x4*)xf,
+                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
+    SPECV_LAUNCH_CHECK("gemm_skinny_kernel");
+    return SPEC_OK;
+}
+
 template <int MT, int NT, int KC, int RS = 1>
 int launch_variant(const GemmPlan& p, const void* xf, const void* w, int M, int K, int n_tiles, float* partial,
                    hipStream_t s)
 {
     if constexpr (RS == 2) {
-        if (p.cg == 3) {
-            const int n_blocks = (n_tiles + 3 * NT - 1) / (3 * NT);
-            int grid = n_blocks * p.n_split;
-            if (p.n_split < 8) grid = (n_blocks + (8 / p.n_split) - 1) / (8 / p.n_split) * 8;
-            if (p.planes == 2)
-                hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 2, RS, 0, 3>), dim3(grid), dim3(192 * RS), 0, s, (const u32x4*)xf,
-                                   (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
-            else
-                hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 1, RS, 0, 3>), dim3(grid), dim3(192 * RS), 0, s, (const u32x4*)xf,
-                                   (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
-            SPECV_LAUNCH_CHECK("gemm_skinny_kernel");
-            return SPEC_OK;
-        }
+        if (p.cg == 3) return launch_groups<MT, NT, KC, RS, 3>(p, xf, w, M, K, n_tiles, partial, s);
     }
-    const int n_blocks = (n_tiles + 4 * NT - 1) / (4 * NT);
-    int grid = n_blocks * p.n_split;
-    if (p.n_split < 8) grid = (n_blocks + (8 / p.n_split) - 1) / (8 / p.n_split) * 8;
-    if (p.planes == 2)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 2, RS>), dim3(grid), dim3(256 * RS), 0, s, (const u32x4*)xf,
-                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
-    else
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, KC, 1, RS>), dim3(grid), dim3(256 * RS), 0, s, (const u32x4*)xf,
-                           (const u32x4*)w, partial, M, n_tiles, K / 32, p.kb_per_split, p.n_split, n_blocks, SwigluOut{});
-    SPECV_LAUNCH_CHECK("gemm_skinny_kernel");
-    return SPEC_OK;
+    return launch_groups<MT, NT, KC, RS, 4>(p, xf, w, M, K, n_tiles, partial, s);
 }
 
 struct Variant {
@@ -482,6 +477,7 @@ const Variant* pick_variant(int M)
 }
 
 int g_wg_target = 0;   // workgroups per launch to aim for; 0 = two thirds of the compute units
+int g_balance_groups = 1;   // many-row launches: four column groups of three tiles instead of three of four
 
 }  // namespace
 
@@ -507,7 +503,9 @@ GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
         p.nt = 4;
         kc = 2;
     }
-    const int wg_x = (n_tiles + 4 * p.nt - 1) / (4 * p.nt);
+    p.cg = 4;
+    p.rs = p.mt >= 8 ? 2 : 1;
+    const int wg_x = (n_tiles + p.cg * p.nt - 1) / (p.cg * p.nt);
     const int kb_total = K / 32;
     // K ranges: a power of two, just enough of them that the launch has about `target` workgroups.
     // Measured on MI355X: every launch pays a few microseconds of ramp-up and tail whatever its
@@ -523,10 +521,15 @@ GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
     // brings the launch from under four fifths of the compute units to at most all of them
     // (157 rows: QKV 192 -> 256 workgroups, gate/up 172 -> 230; GEMM time of that step -6 %).  With
     // few rows, where HBM sets the pace, the same change gained nothing and is not made.
-    p.cg = 4;
-    if (p.mt >= 8) {
+    if (p.mt >= 8 && p.rs == 2) {
         const int wg3 = (n_tiles + 3 * p.nt - 1) / (3 * p.nt) * s;
-        if (wg_x * s * 5 < cu_count * 4 && wg3 <= cu_count) p.cg = 3;
+        if (wg_x * s * 5 < cu_count * 4 && wg3 <= cu_count) {
+            // Twelve column tiles per workgroup either way; as four column groups of three tiles the
+            // workgroup keeps eight wavefronts, two on every SIMD, where three groups of four tiles
+            // put two wavefronts on two SIMDs and one on the others (the loaded ones set the pace).
+            if (p.nt == 4 && g_balance_groups) p.nt = 3;
+            else p.cg = 3;
+        }
     }
     // ranges start on a K group of the packed order so that every chunk is one contiguous run
     p.kb_per_split = ((kb_total + s - 1) / s + WPACK_KG - 1) / WPACK_KG * WPACK_KG;
@@ -542,7 +545,7 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     if (K % 32) return fail(SPEC_ERR_SHAPE, "GEMM needs K %% 32 == 0, got %d", K);
     const int n_tiles = (N + 15) / 16;
 #define SPECV_GEMM(MT_, NT_, KC_, ...)                                                                  \
-    if (p.mt == MT_ && p.nt == NT_)                                                                      \
+    if (p.mt == MT_ && p.nt == NT_ && p.rs == (1, ##__VA_ARGS__))                                         \
         return launch_variant<MT_, NT_, KC_, ##__VA_ARGS__>(p, x_frags, w_packed, M, K, n_tiles, partial, s)
     SPECV_GEMM(1, 4, 2);
     SPECV_GEMM(2, 4, 2);
@@ -554,6 +557,9 @@ int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packe
     SPECV_GEMM(4, 2, 2);
     SPECV_GEMM(5, 4, 2);
     SPECV_GEMM(6, 4, 2);
+    SPECV_GEMM(8, 3, 1, 2);
+    SPECV_GEMM(10, 3, 1, 2);
+    SPECV_GEMM(12, 3, 1, 2);
     SPECV_GEMM(8, 4, 1, 2);
     SPECV_GEMM(10, 4, 1, 2);
     SPECV_GEMM(12, 4, 1, 2);
@@ -684,6 +690,7 @@ extern "C" int spec_pack_weight(const void* src, void* dst, int32_t n_out, int32
 }
 
 extern "C" void spec_k_set_gemm_wg_target(int32_t workgroups) { set_gemm_wg_target(workgroups); }
+extern "C" void spec_k_set_gemm_balance_groups(int32_t on) { g_balance_groups = on != 0; }
 extern "C" void spec_k_set_swiglu_min_wgs(int32_t workgroups) { set_swiglu_min_wgs(workgroups); }
 extern "C" void spec_k_set_swiglu_column_groups(int32_t groups) { set_swiglu_column_groups(groups); }
 extern "C" void spec_k_set_attn_items_per_cu(int32_t items) { set_attn_items_per_cu(items); }

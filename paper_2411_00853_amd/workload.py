@@ -216,6 +216,14 @@ def workload_dyn(batch: int = 32) -> Workload:
     return Workload("dyn", SEVEN_B, batch, tuple(n), tuple(k), 10, 4096 + 11, 1.0, seed, "synthetic")
 
 
+def workload_rows352() -> Workload:
+    """The largest window the projection kernels take: 32 sequences x (10 proposals + 1) = 352 rows on
+    the 7B-shape weights, with short caches (64 positions) so that the step is almost only the
+    projections.  Not one of the benchmark's configurations: the point at which the GEMM family's
+    matrix-core utilisation is reported (its intensity, 352 flop/B, is just past the ridge)."""
+    return Workload("rows352", SEVEN_B, 32, (64,) * 32, (10,) * 32, 10, 64 + 11, 1.0, SEED_BASE + 5000, "synthetic")
+
+
 # A drafted token tree of 10 nodes (3 candidates for the first token, 2 for the second below the
 # first two of them, then single continuations): depth 4, 5 leaves.
 TREE10_PARENT = (-1, -1, -1, 0, 0, 1, 3, 3, 4, 6)

@@ -82,3 +82,25 @@ def test_gemm_is_reproducible_bit_for_bit():
     b = sv.spec_k_gemm_bf16(xd, wp, 2048).clone()
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("M,N,K", [(120, 352, 1024), (157, 352, 1024), (185, 5440, 64), (192, 400, 512)])
+@pytest.mark.parametrize("balanced", [True, False])
+def test_many_row_gemm_both_workgroup_shapes(M, N, K, balanced):
+    """Launches of more than 112 rows that fill too few compute units take twelve column tiles per
+    workgroup either as four column groups of three tiles (eight wavefronts, the default) or as three
+    groups of four (six wavefronts): both against a library product, and bit-identical to each other
+    (the same products are added in the same order)."""
+    from paper_2411_00853_amd import binding as sv
+    x, w = _case(M, N, K, 300 + M)
+    wp = sv.spec_pack_weight(w.cuda())
+    sv.spec_k_set_gemm_balance_groups(balanced)
+    try:
+        y = sv.spec_k_gemm_bf16(x.cuda(), wp, N).cpu()
+    finally:
+        sv.spec_k_set_gemm_balance_groups(True)
+    full = x.double() @ w.double().T
+    scale = full.pow(2).mean().sqrt().item()
+    assert (y.double() - full).abs().max().item() < 3e-5 * scale
+    y2 = sv.spec_k_gemm_bf16(x.cuda(), wp, N).cpu()
+    assert torch.equal(y, y2)
