@@ -83,6 +83,7 @@ def parse():
                          "per-launch figures are unchanged, whole-step figures are not those of the workload)")
     ap.add_argument("--attn-items-per-cu", type=int, default=0, help="tuning: attention work items per compute unit")
     ap.add_argument("--attn-merge-min-pairs", type=int, default=0, help="tuning: fewest (sequence, kv head) pairs for merging chunks inside the workgroup")
+    ap.add_argument("--attn-max-chunks", type=int, default=0, help="tuning: most position chunks per (sequence, kv head)")
     ap.add_argument("--gemm-wg-target", type=int, default=0, help="tuning: workgroups per GEMM launch")
     ap.add_argument("--gemm-balance-groups", type=int, default=1, help="tuning: many-row GEMMs as four column groups of three tiles")
     ap.add_argument("--swiglu-min-wgs", type=int, default=0, help="tuning: fewest workgroups for SwiGLU inside the gate/up GEMM")
@@ -453,6 +454,7 @@ def main():
     sv.spec_k_set_attn_items_per_cu(args.attn_items_per_cu)
     sv.spec_k_set_gemm_wg_target(args.gemm_wg_target)
     sv.spec_k_set_attn_merge_min_pairs(args.attn_merge_min_pairs)
+    sv.spec_k_set_attn_max_chunks(args.attn_max_chunks)
     sv.spec_k_set_swiglu_min_wgs(args.swiglu_min_wgs)
     sv.spec_k_set_gemm_balance_groups(args.gemm_balance_groups)
     if args.workload == "stress":
