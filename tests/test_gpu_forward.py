@@ -403,3 +403,23 @@ def test_tuning_knobs_raised_after_init_are_refused_not_overrun():
         rig.kv_len.zero_()                                  # the refused step's bookkeeping kernel had run
     err, *_ = _check_step(rig, slots, t0, look, 1.0, 5)
     assert err < 5e-3
+
+
+@pytest.mark.parametrize("B,Kmax", [(32, 10), (20, 9), (13, 15)])
+def test_largest_windows_on_a_small_model(B, Kmax):
+    """Up to 352 window rows in one step (32 sequences x 11 rows: the most the projections take), and
+    the row counts between 192 and 352 whose GEMM variants the benchmark's configurations do not reach:
+    every row against the oracle."""
+    shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
+    rig = Rig(shape, B, 80, Kmax, seed=13, std=0.05)
+    rng = wl.Rng(14, "cpu")
+    lens = rng.randint(1, (B,), 60).tolist()
+    for s, n in enumerate(lens):
+        rig.prefill(s, rng.randint(100 + s, (n,), shape.vocab).tolist())
+    look = [Kmax] * B
+    look[1] = Kmax - 1 if B == 20 else Kmax          # 20 x 10 - 1 = 199 rows: a ragged tail inside a row tile
+    t0 = rng.randint(3, (B,), shape.vocab).tolist()
+    err, chk, na, ot, logits, want = _check_step(rig, list(range(B)), t0, look, 1.0, 99)
+    assert logits.shape[0] == sum(k + 1 for k in look)
+    assert err < 5e-3
+    assert chk.exact_accept + chk.margin_accept == B

@@ -107,3 +107,37 @@ def test_sizes_beyond_the_fixed_workspace_are_refused():
         with pytest.raises(sv.SpecError) as e:
             sv.spec_sample_step_noalloc(vocab, kmax, look, us, 1.0, na, ot, tl)
         assert e.value.status == -2
+
+
+def test_the_stated_maximum_sizes_fit_the_fixed_workspace():
+    """64 sequences, lookahead 15, vocabulary 262144 (the limits in the header): every table of the
+    fixed workspace is used up to its last entry; results bit-identical to the handle's step."""
+    from paper_2411_00853_amd import binding as sv
+    B, Kmax, V, T = 64, 15, 262144, 1.0
+    rng = wl.Rng(505, "cuda")
+    look = [Kmax] * B
+    tl = rng.normal(1, (B * (Kmax + 1), V), 1.0)
+    dl = tl.view(B, Kmax + 1, V)[:, :Kmax].contiguous()
+    dl += rng.normal(2, (B, Kmax, V), 0.3)
+    toks = wl.pick_tokens(rng, dl, T, 3)
+    us = rng.uniform(4, (B, Kmax + 1))
+    h = sv.spec_verify_init(sv.sampler_cfg(V, B, Kmax), None, None, None)
+    na1 = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    ot1 = torch.full((B, Kmax + 1), -7, dtype=torch.int32, device="cuda")
+    sv.spec_verify_step(h, look, us, T, na1, ot1, draft_tokens=toks, draft_logits=dl, target_logits_in=tl)
+    torch.cuda.synchronize()
+    sv.spec_verify_poll(h)
+    h.close()
+    na2 = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    ot2 = torch.full((B, Kmax + 1), -7, dtype=torch.int32, device="cuda")
+    sv.spec_sample_step_noalloc(V, Kmax, look, us, T, na2, ot2, tl, draft_tokens=toks, draft_logits=dl)
+    torch.cuda.synchronize()
+    assert torch.equal(na1, na2) and torch.equal(ot1, ot2)
+    assert int(na2.min()) >= 0 and len(set(na2.tolist())) >= 3
+    # one sequence against the oracle as well
+    from helpers import SamplerCheck
+    b = 17
+    chk = SamplerCheck()
+    chk.compare(tl[b * (Kmax + 1):(b + 1) * (Kmax + 1)].cpu(), dl[b].cpu(), toks[b].cpu().tolist(), us[b].cpu().tolist(), T,
+                int(na2[b]), ot2[b].cpu().tolist(), Kmax)
+    assert chk.exact_accept + chk.margin_accept == 1
