@@ -21,6 +21,10 @@
  *  - Work is enqueued on the given hipStream_t (passed as void*; NULL = the default stream) and
  *    is NOT synchronised: outputs are valid once the caller has synchronised the stream.
  *    Calls on one handle must not overlap in time (they share its workspace).
+ *    spec_verify_step, spec_verify_tree_step, spec_kv_rollback and spec_sample_step_noalloc only queue
+ *    kernels (and one device-to-device copy when target_logits_in and logits_out are both given): no
+ *    allocation, no synchronisation, no memset -- they may be recorded into a HIP graph and replayed;
+ *    per-sequence lookaheads and rollback lengths are host values and are frozen into the recording.
  *  - Host-checkable arguments are validated before anything is launched.  Conditions that depend
  *    on device data (kv_len + K + 1 > max_kv_len, token id >= vocab, rollback beyond the current
  *    length) make the affected sequence a no-op (its n_accepted is written as -1), raise a flag
