@@ -206,6 +206,54 @@ def test_tree_step_whose_kept_nodes_sit_beyond_a_block_boundary():
     assert err < 5e-3
 
 
+def test_greedy_tree_step_whose_kept_nodes_sit_beyond_a_block_boundary():
+    """The same situation at temperature 0 (the greedy walk has its own kernel): nodes 3 and 6 carry the
+    most likely tokens of their parents' rows, every other node a different token."""
+    from test_gpu_forward import Rig, PagedRig
+    from test_gpu_tree import _tree_step
+    Kmax, V = 7, SHAPE.vocab
+    base = Rig(SHAPE, 2, 96, Kmax, seed=7, std=0.3)           # large weights: clear logit gaps
+    rng = wl.Rng(23, "cpu")
+    lens = {0: 28, 1: 61}
+    for s, n in lens.items():
+        base.prefill(s, rng.randint(20 + s, (n,), V).tolist())
+    paged = PagedRig(base, 2, 96, Kmax, n_pages=6)
+    for s in lens:
+        paged.load(base, s)
+    slots, t0 = [0, 1], [11, 12]
+    parent = [-1, -1, -1, -1, 3, 3, 3]
+    toks = []
+    for b, s in enumerate(slots):
+        c = base.caches[s].clone()
+        top0 = int(torch.argmax(base.om.verify_sequential(c, lens[s], [t0[b]])[0]))
+        top3 = int(torch.argmax(base.om.verify_sequential(c, lens[s], [t0[b], top0])[1]))
+        toks.append([(top0 + 1) % V, (top0 + 2) % V, (top0 + 3) % V, top0, (top3 + 1) % V, (top3 + 2) % V, top3])
+    par_t = torch.tensor([parent, parent], dtype=torch.int32)
+    tok_t = torch.tensor(toks, dtype=torch.int32)
+    dl = torch.zeros((2, Kmax + 1, V))
+    us = torch.zeros((2, Kmax + 1))
+    a1 = _tree_step(base, slots, t0, [7, 7], par_t, tok_t, dl, us, 0.0)
+    a2 = _tree_step(paged, slots, t0, [7, 7], par_t, tok_t, dl, us, 0.0)
+    for x, y in zip(a1, a2):
+        assert torch.equal(x, y)
+    logits, na, ot, pt = a2
+    for b, s in enumerate(slots):
+        rows = logits[8 * b:8 * b + 8].contiguous()
+        a, path, out, gap = oracle.tree_greedy(parent, toks[b], rows)
+        assert (a, path) == (2, [3, 6]) and gap > 1e-2, "the planted walk should keep nodes 3 and 6 by a clear gap"
+        assert int(na[b]) == 2 and pt[b, :2].tolist() == [3, 6] and ot[b, :3].tolist() == out[:3]
+    kl = paged.kv_len.cpu().tolist()
+    assert kl == [31, 64] and kl == base.kv_len.cpu().tolist()
+    assert paged.free() == 6 - (1 + 2)
+    for b, s in enumerate(slots):
+        x, y = _export(base, s, 0, kl[s]), _export(paged, s, 0, kl[s])
+        assert torch.equal(x, y)
+        ref = base.caches[s]
+        base.om.verify_sequential(ref, lens[s], [t0[b], toks[b][3], toks[b][6]])
+        diff = (y[:, :, :, lens[s]:].float() - ref[:, :, :, lens[s]:kl[s]].float()).abs().max().item()
+        assert diff <= 0.5, f"compacted cache of slot {s} differs from the oracle's by {diff}"   # bf16 ulp at |v| ~ 30
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2, 3, 5, 7, 9, 11, 12, 13])
 def test_random_small_models_on_a_page_pool(seed):
     """The seeded random cases of test_gpu_forward (bf16 ones) on a page pool: logits against the
