@@ -84,6 +84,7 @@ def parse():
     ap.add_argument("--attn-items-per-cu", type=int, default=0, help="tuning: attention work items per compute unit")
     ap.add_argument("--attn-merge-min-pairs", type=int, default=0, help="tuning: fewest (sequence, kv head) pairs for merging chunks inside the workgroup")
     ap.add_argument("--attn-max-chunks", type=int, default=0, help="tuning: most position chunks per (sequence, kv head)")
+    ap.add_argument("--kv-pad", type=int, default=0, help="tuning: extra positions of cache capacity per slot (changes the strides between heads and slots)")
     ap.add_argument("--gemm-wg-target", type=int, default=0, help="tuning: workgroups per GEMM launch")
     ap.add_argument("--gemm-balance-groups", type=int, default=1, help="tuning: many-row GEMMs as four column groups of three tiles")
     ap.add_argument("--swiglu-min-wgs", type=int, default=0, help="tuning: fewest workgroups for SwiGLU inside the gate/up GEMM")
@@ -469,6 +470,9 @@ def main():
     if args.layers > 0:
         from dataclasses import replace
         w = replace(w, shape=replace(w.shape, n_layers=args.layers), name=f"{w.name}-{args.layers}layers")
+    if args.kv_pad:
+        from dataclasses import replace
+        w = replace(w, max_kv_len=w.max_kv_len + args.kv_pad)
     shape, B, Kmax, V = w.shape, w.batch, w.max_lookahead, w.shape.vocab
     want_cpu = not args.no_cpu_baseline
     n_sample = min(8, B)       # sequences the CPU oracle is timed on (~10 s of CPU work at 7B-shape)

@@ -57,13 +57,19 @@ typedef struct spec_handle spec_handle;   /* opaque */
 #define SPEC_DTYPE_BF16 1   /* weights, embedding and KV cache in bf16; fp32 accumulation */
 #define SPEC_MAX_BATCH 256
 #define SPEC_MAX_LOOKAHEAD 15
+#define SPEC_MAX_STEP_ROWS 352   /* bf16 models: window rows (sum of K_b + 1) one step may carry */
 
 /* Decoder-only transformer: pre-norm residual blocks, RMSNorm, rotary position embedding with
  * dimension i paired with i + head_dim/2 and angle pos * rope_theta^(-2i/head_dim), grouped-query
  * attention with score scale 1/sqrt(head_dim), SwiGLU feed-forward, untied LM head, no biases.
  * Requirements: n_q_heads % n_kv_heads == 0; head_dim in {64, 128} for bf16 (any even value for
  * fp32); d_model, n_q_heads*head_dim and d_ffn multiples of 32 for bf16;
- * 1 <= max_batch <= SPEC_MAX_BATCH; 0 <= max_lookahead <= SPEC_MAX_LOOKAHEAD. */
+ * 1 <= max_batch <= SPEC_MAX_BATCH; 0 <= max_lookahead <= SPEC_MAX_LOOKAHEAD.
+ * bf16 models: the projections take at most SPEC_MAX_STEP_ROWS rows per launch.  max_batch *
+ * (max_lookahead + 1) may exceed that; what is limited is the number of window rows of each step
+ * (linear or tree: the sum of K_b + 1 over its sequences), and a step beyond it is refused with
+ * SPEC_ERR_SHAPE before anything is launched (caches and lengths untouched).  fp32 models have no
+ * such limit. */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
     int32_t max_batch;       /* sequences per step, and number of KV-cache slots */

@@ -230,6 +230,7 @@ struct GemmPlan {
     int rs;           // row parts per workgroup: 1 (every wavefront takes all row tiles), 2 or 4
     int cg;           // column groups (of nt tiles) per workgroup: 4, or 3 for many-row launches that then fill more compute units
 };
+constexpr int GEMM_MAX_ROWS = SPEC_MAX_STEP_ROWS;   // rows the largest variant of the bf16 GEMM takes
 GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x);
 int gemm_row_tiles(int M);   // row tiles (mt) of the variant that serves M rows; 0 if none
 size_t gemm_partial_elems(const GemmPlan& p, int M);

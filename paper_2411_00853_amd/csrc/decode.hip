@@ -269,6 +269,12 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
     hipStream_t s = (hipStream_t)stream;
     spec_handle* tg = d->target;
     spec_handle* dr = d->draft;
+    if (B * (K + 1) > tg->row_cap)
+        return fail(SPEC_ERR_SHAPE, "spec_decode_round: %d sequences x %d window rows exceed the %d rows a step of the target takes",
+                    B, K + 1, tg->row_cap);
+    if (dr && 2 * B > dr->row_cap)
+        return fail(SPEC_ERR_SHAPE, "spec_decode_round: %d sequences x 2 rows exceed the %d rows a step of the draft takes", B,
+                    dr->row_cap);
     tg->tables.tree = 0;
     if (dr) dr->tables.tree = 0;
     int rc;

@@ -34,9 +34,11 @@ int forward_init(spec_handle* h, int max_rows)
     const Dims z = dims_of(c);
     h->max_rows = max_rows;
     if (!h->geom.table) h->geom = make_cache_geom(c);   // a paged handle set its geometry already
-    if (c.dtype == SPEC_DTYPE_BF16 && max_rows > 352)
-        return fail(SPEC_ERR_SHAPE, "max_batch*(max_lookahead+1) = %d rows exceeds the 352 the bf16 GEMM supports",
-                    max_rows);
+    // The bf16 projections take at most GEMM_MAX_ROWS rows per launch.  A handle whose batch and
+    // lookahead limits multiply to more than that is still usable: the limit then applies to the rows
+    // of each step (the sum of K_b + 1), which the step checks.
+    h->row_cap = c.dtype == SPEC_DTYPE_BF16 ? std::min(max_rows, GEMM_MAX_ROWS) : max_rows;
+    max_rows = h->row_cap;
     int rc = SPEC_OK;
     Arena& a = h->arena;
     auto A = [&](float** p, size_t count) {
@@ -66,7 +68,7 @@ int forward_init(spec_handle* h, int max_rows)
         // partial-sum space for the largest GEMM at any row count
         const int Ns[G_COUNT] = {z.nqkv, z.d, 2 * z.F, z.d, z.V};
         const int Ks[G_COUNT] = {z.d, z.dq, z.d, z.F, z.d};
-        for (int M = 16; M <= (max_rows + 15) / 16 * 16 && M <= 352; M += 16)
+        for (int M = 16; M <= (max_rows + 15) / 16 * 16 && M <= GEMM_MAX_ROWS; M += 16)
             for (int i = 0; i < G_COUNT; ++i) {
                 const int rows = M < max_rows ? M : max_rows;
                 const size_t e = gemm_partial_elems(plan_gemm(rows, Ns[i], Ks[i], h->cu_count, true), rows);
@@ -107,6 +109,7 @@ int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* lo
     const bool bf16 = c.dtype == SPEC_DTYPE_BF16;
     const StepTables& t = h->tables;
     int rc;
+    if (M < 1 || M > h->row_cap) return fail(SPEC_ERR_SHAPE, "%d window rows; the handle takes 1..%d per step", M, h->row_cap);
 #define RUN(cls, expr)                          \
     do {                                        \
         {                                       \

@@ -541,7 +541,7 @@ size_t gemm_partial_elems(const GemmPlan& p, int M) { return (size_t)p.n_split *
 int launch_gemm_bf16(const GemmPlan& p, const void* x_frags, const void* w_packed, int M, int N, int K, float* partial,
                      hipStream_t s)
 {
-    if (M < 1 || M > 352) return fail(SPEC_ERR_SHAPE, "GEMM supports 1..352 rows, got %d", M);
+    if (M < 1 || M > GEMM_MAX_ROWS) return fail(SPEC_ERR_SHAPE, "GEMM supports 1..%d rows, got %d", GEMM_MAX_ROWS, M);
     if (K % 32) return fail(SPEC_ERR_SHAPE, "GEMM needs K %% 32 == 0, got %d", K);
     const int n_tiles = (N + 15) / 16;
 #define SPECV_GEMM(MT_, NT_, KC_, ...)                                                                  \
@@ -699,7 +699,7 @@ extern "C" void spec_k_set_attn_max_chunks(int32_t chunks) { set_attn_max_chunks
 
 extern "C" size_t spec_k_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K)
 {
-    if (M < 1 || M > 352 || N < 1 || K < 32 || K % 32) return 0;
+    if (M < 1 || M > GEMM_MAX_ROWS || N < 1 || K < 32 || K % 32) return 0;
     GemmPlan p = plan_gemm(M, N, K, 256, true);
     // partial sums of the widest plan (16 ranges) + the X fragment buffer (both planes)
     const size_t part = (size_t)16 * M * p.n_pad * sizeof(float);
@@ -710,7 +710,7 @@ extern "C" int spec_k_gemm_bf16(const float* x, const void* w_packed, float* y, 
                                 int32_t split_x, void* workspace, void* stream)
 {
     if (!x || !w_packed || !y || !workspace) return fail(SPEC_ERR_INVALID_ARG, "spec_k_gemm_bf16: null pointer");
-    if (M < 1 || M > 352 || N < 1 || K < 32 || K % 32) return fail(SPEC_ERR_SHAPE, "spec_k_gemm_bf16: unsupported shape");
+    if (M < 1 || M > GEMM_MAX_ROWS || N < 1 || K < 32 || K % 32) return fail(SPEC_ERR_SHAPE, "spec_k_gemm_bf16: unsupported shape");
     GemmPlan p = plan_gemm(M, N, K, 256, split_x != 0);
     float* partial = (float*)workspace;
     char* xf = (char*)workspace + (((size_t)16 * M * p.n_pad * sizeof(float) + 255) & ~(size_t)255);

@@ -56,7 +56,8 @@ struct spec_handle {
     float* attn_part_o = nullptr;
     float* attn_part_ml = nullptr;
     size_t attn_part_cap = 0;  // capacity of attn_part_o in floats (attn_part_ml holds 2/head_dim of that)
-    int max_rows = 0;
+    int max_rows = 0;   // max_batch * (max_lookahead + 1): what the row tables hold
+    int row_cap = 0;    // window rows one step may carry (the activation buffers are sized for it)
 };
 
 namespace specv {

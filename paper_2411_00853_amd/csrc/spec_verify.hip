@@ -354,6 +354,8 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     if (run_model) {
         if (!h->has_model) return fail(SPEC_ERR_INVALID_ARG, "sampler-only handle needs target_logits_in");
         if (!args->seq_slot || !args->last_token) return fail(SPEC_ERR_INVALID_ARG, "seq_slot or last_token is NULL");
+        if (M > h->row_cap)
+            return fail(SPEC_ERR_SHAPE, "this step has %d window rows; the handle takes at most %d per step", M, h->row_cap);
     }
     hipStream_t s = (hipStream_t)stream;
     // draft_tokens may be NULL when every K_b is 0; the kernels then never read it
@@ -413,6 +415,8 @@ extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args,
     if (run_model) {
         if (!h->has_model) return fail(SPEC_ERR_INVALID_ARG, "sampler-only handle needs target_logits_in");
         if (!args->seq_slot || !args->last_token) return fail(SPEC_ERR_INVALID_ARG, "seq_slot or last_token is NULL");
+        if (M > h->row_cap)
+            return fail(SPEC_ERR_SHAPE, "this step has %d window rows; the handle takes at most %d per step", M, h->row_cap);
     }
     hipStream_t s = (hipStream_t)stream;
     int rc;

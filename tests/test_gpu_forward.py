@@ -423,3 +423,38 @@ def test_largest_windows_on_a_small_model(B, Kmax):
     assert logits.shape[0] == sum(k + 1 for k in look)
     assert err < 5e-3
     assert chk.exact_accept + chk.margin_accept == B
+
+
+def test_handle_whose_limits_multiply_past_the_row_limit():
+    """max_batch x (max_lookahead + 1) = 40 x 11 = 440 rows is more than one launch of the projections
+    takes (352); the handle is still created, steps whose own windows add up to at most 352 rows are
+    scored as usual (every row against the oracle), and a step beyond that is refused on the host
+    before anything is launched: lengths and caches stay as they were."""
+    from paper_2411_00853_amd import binding as sv
+    shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
+    B, Kmax = 40, 10
+    rig = Rig(shape, B, 80, Kmax, seed=17, std=0.05)
+    rng = wl.Rng(18, "cpu")
+    lens = rng.randint(1, (B,), 50).tolist()
+    for s, n in enumerate(lens):
+        rig.prefill(s, rng.randint(200 + s, (n,), shape.vocab).tolist())
+    t0 = rng.randint(3, (B,), shape.vocab).tolist()
+    before = rig.kv_len.clone()
+    toks, dl = _drafts(rng, B, Kmax, shape.vocab, 1.0)
+    us = rng.uniform(5, (B, Kmax + 1))
+    with pytest.raises(sv.SpecError) as e:
+        rig.step(list(range(B)), t0, [Kmax] * B, toks, dl, us, 1.0)
+    assert e.value.status == -2 and "352" in str(e.value)
+    torch.cuda.synchronize()
+    assert torch.equal(rig.kv_len, before)
+    # 32 sequences with K = 10 and 8 with K = 0: 360 rows, still too many; 31 and 9: 350 rows
+    look = [Kmax] * 32 + [0] * 8
+    with pytest.raises(sv.SpecError):
+        rig.step(list(range(B)), t0, look, toks, dl, us, 1.0)
+    torch.cuda.synchronize()
+    assert torch.equal(rig.kv_len, before)
+    look = [Kmax] * 31 + [0] * 9
+    err, chk, na, ot, logits, want = _check_step(rig, list(range(B)), t0, look, 1.0, 77)
+    assert logits.shape[0] == 350
+    assert err < 5e-3
+    assert chk.exact_accept + chk.margin_accept == B
