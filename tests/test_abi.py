@@ -83,3 +83,44 @@ def test_build_lists_name_existing_sources():
         assert os.path.exists(os.path.join(b.CSRC, src)), src
     assert set(b.SOURCE_FLAGS) <= set(b.SOURCES)
     assert "--offload-arch=gfx950" in b.FLAGS and "-packed-fp32-ops" in b.FLAGS
+
+
+def test_headers_are_plain_c_and_the_binding_mirrors_their_structs(tmp_path):
+    """The three headers compile as strict C11 (no C++ needed to call the library), and every struct the
+    Python binding marshals has the size and field offsets the C compiler gives it."""
+    import ctypes as C
+    import subprocess
+    from paper_2411_00853_amd import binding as sv
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    names = ["spec_model_cfg", "spec_layer_weights", "spec_weights", "spec_step_args", "spec_step_out",
+             "spec_tree_args", "spec_tree_out", "spec_decode_cfg", "spec_round_args", "spec_lookahead_cfg",
+             "spec_decode_view"]
+    lines = ['#include <stddef.h>', '#include <stdio.h>', '#include "spec_verify.h"', '#include "spec_decode.h"',
+             '#include "spec_kernels.h"', 'int main(void) {']
+    for n in names:
+        cls = getattr(sv, n)
+        lines.append(f'  printf("{n} size %zu\\n", sizeof({n}));')
+        for f, _ in cls._fields_:
+            lines.append(f'  printf("{n} {f} %zu\\n", offsetof({n}, {f}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(root, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    seen = 0
+    for line in out:
+        if not line:
+            continue
+        n, f, v = line.split()
+        cls = getattr(sv, n)
+        want = C.sizeof(cls) if f == "size" else getattr(cls, f).offset
+        assert int(v) == want, line
+        seen += 1
+    assert seen == sum(len(getattr(sv, n)._fields_) + 1 for n in names)
+    # and the limits the binding or the tests rely on are the header's
+    text = open(os.path.join(root, "include", "spec_verify.h")).read()
+    for macro, value in (("SPEC_MAX_BATCH", 256), ("SPEC_MAX_LOOKAHEAD", 15), ("SPEC_MAX_STEP_ROWS", 352),
+                         ("SPEC_NOALLOC_MAX_BATCH", 64), ("SPEC_NOALLOC_MAX_VOCAB", 262144)):
+        assert f"#define {macro} {value}" in text, macro
