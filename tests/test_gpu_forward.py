@@ -251,7 +251,7 @@ def _random_case(seed):
     return shape, n_slots, cap, kmax, lens, look, order, r.choice([0.6, 1.0, 1.7])
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(72))
 def test_random_small_models(seed):
     shape, n_slots, cap, kmax, lens, look, order, T = _random_case(1000 + seed)
     rig = Rig(shape, n_slots, cap, kmax, seed=20 + seed, std=0.05)

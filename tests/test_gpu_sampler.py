@@ -172,3 +172,31 @@ def test_greedy_rule_at_temperature_zero(V):
         seen.add(a)
         r0 += k + 1
     assert len(seen) >= 4
+
+
+def test_many_random_shapes_linear_and_tree():
+    """150 seeded draws of (vocabulary, lookahead, temperature, batch, draft noise): the linear rule and
+    the tree rule, every sequence against the oracle (decisions bit-exact outside the margins, tokens
+    exact or valid inside the band)."""
+    import random
+    import test_gpu_tree as TT
+    from helpers import check_sampler_against_oracle, run_sampler_gpu
+    seqs = walks = 0
+    for seed in range(150):
+        r = random.Random(seed)
+        V = r.choice([97, 301, 1000, 4099, 32000, 50257])
+        Kmax = r.choice([1, 2, 5, 8, 12, 15])
+        T = r.choice([0.5, 0.7, 1.0, 1.3, 2.0])
+        B = r.choice([1, 2, 5, 12, 33])
+        sigma = r.choice([0.1, 0.5, 1.5])
+        inp = TT.make_tree_inputs(1000 + seed, B, Kmax, V, T, sigma)
+        na, ot, pt = TT.run_tree_sampler(*inp, T, Kmax)
+        chk = TT.check_trees(*inp, T, Kmax, na, ot, pt)
+        seqs += B
+        walks += chk.exact_walk
+        look = [r.randrange(0, Kmax + 1) for _ in range(B)]
+        look[0] = Kmax
+        tl, dl, toks, us = _random_inputs(2000 + seed, look, Kmax, V, sigma, T)
+        na, ot = run_sampler_gpu(tl, dl, toks, us, look, T, Kmax)
+        check_sampler_against_oracle(tl, dl, toks, us, look, T, Kmax, na, ot)
+    assert walks >= seqs - 5     # nearly every walk is decided outside the margin
