@@ -57,7 +57,7 @@ typedef struct spec_handle spec_handle;   /* opaque */
 #define SPEC_DTYPE_BF16 1   /* weights, embedding and KV cache in bf16; fp32 accumulation */
 #define SPEC_MAX_BATCH 256
 #define SPEC_MAX_LOOKAHEAD 15
-#define SPEC_MAX_STEP_ROWS 352   /* bf16 models: window rows (sum of K_b + 1) one step may carry */
+#define SPEC_MAX_STEP_ROWS 352   /* bf16 models: window rows (sum of K_b + 1) one pass of the decoder takes */
 
 /* Decoder-only transformer: pre-norm residual blocks, RMSNorm, rotary position embedding with
  * dimension i paired with i + head_dim/2 and angle pos * rope_theta^(-2i/head_dim), grouped-query
@@ -65,11 +65,12 @@ typedef struct spec_handle spec_handle;   /* opaque */
  * Requirements: n_q_heads % n_kv_heads == 0; head_dim in {64, 128} for bf16 (any even value for
  * fp32); d_model, n_q_heads*head_dim and d_ffn multiples of 32 for bf16;
  * 1 <= max_batch <= SPEC_MAX_BATCH; 0 <= max_lookahead <= SPEC_MAX_LOOKAHEAD.
- * bf16 models: the projections take at most SPEC_MAX_STEP_ROWS rows per launch.  max_batch *
- * (max_lookahead + 1) may exceed that; what is limited is the number of window rows of each step
- * (linear or tree: the sum of K_b + 1 over its sequences), and a step beyond it is refused with
- * SPEC_ERR_SHAPE before anything is launched (caches and lengths untouched).  fp32 models have no
- * such limit. */
+ * bf16 models: the projections take at most SPEC_MAX_STEP_ROWS rows per launch.  A step (linear or
+ * tree) whose windows add up to more rows is scored in several passes of the decoder over groups of
+ * consecutive sequences -- the weights are streamed once per pass, everything else (row bookkeeping,
+ * sampling, rollback, results) is as for one pass.  spec_decode_round does not do this: there
+ * batch * (lookahead + 1) must not exceed SPEC_MAX_STEP_ROWS (SPEC_ERR_SHAPE otherwise, before
+ * anything is launched). */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
     int32_t max_batch;       /* sequences per step, and number of KV-cache slots */

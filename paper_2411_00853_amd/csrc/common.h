@@ -149,6 +149,8 @@ int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len
                     hipStream_t s);
 // paged caches, after launch_kv_compact: return the pages beyond n + n_accepted + 1 of every sequence
 int launch_tree_trim(const StepTables& t, int B, const int32_t* n_accepted, hipStream_t s);
+// sub := the tables of sequences [b0, b0 + Bg) of full, rows and sequence numbers counted from that group's start
+int launch_slice_tables(const StepTables& full, const StepTables& sub, int b0, int Bg, hipStream_t s);
 // paged caches: make sure positions [pos0, pos1) of a slot have pages (flags SPEC_ERR_KV_OVERFLOW if not)
 int launch_pool_cover(const PagePool& pool, int slot, int pos0, int pos1, int32_t* flag, hipStream_t s);
 

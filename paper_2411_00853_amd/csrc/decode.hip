@@ -294,7 +294,7 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
             rc = launch_prepare(dr->tables, ks, B, d->Kd, V, dr->cfg.max_batch, dr->cfg.max_kv_len, true, d->seq_slot,
                                 i == 0 ? d->prev_tok : d->cur_tok, d->win, dr->kv_len, dr->flag, s);
             if (rc) return rc;
-            rc = forward_run(dr, ks, B, rows, dr->logits, s);
+            rc = forward_run(dr, dr->tables, ks, B, rows, dr->logits, s);
             if (rc) return rc;
             DrawEmit em{};
             em.tokens = d->draft_tokens;
@@ -322,7 +322,7 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
     rc = launch_prepare(tg->tables, ks, B, Kt, V, tg->cfg.max_batch, tg->cfg.max_kv_len, true, d->seq_slot, d->last_tok,
                         d->draft_tokens, tg->kv_len, tg->flag, s);
     if (rc) return rc;
-    rc = forward_run(tg, ks, B, M, tg->logits, s);
+    rc = forward_run(tg, tg->tables, ks, B, M, tg->logits, s);
     if (rc) return rc;
     if (greedy)
         rc = launch_greedy(tg->tables, tg->sampler, ks, B, Kt, V, M, tg->logits, d->draft_tokens, 1, tg->kv_len,

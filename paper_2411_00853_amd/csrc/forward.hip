@@ -4,6 +4,7 @@
 // (+residual); then the final norm and the LM head.  Every reduction of GEMM K-range partial sums
 // is folded into the kernel that consumes the GEMM's result.
 #include <cmath>
+#include <cstring>
 #include <vector>
 
 #include "frag.h"
@@ -38,6 +39,7 @@ int forward_init(spec_handle* h, int max_rows)
     // lookahead limits multiply to more than that is still usable: the limit then applies to the rows
     // of each step (the sum of K_b + 1), which the step checks.
     h->row_cap = c.dtype == SPEC_DTYPE_BF16 ? std::min(max_rows, GEMM_MAX_ROWS) : max_rows;
+    const int all_rows = max_rows;   // the logits of a whole step, however many passes it takes
     max_rows = h->row_cap;
     int rc = SPEC_OK;
     Arena& a = h->arena;
@@ -50,7 +52,7 @@ int forward_init(spec_handle* h, int max_rows)
     A(&h->q, (size_t)max_rows * z.dq);
     A(&h->att, (size_t)max_rows * z.dq);
     A(&h->act, (size_t)max_rows * z.F);
-    A(&h->logits, (size_t)max_rows * z.V);
+    A(&h->logits, (size_t)all_rows * z.V);
     A(&h->cos_sin, (size_t)c.max_kv_len * c.head_dim);
     size_t part = 0;
     if (c.dtype == SPEC_DTYPE_BF16) {
@@ -102,12 +104,40 @@ int forward_init(spec_handle* h, int max_rows)
     return SPEC_OK;
 }
 
-int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s)
+int forward_run_grouped(spec_handle* h, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s)
+{
+    if (M <= h->row_cap) return forward_run(h, h->tables, ks, B, M, logits_out, s);
+    if (!h->group_tables.seq_row0) return fail(SPEC_ERR_SHAPE, "%d window rows exceed the %d the handle takes", M, h->row_cap);
+    // groups of consecutive sequences, about equally many rows each
+    const int cap = h->row_cap, n_groups = (M + cap - 1) / cap, target = (M + n_groups - 1) / n_groups;
+    StepTables sub = h->group_tables;
+    sub.pool = h->tables.pool;
+    sub.tree = h->tables.tree;
+    int b0 = 0, r0 = 0;
+    while (b0 < B) {
+        LookaheadPack kg;
+        memset(&kg, 0, sizeof(kg));
+        int Bg = 0, Mg = 0;
+        while (b0 + Bg < B && Mg < target && Mg + ks.k[b0 + Bg] + 1 <= cap) {
+            kg.k[Bg] = ks.k[b0 + Bg];
+            Mg += ks.k[b0 + Bg] + 1;
+            ++Bg;
+        }
+        int rc = launch_slice_tables(h->tables, sub, b0, Bg, s);
+        if (rc) return rc;
+        rc = forward_run(h, sub, kg, Bg, Mg, logits_out + (size_t)r0 * h->cfg.vocab, s);
+        if (rc) return rc;
+        b0 += Bg;
+        r0 += Mg;
+    }
+    return SPEC_OK;
+}
+
+int forward_run(spec_handle* h, const StepTables& t, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s)
 {
     const spec_model_cfg& c = h->cfg;
     const Dims z = dims_of(c);
     const bool bf16 = c.dtype == SPEC_DTYPE_BF16;
-    const StepTables& t = h->tables;
     int rc;
     if (M < 1 || M > h->row_cap) return fail(SPEC_ERR_SHAPE, "%d window rows; the handle takes 1..%d per step", M, h->row_cap);
 #define RUN(cls, expr)                          \

@@ -28,6 +28,7 @@ struct spec_handle {
     int32_t* flag = nullptr;
     specv::Arena arena;
     specv::StepTables tables{};
+    specv::StepTables group_tables{};   // one pass's share of `tables` when a step is scored in several passes
     specv::SamplerWorkspace sampler{};
     specv::Profiler prof;
 
@@ -62,5 +63,8 @@ struct spec_handle {
 
 namespace specv {
 int forward_init(spec_handle* h, int max_rows);
-int forward_run(spec_handle* h, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s);
+// one decoder pass over the B sequences (M <= row_cap window rows) that t describes
+int forward_run(spec_handle* h, const StepTables& t, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s);
+// the same for any M: sequences are taken in groups of at most row_cap rows, one pass each (t = h->tables)
+int forward_run_grouped(spec_handle* h, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s);
 }  // namespace specv

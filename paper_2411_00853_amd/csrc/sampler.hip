@@ -103,6 +103,32 @@ __global__ void __launch_bounds__(TPB) prepare_kernel(StepTables t, LookaheadPac
     }
 }
 
+// A step with more window rows than one decoder pass takes is scored group by group: the row
+// bookkeeping above runs once for the whole step (so that what it decides -- skipped sequences, a slot
+// named twice, pages taken -- is decided once), and each pass gets the entries of its own sequences
+// with rows and sequence numbers counted from the group's start.
+__global__ void __launch_bounds__(TPB) slice_tables_kernel(StepTables full, StepTables sub, int b0, int Bg)
+{
+    const int r0 = full.seq_row0[b0], st0 = full.seq_stat0[b0];
+    const int n_rows = full.seq_row0[b0 + Bg] - r0;
+    for (int i = threadIdx.x; i <= Bg; i += TPB) {
+        sub.seq_row0[i] = full.seq_row0[b0 + i] - r0;
+        sub.seq_stat0[i] = full.seq_stat0[b0 + i] - st0;
+        if (i < Bg) {
+            sub.seq_n[i] = full.seq_n[b0 + i];
+            sub.seq_ok[i] = full.seq_ok[b0 + i];
+            sub.seq_slot[i] = full.seq_slot[b0 + i];
+        }
+    }
+    for (int r = threadIdx.x; r < n_rows; r += TPB) {
+        sub.row_seq[r] = full.row_seq[r0 + r] - b0;
+        sub.row_pos[r] = full.row_pos[r0 + r];
+        sub.row_tok[r] = full.row_tok[r0 + r];
+        sub.row_rope[r] = full.row_rope[r0 + r];
+        sub.row_mask[r] = full.row_mask[r0 + r];
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Pass 1: per (row, chunk) maximum and sum of exp((l - max)/T).
 // Statistics rows of sequence b: K_b+1 target rows, then K_b draft rows.
@@ -1128,6 +1154,13 @@ int launch_rollback(const RollbackPack& p, int n, int max_batch, int32_t* kv_len
 {
     hipLaunchKernelGGL(rollback_kernel, dim3(1), dim3(TPB), 0, s, p, n, max_batch, kv_len, flag, pool);
     SPECV_LAUNCH_CHECK("rollback_kernel");
+    return SPEC_OK;
+}
+
+int launch_slice_tables(const StepTables& full, const StepTables& sub, int b0, int Bg, hipStream_t s)
+{
+    hipLaunchKernelGGL(slice_tables_kernel, dim3(1), dim3(TPB), 0, s, full, sub, b0, Bg);
+    SPECV_LAUNCH_CHECK("slice_tables_kernel");
     return SPEC_OK;
 }
 

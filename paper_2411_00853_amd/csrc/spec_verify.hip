@@ -209,6 +209,20 @@ static int init_common(const spec_model_cfg* cfg, const spec_weights* weights, v
     A(&h->tables.row_tok, max_rows);
     A(&h->tables.row_rope, max_rows);
     A(&h->tables.row_mask, max_rows);
+    if (cfg->dtype == SPEC_DTYPE_BF16 && max_rows > GEMM_MAX_ROWS && weights) {
+        // a step may need several decoder passes: tables for one pass's share
+        StepTables& g = h->group_tables;
+        A(&g.seq_row0, B + 1);
+        A(&g.seq_stat0, B + 1);
+        A(&g.seq_n, B);
+        A(&g.seq_ok, B);
+        A(&g.seq_slot, B);
+        A(&g.row_seq, GEMM_MAX_ROWS);
+        A(&g.row_pos, GEMM_MAX_ROWS);
+        A(&g.row_tok, GEMM_MAX_ROWS);
+        A(&g.row_rope, GEMM_MAX_ROWS);
+        A(&g.row_mask, GEMM_MAX_ROWS);
+    }
     A(&h->sampler.part_max, (size_t)max_stat * n_stat_chunks);
     A(&h->sampler.part_sum, (size_t)max_stat * n_stat_chunks);
     A(&h->sampler.chunk_mass, (size_t)B * n_res_chunks);
@@ -354,8 +368,6 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     if (run_model) {
         if (!h->has_model) return fail(SPEC_ERR_INVALID_ARG, "sampler-only handle needs target_logits_in");
         if (!args->seq_slot || !args->last_token) return fail(SPEC_ERR_INVALID_ARG, "seq_slot or last_token is NULL");
-        if (M > h->row_cap)
-            return fail(SPEC_ERR_SHAPE, "this step has %d window rows; the handle takes at most %d per step", M, h->row_cap);
     }
     hipStream_t s = (hipStream_t)stream;
     // draft_tokens may be NULL when every K_b is 0; the kernels then never read it
@@ -370,7 +382,7 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     const float* logits = args->target_logits_in;
     if (run_model) {
         float* dst = out->logits_out ? out->logits_out : h->logits;
-        rc = forward_run(h, ks, B, M, dst, s);
+        rc = forward_run_grouped(h, ks, B, M, dst, s);
         if (rc) return rc;
         logits = dst;
     } else if (out->logits_out) {
@@ -415,8 +427,6 @@ extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args,
     if (run_model) {
         if (!h->has_model) return fail(SPEC_ERR_INVALID_ARG, "sampler-only handle needs target_logits_in");
         if (!args->seq_slot || !args->last_token) return fail(SPEC_ERR_INVALID_ARG, "seq_slot or last_token is NULL");
-        if (M > h->row_cap)
-            return fail(SPEC_ERR_SHAPE, "this step has %d window rows; the handle takes at most %d per step", M, h->row_cap);
     }
     hipStream_t s = (hipStream_t)stream;
     int rc;
@@ -431,7 +441,7 @@ extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args,
     const float* logits = args->target_logits_in;
     if (run_model) {
         float* dst = out->logits_out ? out->logits_out : h->logits;
-        rc = forward_run(h, ks, B, M, dst, s);
+        rc = forward_run_grouped(h, ks, B, M, dst, s);
         if (rc) return rc;
         logits = dst;
     } else if (out->logits_out) {

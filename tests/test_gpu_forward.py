@@ -425,36 +425,68 @@ def test_largest_windows_on_a_small_model(B, Kmax):
     assert chk.exact_accept + chk.margin_accept == B
 
 
-def test_handle_whose_limits_multiply_past_the_row_limit():
-    """max_batch x (max_lookahead + 1) = 40 x 11 = 440 rows is more than one launch of the projections
-    takes (352); the handle is still created, steps whose own windows add up to at most 352 rows are
-    scored as usual (every row against the oracle), and a step beyond that is refused on the host
-    before anything is launched: lengths and caches stay as they were."""
-    from paper_2411_00853_amd import binding as sv
+def test_steps_with_more_rows_than_one_decoder_pass():
+    """40 sequences x 11 window rows = 440 rows, more than one launch of the projections takes (352): the
+    step scores its sequences in two passes, and nothing else changes -- every row against the oracle,
+    the sampler rules, the cache lengths; the same on a page pool, bit for bit; a ragged 408-row step
+    from the state the first left; and a slot named by a sequence of each pass is refused for the
+    later one only, as in a single pass."""
     shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
     B, Kmax = 40, 10
     rig = Rig(shape, B, 80, Kmax, seed=17, std=0.05)
     rng = wl.Rng(18, "cpu")
-    lens = rng.randint(1, (B,), 50).tolist()
+    lens = rng.randint(1, (B,), 40).tolist()
     for s, n in enumerate(lens):
         rig.prefill(s, rng.randint(200 + s, (n,), shape.vocab).tolist())
+    paged = PagedRig(rig, B, 80, Kmax, n_pages=B * 3)
+    for s in range(B):
+        paged.load(rig, s)
+    slots = list(range(B))
     t0 = rng.randint(3, (B,), shape.vocab).tolist()
-    before = rig.kv_len.clone()
-    toks, dl = _drafts(rng, B, Kmax, shape.vocab, 1.0)
-    us = rng.uniform(5, (B, Kmax + 1))
-    with pytest.raises(sv.SpecError) as e:
-        rig.step(list(range(B)), t0, [Kmax] * B, toks, dl, us, 1.0)
-    assert e.value.status == -2 and "352" in str(e.value)
-    torch.cuda.synchronize()
-    assert torch.equal(rig.kv_len, before)
-    # 32 sequences with K = 10 and 8 with K = 0: 360 rows, still too many; 31 and 9: 350 rows
-    look = [Kmax] * 32 + [0] * 8
-    with pytest.raises(sv.SpecError):
-        rig.step(list(range(B)), t0, look, toks, dl, us, 1.0)
-    torch.cuda.synchronize()
-    assert torch.equal(rig.kv_len, before)
-    look = [Kmax] * 31 + [0] * 9
-    err, chk, na, ot, logits, want = _check_step(rig, list(range(B)), t0, look, 1.0, 77)
-    assert logits.shape[0] == 350
-    assert err < 5e-3
+    look = [Kmax] * B
+    # the paged handle first, on the same inputs _check_step will build (it advances the oracle's caches)
+    r2 = wl.Rng(77, "cpu")
+    toks, dl = _drafts(r2, B, Kmax, shape.vocab, 1.0)
+    us = r2.uniform(52, (B, Kmax + 1))
+    err, chk, na, ot, logits, want = _check_step(rig, slots, t0, look, 1.0, 77)
+    assert logits.shape[0] == 440 and err < 5e-3
     assert chk.exact_accept + chk.margin_accept == B
+    r0 = 0
+    for b, k in enumerate(look):
+        dl[b, :k] = want[r0:r0 + k] + r2.normal(60 + b, (k, shape.vocab), 0.3)
+        r0 += k + 1
+    lp, nap, otp = paged.step(slots, t0, look, toks, dl, us, 1.0)
+    assert torch.equal(lp, logits) and torch.equal(nap, na) and torch.equal(otp, ot)
+    assert torch.equal(paged.kv_len, rig.kv_len)
+    # next step: ragged windows, 360 rows, sequences in another order
+    for b in range(B):
+        rig.n[b] = lens[b] + int(na[b]) + 1
+    order = list(reversed(slots))
+    look2 = [Kmax if i % 5 else 6 for i in range(B)]
+    assert sum(k + 1 for k in look2) == 408
+    nxt = [int(ot[s, int(na[s])]) for s in order]
+    err2, chk2, na2, ot2, logits2, _ = _check_step(rig, order, nxt, look2, 1.0, 78)
+    assert logits2.shape[0] == 408 and err2 < 5e-3
+    assert chk2.exact_accept + chk2.margin_accept == B
+    # one slot named twice, by a sequence of the first pass and one of the second
+    before = rig.kv_len.clone()
+    dup = list(slots)
+    dup[B - 1] = dup[0]
+    toks3, dl3 = _drafts(rng, B, Kmax, shape.vocab, 1.0)
+    us3 = rng.uniform(9, (B, Kmax + 1))
+    from paper_2411_00853_amd import binding as sv
+    lo = torch.zeros((440, shape.vocab), device="cuda")
+    na3 = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+    ot3 = torch.full((B, Kmax + 1), -9, dtype=torch.int32, device="cuda")
+    sv.spec_verify_step(rig.h, look, us3.cuda(), 1.0, na3, ot3,
+                        seq_slot=torch.tensor(dup, dtype=torch.int32, device="cuda"),
+                        last_token=torch.tensor(t0, dtype=torch.int32, device="cuda"), draft_tokens=toks3.cuda(),
+                        draft_logits=dl3.cuda(), logits_out=lo)
+    torch.cuda.synchronize()
+    with pytest.raises(sv.SpecError):
+        sv.spec_verify_poll(rig.h)
+    na3 = na3.cpu()
+    assert int(na3[B - 1]) == -1 and (na3[:B - 1] >= 0).all()
+    after = rig.kv_len.cpu()
+    assert int(after[B - 1]) == int(before[B - 1])                     # the slot the refused sequence did not get
+    assert int(after[0]) == int(before[0]) + int(na3[0]) + 1

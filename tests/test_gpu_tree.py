@@ -251,3 +251,63 @@ def test_greedy_tree_walk_at_temperature_zero():
         seen.add(a)
         r0 += n + 1
     assert len(seen) >= 3
+
+
+def test_tree_step_with_more_rows_than_one_decoder_pass():
+    """36 token trees of up to 10 nodes (390-odd window rows, more than one launch of the projections
+    takes): the step scores them in two passes; logits of every node against the oracle's path-by-path
+    decoding, every walk against the oracle's rule, and the compacted caches of all sequences."""
+    from test_gpu_forward import Rig
+    from helpers import TreeCheck
+    shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
+    B, Kmax, T = 36, 10, 1.0
+    rig = Rig(shape, B, 64, Kmax, seed=31, std=0.05)
+    rng = wl.Rng(32, "cpu")
+    lens = rng.randint(1, (B,), 36).tolist()
+    for s, n in enumerate(lens):
+        rig.prefill(s, rng.randint(40 + s, (n,), shape.vocab).tolist())
+    slots = list(range(B))
+    t0 = rng.randint(2, (B,), shape.vocab).tolist()
+    n_nodes = [Kmax] * B
+    n_nodes[3], n_nodes[20] = 0, 4
+    V = shape.vocab
+    parent = torch.full((B, Kmax), -1, dtype=torch.int32)
+    for b in range(B):
+        if n_nodes[b]:
+            parent[b, :n_nodes[b]] = torch.tensor(random_tree(rng, 100 + b, n_nodes[b]), dtype=torch.int32)
+    toks = rng.randint(60, (B, Kmax), V)
+    want = torch.cat([oracle.tree_logits(rig.om, rig.caches[s].clone(), rig.n[s], t0[b],
+                                         parent[b, :n_nodes[b]].tolist(), toks[b, :n_nodes[b]].tolist())
+                      for b, s in enumerate(slots)])
+    M = sum(n + 1 for n in n_nodes)
+    assert M > 352 and want.shape[0] == M
+    dl = torch.zeros((B, Kmax + 1, V))
+    r0 = 0
+    for b, n in enumerate(n_nodes):
+        dl[b, :n + 1] = want[r0:r0 + n + 1] + rng.normal(700 + b, (n + 1, V), 0.3)
+        r0 += n + 1
+    us = rng.uniform(80, (B, Kmax + 1))
+    logits, na, ot, pt = _tree_step(rig, slots, t0, n_nodes, parent, toks, dl, us, T)
+    err = (logits - want).abs().max().item()
+    assert err < 5e-3, f"tree logits max-abs error {err}"
+    chk = TreeCheck()
+    r0 = 0
+    for b, n in enumerate(n_nodes):
+        chk.compare(parent[b, :n].tolist(), toks[b, :n].tolist(), logits[r0:r0 + n + 1].contiguous(), dl[b, :n + 1],
+                    us[b, :n + 1].tolist(), T, int(na[b]), pt[b].tolist(), ot[b].tolist(), Kmax)
+        r0 += n + 1
+    assert chk.exact_walk >= B - 2
+    kl = rig.kv_len.cpu().tolist()
+    for b, s in enumerate(slots):
+        a = int(na[b])
+        assert kl[s] == lens[s] + a + 1
+        kept = [int(toks[b, i]) for i in pt[b, :a].tolist()]
+        ref = rig.caches[s]
+        rig.om.verify_sequential(ref, lens[s], [t0[b]] + kept)
+        got = torch.empty((shape.n_layers, 2, shape.n_kv_heads, a + 1, shape.head_dim), dtype=shape.torch_dtype,
+                          device="cuda")
+        rig.sv.spec_kv_export(rig.h, s, lens[s], got)
+        torch.cuda.synchronize()
+        diff = (got.cpu().float() - ref[:, :, :, lens[s]:lens[s] + a + 1].float()).abs().max().item()
+        assert diff <= 0.07, f"compacted cache of sequence {b} differs by {diff}"
+    assert int(na.max()) >= 1
