@@ -68,8 +68,7 @@ typedef struct {
                                        text is then the target's greedy text whatever the draft proposes) */
 } spec_round_args;
 
-/* Queue one round.  Launches only; reads nothing back.  bf16 targets: batch * (lookahead + 1) window
- * rows must fit one decoder pass (SPEC_MAX_STEP_ROWS), SPEC_ERR_SHAPE otherwise. */
+/* Queue one round.  Launches only; reads nothing back. */
 int spec_decode_round(spec_decoder* d, const spec_round_args* args, void* stream);
 
 typedef struct {

@@ -68,9 +68,8 @@ typedef struct spec_handle spec_handle;   /* opaque */
  * bf16 models: the projections take at most SPEC_MAX_STEP_ROWS rows per launch.  A step (linear or
  * tree) whose windows add up to more rows is scored in several passes of the decoder over groups of
  * consecutive sequences -- the weights are streamed once per pass, everything else (row bookkeeping,
- * sampling, rollback, results) is as for one pass.  spec_decode_round does not do this: there
- * batch * (lookahead + 1) must not exceed SPEC_MAX_STEP_ROWS (SPEC_ERR_SHAPE otherwise, before
- * anything is launched). */
+ * sampling, rollback, results) is as for one pass; the decoding round of spec_decode.h does the same
+ * for both of its models. */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
     int32_t max_batch;       /* sequences per step, and number of KV-cache slots */

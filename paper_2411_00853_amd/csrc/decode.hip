@@ -269,12 +269,6 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
     hipStream_t s = (hipStream_t)stream;
     spec_handle* tg = d->target;
     spec_handle* dr = d->draft;
-    if (B * (K + 1) > tg->row_cap)
-        return fail(SPEC_ERR_SHAPE, "spec_decode_round: %d sequences x %d window rows exceed the %d rows a step of the target takes",
-                    B, K + 1, tg->row_cap);
-    if (dr && 2 * B > dr->row_cap)
-        return fail(SPEC_ERR_SHAPE, "spec_decode_round: %d sequences x 2 rows exceed the %d rows a step of the draft takes", B,
-                    dr->row_cap);
     tg->tables.tree = 0;
     if (dr) dr->tables.tree = 0;
     int rc;
@@ -294,7 +288,7 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
             rc = launch_prepare(dr->tables, ks, B, d->Kd, V, dr->cfg.max_batch, dr->cfg.max_kv_len, true, d->seq_slot,
                                 i == 0 ? d->prev_tok : d->cur_tok, d->win, dr->kv_len, dr->flag, s);
             if (rc) return rc;
-            rc = forward_run(dr, dr->tables, ks, B, rows, dr->logits, s);
+            rc = forward_run_grouped(dr, ks, B, rows, dr->logits, s);
             if (rc) return rc;
             DrawEmit em{};
             em.tokens = d->draft_tokens;
@@ -322,7 +316,7 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
     rc = launch_prepare(tg->tables, ks, B, Kt, V, tg->cfg.max_batch, tg->cfg.max_kv_len, true, d->seq_slot, d->last_tok,
                         d->draft_tokens, tg->kv_len, tg->flag, s);
     if (rc) return rc;
-    rc = forward_run(tg, tg->tables, ks, B, M, tg->logits, s);
+    rc = forward_run_grouped(tg, ks, B, M, tg->logits, s);
     if (rc) return rc;
     if (greedy)
         rc = launch_greedy(tg->tables, tg->sampler, ks, B, Kt, V, M, tg->logits, d->draft_tokens, 1, tg->kv_len,

@@ -187,6 +187,22 @@ def test_rounds_with_a_lookahead_that_changes_every_round():
     assert chk.exact_accept >= 16
 
 
+@pytest.mark.parametrize("B,K", [(40, 10), (180, 1)])
+def test_rounds_with_more_rows_than_one_decoder_pass(B, K):
+    """Rounds whose verification window (40 x 11 = 440 rows), or whose first draft step and window
+    (180 x 2 = 360 rows each), exceed what one launch of the projections takes: the models score their
+    sequences in two passes and the oracle follows every row, draw, decision and length as usual."""
+    import random
+    r = random.Random(B)
+    contexts = [[r.randrange(1000) for _ in range(r.choice([2, 3, 5, 8]))] for _ in range(B)]
+    t_shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
+    d_shape = wl.ModelShape(1, 128, 2, 1, 64, 256, 1000)
+    pair, chk, tally, kept = run_following(t_shape, d_shape, contexts, K=K, Kt=K, rounds=2, T=0.9, seed=40 + K)
+    assert chk.exact_accept + chk.margin_accept == 2 * B
+    assert tally["draft_err"] < 5e-3 and tally["target_err"] < 5e-3
+    assert 0 < kept < 2 * B * K
+
+
 def test_free_running_text_equals_the_oracles_fp32():
     """Both sides run on their own from the same start; the generated text must be the same for as
     long as no decision of the oracle's run was closer to its threshold than the margins that the
