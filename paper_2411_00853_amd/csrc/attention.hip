@@ -60,8 +60,8 @@ __device__ __forceinline__ int seq_chunk_keys(int total, int max_chunks)
 // chunk results to part_o / part_ml for attn_merge_kernel (more chunks than a workgroup can hold).
 template <int HD, int RT, bool PAGED, bool FUSED, int CW>
 __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
-    attn_chunk_kernel(StepTables t, LookaheadPack ks, CacheGeom g, int n_q_heads, int layer, const uint4* cache,
-                      const float* __restrict__ q, int max_chunks, int r_cap, float scale_log2e,
+    attn_chunk_kernel(StepTables t, LookaheadPack ks, CacheGeom g, int n_q_heads, int kv_share, int layer,
+                      const uint4* cache, const float* __restrict__ q, int max_chunks, int r_cap, float scale_log2e,
                       float* __restrict__ part_o, float* __restrict__ part_ml, QkvSrc src, uint16_t* cache_w, XOut xo)
 {
     constexpr int STEPS = HD / 32;     // 32-dim steps of the score product
@@ -70,10 +70,14 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
     const int lane = threadIdx.x & 63, c16 = lane & 15, gq = lane >> 4;
     const int item = CW > 0 ? blockIdx.x * max_chunks + (threadIdx.x >> 6) : blockIdx.x;   // ((b, hkv), chunk)
     const int chunk = CW > 0 ? (int)(threadIdx.x >> 6) : item % max_chunks;
-    const int hkv = (CW > 0 ? blockIdx.x : item / max_chunks) % g.n_kv_heads;
-    const int b = (CW > 0 ? blockIdx.x : item / max_chunks) / g.n_kv_heads;
+    // kv_share > 1: the query heads of one kv head are dealt to kv_share work items ("hkv" counts those,
+    // "group" is the heads of one item), which all stream the keys and values of cache head hkc
+    const int n_items_kv = g.n_kv_heads * kv_share;
+    const int hkv = (CW > 0 ? blockIdx.x : item / max_chunks) % n_items_kv;
+    const int b = (CW > 0 ? blockIdx.x : item / max_chunks) / n_items_kv;
+    const int hkc = hkv / kv_share;
     const int K = ks.k[b];
-    const int group = n_q_heads / g.n_kv_heads;
+    const int group = n_q_heads / n_items_kv;
     const int rows = (K + 1) * group;
     const int row0 = t.seq_row0[b];
     if (!t.seq_ok[b]) {
@@ -112,11 +116,11 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
     const uint4* head;
     int my_page = 0;
     if constexpr (PAGED) {
-        head = cache + ((size_t)layer * g.n_kv_heads + hkv) * (64 * HD) / 8;   // offset inside a page
+        head = cache + ((size_t)layer * g.n_kv_heads + hkc) * (64 * HD) / 8;   // offset inside a page
         const int p = g.table[(size_t)t.seq_slot[b] * g.blocks_per_slot + min(blk0 + lane, blk1 - 1)];
         my_page = p < 0 ? 0 : p;
     } else {
-        head = cache + cache_head_base(g, layer, t.seq_slot[b], hkv) / 8;
+        head = cache + cache_head_base(g, layer, t.seq_slot[b], hkc) / 8;
     }
 
     uint4 ka[2][STEPS], va[DT], kb[2][STEPS], vb[DT];
@@ -338,7 +342,7 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
             constexpr int HALF = HD / 2, LP = HD / 8, PPR = 64 / LP, NR = 8 / PPR;
             const int u = lane / LP, tq = lane % LP;
             const int slot = t.seq_slot[b];
-            const int kcol = n_q_heads * HD + hkv * HD, vcol = (n_q_heads + g.n_kv_heads) * HD + hkv * HD;
+            const int kcol = n_q_heads * HD + hkc * HD, vcol = (n_q_heads + g.n_kv_heads) * HD + hkc * HD;
             for (int p0 = w0; p0 < w1; p0 += 8) {
                 float kr[NR][8], vr[NR][8];
                 int posr[NR];
@@ -371,7 +375,7 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
 #pragma unroll
                 for (int h = 0; h < NR; ++h) {
                     if (p0 + PPR * h + u < w1) {
-                        const size_t blk = cache_block_base(g, layer, slot, hkv, posr[h] >> 5);
+                        const size_t blk = cache_block_base(g, layer, slot, hkc, posr[h] >> 5);
                         const int t32 = posr[h] & 31;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
@@ -641,14 +645,29 @@ AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count,
     return p;
 }
 
+// A wavefront holds at most 64 query rows (four row tiles) of one kv head: (query heads per kv head) x
+// (window length).  When a step's longest window gives more, the query heads of a kv head are dealt to
+// kv_share work items of group / kv_share heads each -- to the kernel they look like kv heads of their
+// own that happen to read the same cache head, which is then streamed kv_share times.  The smallest
+// divisor of the group that brings the rows down to 64 (a window has at most 16 rows, so one exists).
+static int attn_kv_share(int group, int window)
+{
+    for (int s = 1; s < group; ++s)
+        if (group % s == 0 && (group / s) * window <= 64) return s;
+    return group;
+}
+
 size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
                            int cu_count, bool paged)
 {
     size_t worst = 0;
-    for (int b = 1; b <= max_batch; ++b) {
-        const AttnPlan p = plan_attention(max_kv_len, b, n_kv_heads, cu_count, paged);
-        const size_t e = (size_t)b * n_kv_heads * p.max_chunks * group * max_window * hd;
-        if (e > worst) worst = e;
+    for (int share = 1; share <= group; ++share) {
+        if (group % share) continue;
+        for (int b = 1; b <= max_batch; ++b) {
+            const AttnPlan p = plan_attention(max_kv_len, b, n_kv_heads * share, cu_count, paged);
+            const size_t e = (size_t)b * n_kv_heads * p.max_chunks * group * max_window * hd;
+            if (e > worst) worst = e;
+        }
     }
     return worst;
 }
@@ -678,13 +697,13 @@ static int merge_width(int hd, int rt, int max_chunks, int n_pairs, int cu_count
 
 template <int HD>
 static int launch_chunks(int rt, int cw, dim3 grid, dim3 wg_grid, hipStream_t s, const StepTables& t, const LookaheadPack& ks,
-                         const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
+                         const CacheGeom& g, int n_q_heads, int kv_share, int layer, const void* cache, const float* q,
                          const AttnPlan& p, int r_cap, float sl2, float* part_o, float* part_ml, const QkvSrc& src,
                          void* cache_w, const XOut& xo)
 {
 #define SPECV_ATTN_CW(RT, PG, FU, CW_)                                                                         \
     hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, PG, FU, CW_>), CW_ > 0 ? wg_grid : grid, dim3(CW_ > 0 ? 64 * CW_ : 64), \
-                       0, s, t, ks, g, n_q_heads, layer, (const uint4*)cache, q, p.max_chunks, r_cap, sl2, part_o,   \
+                       0, s, t, ks, g, n_q_heads, kv_share, layer, (const uint4*)cache, q, p.max_chunks, r_cap, sl2, part_o, \
                        part_ml, src, (uint16_t*)cache_w, xo)
 #define SPECV_ATTN_GO(RT, PG, FU)                                                                              \
     do {                                                                                                         \
@@ -725,12 +744,13 @@ bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack&
     if (g.dtype != SPEC_DTYPE_BF16) return false;
     int kmax = 0;
     for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
-    const int rt = ((kmax + 1) * (n_q_heads / g.n_kv_heads) + 15) / 16;
+    const int group = n_q_heads / g.n_kv_heads, share = attn_kv_share(group, kmax + 1);
+    const int rt = ((kmax + 1) * (group / share) + 15) / 16;
     if (!fused_fits(g.head_dim, rt)) return false;
     // Every wavefront of a (sequence, kv head) puts the queries together again: with short chunks
     // (few sequences, many chunks each) that costs more than the separate kernel it replaces
     // (measured: batch 1 at 1B-shape, 128-position chunks, 2 % slower; 256-position chunks faster).
-    const AttnPlan p = plan_attention(max_kv_len, B, g.n_kv_heads, cu_count, g.table != nullptr);
+    const AttnPlan p = plan_attention(max_kv_len, B, g.n_kv_heads * share, cu_count, g.table != nullptr);
     return p.chunk_keys >= 192;
 }
 
@@ -754,37 +774,39 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
         return SPEC_OK;
     }
     (void)p_unused;
-    const AttnPlan p = plan_attention(max_kv_len, B, g.n_kv_heads, cu_count, g.table != nullptr);
+    int kmax = 0;
+    for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
+    const int share = attn_kv_share(n_q_heads / g.n_kv_heads, kmax + 1);
+    const int n_items_kv = g.n_kv_heads * share;          // (sequence, kv head) work items per sequence
+    const AttnPlan p = plan_attention(max_kv_len, B, n_items_kv, cu_count, g.table != nullptr);
     if (g.table && p.chunk_keys > 2048)
         return fail(SPEC_ERR_SHAPE, "paged attention handles chunks of up to 2048 positions (max_kv_len up to 32768)");
-    const int group = n_q_heads / g.n_kv_heads;
+    const int group = n_q_heads / n_items_kv;             // query heads of one work item
     const int r_cap = group * max_window;
-    const size_t part_need = (size_t)B * g.n_kv_heads * p.max_chunks * r_cap * hd;
+    const size_t part_need = (size_t)B * n_items_kv * p.max_chunks * r_cap * hd;
     if (part_need > part_cap)
         return fail(SPEC_ERR_SHAPE, "this step's attention plan (%d chunks per sequence and kv head) needs %zu floats of "
                     "chunk results, the handle holds %zu: set the attention tuning knobs before spec_verify_init",
                     p.max_chunks, part_need, part_cap);
-    int kmax = 0;
-    for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
     const int rt = ((kmax + 1) * group + 15) / 16;
-    const dim3 grid((unsigned)B * g.n_kv_heads * p.max_chunks), wg_grid((unsigned)B * g.n_kv_heads);
+    const dim3 grid((unsigned)B * n_items_kv * p.max_chunks), wg_grid((unsigned)B * n_items_kv);
     const float sl2 = scale * 1.4426950408889634f;
     if (hd != 64 && hd != 128) return fail(SPEC_ERR_SHAPE, "bf16 attention needs head_dim 64 or 128");
-    const int cw = rt >= 1 && rt <= 4 ? merge_width(hd, rt, p.max_chunks, B * g.n_kv_heads, cu_count) : 0;
+    const int cw = rt >= 1 && rt <= 4 ? merge_width(hd, rt, p.max_chunks, B * n_items_kv, cu_count) : 0;
     int rc;
     {
         ProfScope ps(prof, SPEC_PROF_ATTENTION, s);
         if (hd == 128)
-            rc = launch_chunks<128>(rt, cw, grid, wg_grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o,
+            rc = launch_chunks<128>(rt, cw, grid, wg_grid, s, t, ks, g, n_q_heads, share, layer, cache, q, p, r_cap, sl2, part_o,
                                     part_ml, src, cache_w, xo);
         else
-            rc = launch_chunks<64>(rt, cw, grid, wg_grid, s, t, ks, g, n_q_heads, layer, cache, q, p, r_cap, sl2, part_o,
+            rc = launch_chunks<64>(rt, cw, grid, wg_grid, s, t, ks, g, n_q_heads, share, layer, cache, q, p, r_cap, sl2, part_o,
                                    part_ml, src, cache_w, xo);
     }
     if (rc) return rc;
     if (cw > 0) return SPEC_OK;   // the workgroups merged their chunks themselves
     ProfScope ps(prof, SPEC_PROF_ATTN_MERGE, s);
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(M, (n_q_heads * hd / 8 + 63) / 64), dim3(64), 0, s, t, ks, g.n_kv_heads,
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(M, (n_q_heads * hd / 8 + 63) / 64), dim3(64), 0, s, t, ks, n_items_kv,
                        n_q_heads, hd, p.max_chunks, r_cap, part_o, part_ml, xo);
     SPECV_LAUNCH_CHECK("attn_merge_kernel");
     return SPEC_OK;

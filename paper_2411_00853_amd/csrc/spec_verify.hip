@@ -101,8 +101,6 @@ static int check_cfg(const spec_model_cfg* c, bool has_model)
         if (c->head_dim != 64 && c->head_dim != 128) return fail(SPEC_ERR_SHAPE, "bf16 needs head_dim 64 or 128");
         if (c->d_model % 32 || (c->n_q_heads * c->head_dim) % 32 || c->d_ffn % 32)
             return fail(SPEC_ERR_SHAPE, "bf16 needs d_model, n_q_heads*head_dim and d_ffn multiples of 32");
-        if ((c->n_q_heads / c->n_kv_heads) * (c->max_lookahead + 1) > 64)
-            return fail(SPEC_ERR_SHAPE, "query heads per kv head times window length must not exceed 64");
     } else {
         if (c->head_dim > 256) return fail(SPEC_ERR_SHAPE, "fp32 needs head_dim <= 256");
     }

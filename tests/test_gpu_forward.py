@@ -238,8 +238,6 @@ def _random_case(seed):
     vocab = r.choice([257, 1000, 4099])
     dtype = r.choice(["bf16", "bf16", "fp32"])
     kmax = r.choice([1, 3, 6, 9, 15])
-    if (kmax + 1) * group > 64:          # the attention kernels take at most 64 query rows per kv head
-        kmax = 64 // group - 1
     shape = wl.ModelShape(r.choice([1, 2]), d, n_q, n_kv, hd, ffn, vocab, dtype=dtype)
     n_slots = r.choice([1, 2, 3, 5])
     cap = r.choice([96, 300, 1500])
@@ -490,3 +488,42 @@ def test_steps_with_more_rows_than_one_decoder_pass():
     after = rig.kv_len.cpu()
     assert int(after[B - 1]) == int(before[B - 1])                     # the slot the refused sequence did not get
     assert int(after[0]) == int(before[0]) + int(na3[0]) + 1
+
+
+@pytest.mark.parametrize("n_kv,group,hd,Kmax", [(2, 8, 64, 15), (1, 8, 128, 15), (2, 6, 64, 11), (1, 16, 64, 15),
+                                                 (2, 8, 128, 9)])
+def test_more_than_64_query_rows_per_kv_head(n_kv, group, hd, Kmax):
+    """(query heads per kv head) x (window length) beyond the 64 rows a wavefront holds: the heads of a
+    kv head are dealt to two or four work items that stream the same cache head.  Every row against
+    the oracle, on a contiguous cache and on a page pool (bit-identical), short and long windows in
+    one step, then a second step from the state the first left."""
+    shape = wl.ModelShape(2, 256, n_kv * group, n_kv, hd, 512, 1000)
+    B = 5
+    rig = Rig(shape, B, 400, Kmax, seed=21, std=0.05)
+    rng = wl.Rng(22, "cpu")
+    lens = [0, 31, 150, 333, 64]
+    for s, n in enumerate(lens):
+        rig.prefill(s, rng.randint(300 + s, (n,), shape.vocab).tolist())
+    paged = PagedRig(rig, B, 400, Kmax, n_pages=40)
+    for s in range(B):
+        paged.load(rig, s)
+    slots = [3, 0, 4, 1, 2]
+    t0 = rng.randint(3, (B,), shape.vocab).tolist()
+    look = [Kmax, 2, Kmax, 0, Kmax - 1]
+    r2 = wl.Rng(91, "cpu")
+    toks, dl = _drafts(r2, B, Kmax, shape.vocab, 1.0)
+    us = r2.uniform(52, (B, Kmax + 1))
+    err, chk, na, ot, logits, want = _check_step(rig, slots, t0, look, 1.0, 91)
+    assert err < 5e-3
+    assert chk.exact_accept + chk.margin_accept == B
+    r0 = 0
+    for b, k in enumerate(look):
+        dl[b, :k] = want[r0:r0 + k] + r2.normal(60 + b, (k, shape.vocab), 0.3)
+        r0 += k + 1
+    lp, nap, otp = paged.step(slots, t0, look, toks, dl, us, 1.0)
+    assert torch.equal(lp, logits) and torch.equal(nap, na) and torch.equal(otp, ot)
+    for b, s in enumerate(slots):
+        rig.n[s] += int(na[b]) + 1
+    nxt = [int(ot[b, int(na[b])]) for b in range(B)]
+    err2, chk2, *_ = _check_step(rig, slots, nxt, [Kmax] * B, 1.0, 92)
+    assert err2 < 5e-3

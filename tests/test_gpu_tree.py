@@ -253,13 +253,16 @@ def test_greedy_tree_walk_at_temperature_zero():
     assert len(seen) >= 3
 
 
-def test_tree_step_with_more_rows_than_one_decoder_pass():
+@pytest.mark.parametrize("n_q", [8, 16])
+def test_tree_step_with_more_rows_than_one_decoder_pass(n_q):
     """36 token trees of up to 10 nodes (390-odd window rows, more than one launch of the projections
     takes): the step scores them in two passes; logits of every node against the oracle's path-by-path
-    decoding, every walk against the oracle's rule, and the compacted caches of all sequences."""
+    decoding, every walk against the oracle's rule, and the compacted caches of all sequences.  With 16
+    query heads on 2 kv heads a tree also has 88 query rows per kv head, more than a wavefront of the
+    attention kernel holds: the heads of a kv head are then dealt to two work items."""
     from test_gpu_forward import Rig
     from helpers import TreeCheck
-    shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
+    shape = wl.ModelShape(2, 256, n_q, 2, 64, 512, 1000)
     B, Kmax, T = 36, 10, 1.0
     rig = Rig(shape, B, 64, Kmax, seed=31, std=0.05)
     rng = wl.Rng(32, "cpu")
