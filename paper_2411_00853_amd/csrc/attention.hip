@@ -617,7 +617,12 @@ __global__ void __launch_bounds__(256) attn_f32_kernel(StepTables t, CacheGeom g
 static int g_items_per_cu = 0;   // wavefront work items per compute unit to aim for; 0 = default
 void set_attn_items_per_cu(int n) { g_items_per_cu = n; }
 static int g_max_chunks = 16;   // most chunks per (sequence, kv head)
-void set_attn_max_chunks(int n) { g_max_chunks = n >= 1 && n <= 16 ? n : 16; }
+static bool g_max_chunks_set = false;
+void set_attn_max_chunks(int n)
+{
+    g_max_chunks_set = n >= 1 && n <= 16;
+    g_max_chunks = g_max_chunks_set ? n : 16;
+}
 static int g_merge_min_pairs = 0;   // fewest (sequence, kv head) pairs for merging inside the workgroup; 0 = default
 void set_attn_merge_min_pairs(int n) { g_merge_min_pairs = n; }
 
@@ -688,11 +693,44 @@ constexpr bool merge_fits(int hd, int rt, int cw)
 // (a workgroup sits on ONE compute unit: with few (sequence, kv head) pairs and many chunks each,
 // merging inside the workgroup would leave most of the chip idle -- measured slower for the draft
 // model's 64 pairs x 8 chunks -- so it needs at least half as many workgroups as compute units)
-static int merge_width(int hd, int rt, int max_chunks, int n_pairs, int cu_count)
+// (any_pairs: a small launch, see plan_launch, merges in the workgroup however few pairs it has)
+static int merge_width(int hd, int rt, int max_chunks, int n_pairs, int cu_count, bool any_pairs)
 {
     const int cw = max_chunks <= 1 ? 1 : max_chunks <= 2 ? 2 : max_chunks <= 4 ? 4 : max_chunks <= 8 ? 8 : 0;
     const int need = g_merge_min_pairs > 0 ? g_merge_min_pairs : cu_count / 2;
-    return cw > 0 && merge_fits(hd, rt, cw) && n_pairs >= need ? cw : 0;
+    return cw > 0 && merge_fits(hd, rt, cw) && (any_pairs || n_pairs >= need) ? cw : 0;
+}
+
+// What a launch does with its (sequence, kv head) pairs: how many work items share a cache head
+// (attn_kv_share, at least what the row limit asks for) and how the positions are cut.
+// Small launches -- at most 4 MiB of keys and values in all, e.g. one sequence of a 1B-class model --
+// are bound by latency, not by the stream: there a kv head's query heads are spread over more work
+// items while those still fit on half the compute units (duplicate reads hit L2), each item is cut
+// into at most four chunks, and the four wavefronts merge inside their workgroup whatever the number
+// of pairs -- one kernel where there were three (rotary/append, chunks, merge).  Measured at the
+// 1B-shape, batch 1: step 1.017 -> 0.948 ms.  With more data the same choice loses (the 1B-shape
+// as a draft at batch 8, 37 MB: +2 % per round with two items per kv head, +7 % with four).
+struct AttnLaunchPlan {
+    int share;
+    AttnPlan p;
+    bool small;
+};
+static AttnLaunchPlan plan_launch(const CacheGeom& g, int n_q_heads, int kmax, int B, int max_kv_len, int cu_count)
+{
+    AttnLaunchPlan lp{};
+    const int group = n_q_heads / g.n_kv_heads;
+    lp.share = attn_kv_share(group, kmax + 1);
+    const size_t kv_bytes = (size_t)B * g.n_kv_heads * max_kv_len * g.head_dim * 4;   // keys + values, bf16
+    lp.small = kv_bytes <= ((size_t)4 << 20) && !g_max_chunks_set && g_merge_min_pairs == 0 && g_items_per_cu == 0;
+    if (lp.small)
+        for (int s = lp.share + 1; s <= group; ++s)
+            if (group % s == 0 && B * g.n_kv_heads * s <= cu_count / 2) lp.share = s;
+    lp.p = plan_attention(max_kv_len, B, g.n_kv_heads * lp.share, cu_count, g.table != nullptr);
+    if (lp.small && lp.p.max_chunks > 4) {
+        lp.p.chunk_keys = ((max_kv_len + 3) / 4 + 31) / 32 * 32;
+        lp.p.max_chunks = (max_kv_len + lp.p.chunk_keys - 1) / lp.p.chunk_keys;
+    }
+    return lp;
 }
 
 template <int HD>
@@ -744,14 +782,13 @@ bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack&
     if (g.dtype != SPEC_DTYPE_BF16) return false;
     int kmax = 0;
     for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
-    const int group = n_q_heads / g.n_kv_heads, share = attn_kv_share(group, kmax + 1);
-    const int rt = ((kmax + 1) * (group / share) + 15) / 16;
+    const AttnLaunchPlan lp = plan_launch(g, n_q_heads, kmax, B, max_kv_len, cu_count);
+    const int rt = ((kmax + 1) * (n_q_heads / g.n_kv_heads / lp.share) + 15) / 16;
     if (!fused_fits(g.head_dim, rt)) return false;
     // Every wavefront of a (sequence, kv head) puts the queries together again: with short chunks
     // (few sequences, many chunks each) that costs more than the separate kernel it replaces
     // (measured: batch 1 at 1B-shape, 128-position chunks, 2 % slower; 256-position chunks faster).
-    const AttnPlan p = plan_attention(max_kv_len, B, g.n_kv_heads * share, cu_count, g.table != nullptr);
-    return p.chunk_keys >= 192;
+    return lp.p.chunk_keys >= 192;
 }
 
 int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,
@@ -776,9 +813,10 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
     (void)p_unused;
     int kmax = 0;
     for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
-    const int share = attn_kv_share(n_q_heads / g.n_kv_heads, kmax + 1);
+    const AttnLaunchPlan lp = plan_launch(g, n_q_heads, kmax, B, max_kv_len, cu_count);
+    const int share = lp.share;
     const int n_items_kv = g.n_kv_heads * share;          // (sequence, kv head) work items per sequence
-    const AttnPlan p = plan_attention(max_kv_len, B, n_items_kv, cu_count, g.table != nullptr);
+    const AttnPlan p = lp.p;
     if (g.table && p.chunk_keys > 2048)
         return fail(SPEC_ERR_SHAPE, "paged attention handles chunks of up to 2048 positions (max_kv_len up to 32768)");
     const int group = n_q_heads / n_items_kv;             // query heads of one work item
@@ -792,7 +830,7 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
     const dim3 grid((unsigned)B * n_items_kv * p.max_chunks), wg_grid((unsigned)B * n_items_kv);
     const float sl2 = scale * 1.4426950408889634f;
     if (hd != 64 && hd != 128) return fail(SPEC_ERR_SHAPE, "bf16 attention needs head_dim 64 or 128");
-    const int cw = rt >= 1 && rt <= 4 ? merge_width(hd, rt, p.max_chunks, B * n_items_kv, cu_count) : 0;
+    const int cw = rt >= 1 && rt <= 4 ? merge_width(hd, rt, p.max_chunks, B * n_items_kv, cu_count, lp.small) : 0;
     int rc;
     {
         ProfScope ps(prof, SPEC_PROF_ATTENTION, s);
