@@ -124,11 +124,13 @@ struct DrawEmit {
 };
 
 // uniforms: sequence b reads uniforms[b * u_stride + i] (i < K_b: proposal i; i = K_b: the final draw)
+// prepare_flag != NULL: no launch_prepare ran for this step (no decoder pass, no cache); the statistics pass
+// fills t itself, reporting bad tokens through that flag
 int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const LookaheadPack& ks, int B, int Kmax,
                    int V, int n_stat_rows, const float* target_logits, const float* draft_logits,
                    const int32_t* draft_tokens, const float* uniforms, int u_stride, float temperature,
                    int auto_rollback, int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens,
-                   const DrawEmit* emit, Profiler* prof, hipStream_t s);
+                   const DrawEmit* emit, Profiler* prof, hipStream_t s, int32_t* prepare_flag = nullptr);
 
 // Token-tree variants: parent/tokens [B][Kmax], draft logits [B][Kmax+1][V] (row 0: the root)
 int launch_prepare_tree(const StepTables& t, const LookaheadPack& ks, int B, int Kmax, int V, int max_batch,

@@ -40,14 +40,14 @@ __device__ __forceinline__ double wave_sum(double v)
 // ---------------------------------------------------------------------------------------------
 // Row bookkeeping.  One workgroup; thread b owns sequence b.
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(TPB) prepare_kernel(StepTables t, LookaheadPack ks, int B, int Kmax, int V,
-                                                      int max_batch, int max_kv_len, int has_cache,
-                                                      const int32_t* __restrict__ seq_slot,
-                                                      const int32_t* __restrict__ last_token,
-                                                      const int32_t* __restrict__ draft_tokens,
-                                                      const int32_t* __restrict__ kv_len, int32_t* flag)
+// (a workgroup of TPB threads, all of them calling; row0: SPEC_MAX_BATCH + 1 ints of LDS)
+__device__ __forceinline__ void prepare_rows(const StepTables& t, const LookaheadPack& ks, int B, int Kmax, int V,
+                                             int max_batch, int max_kv_len, int has_cache,
+                                             const int32_t* __restrict__ seq_slot,
+                                             const int32_t* __restrict__ last_token,
+                                             const int32_t* __restrict__ draft_tokens,
+                                             const int32_t* __restrict__ kv_len, int32_t* flag, int* row0)
 {
-    __shared__ int row0[SPEC_MAX_BATCH + 1];
     const int b = threadIdx.x;
     if (b == 0) {
         int r = 0, st = 0;
@@ -103,6 +103,18 @@ __global__ void __launch_bounds__(TPB) prepare_kernel(StepTables t, LookaheadPac
     }
 }
 
+__global__ void __launch_bounds__(TPB) prepare_kernel(StepTables t, LookaheadPack ks, int B, int Kmax, int V,
+                                                      int max_batch, int max_kv_len, int has_cache,
+                                                      const int32_t* __restrict__ seq_slot,
+                                                      const int32_t* __restrict__ last_token,
+                                                      const int32_t* __restrict__ draft_tokens,
+                                                      const int32_t* __restrict__ kv_len, int32_t* flag)
+{
+    __shared__ int row0[SPEC_MAX_BATCH + 1];
+    prepare_rows(t, ks, B, Kmax, V, max_batch, max_kv_len, has_cache, seq_slot, last_token, draft_tokens, kv_len, flag,
+                 row0);
+}
+
 // A step with more window rows than one decoder pass takes is scored group by group: the row
 // bookkeeping above runs once for the whole step (so that what it decides -- skipped sequences, a slot
 // named twice, pages taken -- is decided once), and each pass gets the entries of its own sequences
@@ -135,12 +147,66 @@ __global__ void __launch_bounds__(TPB) slice_tables_kernel(StepTables full, Step
 // ---------------------------------------------------------------------------------------------
 // draft_rows: draft logits rows per sequence in memory (Kmax for a chain of proposals; Kmax+1 for
 // a tree, whose root has a row of its own)
-__device__ __forceinline__ const float* stat_row_ptr(const StepTables& t, const LookaheadPack& ks, int b, int local,
-                                                     int draft_rows, int V, const float* target, const float* draft)
+// Which rows the pass walks.  STAT_CHAIN / STAT_TREE: sequence b has K_b + 1 target rows and K_b
+// (chain) or K_b + 1 (tree) draft rows, found from the lookaheads in the kernel arguments alone, so
+// the pass does not depend on the row tables.  STAT_PLAIN: one row per sequence, its logits row taken
+// from seq_row0 (a proposing model's draw, whose row is not the one the lookaheads would give).
+enum { STAT_CHAIN = 0, STAT_TREE = 1, STAT_PLAIN = 2 };
+
+// The row bookkeeping of a step that runs no decoder pass (logits supplied by the caller), done by the
+// statistics pass's first workgroup next to its own chunk instead of by a kernel of its own: the pass
+// itself does not read the tables, the kernels after it do.
+struct PrepIn {
+    int on, Kmax;
+    const int32_t* draft_tokens;
+    int32_t* flag;
+};
+
+// The sequence b that statistics row srow belongs to, the row's number inside the sequence (local), the
+// sequence's first target row (r0) and its lookahead (K), from the lookaheads in the kernel arguments.
+// Every wavefront finds it for itself: lane i takes sequences i, i + 64, ... (all loads issued together,
+// one memory round trip; walking the sequences one after the other costs one round trip each),
+// prefix sums across the lanes place each sequence's rows, and the lane whose range holds srow answers.
+__device__ __forceinline__ void find_stat_row(const LookaheadPack& ks, int B, int srow, bool tree, int* b_out,
+                                              int* local_out, int* r0_out, int* K_out)
 {
-    const int K = ks.k[b];
-    if (local <= K) return target + (size_t)(t.seq_row0[b] + local) * V;
-    return draft + ((size_t)b * draft_rows + (local - K - 1)) * V;
+    constexpr int ROUNDS = SPEC_MAX_BATCH / 64;
+    const int lane = threadIdx.x & 63;
+    int kk[ROUNDS];
+#pragma unroll
+    for (int g = 0; g < ROUNDS; ++g) kk[g] = ks.k[min(g * 64 + lane, SPEC_MAX_BATCH - 1)];
+    int base_st = 0, base_r = 0, b = 0, st = 0, r0 = 0, K = 0;
+#pragma unroll
+    for (int g = 0; g < ROUNDS; ++g) {
+        const int i = g * 64 + lane;
+        const int k = kk[g];
+        const int n = i < B ? 2 * k + 1 + (tree ? 1 : 0) : 0, r = i < B ? k + 1 : 0;
+        int ps = n, pr = r;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int a = __shfl_up(ps, off), c = __shfl_up(pr, off);
+            if (lane >= off) {
+                ps += a;
+                pr += c;
+            }
+        }
+        const int st_excl = base_st + ps - n;
+        const bool hit = n > 0 && st_excl <= srow && srow < st_excl + n;
+        const unsigned long long m = __ballot(hit);
+        if (m) {
+            const int src = __ffsll((long long)m) - 1;
+            b = g * 64 + src;
+            st = __shfl(st_excl, src);
+            r0 = __shfl(base_r + pr - r, src);
+            K = __shfl(k, src);
+        }
+        base_st += __shfl(ps, 63);
+        base_r += __shfl(pr, 63);
+    }
+    *b_out = b;
+    *local_out = srow - st;
+    *r0_out = r0;
+    *K_out = K;
 }
 
 template <bool VEC4>
@@ -148,16 +214,25 @@ __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack 
                                                     int n_chunks, const float* __restrict__ target,
                                                     const float* __restrict__ draft, float inv_T,
                                                     float* __restrict__ part_max, double* __restrict__ part_sum,
-                                                    float* __restrict__ copy_out, size_t copy_stride)
+                                                    float* __restrict__ copy_out, size_t copy_stride, int layout,
+                                                    PrepIn prep)
 {
     __shared__ float smax[TPB / 64];
     __shared__ double ssum[TPB / 64];
+    __shared__ int prep_row0[SPEC_MAX_BATCH + 1];
+    if (prep.on && blockIdx.x == 0)
+        prepare_rows(t, ks, B, prep.Kmax, V, SPEC_MAX_BATCH, 0, 0, nullptr, nullptr, prep.draft_tokens, nullptr, prep.flag,
+                     prep_row0);
     const int srow = blockIdx.x / n_chunks;
     const int chunk = blockIdx.x % n_chunks;
-    // find the sequence of this statistics row (B <= 256: a short scan of the prefix array)
-    int b = 0;
-    while (b + 1 < B && t.seq_stat0[b + 1] <= srow) ++b;
-    const float* row = stat_row_ptr(t, ks, b, srow - t.seq_stat0[b], draft_rows, V, target, draft);
+    const float* row;
+    if (layout == STAT_PLAIN) {
+        row = target + (size_t)t.seq_row0[srow] * V;
+    } else {
+        int b, local, r0, K;
+        find_stat_row(ks, B, srow, layout == STAT_TREE, &b, &local, &r0, &K);
+        row = local <= K ? target + (size_t)(r0 + local) * V : draft + ((size_t)b * draft_rows + (local - K - 1)) * V;
+    }
     const int base = chunk * STAT_CHUNK;
     const int lim = min(STAT_CHUNK, V - base);
 
@@ -1135,10 +1210,12 @@ int launch_tree_sampler(const StepTables& t, const SamplerWorkspace& w, const Lo
         ProfScope ps(prof, SPEC_PROF_SAMPLER_STATS, s);
         if (vec4)
             hipLaunchKernelGGL(stats_kernel<true>, g1, dim3(TPB), 0, s, t, ks, B, Kmax + 1, V, n_stat_chunks,
-                               target_logits, draft_logits, inv_T, w.part_max, w.part_sum, (float*)nullptr, (size_t)0);
+                               target_logits, draft_logits, inv_T, w.part_max, w.part_sum, (float*)nullptr, (size_t)0,
+                               (int)STAT_TREE, PrepIn{});
         else
             hipLaunchKernelGGL(stats_kernel<false>, g1, dim3(TPB), 0, s, t, ks, B, Kmax + 1, V, n_stat_chunks,
-                               target_logits, draft_logits, inv_T, w.part_max, w.part_sum, (float*)nullptr, (size_t)0);
+                               target_logits, draft_logits, inv_T, w.part_max, w.part_sum, (float*)nullptr, (size_t)0,
+                               (int)STAT_TREE, PrepIn{});
         SPECV_LAUNCH_CHECK("stats_kernel");
     }
     ProfScope ps(prof, SPEC_PROF_SAMPLER_DRAW, s);
@@ -1184,11 +1261,19 @@ int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const Lookahe
                    int V, int n_stat_rows, const float* target_logits, const float* draft_logits,
                    const int32_t* draft_tokens, const float* uniforms, int u_stride, float temperature,
                    int auto_rollback, int32_t* kv_len, int32_t* n_accepted, int32_t* out_tokens,
-                   const DrawEmit* emit, Profiler* prof, hipStream_t s)
+                   const DrawEmit* emit, Profiler* prof, hipStream_t s, int32_t* prepare_flag)
 {
     const int n_stat_chunks = (V + STAT_CHUNK - 1) / STAT_CHUNK;
     const int n_res_chunks = (V + RES_CHUNK - 1) / RES_CHUNK;
     const float inv_T = 1.0f / temperature;
+    PrepIn prep{};
+    if (prepare_flag) {   // no decoder pass ran: the statistics pass fills the row tables itself
+        prep.on = 1;
+        prep.Kmax = Kmax;
+        prep.draft_tokens = draft_tokens;
+        prep.flag = prepare_flag;
+    }
+    const int layout = emit ? (int)STAT_PLAIN : (int)STAT_CHAIN;
     DrawEmit em{};
     if (emit) {
         if (n_stat_rows != B) return fail(SPEC_ERR_INVALID_ARG, "a plain draw needs every lookahead to be 0");
@@ -1202,10 +1287,12 @@ int launch_sampler(const StepTables& t, const SamplerWorkspace& w, const Lookahe
     ProfScope ps(prof, SPEC_PROF_SAMPLER_STATS, s);
     if (vec4)
         hipLaunchKernelGGL(stats_kernel<true>, g1, dim3(TPB), 0, s, t, ks, B, Kmax, V, n_stat_chunks,
-                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum, em.logits_copy, em.copy_stride);
+                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum, em.logits_copy, em.copy_stride,
+                           layout, prep);
     else
         hipLaunchKernelGGL(stats_kernel<false>, g1, dim3(TPB), 0, s, t, ks, B, Kmax, V, n_stat_chunks,
-                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum, em.logits_copy, em.copy_stride);
+                           target_logits, draft_logits, inv_T, w.part_max, w.part_sum, em.logits_copy, em.copy_stride,
+                           layout, prep);
     SPECV_LAUNCH_CHECK("stats_kernel");
     }
     ProfScope ps(prof, SPEC_PROF_SAMPLER_DRAW, s);
@@ -1346,9 +1433,11 @@ extern "C" int spec_sample_step_noalloc(int32_t vocab, int32_t max_lookahead, co
     sw.row_inv_z = w->row_inv_z;
     sw.row_max = w->row_max;
     sw.part_idx = w->part_idx;
-    rc = launch_prepare(t, ks, B, Kmax, vocab, NA_MAX_BATCH, 0, false, nullptr, nullptr, args->draft_tokens, nullptr,
-                        w->flag, s);
-    if (rc) return rc;
+    if (greedy) {   // the greedy rule's kernels read the tables from the start
+        rc = launch_prepare(t, ks, B, Kmax, vocab, NA_MAX_BATCH, 0, false, nullptr, nullptr, args->draft_tokens, nullptr,
+                            w->flag, s);
+        if (rc) return rc;
+    }
     if (out->logits_out) {
         // a copy node, not an allocation; callers under capture simply pass logits_out = NULL
         SPECV_HIP(hipMemcpyAsync(out->logits_out, args->target_logits_in, (size_t)M * vocab * sizeof(float),
@@ -1359,5 +1448,5 @@ extern "C" int spec_sample_step_noalloc(int32_t vocab, int32_t max_lookahead, co
                              out->n_accepted, out->out_tokens, nullptr, nullptr, s);
     return launch_sampler(t, sw, ks, B, Kmax, vocab, n_stat, args->target_logits_in, args->draft_logits,
                           args->draft_tokens, args->uniforms, Kmax + 1, args->temperature, 0, nullptr, out->n_accepted,
-                          out->out_tokens, nullptr, nullptr, s);
+                          out->out_tokens, nullptr, nullptr, s, w->flag);
 }

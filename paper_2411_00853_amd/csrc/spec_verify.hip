@@ -371,12 +371,15 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
     // draft_tokens may be NULL when every K_b is 0; the kernels then never read it
     int rc;
     h->tables.tree = 0;
-    {
+    // without a decoder pass nothing needs the row tables before the sampler's second kernel: its first
+    // one fills them (the greedy rule's kernels read them from the start)
+    const bool prepare_in_sampler = !run_model && !greedy;
+    if (!prepare_in_sampler) {
         ProfScope ps(&h->prof, SPEC_PROF_PREPARE, s);
         rc = launch_prepare(h->tables, ks, B, Kmax, c.vocab, c.max_batch, c.max_kv_len, run_model, args->seq_slot,
                             run_model ? args->last_token : nullptr, args->draft_tokens, h->kv_len, h->flag, s);
+        if (rc) return rc;
     }
-    if (rc) return rc;
     const float* logits = args->target_logits_in;
     if (run_model) {
         float* dst = out->logits_out ? out->logits_out : h->logits;
@@ -393,7 +396,8 @@ extern "C" int spec_verify_step(spec_handle* h, const spec_step_args* args, cons
                              nullptr, &h->prof, s);
     return launch_sampler(h->tables, h->sampler, ks, B, Kmax, c.vocab, n_stat, logits, args->draft_logits,
                           args->draft_tokens, args->uniforms, Kmax + 1, args->temperature, args->auto_rollback,
-                          run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, nullptr, &h->prof, s);
+                          run_model ? h->kv_len : nullptr, out->n_accepted, out->out_tokens, nullptr, &h->prof, s,
+                          prepare_in_sampler ? h->flag : nullptr);
 }
 
 extern "C" int spec_verify_tree_step(spec_handle* h, const spec_tree_args* args, const spec_tree_out* out, void* stream)
