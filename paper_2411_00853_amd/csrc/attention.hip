@@ -791,7 +791,7 @@ bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack&
     return lp.p.chunk_keys >= 192;
 }
 
-int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,
+int launch_attention(int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M, const CacheGeom& g,
                      int n_q_heads, int layer, const void* cache, const float* q, float* part_o, float* part_ml,
                      size_t part_cap, const XOut& xo, int max_window, Profiler* prof, hipStream_t s, const QkvSrc* qkv,
                      void* cache_w)
@@ -810,7 +810,6 @@ int launch_attention(const AttnPlan& p_unused, int max_kv_len, int cu_count, con
         SPECV_LAUNCH_CHECK("attn_f32_kernel");
         return SPEC_OK;
     }
-    (void)p_unused;
     int kmax = 0;
     for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
     const AttnLaunchPlan lp = plan_launch(g, n_q_heads, kmax, B, max_kv_len, cu_count);

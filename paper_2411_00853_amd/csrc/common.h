@@ -281,7 +281,7 @@ size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int gr
 // Whether the bf16 attention kernel can take the QKV projection's partial sums itself (QkvSrc) for
 // this step's shapes; if not, launch_rope_append has to run first.
 bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack& ks, int B, int max_kv_len, int cu_count);
-int launch_attention(const AttnPlan& p, int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M,
+int launch_attention(int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M,
                      const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
                      float* part_o, float* part_ml, size_t part_cap, const XOut& xo, int max_window, Profiler* prof,
                      hipStream_t s, const QkvSrc* qkv = nullptr, void* cache_w = nullptr);

@@ -76,7 +76,6 @@ int forward_init(spec_handle* h, int max_rows)
                 const size_t e = gemm_partial_elems(plan_gemm(rows, Ns[i], Ks[i], h->cu_count, true), rows);
                 if (e > part) part = e;
             }
-        h->attn_plan = plan_attention(c.max_kv_len, c.max_batch, c.n_kv_heads, h->cu_count, h->geom.table != nullptr);
         const int group = c.n_q_heads / c.n_kv_heads;
         const size_t po = attn_partial_floats(c.max_kv_len, c.max_batch, c.n_kv_heads, group, c.max_lookahead + 1,
                                               c.head_dim, h->cu_count, h->geom.table != nullptr);
@@ -205,13 +204,13 @@ int forward_run(spec_handle* h, const StepTables& t, const LookaheadPack& ks, in
         if (fuse) {
             // the attention kernel adds up, scales and rotates q, k, v itself and appends k, v
             const QkvSrc qkv{h->partial, o.n_split, o.stride, o.ld, scaled, h->cos_sin};
-            rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache,
+            rc = launch_attention(c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache,
                                   h->q, h->attn_part_o, h->attn_part_ml, h->attn_part_cap, to_att, c.max_lookahead + 1, &h->prof, s, &qkv,
                                   h->kv_cache);
         } else {
             RUN(SPEC_PROF_GLUE, launch_rope_append(h->partial, o.n_split, o.stride, o.ld, t, M, h->geom, c.n_q_heads, l,
                                                    h->cos_sin, scaled, h->kv_cache, h->q, s));
-            rc = launch_attention(h->attn_plan, c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache,
+            rc = launch_attention(c.max_kv_len, h->cu_count, t, ks, B, M, h->geom, c.n_q_heads, l, h->kv_cache,
                                   h->q, h->attn_part_o, h->attn_part_ml, h->attn_part_cap, to_att, c.max_lookahead + 1, &h->prof, s);
         }
         if (rc) return rc;

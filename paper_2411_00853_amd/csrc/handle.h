@@ -39,7 +39,6 @@ struct spec_handle {
     const void* lm_head = nullptr;
     specv::CacheGeom geom{};
     int n_pages = 0;           // paged cache: pages in the caller's pool (0: contiguous cache)
-    specv::AttnPlan attn_plan{};
     bool split_act = true;     // feed activations to the matrix cores as bf16 head + remainder
     bool fuse_rope = true;     // bf16: rotary + KV append happen inside the attention kernel
     float* x = nullptr;        // [rows][d_model] residual stream
