@@ -10,6 +10,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "spec_verify.h"
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -104,6 +106,35 @@ struct spec_handle;
 int spec_verify_profile_begin(struct spec_handle* h);
 int spec_verify_profile_end(struct spec_handle* h, void* stream, double* ms, int32_t* launches,
                             double* empty_pair_ms);
+
+/* What a step would launch, without touching a device: the host-side planning of spec_verify_step
+ * for a bf16 model of cfg and a batch with the given lookaheads, on a chip with cu_count compute
+ * units.  For tests of that logic and for sizing questions ("how many passes, how much workspace").
+ * The figures are those of the tuning knobs in force at the call. */
+#define SPEC_PLAN_MAX_PASSES 32
+#define SPEC_PLAN_PROJECTIONS 5   /* QKV, output, gate/up, down, LM head */
+typedef struct {
+    int32_t rows;                 /* sum of K_b + 1 */
+    int32_t n_passes;             /* decoder passes (1 unless rows > SPEC_MAX_STEP_ROWS) */
+    int32_t pass_seqs[SPEC_PLAN_MAX_PASSES], pass_rows[SPEC_PLAN_MAX_PASSES];
+    /* the projections of the first pass: variant and launch shape (gate/up: the plan used when SwiGLU is
+     * not finished inside the GEMM) */
+    int32_t gemm_row_tiles[SPEC_PLAN_PROJECTIONS], gemm_col_tiles[SPEC_PLAN_PROJECTIONS];
+    int32_t gemm_k_ranges[SPEC_PLAN_PROJECTIONS], gemm_k_blocks_per_range[SPEC_PLAN_PROJECTIONS];
+    int32_t gemm_row_parts[SPEC_PLAN_PROJECTIONS], gemm_col_groups[SPEC_PLAN_PROJECTIONS];
+    int32_t gemm_workgroups[SPEC_PLAN_PROJECTIONS];
+    uint64_t gemm_partial_floats[SPEC_PLAN_PROJECTIONS];
+    uint64_t gemm_partial_capacity;   /* what spec_verify_init would allocate for them */
+    /* the attention launch of the first pass */
+    int32_t attn_kv_share;        /* work items per kv head */
+    int32_t attn_small;           /* 1: the small-launch plan */
+    int32_t attn_chunks, attn_chunk_keys, attn_row_tiles;
+    int32_t attn_wavefronts;      /* per workgroup when the chunks merge there; 0: merge kernel */
+    int32_t attn_fused;           /* 1: rotary/append inside the attention kernel */
+    uint64_t attn_partial_floats, attn_partial_capacity;
+} spec_step_plan;
+int spec_k_plan_step(const spec_model_cfg* cfg, int32_t batch, const int32_t* lookahead, int32_t cu_count,
+                     int32_t paged, spec_step_plan* out);
 
 #ifdef __cplusplus
 }

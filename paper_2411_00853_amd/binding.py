@@ -81,6 +81,21 @@ class spec_decode_view(C.Structure):
                                           "target_logits", "prev_token", "last_token", "counters")]
 
 
+PLAN_MAX_PASSES, PLAN_PROJECTIONS = 32, 5
+
+
+class spec_step_plan(C.Structure):
+    _fields_ = [("rows", C.c_int32), ("n_passes", C.c_int32),
+                ("pass_seqs", C.c_int32 * PLAN_MAX_PASSES), ("pass_rows", C.c_int32 * PLAN_MAX_PASSES)] + \
+               [(n, C.c_int32 * PLAN_PROJECTIONS) for n in ("gemm_row_tiles", "gemm_col_tiles", "gemm_k_ranges",
+                                                            "gemm_k_blocks_per_range", "gemm_row_parts",
+                                                            "gemm_col_groups", "gemm_workgroups")] + \
+               [("gemm_partial_floats", C.c_uint64 * PLAN_PROJECTIONS), ("gemm_partial_capacity", C.c_uint64)] + \
+               [(n, C.c_int32) for n in ("attn_kv_share", "attn_small", "attn_chunks", "attn_chunk_keys",
+                                         "attn_row_tiles", "attn_wavefronts", "attn_fused")] + \
+               [("attn_partial_floats", C.c_uint64), ("attn_partial_capacity", C.c_uint64)]
+
+
 _lib = None
 
 
@@ -521,3 +536,11 @@ def spec_verify_profile_end(h: Handle, stream=None):
     empty = C.c_double(0.0)
     _check(lib().spec_verify_profile_end(h.ptr, _stream(stream), ms, cnt, C.byref(empty)))
     return {PROF_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}, float(empty.value)
+
+
+def spec_k_plan_step(cfg, lookahead, cu_count=256, paged=False) -> spec_step_plan:
+    """Host-side planning of one step (no device work): passes, projection launch shapes, attention plan."""
+    out = spec_step_plan()
+    look = (C.c_int32 * len(lookahead))(*[int(k) for k in lookahead])
+    _check(lib().spec_k_plan_step(C.byref(cfg), len(lookahead), look, int(cu_count), 1 if paged else 0, C.byref(out)))
+    return out

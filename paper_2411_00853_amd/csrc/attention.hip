@@ -715,7 +715,8 @@ struct AttnLaunchPlan {
     AttnPlan p;
     bool small;
 };
-static AttnLaunchPlan plan_launch(const CacheGeom& g, int n_q_heads, int kmax, int B, int max_kv_len, int cu_count)
+static AttnLaunchPlan plan_launch(const CacheGeom& g, bool paged, int n_q_heads, int kmax, int B, int max_kv_len,
+                                  int cu_count)
 {
     AttnLaunchPlan lp{};
     const int group = n_q_heads / g.n_kv_heads;
@@ -725,9 +726,11 @@ static AttnLaunchPlan plan_launch(const CacheGeom& g, int n_q_heads, int kmax, i
     if (lp.small)
         for (int s = lp.share + 1; s <= group; ++s)
             if (group % s == 0 && B * g.n_kv_heads * s <= cu_count / 2) lp.share = s;
-    lp.p = plan_attention(max_kv_len, B, g.n_kv_heads * lp.share, cu_count, g.table != nullptr);
-    if (lp.small && lp.p.max_chunks > 4) {
-        lp.p.chunk_keys = ((max_kv_len + 3) / 4 + 31) / 32 * 32;
+    lp.p = plan_attention(max_kv_len, B, g.n_kv_heads * lp.share, cu_count, paged);
+    // (a paged wavefront holds the page numbers of at most 64 blocks: no chunk beyond 2048 positions)
+    const int few = std::max(4, paged ? (max_kv_len + 2047) / 2048 : 1);
+    if (lp.small && lp.p.max_chunks > few) {
+        lp.p.chunk_keys = ((max_kv_len + few - 1) / few + 31) / 32 * 32;
         lp.p.max_chunks = (max_kv_len + lp.p.chunk_keys - 1) / lp.p.chunk_keys;
     }
     return lp;
@@ -777,12 +780,31 @@ static int launch_chunks(int rt, int cw, dim3 grid, dim3 wg_grid, hipStream_t s,
     return SPEC_OK;
 }
 
+AttnDescription describe_attention(const CacheGeom& g, bool paged, int n_q_heads, int kmax, int B, int max_kv_len,
+                                   int max_window, int cu_count)
+{
+    AttnDescription d{};
+    const AttnLaunchPlan lp = plan_launch(g, paged, n_q_heads, kmax, B, max_kv_len, cu_count);
+    const int group = n_q_heads / (g.n_kv_heads * lp.share);
+    d.share = lp.share;
+    d.small = lp.small ? 1 : 0;
+    d.max_chunks = lp.p.max_chunks;
+    d.chunk_keys = lp.p.chunk_keys;
+    d.row_tiles = ((kmax + 1) * group + 15) / 16;
+    d.wavefronts = d.row_tiles >= 1 && d.row_tiles <= 4
+                       ? merge_width(g.head_dim, d.row_tiles, lp.p.max_chunks, B * g.n_kv_heads * lp.share, cu_count, lp.small)
+                       : 0;
+    d.fused = fused_fits(g.head_dim, d.row_tiles) && lp.p.chunk_keys >= 192 ? 1 : 0;
+    d.partial_floats = (size_t)B * g.n_kv_heads * lp.share * lp.p.max_chunks * group * max_window * g.head_dim;
+    return d;
+}
+
 bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack& ks, int B, int max_kv_len, int cu_count)
 {
     if (g.dtype != SPEC_DTYPE_BF16) return false;
     int kmax = 0;
     for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
-    const AttnLaunchPlan lp = plan_launch(g, n_q_heads, kmax, B, max_kv_len, cu_count);
+    const AttnLaunchPlan lp = plan_launch(g, g.table != nullptr, n_q_heads, kmax, B, max_kv_len, cu_count);
     const int rt = ((kmax + 1) * (n_q_heads / g.n_kv_heads / lp.share) + 15) / 16;
     if (!fused_fits(g.head_dim, rt)) return false;
     // Every wavefront of a (sequence, kv head) puts the queries together again: with short chunks
@@ -812,7 +834,7 @@ int launch_attention(int max_kv_len, int cu_count, const StepTables& t, const Lo
     }
     int kmax = 0;
     for (int b = 0; b < B; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
-    const AttnLaunchPlan lp = plan_launch(g, n_q_heads, kmax, B, max_kv_len, cu_count);
+    const AttnLaunchPlan lp = plan_launch(g, g.table != nullptr, n_q_heads, kmax, B, max_kv_len, cu_count);
     const int share = lp.share;
     const int n_items_kv = g.n_kv_heads * share;          // (sequence, kv head) work items per sequence
     const AttnPlan p = lp.p;

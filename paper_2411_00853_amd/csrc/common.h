@@ -281,6 +281,13 @@ size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int gr
 // Whether the bf16 attention kernel can take the QKV projection's partial sums itself (QkvSrc) for
 // this step's shapes; if not, launch_rope_append has to run first.
 bool attention_takes_qkv(const CacheGeom& g, int n_q_heads, const LookaheadPack& ks, int B, int max_kv_len, int cu_count);
+// What launch_attention would do for a step of B sequences whose longest window has kmax + 1 rows (host logic only)
+struct AttnDescription {
+    int share, small, max_chunks, chunk_keys, row_tiles, wavefronts, fused;
+    size_t partial_floats;   // chunk results the launch writes when they go through memory
+};
+AttnDescription describe_attention(const CacheGeom& g, bool paged, int n_q_heads, int kmax, int B, int max_kv_len,
+                                   int max_window, int cu_count);
 int launch_attention(int max_kv_len, int cu_count, const StepTables& t, const LookaheadPack& ks, int B, int M,
                      const CacheGeom& g, int n_q_heads, int layer, const void* cache, const float* q,
                      float* part_o, float* part_ml, size_t part_cap, const XOut& xo, int max_window, Profiler* prof,

@@ -67,15 +67,7 @@ int forward_init(spec_handle* h, int max_rows)
         const size_t xa_bytes = xfrag_uint4s(gemm_row_tiles(std::min(max_rows, 64)), 2, z.F) * sizeof(uint4);
         if (rc == SPEC_OK) rc = a.alloc(&h->xf_act, xa_bytes);
         if (rc == SPEC_OK && hipMemset(h->xf_act, 0, xa_bytes) != hipSuccess) rc = fail(SPEC_ERR_DEVICE, "hipMemset failed");
-        // partial-sum space for the largest GEMM at any row count
-        const int Ns[G_COUNT] = {z.nqkv, z.d, 2 * z.F, z.d, z.V};
-        const int Ks[G_COUNT] = {z.d, z.dq, z.d, z.F, z.d};
-        for (int M = 16; M <= (max_rows + 15) / 16 * 16 && M <= GEMM_MAX_ROWS; M += 16)
-            for (int i = 0; i < G_COUNT; ++i) {
-                const int rows = M < max_rows ? M : max_rows;
-                const size_t e = gemm_partial_elems(plan_gemm(rows, Ns[i], Ks[i], h->cu_count, true), rows);
-                if (e > part) part = e;
-            }
+        part = gemm_partial_capacity(c, max_rows, h->cu_count);
         const int group = c.n_q_heads / c.n_kv_heads;
         const size_t po = attn_partial_floats(c.max_kv_len, c.max_batch, c.n_kv_heads, group, c.max_lookahead + 1,
                                               c.head_dim, h->cu_count, h->geom.table != nullptr);
@@ -103,31 +95,86 @@ int forward_init(spec_handle* h, int max_rows)
     return SPEC_OK;
 }
 
+// partial-sum space (floats) for the largest projection at any row count up to max_rows
+size_t gemm_partial_capacity(const spec_model_cfg& c, int max_rows, int cu_count)
+{
+    const Dims z = dims_of(c);
+    const int Ns[G_COUNT] = {z.nqkv, z.d, 2 * z.F, z.d, z.V};
+    const int Ks[G_COUNT] = {z.d, z.dq, z.d, z.F, z.d};
+    size_t part = 0;
+    for (int M = 16; M <= (max_rows + 15) / 16 * 16 && M <= GEMM_MAX_ROWS; M += 16)
+        for (int i = 0; i < G_COUNT; ++i) {
+            const int rows = M < max_rows ? M : max_rows;
+            const size_t e = gemm_partial_elems(plan_gemm(rows, Ns[i], Ks[i], cu_count, true), rows);
+            if (e > part) part = e;
+        }
+    return part;
+}
+
+void projection_shapes(const spec_model_cfg& c, int* n_out, int* n_in)
+{
+    const Dims z = dims_of(c);
+    const int Ns[G_COUNT] = {z.nqkv, z.d, 2 * z.F, z.d, z.V};
+    const int Ks[G_COUNT] = {z.d, z.dq, z.d, z.F, z.d};
+    for (int i = 0; i < G_COUNT; ++i) {
+        n_out[i] = Ns[i];
+        n_in[i] = Ks[i];
+    }
+}
+
+// Decoder passes of a step of M rows when one pass takes at most cap: groups of consecutive sequences,
+// as few groups as filling each to the brim would give (every pass streams all the weights), and among
+// the partitions with that many groups the one whose largest group is smallest.  Returns the number of
+// passes (0 if max_passes is too few).
+int plan_passes(const LookaheadPack& ks, int B, int M, int cap, int* pass_seqs, int* pass_rows, int max_passes)
+{
+    // groups when each takes sequences while they fit under `limit`
+    auto fill = [&](int limit, bool record) {
+        int b0 = 0, n = 0;
+        while (b0 < B) {
+            int Bg = 0, Mg = 0;
+            while (b0 + Bg < B && Mg + ks.k[b0 + Bg] + 1 <= limit) {
+                Mg += ks.k[b0 + Bg] + 1;
+                ++Bg;
+            }
+            if (Bg == 0) return B + 1;          // a window longer than the limit: no partition
+            if (record) {
+                if (n == max_passes) return 0;
+                pass_seqs[n] = Bg;
+                pass_rows[n] = Mg;
+            }
+            ++n;
+            b0 += Bg;
+        }
+        return n;
+    };
+    const int fewest = fill(cap, false);
+    int limit = (M + fewest - 1) / fewest;       // no partition into `fewest` groups has a smaller largest group
+    while (limit < cap && fill(limit, false) > fewest) ++limit;
+    return fill(limit, true);
+}
+
 int forward_run_grouped(spec_handle* h, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s)
 {
     if (M <= h->row_cap) return forward_run(h, h->tables, ks, B, M, logits_out, s);
     if (!h->group_tables.seq_row0) return fail(SPEC_ERR_SHAPE, "%d window rows exceed the %d the handle takes", M, h->row_cap);
-    // groups of consecutive sequences, about equally many rows each
-    const int cap = h->row_cap, n_groups = (M + cap - 1) / cap, target = (M + n_groups - 1) / n_groups;
+    int pass_seqs[SPEC_PLAN_MAX_PASSES], pass_rows[SPEC_PLAN_MAX_PASSES];
+    const int n_passes = plan_passes(ks, B, M, h->row_cap, pass_seqs, pass_rows, SPEC_PLAN_MAX_PASSES);
+    if (n_passes == 0) return fail(SPEC_ERR_SHAPE, "a step of %d rows needs more than %d decoder passes", M, SPEC_PLAN_MAX_PASSES);
     StepTables sub = h->group_tables;
     sub.pool = h->tables.pool;
     sub.tree = h->tables.tree;
     int b0 = 0, r0 = 0;
-    while (b0 < B) {
+    for (int g = 0; g < n_passes; ++g) {
         LookaheadPack kg;
         memset(&kg, 0, sizeof(kg));
-        int Bg = 0, Mg = 0;
-        while (b0 + Bg < B && Mg < target && Mg + ks.k[b0 + Bg] + 1 <= cap) {
-            kg.k[Bg] = ks.k[b0 + Bg];
-            Mg += ks.k[b0 + Bg] + 1;
-            ++Bg;
-        }
-        int rc = launch_slice_tables(h->tables, sub, b0, Bg, s);
+        for (int i = 0; i < pass_seqs[g]; ++i) kg.k[i] = ks.k[b0 + i];
+        int rc = launch_slice_tables(h->tables, sub, b0, pass_seqs[g], s);
         if (rc) return rc;
-        rc = forward_run(h, sub, kg, Bg, Mg, logits_out + (size_t)r0 * h->cfg.vocab, s);
+        rc = forward_run(h, sub, kg, pass_seqs[g], pass_rows[g], logits_out + (size_t)r0 * h->cfg.vocab, s);
         if (rc) return rc;
-        b0 += Bg;
-        r0 += Mg;
+        b0 += pass_seqs[g];
+        r0 += pass_rows[g];
     }
     return SPEC_OK;
 }

@@ -513,8 +513,17 @@ GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
     // two thirds of the compute units have a workgroup; more ranges only add partial-sum traffic
     // (M*N*4 bytes each way per range).  At most 16 ranges, each at least two LDS chunks long.
     const int target = g_wg_target > 0 ? g_wg_target : (2 * cu_count) / 3;
+    // Ranges are whole K groups of the packed order (below), so cutting a short K too finely leaves
+    // ranges with nothing in them -- workgroups that only write zeros for the consumer to add; no
+    // doubling that would leave more than one range in eight empty.
+    auto ranges_with_work = [&](int n) {
+        const int per = ((kb_total + n - 1) / n + WPACK_KG - 1) / WPACK_KG * WPACK_KG;
+        return (kb_total + per - 1) / per;
+    };
     int s = 1;
-    while (s < 16 && wg_x * s < target && (kb_total + 2 * s - 1) / (2 * s) >= 2 * kc) s *= 2;
+    while (s < 16 && wg_x * s < target && (kb_total + 2 * s - 1) / (2 * s) >= 2 * kc
+           && ranges_with_work(2 * s) * 8 >= 2 * s * 7)
+        s *= 2;
     p.n_split = s;
     // Many rows (the eight-wavefront variants): the matrix instructions set the pace, so compute units
     // without a workgroup are lost time; three column groups per workgroup instead of four when that

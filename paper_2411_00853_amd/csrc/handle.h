@@ -66,4 +66,8 @@ int forward_init(spec_handle* h, int max_rows);
 int forward_run(spec_handle* h, const StepTables& t, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s);
 // the same for any M: sequences are taken in groups of at most row_cap rows, one pass each (t = h->tables)
 int forward_run_grouped(spec_handle* h, const LookaheadPack& ks, int B, int M, float* logits_out, hipStream_t s);
+// host logic behind the two (no device work): see forward.hip
+size_t gemm_partial_capacity(const spec_model_cfg& c, int max_rows, int cu_count);
+void projection_shapes(const spec_model_cfg& c, int* n_out, int* n_in);   // [SPEC_PLAN_PROJECTIONS]
+int plan_passes(const LookaheadPack& ks, int B, int M, int cap, int* pass_seqs, int* pass_rows, int max_passes);
 }  // namespace specv

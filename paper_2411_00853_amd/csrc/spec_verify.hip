@@ -539,3 +539,67 @@ extern "C" int spec_verify_poll(spec_handle* h, void* stream)
     }
     return SPEC_OK;
 }
+
+extern "C" int spec_k_plan_step(const spec_model_cfg* cfg, int32_t batch, const int32_t* lookahead, int32_t cu_count,
+                                int32_t paged, spec_step_plan* out)
+{
+    if (!cfg || !lookahead || !out) return fail(SPEC_ERR_INVALID_ARG, "spec_k_plan_step: NULL argument");
+    int rc = check_cfg(cfg, true);
+    if (rc) return rc;
+    if (cfg->dtype != SPEC_DTYPE_BF16) return fail(SPEC_ERR_INVALID_ARG, "spec_k_plan_step: bf16 models only");
+    if (batch < 1 || batch > cfg->max_batch) return fail(SPEC_ERR_INVALID_ARG, "batch %d outside 1..%d", batch, cfg->max_batch);
+    if (cu_count < 1) return fail(SPEC_ERR_INVALID_ARG, "cu_count must be positive");
+    memset(out, 0, sizeof(*out));
+    LookaheadPack ks;
+    memset(&ks, 0, sizeof(ks));
+    int M = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int k = lookahead[b];
+        if (k < 0 || k > cfg->max_lookahead)
+            return fail(SPEC_ERR_INVALID_ARG, "lookahead[%d] = %d outside 0..%d", b, k, cfg->max_lookahead);
+        ks.k[b] = (uint8_t)k;
+        M += k + 1;
+    }
+    out->rows = M;
+    int seqs[SPEC_PLAN_MAX_PASSES], rows[SPEC_PLAN_MAX_PASSES];
+    const int n = plan_passes(ks, batch, M, GEMM_MAX_ROWS, seqs, rows, SPEC_PLAN_MAX_PASSES);
+    if (n == 0) return fail(SPEC_ERR_SHAPE, "a step of %d rows needs more than %d decoder passes", M, SPEC_PLAN_MAX_PASSES);
+    out->n_passes = n;
+    for (int i = 0; i < n; ++i) {
+        out->pass_seqs[i] = seqs[i];
+        out->pass_rows[i] = rows[i];
+    }
+    const int max_rows = std::min(cfg->max_batch * (cfg->max_lookahead + 1), GEMM_MAX_ROWS);
+    int n_out[SPEC_PLAN_PROJECTIONS], n_in[SPEC_PLAN_PROJECTIONS];
+    projection_shapes(*cfg, n_out, n_in);
+    for (int i = 0; i < SPEC_PLAN_PROJECTIONS; ++i) {
+        const GemmPlan p = plan_gemm(rows[0], n_out[i], n_in[i], cu_count, true);
+        out->gemm_row_tiles[i] = p.mt;
+        out->gemm_col_tiles[i] = p.nt;
+        out->gemm_k_ranges[i] = p.n_split;
+        out->gemm_k_blocks_per_range[i] = p.kb_per_split;
+        out->gemm_row_parts[i] = p.rs;
+        out->gemm_col_groups[i] = p.cg;
+        const int n_tiles = p.n_pad / 16;
+        out->gemm_workgroups[i] = (n_tiles + p.cg * p.nt - 1) / (p.cg * p.nt) * p.n_split;
+        out->gemm_partial_floats[i] = gemm_partial_elems(p, rows[0]);
+    }
+    out->gemm_partial_capacity = gemm_partial_capacity(*cfg, max_rows, cu_count);
+    int kmax = 0;
+    for (int b = 0; b < seqs[0]; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
+    const CacheGeom g = make_cache_geom(*cfg);
+    const AttnDescription d = describe_attention(g, paged != 0, cfg->n_q_heads, kmax, seqs[0], cfg->max_kv_len,
+                                                 cfg->max_lookahead + 1, cu_count);
+    out->attn_kv_share = d.share;
+    out->attn_small = d.small;
+    out->attn_chunks = d.max_chunks;
+    out->attn_chunk_keys = d.chunk_keys;
+    out->attn_row_tiles = d.row_tiles;
+    out->attn_wavefronts = d.wavefronts;
+    out->attn_fused = d.fused;
+    out->attn_partial_floats = d.partial_floats;
+    out->attn_partial_capacity = attn_partial_floats(cfg->max_kv_len, cfg->max_batch, cfg->n_kv_heads,
+                                                     cfg->n_q_heads / cfg->n_kv_heads, cfg->max_lookahead + 1, cfg->head_dim,
+                                                     cu_count, paged != 0);
+    return SPEC_OK;
+}

@@ -288,6 +288,38 @@ def test_random_small_models_on_a_page_pool(seed):
     assert paged.free() == n_pages - sum((n + 31) // 32 for n in kl)
 
 
+def test_long_slots_of_a_small_model_on_a_page_pool():
+    """A handle whose slots can grow to 16384 positions while the model and the batch are small (a
+    launch with a few MiB of keys and values): a paged wavefront keeps the page numbers of at most 64
+    blocks, so such a launch still cuts its sequences into chunks of at most 2048 positions.  Logits
+    against the oracle, results equal to the contiguous cache's."""
+    from test_gpu_forward import Rig, PagedRig
+    shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
+    cap, kmax = 16384, 5
+    base = Rig(shape, 2, cap, kmax, seed=41, std=0.05)
+    rng = wl.Rng(42, "cpu")
+    lens = [40, 2100]
+    for s, n in enumerate(lens):
+        base.prefill(s, rng.randint(70 + s, (n,), shape.vocab).tolist())
+    paged = PagedRig(base, 2, cap, kmax, n_pages=80)
+    for s in range(2):
+        paged.load(base, s)
+    V = shape.vocab
+    t0 = rng.randint(90, (2,), V).tolist()
+    lk = [kmax, 3]
+    toks = rng.randint(91, (2, kmax), V)
+    dl = rng.normal(92, (2, kmax, V), 1.0)
+    us = rng.uniform(93, (2, kmax + 1))
+    want = _linear(base, base.sv, [0, 1], t0, lk, toks, dl, us, 1.0, kmax, V)
+    got = _linear(paged, paged.sv, [0, 1], t0, lk, toks, dl, us, 1.0, kmax, V)
+    paged.sv.spec_verify_poll(paged.h)
+    _, err, chk = _against_oracle(paged, [0, 1], t0, lk, toks, dl, us, 1.0, kmax, V, got)
+    assert err <= 5e-3
+    assert torch.equal(want[1], got[1]) and torch.equal(want[2], got[2])
+    assert (want[0] - got[0]).abs().max().item() <= 1e-4      # the two caches cut the positions differently
+    assert paged.kv_len.cpu().tolist() == base.kv_len.cpu().tolist()
+
+
 def test_pool_exhaustion_skips_the_sequence_and_is_reported():
     from test_gpu_forward import Rig, PagedRig
     Kmax, T, V = 4, 1.0, SHAPE.vocab
