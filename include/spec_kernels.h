@@ -125,6 +125,11 @@ typedef struct {
     int32_t gemm_workgroups[SPEC_PLAN_PROJECTIONS];
     uint64_t gemm_partial_floats[SPEC_PLAN_PROJECTIONS];
     uint64_t gemm_partial_capacity;   /* what spec_verify_init would allocate for them */
+    int32_t gate_up_swiglu_inside;    /* 1: the gate/up projection finishes SwiGLU itself (one K range) */
+    int32_t reserved0;
+    /* operand-fragment buffers, in 16-byte units: what the first pass writes and what init allocates;
+     * the second pair is the down projection's operand when SwiGLU is finished inside the GEMM */
+    uint64_t xfrag_units, xfrag_capacity, xfrag_act_units, xfrag_act_capacity;
     /* the attention launch of the first pass */
     int32_t attn_kv_share;        /* work items per kv head */
     int32_t attn_small;           /* 1: the small-launch plan */

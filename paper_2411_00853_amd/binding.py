@@ -90,7 +90,9 @@ class spec_step_plan(C.Structure):
                [(n, C.c_int32 * PLAN_PROJECTIONS) for n in ("gemm_row_tiles", "gemm_col_tiles", "gemm_k_ranges",
                                                             "gemm_k_blocks_per_range", "gemm_row_parts",
                                                             "gemm_col_groups", "gemm_workgroups")] + \
-               [("gemm_partial_floats", C.c_uint64 * PLAN_PROJECTIONS), ("gemm_partial_capacity", C.c_uint64)] + \
+               [("gemm_partial_floats", C.c_uint64 * PLAN_PROJECTIONS), ("gemm_partial_capacity", C.c_uint64),
+                ("gate_up_swiglu_inside", C.c_int32), ("reserved0", C.c_int32), ("xfrag_units", C.c_uint64),
+                ("xfrag_capacity", C.c_uint64), ("xfrag_act_units", C.c_uint64), ("xfrag_act_capacity", C.c_uint64)] + \
                [(n, C.c_int32) for n in ("attn_kv_share", "attn_small", "attn_chunks", "attn_chunk_keys",
                                          "attn_row_tiles", "attn_wavefronts", "attn_fused")] + \
                [("attn_partial_floats", C.c_uint64), ("attn_partial_capacity", C.c_uint64)]

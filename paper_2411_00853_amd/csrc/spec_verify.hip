@@ -4,6 +4,7 @@
 #include "common.h"
 #include <vector>
 
+#include "frag.h"
 #include "handle.h"
 
 #include <cstdarg>
@@ -585,6 +586,12 @@ extern "C" int spec_k_plan_step(const spec_model_cfg* cfg, int32_t batch, const 
         out->gemm_partial_floats[i] = gemm_partial_elems(p, rows[0]);
     }
     out->gemm_partial_capacity = gemm_partial_capacity(*cfg, max_rows, cu_count);
+    const int widest = std::max(std::max(cfg->d_model, cfg->n_q_heads * cfg->head_dim), cfg->d_ffn);
+    out->gate_up_swiglu_inside = gemm_swiglu_fits(rows[0], cfg->d_ffn, cu_count) ? 1 : 0;
+    out->xfrag_units = xfrag_uint4s(gemm_row_tiles(rows[0]), 2, widest);
+    out->xfrag_capacity = xfrag_uint4s(gemm_row_tiles(max_rows), 2, widest);
+    out->xfrag_act_units = out->gate_up_swiglu_inside ? xfrag_uint4s(gemm_row_tiles(rows[0]), 2, cfg->d_ffn) : 0;
+    out->xfrag_act_capacity = xfrag_uint4s(gemm_row_tiles(std::min(max_rows, 64)), 2, cfg->d_ffn);
     int kmax = 0;
     for (int b = 0; b < seqs[0]; ++b) kmax = ks.k[b] > kmax ? ks.k[b] : kmax;
     const CacheGeom g = make_cache_geom(*cfg);

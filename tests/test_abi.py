@@ -94,7 +94,7 @@ def test_headers_are_plain_c_and_the_binding_mirrors_their_structs(tmp_path):
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     names = ["spec_model_cfg", "spec_layer_weights", "spec_weights", "spec_step_args", "spec_step_out",
              "spec_tree_args", "spec_tree_out", "spec_decode_cfg", "spec_round_args", "spec_lookahead_cfg",
-             "spec_decode_view"]
+             "spec_decode_view", "spec_step_plan"]
     lines = ['#include <stddef.h>', '#include <stdio.h>', '#include "spec_verify.h"', '#include "spec_decode.h"',
              '#include "spec_kernels.h"', 'int main(void) {']
     for n in names:

@@ -50,6 +50,10 @@ def _check_invariants(shape, cfg, look, p, paged):
         assert p.gemm_partial_floats[i] == s * p.pass_rows[0] * n_pad <= p.gemm_partial_capacity
         tiles_per_wg = nt * p.gemm_col_groups[i]
         assert p.gemm_workgroups[i] == -(-(n_pad // 16) // tiles_per_wg) * s
+    # operand fragments fit their buffers; SwiGLU inside the GEMM only up to four row tiles
+    assert p.xfrag_units <= p.xfrag_capacity and p.xfrag_act_units <= p.xfrag_act_capacity
+    if p.gate_up_swiglu_inside:
+        assert p.gemm_row_tiles[2] <= 4 and p.xfrag_act_units > 0
     # attention of the first pass
     group = shape.n_q_heads // shape.n_kv_heads
     window = max(look[:p.pass_seqs[0]]) + 1
@@ -115,6 +119,7 @@ def test_plans_of_the_named_configurations():
     # (the launch rounds these up to whole rounds of the 8 XCDs: 250 runs as a grid of 256)
     assert list(p.gemm_workgroups) == [192, 256, 172, 256, 250]
     assert (p.attn_kv_share, p.attn_small, p.attn_chunks, p.attn_wavefronts, p.attn_fused) == (1, 0, 2, 2, 1)
+    assert p.gate_up_swiglu_inside == 1
     w = wl.workload_1b()
     cfg, p = _plan(w.shape, list(w.lookahead), w.batch, w.max_kv_len, w.max_lookahead)
     assert p.rows == 6 and list(p.gemm_row_tiles) == [1] * 5
