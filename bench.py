@@ -84,6 +84,9 @@ def parse():
     ap.add_argument("--attn-items-per-cu", type=int, default=0, help="tuning: attention work items per compute unit")
     ap.add_argument("--attn-merge-min-pairs", type=int, default=0, help="tuning: fewest (sequence, kv head) pairs for merging chunks inside the workgroup")
     ap.add_argument("--attn-max-chunks", type=int, default=0, help="tuning: most position chunks per (sequence, kv head)")
+    ap.add_argument("--batch", type=int, default=0, help="tuning: reshape the workload to this many sequences (all like the first)")
+    ap.add_argument("--kv-len", type=int, default=0, help="tuning: reshape the workload to this many cached tokens per sequence")
+    ap.add_argument("--attn-small-positions", type=int, default=-1, help="tuning: cache capacity per sequence up to which a launch with few (sequence, kv head) pairs uses the small-launch attention plan")
     ap.add_argument("--kv-pad", type=int, default=0, help="tuning: extra positions of cache capacity per slot (changes the strides between heads and slots)")
     ap.add_argument("--gemm-wg-target", type=int, default=0, help="tuning: workgroups per GEMM launch")
     ap.add_argument("--gemm-balance-groups", type=int, default=1, help="tuning: many-row GEMMs as four column groups of three tiles")
@@ -456,6 +459,7 @@ def main():
     sv.spec_k_set_gemm_wg_target(args.gemm_wg_target)
     sv.spec_k_set_attn_merge_min_pairs(args.attn_merge_min_pairs)
     sv.spec_k_set_attn_max_chunks(args.attn_max_chunks)
+    sv.spec_k_set_attn_small_positions(args.attn_small_positions)
     sv.spec_k_set_swiglu_min_wgs(args.swiglu_min_wgs)
     sv.spec_k_set_gemm_balance_groups(args.gemm_balance_groups)
     if args.workload == "stress":
@@ -470,6 +474,12 @@ def main():
     if args.layers > 0:
         from dataclasses import replace
         w = replace(w, shape=replace(w.shape, n_layers=args.layers), name=f"{w.name}-{args.layers}layers")
+    if args.batch or args.kv_len:
+        from dataclasses import replace
+        nb = args.batch or w.batch
+        n = args.kv_len or w.kv_lens[0]
+        w = replace(w, batch=nb, kv_lens=(n,) * nb, lookahead=(w.lookahead[0],) * nb, max_kv_len=n + w.max_lookahead + 1,
+                    name=f"{w.name}-b{nb}-n{n}")
     if args.kv_pad:
         from dataclasses import replace
         w = replace(w, max_kv_len=w.max_kv_len + args.kv_pad)

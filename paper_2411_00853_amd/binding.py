@@ -152,6 +152,8 @@ def lib():
         L.spec_k_set_attn_merge_min_pairs.argtypes = [C.c_int32]
         L.spec_k_set_attn_max_chunks.restype = None
         L.spec_k_set_attn_max_chunks.argtypes = [C.c_int32]
+        L.spec_k_set_attn_small_positions.restype = None
+        L.spec_k_set_attn_small_positions.argtypes = [C.c_int32]
         L.spec_verify_profile_begin.argtypes = [C.c_void_p]
         L.spec_verify_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32),
                                               C.POINTER(C.c_double)]
@@ -511,6 +513,10 @@ def spec_k_set_attn_merge_min_pairs(pairs: int):
 
 def spec_k_set_attn_max_chunks(chunks: int):
     lib().spec_k_set_attn_max_chunks(int(chunks))
+
+
+def spec_k_set_attn_small_positions(n: int):
+    lib().spec_k_set_attn_small_positions(int(n))
 
 
 def spec_k_gemm_f32(x: torch.Tensor, w: torch.Tensor, stream=None):

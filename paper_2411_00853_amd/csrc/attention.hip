@@ -625,6 +625,8 @@ void set_attn_max_chunks(int n)
 }
 static int g_merge_min_pairs = 0;   // fewest (sequence, kv head) pairs for merging inside the workgroup; 0 = default
 void set_attn_merge_min_pairs(int n) { g_merge_min_pairs = n; }
+static int g_small_positions = 2816;   // cache capacity per sequence up to which the small-launch plan applies
+void set_attn_small_positions(int n) { g_small_positions = n >= 0 ? n : 2816; }
 
 AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count, bool paged)
 {
@@ -703,13 +705,20 @@ static int merge_width(int hd, int rt, int max_chunks, int n_pairs, int cu_count
 
 // What a launch does with its (sequence, kv head) pairs: how many work items share a cache head
 // (attn_kv_share, at least what the row limit asks for) and how the positions are cut.
-// Small launches -- at most 4 MiB of keys and values in all, e.g. one sequence of a 1B-class model --
-// are bound by latency, not by the stream: there a kv head's query heads are spread over more work
-// items while those still fit on half the compute units (duplicate reads hit L2), each item is cut
-// into at most four chunks, and the four wavefronts merge inside their workgroup whatever the number
-// of pairs -- one kernel where there were three (rotary/append, chunks, merge).  Measured at the
-// 1B-shape, batch 1: step 1.017 -> 0.948 ms.  With more data the same choice loses (the 1B-shape
-// as a draft at batch 8, 37 MB: +2 % per round with two items per kv head, +7 % with four).
+// Small launches -- fewer pairs than half the compute units (with more, the plan above already merges
+// inside the workgroup) and short caches -- are bound by latency, not by the stream: there a kv
+// head's query heads are spread over more work items while those still fit on half the compute units
+// (duplicate reads hit L2), each item is cut into at most four chunks, and the four wavefronts merge
+// inside their workgroup -- one kernel where there were three (rotary/append, chunks, merge).
+// Measured at the 1B-shape (8 kv heads x 4 query heads), per step: batch 1 at 1024 positions 1.017 ->
+// 0.948 ms, at 2048 1.071 -> 1.012, at 2560 1.061 -> 1.045, at 3072 1.065 -> 1.077, at 4096 1.083 ->
+// 1.134 (one block in flight per wavefront: chunks of a thousand positions are latency-bound);
+// batch 4 at 3072 1.214 -> 1.193, batch 8 at 2304 1.320 -> 1.279, batch 12 at 2048 1.758 -> 1.696.
+// Hence a limit on the cache capacity per sequence (counted in positions of 64-dim heads: a 128-dim
+// head moves twice the bytes per position).  Only with several query heads per kv head: the work items
+// of one kv head then read the same blocks and most of the traffic stays in L2; with one head per kv
+// head every workgroup streams from HBM through a single compute unit, and the plan loses (7B-shape,
+// 32 x 128-dim kv heads, batch 1 at 1024 positions: 3.35 -> 3.44 ms, at 2048 3.47 -> 3.73, batch 3 4.04 -> 4.07).
 struct AttnLaunchPlan {
     int share;
     AttnPlan p;
@@ -721,8 +730,8 @@ static AttnLaunchPlan plan_launch(const CacheGeom& g, bool paged, int n_q_heads,
     AttnLaunchPlan lp{};
     const int group = n_q_heads / g.n_kv_heads;
     lp.share = attn_kv_share(group, kmax + 1);
-    const size_t kv_bytes = (size_t)B * g.n_kv_heads * max_kv_len * g.head_dim * 4;   // keys + values, bf16
-    lp.small = kv_bytes <= ((size_t)4 << 20) && !g_max_chunks_set && g_merge_min_pairs == 0 && g_items_per_cu == 0;
+    lp.small = group >= 2 && B * g.n_kv_heads < cu_count / 2 && (long)max_kv_len * g.head_dim <= 64L * g_small_positions
+               && !g_max_chunks_set && g_merge_min_pairs == 0 && g_items_per_cu == 0;
     if (lp.small)
         for (int s = lp.share + 1; s <= group; ++s)
             if (group % s == 0 && B * g.n_kv_heads * s <= cu_count / 2) lp.share = s;

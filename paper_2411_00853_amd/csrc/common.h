@@ -274,6 +274,7 @@ AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count,
 void set_attn_items_per_cu(int n);
 void set_attn_merge_min_pairs(int n);
 void set_attn_max_chunks(int n);
+void set_attn_small_positions(int n);
 size_t attn_partial_floats(int max_kv_len, int max_batch, int n_kv_heads, int group, int max_window, int hd,
                            int cu_count, bool paged = false);
 // part_cap: capacity of part_o in floats (part_ml holds 2/head_dim of that); a plan that needs more

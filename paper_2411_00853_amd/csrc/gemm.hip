@@ -716,6 +716,7 @@ extern "C" void spec_k_set_swiglu_column_groups(int32_t groups) { set_swiglu_col
 extern "C" void spec_k_set_attn_items_per_cu(int32_t items) { set_attn_items_per_cu(items); }
 extern "C" void spec_k_set_attn_merge_min_pairs(int32_t pairs) { set_attn_merge_min_pairs(pairs); }
 extern "C" void spec_k_set_attn_max_chunks(int32_t chunks) { set_attn_max_chunks(chunks); }
+extern "C" void spec_k_set_attn_small_positions(int32_t positions) { set_attn_small_positions(positions); }
 
 extern "C" size_t spec_k_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K)
 {
