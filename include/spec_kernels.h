@@ -107,8 +107,8 @@ int spec_verify_profile_begin(struct spec_handle* h);
 int spec_verify_profile_end(struct spec_handle* h, void* stream, double* ms, int32_t* launches,
                             double* empty_pair_ms);
 
-/* Tuning knob: an attention launch of a model with several query heads per kv head, fewer (sequence, kv
- * head) pairs than half the compute units and a cache capacity (max_kv_len, counted in positions of
+/* Tuning knob: an attention launch of a model with several query heads per kv head, at most an eighth as
+ * many (sequence, kv head) pairs as compute units and a cache capacity (max_kv_len, counted in positions of
  * 64-dim heads) of at most this many positions uses the small-launch plan -- a kv
  * head's query heads as work items of their own, at most four position chunks, merged inside the
  * workgroup; negative = default (2816), 0 = never.  Process-wide; set before spec_verify_init. */

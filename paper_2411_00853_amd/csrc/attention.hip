@@ -705,8 +705,8 @@ static int merge_width(int hd, int rt, int max_chunks, int n_pairs, int cu_count
 
 // What a launch does with its (sequence, kv head) pairs: how many work items share a cache head
 // (attn_kv_share, at least what the row limit asks for) and how the positions are cut.
-// Small launches -- fewer pairs than half the compute units (with more, the plan above already merges
-// inside the workgroup) and short caches -- are bound by latency, not by the stream: there a kv
+// Small launches -- at most an eighth as many pairs as compute units and short caches -- are bound by
+// latency, not by the stream: there a kv
 // head's query heads are spread over more work items while those still fit on half the compute units
 // (duplicate reads hit L2), each item is cut into at most four chunks, and the four wavefronts merge
 // inside their workgroup -- one kernel where there were three (rotary/append, chunks, merge).
@@ -714,6 +714,8 @@ static int merge_width(int hd, int rt, int max_chunks, int n_pairs, int cu_count
 // 0.948 ms, at 2048 1.071 -> 1.012, at 2560 1.061 -> 1.045, at 3072 1.065 -> 1.077, at 4096 1.083 ->
 // 1.134 (one block in flight per wavefront: chunks of a thousand positions are latency-bound);
 // batch 4 at 3072 1.214 -> 1.193, batch 8 at 2304 1.320 -> 1.279, batch 12 at 2048 1.758 -> 1.696.
+// The same model as the draft of a decoding round at batch 8 (one or two rows per sequence, 2300
+// positions) loses 1.8 % per round with it, so the plan stops at 32 pairs (batch 4 of this shape).
 // Hence a limit on the cache capacity per sequence (counted in positions of 64-dim heads: a 128-dim
 // head moves twice the bytes per position).  Only with several query heads per kv head: the work items
 // of one kv head then read the same blocks and most of the traffic stays in L2; with one head per kv
@@ -730,7 +732,7 @@ static AttnLaunchPlan plan_launch(const CacheGeom& g, bool paged, int n_q_heads,
     AttnLaunchPlan lp{};
     const int group = n_q_heads / g.n_kv_heads;
     lp.share = attn_kv_share(group, kmax + 1);
-    lp.small = group >= 2 && B * g.n_kv_heads < cu_count / 2 && (long)max_kv_len * g.head_dim <= 64L * g_small_positions
+    lp.small = group >= 2 && B * g.n_kv_heads * 8 <= cu_count && (long)max_kv_len * g.head_dim <= 64L * g_small_positions
                && !g_max_chunks_set && g_merge_min_pairs == 0 && g_items_per_cu == 0;
     if (lp.small)
         for (int s = lp.share + 1; s <= group; ++s)
