@@ -238,6 +238,7 @@ __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack 
 
     constexpr int PER = STAT_CHUNK / TPB;   // 64 values per lane
     float v[PER];
+    // copy_out: plain-draw mode (one statistics row per sequence): keep the row for the verifier
     if constexpr (VEC4) {
         const float4* p4 = reinterpret_cast<const float4*>(row + base);
 #pragma unroll
@@ -247,6 +248,14 @@ __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack 
             if (idx * 4 < lim) x = p4[idx];   // lim is a multiple of 4 when VEC4
             v[4 * i + 0] = x.x; v[4 * i + 1] = x.y; v[4 * i + 2] = x.z; v[4 * i + 3] = x.w;
         }
+        if (copy_out) {   // whole 16-byte stores (the launcher checked the alignment of the copy as well)
+            float4* d4 = reinterpret_cast<float4*>(copy_out + (size_t)srow * copy_stride + base);
+#pragma unroll
+            for (int i = 0; i < PER / 4; ++i) {
+                const int idx = i * TPB + threadIdx.x;
+                if (idx * 4 < lim) d4[idx] = make_float4(v[4 * i + 0], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+            }
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
@@ -254,11 +263,11 @@ __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack 
             v[i] = idx < lim ? row[base + idx] : -INFINITY;
         }
     }
-    if (copy_out) {   // plain-draw mode (one statistics row per sequence): keep the row for the verifier
+    if (!VEC4 && copy_out) {
         float* dst = copy_out + (size_t)srow * copy_stride + base;
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            const int idx = VEC4 ? ((i / 4) * TPB + (int)threadIdx.x) * 4 + (i & 3) : i * TPB + (int)threadIdx.x;
+            const int idx = i * TPB + (int)threadIdx.x;
             if (idx < lim) dst[idx] = v[i];
         }
     }
