@@ -738,6 +738,21 @@ static AttnLaunchPlan plan_launch(const CacheGeom& g, bool paged, int n_q_heads,
         for (int s = lp.share + 1; s <= group; ++s)
             if (group % s == 0 && B * g.n_kv_heads * s <= cu_count / 2) lp.share = s;
     lp.p = plan_attention(max_kv_len, B, g.n_kv_heads * lp.share, cu_count, paged);
+    // The variant that puts queries, keys and values together itself needs, at 128-dim heads, more than
+    // half a SIMD's registers (the prologue parks values in the accumulation registers): one wavefront
+    // per SIMD, 4 per compute unit.  Two chunks per pair that overflow those slots by a quarter to three
+    // quarters run as a full round plus a thin one; one chunk per pair, all resident at once, is faster
+    // (7B-shape, 2048 positions, attention per layer: batch 20 161 -> 140 us, batch 24 176 -> 163, batch
+    // 28 and 32 within 2 %; from batch 40 on two chunks win again).
+    {
+        const long pairs = (long)B * g.n_kv_heads * lp.share, slots = 4L * cu_count;
+        const int rt1 = ((kmax + 1) * (group / lp.share) + 15) / 16;
+        if (g.head_dim == 128 && rt1 == 1 && lp.p.max_chunks == 2 && lp.p.chunk_keys >= 192 && !lp.small && !paged
+            && !g_max_chunks_set && g_items_per_cu == 0 && pairs <= slots && 2 * pairs > slots && 8 * pairs < 7 * slots) {
+            lp.p.chunk_keys = (max_kv_len + 31) / 32 * 32;
+            lp.p.max_chunks = 1;
+        }
+    }
     // (a paged wavefront holds the page numbers of at most 64 blocks: no chunk beyond 2048 positions)
     const int few = std::max(4, paged ? (max_kv_len + 2047) / 2048 : 1);
     if (lp.small && lp.p.max_chunks > few) {

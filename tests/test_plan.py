@@ -153,3 +153,12 @@ def test_bad_arguments_are_refused():
     fp32 = sv.make_cfg(wl.ModelShape(2, 256, 4, 4, 64, 512, 300, dtype="fp32"), 4, 100, 5)
     with pytest.raises(sv.SpecError):
         sv.spec_k_plan_step(fp32, [1], 256)
+
+
+def test_chunks_follow_the_resident_wavefronts_of_the_128_dim_fused_variant():
+    """7B-shape (32 kv heads x 128): two chunks per pair as long as they fit the 1024 wavefronts the chip
+    holds of that variant (or overflow them by at least three quarters); one chunk in between."""
+    for B, chunks in ((8, 2), (16, 2), (18, 1), (20, 1), (24, 1), (27, 1), (28, 2), (32, 2), (48, 2)):
+        cfg = sv.make_cfg(wl.SEVEN_B, B, 2054, 5)
+        p = sv.spec_k_plan_step(cfg, [5] * B, 256, False)
+        assert p.attn_chunks == chunks, (B, p.attn_chunks)
