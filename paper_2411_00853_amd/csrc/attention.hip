@@ -641,7 +641,8 @@ AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count,
     if (chunks < 1) chunks = 1;
     // Never a single chunk for a long cache: the wavefront whose chunk holds the window first puts the
     // window's keys and values together (4-8 us), and with two chunks per pair the other half of the
-    // wavefronts stream meanwhile (batch 32 at 512..4096 positions: attention -2.8 %).
+    // wavefronts stream meanwhile (plan_launch makes the one exception, where two chunks would not all
+    // be resident).
     if (chunks < 2 && max_kv_len >= 1024) chunks = 2;
     if (paged && chunks < (max_kv_len + 2047) / 2048) chunks = (max_kv_len + 2047) / 2048;   // 64 blocks per wavefront
     if (chunks > g_max_chunks) chunks = g_max_chunks;   // (16 unless set: the merge walks a row's chunks one after the other)
@@ -740,15 +741,15 @@ static AttnLaunchPlan plan_launch(const CacheGeom& g, bool paged, int n_q_heads,
     lp.p = plan_attention(max_kv_len, B, g.n_kv_heads * lp.share, cu_count, paged);
     // The variant that puts queries, keys and values together itself needs, at 128-dim heads, more than
     // half a SIMD's registers (the prologue parks values in the accumulation registers): one wavefront
-    // per SIMD, 4 per compute unit.  Two chunks per pair that overflow those slots by a quarter to three
-    // quarters run as a full round plus a thin one; one chunk per pair, all resident at once, is faster
-    // (7B-shape, 2048 positions, attention per layer: batch 20 161 -> 140 us, batch 24 176 -> 163, batch
-    // 28 and 32 within 2 %; from batch 40 on two chunks win again).
+    // per SIMD, 4 per compute unit.  Where two chunks per pair overflow those slots and one chunk per pair
+    // fits them, one chunk, all wavefronts resident at once, is faster (7B-shape, 2048 positions,
+    // attention per layer: batch 20 161 -> 140 us, batch 24 176 -> 163, batch 28 and 32 -2 %; 32 sequences
+    // of 512..4096 positions 8.74 -> 8.55 ms per step; from batch 40 on, where neither fits, two chunks win).
     {
         const long pairs = (long)B * g.n_kv_heads * lp.share, slots = 4L * cu_count;
         const int rt1 = ((kmax + 1) * (group / lp.share) + 15) / 16;
         if (g.head_dim == 128 && rt1 == 1 && lp.p.max_chunks == 2 && lp.p.chunk_keys >= 192 && !lp.small && !paged
-            && !g_max_chunks_set && g_items_per_cu == 0 && pairs <= slots && 2 * pairs > slots && 8 * pairs < 7 * slots) {
+            && !g_max_chunks_set && g_items_per_cu == 0 && pairs <= slots && 2 * pairs > slots) {
             lp.p.chunk_keys = (max_kv_len + 31) / 32 * 32;
             lp.p.max_chunks = 1;
         }

@@ -129,7 +129,7 @@ def test_plans_of_the_named_configurations():
     cfg, p = _plan(w.shape, list(w.lookahead), w.batch, w.max_kv_len, w.max_lookahead)
     assert p.rows == sum(k + 1 for k in w.lookahead) and p.n_passes == 1
     assert list(p.gemm_row_tiles) == [10] * 5 and list(p.gemm_row_parts) == [2] * 5
-    assert (p.attn_kv_share, p.attn_small, p.attn_chunks, p.attn_wavefronts) == (1, 0, 2, 2)
+    assert (p.attn_kv_share, p.attn_small, p.attn_chunks, p.attn_wavefronts) == (1, 0, 1, 1)
 
 
 def test_steps_beyond_one_pass_and_beyond_64_rows_per_kv_head():
@@ -157,8 +157,8 @@ def test_bad_arguments_are_refused():
 
 def test_chunks_follow_the_resident_wavefronts_of_the_128_dim_fused_variant():
     """7B-shape (32 kv heads x 128): two chunks per pair as long as they fit the 1024 wavefronts the chip
-    holds of that variant (or overflow them by at least three quarters); one chunk in between."""
-    for B, chunks in ((8, 2), (16, 2), (18, 1), (20, 1), (24, 1), (27, 1), (28, 2), (32, 2), (48, 2)):
+    holds of that variant, one chunk where only that fits them, two again where neither does."""
+    for B, chunks in ((8, 2), (16, 2), (18, 1), (20, 1), (24, 1), (27, 1), (28, 1), (32, 1), (33, 2), (48, 2)):
         cfg = sv.make_cfg(wl.SEVEN_B, B, 2054, 5)
         p = sv.spec_k_plan_step(cfg, [5] * B, 256, False)
         assert p.attn_chunks == chunks, (B, p.attn_chunks)
