@@ -247,7 +247,7 @@ def bench_decode(args, torch, sv, wl):
     R, W = args.steps, max(args.warmup, 2)
     n_cal = 3
     rounds_total = R + W
-    max_kv = n0 + (rounds_total + 2 * n_cal + 2) * (Kt + 1) + 8
+    max_kv = n0 + (rounds_total + 3 * n_cal + 2) * (Kt + 1) + 8
     t_setup = time.time()
     tg, tg_len, keep_t = synthetic_model(sv, wl, torch, wl.SEVEN_B, wl.SEED_BASE + 2, B, max_kv, Kt, [n0] * B)
     d_shape = wl.SEVEN_B_DRAFT if args.draft == "config" else wl.ONE_B
@@ -260,7 +260,7 @@ def bench_decode(args, torch, sv, wl):
     slots = torch.arange(B, dtype=torch.int32, device="cuda")
     prev = rng.randint(wl.S_TOKENS + 1, (B,), V).to(torch.int32)
     last = rng.randint(wl.S_TOKENS + 2, (B,), V).to(torch.int32)
-    n_u = rounds_total + 2 * n_cal
+    n_u = rounds_total + 3 * n_cal
     du = rng.uniform(wl.S_UNIFORMS + 1, (n_u, B, Kt))
     vu = rng.uniform(wl.S_UNIFORMS + 2, (n_u, B, Kt + 1))
 
@@ -326,6 +326,45 @@ def bench_decode(args, torch, sv, wl):
     dyn_emitted = c1[2] - c0[2]
     alpha_hat = sum(ctl.accept(b) for b in range(B)) / B
     ctl.close()
+
+    # ---- the controller also giving every sequence a window of its own (rows priced at what a unit of
+    # window costs the verification: rounds with Kt draft steps, windows of Kt against windows of 1) ----
+    restart()
+    sv.spec_decode_begin(dec, slots, prev, last)
+
+    def timed_windows(win, r0, n):
+        torch.cuda.synchronize()
+        tic = time.perf_counter()
+        for r in range(r0, r0 + n):
+            sv.spec_decode_round(dec, Kt, du[r], vu[r], T, lookahead_per_seq=[win] * B)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - tic) / n * 1e3
+
+    w_full, w_one = timed_windows(Kt, 0, n_cal), timed_windows(1, n_cal, n_cal)
+    row_ms = max((w_full - w_one) / (Kt - 1), 0.0)
+    ctl = sv.Lookahead(B, draft_ms=max(slope - row_ms, 0.0), verify_ms=max(t1 - slope, 1e-3), verify_ms_per_token=row_ms,
+                       k_min=1, k_max=Kt)
+    k_now, win = ctl.next_per_seq()
+    for r in range(2 * n_cal, 2 * n_cal + W):
+        sv.spec_decode_round(dec, k_now, du[r], vu[r], T, lookahead_per_seq=win)
+        ctl.update_per_seq(sv.device_array(view.n_accepted, (B,), torch.int32).cpu().tolist(), win)
+        k_now, win = ctl.next_per_seq()
+    c0 = counters(dec)
+    wins, ks2 = [], []
+    tic = time.perf_counter()
+    for r in range(2 * n_cal + W, 2 * n_cal + W + R):
+        sv.spec_decode_round(dec, k_now, du[r], vu[r], T, lookahead_per_seq=win)
+        ks2.append(k_now)
+        wins.extend(win)
+        ctl.update_per_seq(sv.device_array(view.n_accepted, (B,), torch.int32).cpu().tolist(), win)
+        k_now, win = ctl.next_per_seq()
+    torch.cuda.synchronize()
+    t_win = time.perf_counter() - tic
+    c1 = counters(dec)
+    sv.spec_verify_poll(tg)
+    sv.spec_verify_poll(dr)
+    win_emitted = c1[2] - c0[2]
+    ctl.close()
     dec.close()
 
     # ---- plain sampling from the target from the same starting point ----
@@ -343,7 +382,7 @@ def bench_decode(args, torch, sv, wl):
     t_base = time.perf_counter() - tic
     sv.spec_verify_poll(tg)
     base.close()
-    spec_tps, base_tps, dyn_tps = emitted / t_spec, B * R / t_base, dyn_emitted / t_dyn
+    spec_tps, base_tps, dyn_tps, win_tps = emitted / t_spec, B * R / t_base, dyn_emitted / t_dyn, win_emitted / t_win
     print(json.dumps({
         "metric": "emitted tokens/sec, speculative decoding loop", "value": spec_tps, "unit": "tokens/s", "n_gpus": 1,
         "steps": R, "warmup": W, "ms_per_step": t_spec / R * 1e3, "higher_is_better": True, "scaling": "weak",
@@ -357,6 +396,12 @@ def bench_decode(args, torch, sv, wl):
                        "speedup_over_fixed_K": dyn_tps / spec_tps, "mean_K": sum(ks) / len(ks),
                        "K_histogram": {str(k): ks.count(k) for k in sorted(set(ks))},
                        "estimated_acceptance": alpha_hat, "cost_model_ms": {"per_K": slope, "fixed": t1 - slope}},
+        "controller_windows_per_sequence": {
+            "tokens_per_s": win_tps, "speedup_over_plain_sampling": win_tps / base_tps,
+            "speedup_over_one_K_controller": win_tps / dyn_tps, "mean_K": sum(ks2) / len(ks2),
+            "mean_window": sum(wins) / len(wins), "window_histogram": {str(k): wins.count(k) for k in sorted(set(wins))},
+            "row_cost_ms_per_unit_window": row_ms,
+            "round_ms_windows_of_Kt": w_full, "round_ms_windows_of_1": w_one},
         "roofline": None, "cpu_baseline": None}), flush=True)
     tg.close()
     dr.close()

@@ -66,6 +66,12 @@ typedef struct {
                                        the draft's most likely token, the verification is the greedy rule of
                                        spec_verify_step, and neither uniforms array is read (the emitted
                                        text is then the target's greedy text whatever the draft proposes) */
+    const int32_t* lookahead_per_seq; /* optional HOST int32[batch]: K_b in 0..lookahead, the proposals of
+                                       sequence b that are put to the target (the draft still runs
+                                       `lookahead` steps for the whole batch; the rest of a sequence's
+                                       proposals are dropped).  NULL: K_b = lookahead for every sequence.
+                                       Rows of target_logits and uniforms follow spec_verify_step: sequence b
+                                       has K_b + 1 rows, its final draw reads verify_uniforms[b][K_b] */
 } spec_round_args;
 
 /* Queue one round.  Launches only; reads nothing back. */
@@ -102,11 +108,18 @@ int spec_decode_get_view(spec_decoder* d, spec_decode_view* out);
  * tested if a_b < K, else K:   tested_b <- forget * tested_b + min(a_b + 1, K),
  * kept_b <- forget * kept_b + a_b.  Sequences with a_b < 0 (skipped) are left alone.
  * All host-side, double precision, no device access: the caller copies n_accepted back itself.
- * One K per round for the whole batch, not one per sequence: the draft steps and the verification
- * are launched for the batch and their cost is set by the longest window, so a sequence gains
- * nothing by proposing fewer tokens than its neighbours; the estimates are kept per sequence because
- * tokens(K) is a sum over sequences with different alpha_b.  (spec_verify_step itself takes a
- * lookahead per sequence; a caller that wants ragged windows passes them there.) */
+ * One K per round for the whole batch sets the number of draft steps: those are launched for the batch
+ * and cost what the longest window costs; the estimates are kept per sequence because tokens(K) is a
+ * sum over sequences with different alpha_b.
+ * On top of that K the controller can give every sequence a window of its own (spec_lookahead_next_per_seq,
+ * for spec_round_args.lookahead_per_seq): with rate = tokens(K) / cost(K) of the chosen K, proposal k of
+ * sequence b is put to the target only while the chance that it is reached and kept, alpha_b^k, is
+ * worth the verification row it costs at that rate:
+ *     K_b = the largest k in [1, K] with alpha_b^k >= rate * verify_ms_per_token / batch, else 1
+ * (the verification's cost per unit of K is shared by the batch's rows; at least one proposal is always
+ * tested, or a sequence that fell behind could never show that it has recovered).  With the costs measured on
+ * this hardware a row is so cheap next to a draft step that K_b = K almost always: what adapts to the
+ * data is the one K; the per-sequence windows are there for cost models where rows are dear. */
 typedef struct {
     double draft_ms;             /* cost of one draft decode step for the batch */
     double verify_ms;            /* cost of a verification with an empty window (K = 0) */
@@ -125,6 +138,11 @@ void spec_lookahead_destroy(spec_lookahead* c);
 int spec_lookahead_update(spec_lookahead* c, const int32_t* n_accepted, int32_t K);
 /* K for the next round (k_min..k_max), or a negative status */
 int32_t spec_lookahead_next(const spec_lookahead* c);
+/* The same K, and in K_out (HOST int32[batch]) every sequence's own window 1..K (rule above). */
+int32_t spec_lookahead_next_per_seq(const spec_lookahead* c, int32_t* K_out);
+/* After a round with windows of their own: as spec_lookahead_update with K_b in place of K
+ * (K_per_seq: HOST int32[batch], each 0..SPEC_MAX_LOOKAHEAD; a sequence with K_b = 0 tested nothing). */
+int spec_lookahead_update_per_seq(spec_lookahead* c, const int32_t* n_accepted, const int32_t* K_per_seq);
 /* current estimate alpha_b of one sequence (diagnostics); NaN if out of range */
 double spec_lookahead_accept(const spec_lookahead* c, int32_t b);
 

@@ -157,3 +157,29 @@ class LookaheadRule:
             if rate > best:
                 best, best_k = rate, K
         return best_k
+
+    def next_per_seq(self):
+        """The batch's K and every sequence's own window (at least 1): proposal k is put to the target
+        while alpha_b^k >= rate * verify_ms_per_token / batch (rate = predicted tokens per ms at that K)."""
+        d, v, vt = self.c
+        K = self.next()
+        rate = self.expected_tokens(K) / (K * d + v + K * vt)
+        worth = rate * vt / len(self.tested)
+        out = []
+        for b in range(len(self.tested)):
+            al, reach, kb = self.accept(b), 1.0, 1          # one proposal is always tested
+            for k in range(1, K + 1):
+                reach *= al
+                if reach >= worth:
+                    kb = k
+                else:
+                    break
+            out.append(kb)
+        return K, out
+
+    def update_per_seq(self, n_accepted, K_per_seq):
+        for b, (a, K) in enumerate(zip(n_accepted, K_per_seq)):
+            if a < 0:
+                continue
+            self.tested[b] = self.forget * self.tested[b] + float(min(a + 1, K))
+            self.kept[b] = self.forget * self.kept[b] + float(a)

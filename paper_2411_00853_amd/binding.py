@@ -67,7 +67,7 @@ class spec_decode_cfg(C.Structure):
 
 class spec_round_args(C.Structure):
     _fields_ = [("lookahead", C.c_int32), ("draft_uniforms", C.c_void_p), ("verify_uniforms", C.c_void_p),
-                ("temperature", C.c_float)]
+                ("temperature", C.c_float), ("lookahead_per_seq", C.POINTER(C.c_int32))]
 
 
 class spec_lookahead_cfg(C.Structure):
@@ -169,6 +169,9 @@ def lib():
         L.spec_lookahead_update.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
         L.spec_lookahead_next.argtypes = [C.c_void_p]
         L.spec_lookahead_next.restype = C.c_int32
+        L.spec_lookahead_next_per_seq.restype = C.c_int32
+        L.spec_lookahead_next_per_seq.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        L.spec_lookahead_update_per_seq.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.spec_lookahead_accept.argtypes = [C.c_void_p, C.c_int32]
         L.spec_lookahead_accept.restype = C.c_double
         _lib = L
@@ -397,9 +400,12 @@ def spec_decode_begin(d: Decoder, seq_slot: torch.Tensor, prev_token: Optional[t
 
 
 def spec_decode_round(d: Decoder, lookahead: int, draft_uniforms: Optional[torch.Tensor],
-                      verify_uniforms: torch.Tensor, temperature: float, stream=None):
+                      verify_uniforms: torch.Tensor, temperature: float, stream=None, lookahead_per_seq=None):
+    per = None
+    if lookahead_per_seq is not None:
+        per = (C.c_int32 * len(lookahead_per_seq))(*[int(k) for k in lookahead_per_seq])
     args = spec_round_args(int(lookahead), _ptr(draft_uniforms, torch.float32), _ptr(verify_uniforms, torch.float32),
-                           float(temperature))
+                           float(temperature), per)
     _check(lib().spec_decode_round(d.ptr, C.byref(args), _stream(stream)))
 
 
@@ -430,6 +436,19 @@ class Lookahead:
         if k < 0:
             raise SpecError(k, last_error())
         return k
+
+    def next_per_seq(self):
+        """(K of the round, [K_b per sequence])"""
+        out = (C.c_int32 * self.batch)()
+        k = int(lib().spec_lookahead_next_per_seq(self.ptr, out))
+        if k < 0:
+            raise SpecError(k, last_error())
+        return k, list(out)
+
+    def update_per_seq(self, n_accepted: Sequence[int], K_per_seq: Sequence[int]):
+        arr = (C.c_int32 * self.batch)(*[int(v) for v in n_accepted])
+        ks = (C.c_int32 * self.batch)(*[int(v) for v in K_per_seq])
+        _check(lib().spec_lookahead_update_per_seq(self.ptr, arr, ks))
 
     def accept(self, b: int) -> float:
         return float(lib().spec_lookahead_accept(self.ptr, int(b)))

@@ -264,6 +264,11 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
         return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: a decoder without a draft model runs lookahead 0 only");
     }
     if (!(args->temperature >= 0.f)) return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: temperature must be >= 0");
+    if (args->lookahead_per_seq)
+        for (int b = 0; b < B; ++b)
+            if (args->lookahead_per_seq[b] < 0 || args->lookahead_per_seq[b] > K)
+                return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: lookahead_per_seq[%d] = %d outside 0..%d", b,
+                            args->lookahead_per_seq[b], K);
     const bool greedy = args->temperature == 0.f;
     if (!greedy && !args->verify_uniforms) return fail(SPEC_ERR_INVALID_ARG, "spec_decode_round: verify_uniforms is NULL");
     hipStream_t s = (hipStream_t)stream;
@@ -311,8 +316,13 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
     }
 
     memset(&ks, 0, sizeof(ks));
-    for (int b = 0; b < B; ++b) ks.k[b] = (uint8_t)K;
-    const int M = B * (K + 1);
+    int M = 0, n_stat = 0;
+    for (int b = 0; b < B; ++b) {
+        const int kb = args->lookahead_per_seq ? args->lookahead_per_seq[b] : K;
+        ks.k[b] = (uint8_t)kb;
+        M += kb + 1;
+        n_stat += 2 * kb + 1;
+    }
     rc = launch_prepare(tg->tables, ks, B, Kt, V, tg->cfg.max_batch, tg->cfg.max_kv_len, true, d->seq_slot, d->last_tok,
                         d->draft_tokens, tg->kv_len, tg->flag, s);
     if (rc) return rc;
@@ -322,7 +332,7 @@ extern "C" int spec_decode_round(spec_decoder* d, const spec_round_args* args, v
         rc = launch_greedy(tg->tables, tg->sampler, ks, B, Kt, V, M, tg->logits, d->draft_tokens, 1, tg->kv_len,
                            d->n_accepted, d->round_out, nullptr, &tg->prof, s);
     else
-        rc = launch_sampler(tg->tables, tg->sampler, ks, B, Kt, V, B * (2 * K + 1), tg->logits, d->draft_logits,
+        rc = launch_sampler(tg->tables, tg->sampler, ks, B, Kt, V, n_stat, tg->logits, d->draft_logits,
                             d->draft_tokens, args->verify_uniforms, Kt + 1, args->temperature, 1, tg->kv_len,
                             d->n_accepted, d->round_out, nullptr, &tg->prof, s);
     if (rc) return rc;

@@ -56,9 +56,10 @@ extern "C" int spec_lookahead_update(spec_lookahead* c, const int32_t* n_accepte
     return SPEC_OK;
 }
 
-extern "C" int32_t spec_lookahead_next(const spec_lookahead* c)
+namespace {
+// the K with the best predicted tokens per millisecond, and that rate
+int best_k(const spec_lookahead* c, double* rate_out)
 {
-    if (!c) return fail(SPEC_ERR_INVALID_ARG, "spec_lookahead_next: NULL argument");
     int best_k = c->cfg.k_min;
     double best = -1.0;
     for (int K = c->cfg.k_min; K <= c->cfg.k_max; ++K) {
@@ -73,7 +74,54 @@ extern "C" int32_t spec_lookahead_next(const spec_lookahead* c)
             best_k = K;
         }
     }
+    if (rate_out) *rate_out = best;
     return best_k;
+}
+}  // namespace
+
+extern "C" int32_t spec_lookahead_next(const spec_lookahead* c)
+{
+    if (!c) return fail(SPEC_ERR_INVALID_ARG, "spec_lookahead_next: NULL argument");
+    return best_k(c, nullptr);
+}
+
+extern "C" int32_t spec_lookahead_next_per_seq(const spec_lookahead* c, int32_t* K_out)
+{
+    if (!c || !K_out) return fail(SPEC_ERR_INVALID_ARG, "spec_lookahead_next_per_seq: NULL argument");
+    double rate = 0.0;
+    const int K = best_k(c, &rate);
+    const double worth = rate * c->cfg.verify_ms_per_token / (double)c->tested.size();
+    for (size_t b = 0; b < c->tested.size(); ++b) {
+        const double al = alpha_of(c, (int)b);
+        int kb = 1;                               // one proposal is always tested
+        double reach = 1.0;                       // alpha_b^k
+        for (int k = 1; k <= K; ++k) {
+            reach *= al;
+            if (reach >= worth) kb = k;
+            else break;
+        }
+        K_out[b] = kb;
+    }
+    return K;
+}
+
+extern "C" int spec_lookahead_update_per_seq(spec_lookahead* c, const int32_t* n_accepted, const int32_t* K_per_seq)
+{
+    if (!c || !n_accepted || !K_per_seq) return fail(SPEC_ERR_INVALID_ARG, "spec_lookahead_update_per_seq: NULL argument");
+    for (size_t b = 0; b < c->tested.size(); ++b) {
+        const int a = n_accepted[b], K = K_per_seq[b];
+        if (K < 0 || K > SPEC_MAX_LOOKAHEAD)
+            return fail(SPEC_ERR_INVALID_ARG, "spec_lookahead_update_per_seq: K_per_seq[%zu] = %d outside 0..%d", b, K, SPEC_MAX_LOOKAHEAD);
+        if (a > K) return fail(SPEC_ERR_INVALID_ARG, "spec_lookahead_update_per_seq: n_accepted[%zu] = %d exceeds K = %d", b, a, K);
+    }
+    for (size_t b = 0; b < c->tested.size(); ++b) {
+        const int a = n_accepted[b], K = K_per_seq[b];
+        if (a < 0) continue;
+        const int tested = a + 1 < K ? a + 1 : K;
+        c->tested[b] = c->cfg.forget * c->tested[b] + (double)tested;
+        c->kept[b] = c->cfg.forget * c->kept[b] + (double)a;
+    }
+    return SPEC_OK;
 }
 
 extern "C" double spec_lookahead_accept(const spec_lookahead* c, int32_t b)

@@ -55,7 +55,7 @@ class Pair:
                              torch.tensor([c[-2] for c in contexts], dtype=torch.int32, device=dev),
                              torch.tensor([c[-1] for c in contexts], dtype=torch.int32, device=dev))
 
-    def view(self, K):
+    def view(self, K, rows=None):
         sv, v, B, Kt, V = self.sv, self.sv.spec_decode_get_view(self.dec), self.B, self.Kt, self.tg.shape.vocab
         get = lambda p, shape, dt: sv.device_array(p, shape, dt).cpu()
         out = {
@@ -64,7 +64,7 @@ class Pair:
             "n_accepted": get(v.n_accepted, (B,), torch.int32),
             "draft_tokens": get(v.draft_tokens, (B, Kt), torch.int32),
             "draft_logits": get(v.draft_logits, (B, Kt, V), torch.float32),
-            "target_logits": get(v.target_logits, (B * (K + 1), V), torch.float32),
+            "target_logits": get(v.target_logits, (rows if rows is not None else B * (K + 1), V), torch.float32),
             "prev": get(v.prev_token, (B,), torch.int32),
             "last": get(v.last_token, (B,), torch.int32),
             "counters": get(v.counters, (3,), torch.int64),
@@ -72,19 +72,22 @@ class Pair:
         torch.cuda.synchronize()
         return out
 
-    def round(self, K, du, vu, T):
-        self.sv.spec_decode_round(self.dec, K, du.cuda(), vu.cuda(), T)
+    def round(self, K, du, vu, T, per_seq=None):
+        self.sv.spec_decode_round(self.dec, K, du.cuda(), vu.cuda(), T, lookahead_per_seq=per_seq)
         torch.cuda.synchronize()
         self.sv.spec_verify_poll(self.tg.h)
         self.sv.spec_verify_poll(self.dr.h)
-        return self.view(K)
+        return self.view(K, None if per_seq is None else sum(k + 1 for k in per_seq))
 
 
-def follow_round(pair, g, K, du, vu, T, chk, tally):
-    """Make the oracle take the round the GPU took (g = the GPU's view after it) and compare."""
+def follow_round(pair, g, K, du, vu, T, chk, tally, per_seq=None):
+    """Make the oracle take the round the GPU took (g = the GPU's view after it) and compare.
+    per_seq: the proposals of each sequence that were put to the target (all K by default)."""
     from helpers import CDF_MARGIN
     tol = LOGIT_TOL[pair.tg.shape.dtype]
+    row0 = 0
     for b, st in enumerate(pair.states):
+        Kb = K if per_seq is None else per_seq[b]
         L = len(st.tokens)
         a = int(g["n_accepted"][b])
         props = g["draft_tokens"][b, :K].tolist()
@@ -107,8 +110,10 @@ def follow_round(pair, g, K, du, vu, T, chk, tally):
             cur = props[i]
         st.draft_len = L - 1 + K
         # ---- target side ---------------------------------------------------------------------
+        props = props[:Kb]                      # the rest of the draft's proposals were dropped
         want = pair.tg.om.verify_sequential(st.target_cache, L - 1, [st.tokens[-1]] + props)
-        got = g["target_logits"][b * (K + 1):(b + 1) * (K + 1)]
+        got = g["target_logits"][row0:row0 + Kb + 1]
+        row0 += Kb + 1
         err = (want - got).abs().max().item()
         tally["target_err"] = max(tally["target_err"], err)
         assert err <= tol, f"target logits of sequence {b}: max-abs error {err}"
@@ -116,7 +121,7 @@ def follow_round(pair, g, K, du, vu, T, chk, tally):
         n_out = int(g["n_tokens"][b])
         emitted = g["tokens"][b, n_out - (a + 1):n_out].tolist()
         out_gpu = emitted + [-1] * (pair.Kt - a)
-        chk.compare(got.contiguous(), g["draft_logits"][b].contiguous(), props, vu[b, :K + 1].tolist(), T, a, out_gpu,
+        chk.compare(got.contiguous(), g["draft_logits"][b].contiguous(), props, vu[b, :Kb + 1].tolist(), T, a, out_gpu,
                     pair.Kt)
         # ---- bookkeeping ---------------------------------------------------------------------
         assert emitted[:a] == props[:a]
@@ -131,7 +136,7 @@ def follow_round(pair, g, K, du, vu, T, chk, tally):
         assert kt[b] == len(st.tokens) - 1 and kd[b] == len(st.tokens) - 2
 
 
-def run_following(t_shape, d_shape, contexts, K, Kt, rounds, T, seed, paged=None):
+def run_following(t_shape, d_shape, contexts, K, Kt, rounds, T, seed, paged=None, per_seq=None):
     from helpers import SamplerCheck
     pair = Pair(t_shape, d_shape, contexts, 96, Kt, 64, seed=seed, paged=paged)
     chk = SamplerCheck()
@@ -145,13 +150,14 @@ def run_following(t_shape, d_shape, contexts, K, Kt, rounds, T, seed, paged=None
         K = Ks[r]
         du = rng.uniform(wl.S_UNIFORMS + 10 + 2 * r, (B, Kt))
         vu = rng.uniform(wl.S_UNIFORMS + 11 + 2 * r, (B, Kt + 1))
-        g = pair.round(K, du, vu, T)
-        follow_round(pair, g, K, du, vu, T, chk, tally)
+        ps = per_seq[r] if per_seq is not None else None
+        g = pair.round(K, du, vu, T, per_seq=ps)
+        follow_round(pair, g, K, du, vu, T, chk, tally, per_seq=ps)
         kept += int(g["n_accepted"].sum())
         c = g["counters"].tolist()
         assert c[0] == B * (r + 1) and c[1] == kept and c[2] == kept + B * (r + 1)
     # the generated text is in the output lists
-    g = pair.view(K)
+    g = pair.view(0)
     for b, st in enumerate(pair.states):
         n = int(g["n_tokens"][b])
         assert g["tokens"][b, :n].tolist() == st.tokens[len(contexts[b]):]
@@ -201,6 +207,26 @@ def test_rounds_with_more_rows_than_one_decoder_pass(B, K):
     assert chk.exact_accept + chk.margin_accept == 2 * B
     assert tally["draft_err"] < 5e-3 and tally["target_err"] < 5e-3
     assert 0 < kept < 2 * B * K
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_rounds_with_a_lookahead_of_its_own_for_every_sequence(dtype):
+    """The draft proposes K tokens for the whole batch, each sequence puts only its own K_b of them to the
+    target (0 = none: the sequence just draws its next token from the target): ragged verification
+    windows inside the round, the oracle following every row, draw and decision, lengths included."""
+    V = 300 if dtype == "fp32" else 1000
+    t_shape = wl.ModelShape(2, 256, 8, 2, 64, 512, V, dtype=dtype)
+    d_shape = wl.ModelShape(1, 128, 2, 1, 64, 256, V, dtype=dtype)
+    contexts = CONTEXTS + [[3, 1, 4, 1, 5, 9, 2, 6], [8, 8]]
+    per = [[5, 0, 3, 1, 2], [0, 5, 5, 2, 4], [4, 4, 0, 0, 1], [1, 2, 3, 4, 4]]
+    Ks = [5, 5, 4, 4]
+    pair, chk, tally, kept = run_following(t_shape, d_shape, contexts, K=Ks, Kt=5, rounds=4, T=0.9, seed=61, per_seq=per)
+    assert chk.exact_accept + chk.margin_accept == 4 * 5
+    assert kept <= sum(sum(p) for p in per)
+    from paper_2411_00853_amd import binding as sv
+    du = torch.zeros((5, 5)); vu = torch.zeros((5, 6))
+    with pytest.raises(sv.SpecError):
+        pair.round(3, du, vu, 0.9, per_seq=[4, 0, 0, 0, 0])          # beyond the round's lookahead
 
 
 def test_free_running_text_equals_the_oracles_fp32():
@@ -321,14 +347,18 @@ def test_argument_errors():
         sv.spec_decode_round(dec, 0, None, torch.zeros(2, 3, device="cuda"), 1.0)   # no active batch
 
 
-@pytest.mark.parametrize("T,cost", [(1.0, (0.4, 5.0, 0.05)), (2.5, (0.4, 5.0, 0.05)), (2.5, (1.0, 4.0, 0.05))])
-def test_lookahead_controller_in_the_loop_fp32(T, cost):
+@pytest.mark.parametrize("T,cost,per_seq", [(1.0, (0.4, 5.0, 0.05), False), (2.5, (0.4, 5.0, 0.05), False),
+                                             (2.5, (1.0, 4.0, 0.05), False), (2.5, (0.4, 5.0, 1.0), True),
+                                             (1.5, (0.4, 5.0, 1.5), True)])
+def test_lookahead_controller_in_the_loop_fp32(T, cost, per_seq):
     """The lookahead follows the data inside the loop: every round's K is what the library's
     controller (spec_lookahead_next) chooses from the kept counts the GPU reported so far.  The oracle
     runs its own loop from the same start, its K chosen by its own rule (oracle.decode.LookaheadRule)
     from its own results.  The sequence of K, the kept counts, the generated text and the acceptance
     estimates must be the same, for as long as no decision of the oracle's run was closer to its
-    threshold than the margins a 1e-4 logit difference can move."""
+    threshold than the margins a 1e-4 logit difference can move.
+    per_seq: every sequence also gets a window of its own (spec_lookahead_next_per_seq, with a cost model
+    in which verification rows are dear, so that the windows do differ)."""
     from paper_2411_00853_amd import binding as sv
     t_shape = wl.ModelShape(2, 256, 4, 4, 64, 512, 300, dtype="fp32")
     d_shape = wl.ModelShape(1, 128, 2, 2, 64, 256, 300, dtype="fp32")
@@ -343,11 +373,19 @@ def test_lookahead_controller_in_the_loop_fp32(T, cost):
     vu = [rng.uniform(wl.S_UNIFORMS + 200 + r, (B, Kt + 1)) for r in range(R)]
     # ---- the GPU's loop, controller in it ----
     ks_gpu, kept_gpu, est_gpu = [], [], []
+    win_gpu = []
     for r in range(R):
-        k = ctl.next()
-        g = pair.round(k, du[r], vu[r], T)
-        a = g["n_accepted"].tolist()
-        ctl.update(a, k)
+        if per_seq:
+            k, win = ctl.next_per_seq()
+            g = pair.round(k, du[r], vu[r], T, per_seq=win)
+            a = g["n_accepted"].tolist()
+            ctl.update_per_seq(a, win)
+        else:
+            k, win = ctl.next(), None
+            g = pair.round(k, du[r], vu[r], T)
+            a = g["n_accepted"].tolist()
+            ctl.update(a, k)
+        win_gpu.append(win)
         ks_gpu.append(k)
         kept_gpu.append(a)
         est_gpu.append([ctl.accept(b) for b in range(B)])
@@ -358,17 +396,24 @@ def test_lookahead_controller_in_the_loop_fp32(T, cost):
     # decisions the comparison goes on, otherwise the two runs have parted for good and it ends.
     rounds_same, rounds_clear, pos = 0, 0, [0] * B
     for r in range(R):
-        k = rule.next()
-        traces = [od.speculative_round(pair.tg.om, pair.dr.om, st, k, T, du[r][b].tolist(), vu[r][b].tolist())
+        if per_seq:
+            k, win = rule.next_per_seq()
+        else:
+            k, win = rule.next(), [0] * B
+            win = [k] * B
+        traces = [od.speculative_round(pair.tg.om, pair.dr.om, st, win[b], T, du[r][b].tolist(), vu[r][b].tolist())
                   for b, st in enumerate(pair.states)]
-        rule.update([t.n_accepted for t in traces], k)
+        if per_seq:
+            rule.update_per_seq([t.n_accepted for t in traces], win)
+        else:
+            rule.update([t.n_accepted for t in traces], k)
         close = False
         for b, t in enumerate(traces):
             gaps = [min(d.final_target - d.final_cdf_lo, d.final_cdf_hi - d.final_target) for d in t.draft_diags]
             gaps.append(min(t.diag.final_target - t.diag.final_cdf_lo, t.diag.final_cdf_hi - t.diag.final_target))
-            margins = [abs(float(vu[r][b, i]) - t.diag.accept_ratio[i]) for i in range(min(t.n_accepted + 1, k))]
+            margins = [abs(float(vu[r][b, i]) - t.diag.accept_ratio[i]) for i in range(min(t.n_accepted + 1, win[b]))]
             close |= min(gaps) < 5e-5 or (bool(margins) and min(margins) < 1e-3)
-        same = ks_gpu[r] == k and kept_gpu[r] == [t.n_accepted for t in traces] and all(
+        same = ks_gpu[r] == k and (not per_seq or win_gpu[r] == win) and kept_gpu[r] == [t.n_accepted for t in traces] and all(
             text_gpu[b][pos[b]:pos[b] + len(t.emitted)] == t.emitted for b, t in enumerate(traces))
         if not same:
             assert close, (f"round {r}: K {ks_gpu[r]} vs {k}, kept {kept_gpu[r]} vs {[t.n_accepted for t in traces]} "
@@ -380,6 +425,8 @@ def test_lookahead_controller_in_the_loop_fp32(T, cost):
         rounds_same += 1
         rounds_clear += not close
     assert rounds_same >= 5 and rounds_clear >= 2 and sum(pos) >= 20, (rounds_same, rounds_clear, pos)
-    if T > 1.0:
+    if T > 1.0 and not per_seq:
         assert len(set(ks_gpu[:rounds_same])) >= 2, f"the lookahead should have moved with the data: {ks_gpu}"
+    if per_seq:
+        assert any(len(set(w)) >= 2 for w in win_gpu[:rounds_same]), f"the windows should have differed: {win_gpu}"
     ctl.close()

@@ -82,6 +82,66 @@ def test_library_controller_equals_the_oracle_rule():
         lib_c.close()
 
 
+def test_windows_per_sequence_are_where_a_row_stops_paying():
+    """The per-sequence rule against a direct search: with everything else fixed, giving sequence b one
+    more row than K_b lowers the predicted rate of the round, one row fewer does not raise it beyond
+    rounding -- and where rows cost nothing every sequence keeps the whole K."""
+    rng = random.Random(5)
+    for trial in range(40):
+        B = rng.randint(2, 8)
+        d, v, vt = rng.uniform(0.2, 2.0), rng.uniform(2.0, 8.0), rng.uniform(0.2, 6.0)
+        rule = LookaheadRule(B, d, v, vt, 1, 10, prior_weight=1e9, prior_accept=0.5)
+        alphas = [rng.uniform(0.05, 0.95) for _ in range(B)]
+        rule.accept = lambda b, al=alphas: al[b]
+        K, ks = rule.next_per_seq()
+        assert all(1 <= k <= K for k in ks)
+
+        def rate(win):      # tokens per ms with the draft cost of K steps and rows paid one by one
+            tok = sum((1 - alphas[b] ** (win[b] + 1)) / (1 - alphas[b]) for b in range(B))
+            return tok / (K * d + v + vt * sum(win) / B)
+        r0 = rate(ks)
+        # the rule's threshold uses the rate of the uniform-K round, so it is a one-step answer: allow
+        # for the difference between the two rates when checking optimality
+        ref = rule.expected_tokens(K) / (K * d + v + K * vt)
+        for b in range(B):
+            if ks[b] < K:      # the next proposal's chance of counting is below what its row costs at the reference rate
+                assert alphas[b] ** (ks[b] + 1) < ref * vt / B
+            if ks[b] > 1:
+                assert alphas[b] ** ks[b] >= ref * vt / B
+        floor = [max(k, 1) for k in ks]
+        assert ks == floor
+    free = LookaheadRule(3, 1.0, 5.0, 0.0, 1, 8)
+    K, ks = free.next_per_seq()
+    assert ks == [K] * 3
+
+
+def test_library_controller_per_sequence_equals_the_oracle_rule():
+    rng = random.Random(7)
+    for trial in range(20):
+        B = rng.randint(1, 16)
+        args = dict(draft_ms=rng.uniform(0.1, 3.0), verify_ms=rng.uniform(1.0, 9.0),
+                    verify_ms_per_token=rng.uniform(0.0, 8.0), k_min=rng.randint(1, 3), k_max=rng.randint(3, 15),
+                    forget=rng.uniform(0.5, 1.0), prior_accept=rng.uniform(0.0, 1.0), prior_weight=rng.uniform(0.5, 8.0))
+        lib_c = sv.Lookahead(B, **args)
+        ref = LookaheadRule(B, **args)
+        alphas = [rng.random() for _ in range(B)]
+        ragged = 0
+        for _ in range(60):
+            K, ks = lib_c.next_per_seq()
+            assert (K, ks) == ref.next_per_seq()
+            ragged += any(k < K for k in ks)
+            na = [(-1 if rng.random() < 0.05 else simulate_round(rng, alphas[b], ks[b])) for b in range(B)]
+            lib_c.update_per_seq(na, ks)
+            ref.update_per_seq(na, ks)
+            for b in range(B):
+                assert lib_c.accept(b) == ref.accept(b)
+        lib_c.close()
+    c = sv.Lookahead(2, 1.0, 5.0, 0.1, 1, 5)
+    with pytest.raises(sv.SpecError):
+        c.update_per_seq([3, 0], [2, 5])        # more kept than proposed
+    c.close()
+
+
 def test_library_controller_rejects_bad_arguments():
     with pytest.raises(sv.SpecError):
         sv.Lookahead(4, 1.0, 5.0, 0.1, 0, 5)
