@@ -169,6 +169,23 @@ def test_1b_shape_full():
         rig.close()
 
 
+@pytest.mark.parametrize("hd,paged", [(64, False), (128, False), (64, True), (128, True)])
+def test_long_contexts_on_a_small_model(hd, paged):
+    """Caches of up to 32768 positions (the longest a paged handle takes: 16 chunks of 2048 positions, a
+    wavefront holding the page numbers of 64 blocks) on a small model: sequences of 30000, 17001 and 40
+    cached positions in one step, every row against the oracle, contiguous and paged."""
+    shape = wl.ModelShape(2, 256, 8, 2, hd, 512, 1000)
+    w = wl.Workload(f"long-{hd}", shape, 3, (30000, 17001, 40), (5, 3, 5), 5, 32768, 1.0, wl.SEED_BASE + 7000 + hd,
+                    "synthetic")
+    weights = BigWeights(shape, w.seed)
+    rig = BigRig(weights, w.batch, w.max_kv_len, w.max_lookahead, paged_lens=w.kv_lens if paged else None)
+    try:
+        worst, chk = _run_and_check(rig, w, w.name + ("-paged" if paged else ""))
+        assert worst < 5e-3
+    finally:
+        rig.close()
+
+
 @pytest.fixture(scope="module")
 def weights7b():
     return BigWeights(wl.SEVEN_B, wl.workload_7b().seed)
