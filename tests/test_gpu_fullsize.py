@@ -186,6 +186,18 @@ def test_long_contexts_on_a_small_model(hd, paged):
         rig.close()
 
 
+def test_a_hundred_thousand_positions_on_a_contiguous_cache():
+    """A contiguous bf16 cache has no chunk limit: 16 chunks of 8192 positions for a slot of 131072."""
+    shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
+    w = wl.Workload("long-100k", shape, 2, (100000, 513), (5, 2), 5, 131072, 1.0, wl.SEED_BASE + 7500, "synthetic")
+    rig = BigRig(BigWeights(shape, w.seed), w.batch, w.max_kv_len, w.max_lookahead)
+    try:
+        worst, chk = _run_and_check(rig, w, w.name)
+        assert worst < 5e-3
+    finally:
+        rig.close()
+
+
 @pytest.fixture(scope="module")
 def weights7b():
     return BigWeights(wl.SEVEN_B, wl.workload_7b().seed)
