@@ -644,8 +644,9 @@ AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count,
     // wavefronts stream meanwhile (plan_launch makes the one exception, where two chunks would not all
     // be resident).
     if (chunks < 2 && max_kv_len >= 1024) chunks = 2;
-    if (paged && chunks < (max_kv_len + 2047) / 2048) chunks = (max_kv_len + 2047) / 2048;   // 64 blocks per wavefront
     if (chunks > g_max_chunks) chunks = g_max_chunks;   // (16 unless set: the merge walks a row's chunks one after the other)
+    // a paged wavefront keeps the page numbers of at most 64 blocks, whatever that makes of the chunk count
+    if (paged && chunks < (max_kv_len + 2047) / 2048) chunks = (max_kv_len + 2047) / 2048;
     long keys = (max_kv_len + chunks - 1) / chunks;
     keys = (keys + 31) / 32 * 32;
     p.chunk_keys = (int)keys;
@@ -866,7 +867,7 @@ int launch_attention(int max_kv_len, int cu_count, const StepTables& t, const Lo
     const int n_items_kv = g.n_kv_heads * share;          // (sequence, kv head) work items per sequence
     const AttnPlan p = lp.p;
     if (g.table && p.chunk_keys > 2048)
-        return fail(SPEC_ERR_SHAPE, "paged attention handles chunks of up to 2048 positions (max_kv_len up to 32768)");
+        return fail(SPEC_ERR_SHAPE, "paged attention handles chunks of up to 2048 positions, this plan has %d", p.chunk_keys);
     const int group = n_q_heads / n_items_kv;             // query heads of one work item
     const int r_cap = group * max_window;
     const size_t part_need = (size_t)B * n_items_kv * p.max_chunks * r_cap * hd;

@@ -171,8 +171,8 @@ def test_1b_shape_full():
 
 @pytest.mark.parametrize("hd,paged", [(64, False), (128, False), (64, True), (128, True)])
 def test_long_contexts_on_a_small_model(hd, paged):
-    """Caches of up to 32768 positions (the longest a paged handle takes: 16 chunks of 2048 positions, a
-    wavefront holding the page numbers of 64 blocks) on a small model: sequences of 30000, 17001 and 40
+    """Caches of 32768 positions (on a page pool 16 chunks of 2048 positions, a wavefront holding the
+    page numbers of 64 blocks) on a small model: sequences of 30000, 17001 and 40
     cached positions in one step, every row against the oracle, contiguous and paged."""
     shape = wl.ModelShape(2, 256, 8, 2, hd, 512, 1000)
     w = wl.Workload(f"long-{hd}", shape, 3, (30000, 17001, 40), (5, 3, 5), 5, 32768, 1.0, wl.SEED_BASE + 7000 + hd,
@@ -186,11 +186,14 @@ def test_long_contexts_on_a_small_model(hd, paged):
         rig.close()
 
 
-def test_a_hundred_thousand_positions_on_a_contiguous_cache():
-    """A contiguous bf16 cache has no chunk limit: 16 chunks of 8192 positions for a slot of 131072."""
+@pytest.mark.parametrize("paged", [False, True])
+def test_a_hundred_thousand_positions(paged):
+    """A slot of 131072 positions: 16 chunks of 8192 on a contiguous cache; on a page pool, where a
+    wavefront keeps the page numbers of at most 64 blocks, 64 chunks of 2048 through the merge kernel."""
     shape = wl.ModelShape(2, 256, 8, 2, 64, 512, 1000)
     w = wl.Workload("long-100k", shape, 2, (100000, 513), (5, 2), 5, 131072, 1.0, wl.SEED_BASE + 7500, "synthetic")
-    rig = BigRig(BigWeights(shape, w.seed), w.batch, w.max_kv_len, w.max_lookahead)
+    rig = BigRig(BigWeights(shape, w.seed), w.batch, w.max_kv_len, w.max_lookahead,
+                 paged_lens=w.kv_lens if paged else None)
     try:
         worst, chk = _run_and_check(rig, w, w.name)
         assert worst < 5e-3

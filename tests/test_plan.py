@@ -60,14 +60,15 @@ def _check_invariants(shape, cfg, look, p, paged):
     assert group % p.attn_kv_share == 0 and (group // p.attn_kv_share) * window <= 64
     assert p.attn_row_tiles == -(-(group // p.attn_kv_share) * window // 16) and 1 <= p.attn_row_tiles <= 4
     assert p.attn_chunk_keys % 32 == 0 and p.attn_chunks * p.attn_chunk_keys >= cfg.max_kv_len
-    assert (p.attn_chunks - 1) * p.attn_chunk_keys < cfg.max_kv_len and 1 <= p.attn_chunks <= 16
+    assert (p.attn_chunks - 1) * p.attn_chunk_keys < cfg.max_kv_len and 1 <= p.attn_chunks
+    assert p.attn_chunks <= (16 if not paged else max(16, -(-cfg.max_kv_len // 2048)))
     assert p.attn_wavefronts in (0, 1, 2, 4, 8) and (p.attn_wavefronts == 0 or p.attn_chunks <= p.attn_wavefronts)
     if p.attn_wavefronts:                                   # chunk results of a workgroup fit 64 KiB of LDS
         assert p.attn_wavefronts * p.attn_row_tiles * 16 * (shape.head_dim + 2) * 4 <= 64 * 1024
     if p.attn_fused:
         assert not (shape.head_dim == 128 and p.attn_row_tiles >= 3) and p.attn_chunk_keys >= 192
     if paged:
-        assert p.attn_chunk_keys <= 2048 or cfg.max_kv_len > 32768
+        assert p.attn_chunk_keys <= 2048
     if p.attn_small:
         assert p.attn_chunks <= max(4, -(-cfg.max_kv_len // 2048) if paged else 1)
     assert p.attn_partial_floats <= p.attn_partial_capacity
@@ -89,7 +90,7 @@ def test_plans_respect_every_limit(seed):
         look = [r.randrange(0, kmax + 1) for _ in range(B)]
         look[r.randrange(B)] = kmax
         paged = r.random() < 0.3
-        max_kv_len = r.choice([64, 1030, 2054, 4107, 16384, 32768])
+        max_kv_len = r.choice([64, 1030, 2054, 4107, 16384, 32768, 131072])
         if max_kv_len < kmax + 1:
             max_kv_len = 64
         cu = r.choice([256, 256, 64, 304])
