@@ -338,6 +338,67 @@ def test_step_rollback_step_reproduces_bits_and_ignores_stale_slots():
     assert e.value.status == -7
 
 
+def test_two_handles_on_two_streams_at_once():
+    """Handles share no device state: two models queued step by step on two streams, nothing waited
+    for in between, give the bits each gives alone (and the first step of each matches the oracle)."""
+    shapes = (wl.ModelShape(2, 256, 4, 2, 64, 256, 512), wl.ModelShape(3, 384, 8, 2, 128, 352, 1000))
+    rigs, plans = [], []
+    for i, shape in enumerate(shapes):
+        rig = Rig(shape, 3, 160, 4, seed=31 + i, std=0.05)
+        rng = wl.Rng(77 + i, "cpu")
+        lens = [(60, 33, 5), (90, 1, 47)][i]
+        for s_, n in enumerate(lens):
+            rig.prefill(s_, rng.randint(1 + s_, (n,), shape.vocab).tolist())
+        look = [(4, 2, 3), (1, 4, 4)][i]
+        t0 = rng.randint(9, (3,), shape.vocab).tolist()
+        _check_step(rig, [0, 1, 2], t0, list(look), 1.0, 500 + i)       # parity of this handle, alone
+        rig.sv.spec_kv_rollback(rig.h, [0, 1, 2], list(lens))
+        steps = []
+        for j in range(6):                                               # inputs of six consecutive steps
+            toks, dl = _drafts(wl.Rng(900 + 10 * i + j, "cpu"), 3, 4, shape.vocab, 1.0)
+            steps.append((rng.randint(20 + j, (3,), shape.vocab).int().cuda(), toks.cuda(), dl.cuda(),
+                          rng.uniform(40 + j, (3, 5)).cuda()))
+        rigs.append(rig)
+        plans.append((lens, look, steps))
+
+    def queue(i, j, stream, outs):
+        rig, (lens, look, steps) = rigs[i], plans[i]
+        t0, toks, dl, us = steps[j]
+        na = torch.full((3,), -9, dtype=torch.int32, device="cuda")
+        ot = torch.full((3, 5), -9, dtype=torch.int32, device="cuda")
+        lo = torch.zeros((sum(k + 1 for k in look), rig.shape.vocab), dtype=torch.float32, device="cuda")
+        rig.sv.spec_verify_step(rig.h, list(look), us, 1.0, na, ot,
+                                seq_slot=torch.tensor([0, 1, 2], dtype=torch.int32, device="cuda"), last_token=t0,
+                                draft_tokens=toks, draft_logits=dl, logits_out=lo, stream=stream)
+        outs.append((lo, na, ot))
+
+    def run(streams):
+        outs = ([], [])
+        torch.cuda.synchronize()
+        for j in range(6):
+            for i in (0, 1):
+                with torch.cuda.stream(streams[i]):      # the small input tensors are made on that stream too
+                    queue(i, j, streams[i], outs[i])
+        torch.cuda.synchronize()
+        for i in (0, 1):
+            rigs[i].sv.spec_verify_poll(rigs[i].h)
+            kl = rigs[i].kv_len.cpu().tolist()
+            rigs[i].sv.spec_kv_rollback(rigs[i].h, [0, 1, 2], list(plans[i][0]))
+            outs[i].append(kl)
+        torch.cuda.synchronize()
+        return outs
+
+    one = torch.cuda.current_stream()
+    alone = run((one, one))
+    both = run((torch.cuda.Stream(), torch.cuda.Stream()))
+    for i in (0, 1):
+        assert alone[i][-1] == both[i][-1]
+        for j in range(6):
+            for x, y in zip(alone[i][j], both[i][j]):
+                assert torch.equal(x, y), (i, j)
+        assert any(int(v) >= 0 for v in both[i][0][1].tolist())
+
+
 @pytest.mark.parametrize("merge_in_workgroup", [False, True])
 def test_kv_overflow_skips_the_sequence(merge_in_workgroup):
     from paper_2411_00853_amd import binding as sv
