@@ -166,7 +166,12 @@ int spec_kv_pages(spec_handle* h, int32_t* free_pages, int32_t* total_pages, voi
  * Sequence b scores the window [last_token[b], draft_tokens[b][0..K_b-1]] at positions
  * n_b .. n_b+K_b where n_b = kv_len[seq_slot[b]].  Target row j of a sequence gives the
  * distribution of the token following window token j, so row i tests draft i and row K_b is the
- * distribution of the extra token. */
+ * distribution of the extra token.
+ * Logits rows (draft_logits, target_logits_in; the tree step's likewise) may hold -inf entries:
+ * tokens of probability zero, as top-k or nucleus filtering leaves them.  A proposal the target
+ * excludes is rejected, excluded tokens are never emitted, and a row may consist of a single finite
+ * entry.  Every row needs at least one finite logit; NaN and +inf are not supported (the result for
+ * that sequence is then unspecified). */
 typedef struct {
     int32_t batch;                 /* 1 .. max_batch */
     const int32_t* lookahead;      /* HOST int32[B]: K_b in 0 .. Kmax */

@@ -174,6 +174,65 @@ def test_greedy_rule_at_temperature_zero(V):
     assert len(seen) >= 4
 
 
+@pytest.mark.parametrize("V,Kmax,T,share", [(301, 4, 1.0, 0.4), (4099, 8, 0.7, 0.9), (32000, 5, 1.3, 0.98),
+                                            (128256, 3, 1.0, 0.999)])
+def test_masked_logits(V, Kmax, T, share):
+    """Rows filtered the way top-k / nucleus sampling leaves them: a share of the entries of every
+    target and draft row is -inf (probability zero), with different masks on the two sides, so that
+    proposals the target excludes (p = 0: always rejected) and residuals with few survivors occur."""
+    from helpers import check_sampler_against_oracle, run_sampler_gpu
+    B = 12
+    look = [Kmax, 0] + [1 + (b * 5) % Kmax for b in range(B - 2)]
+    tl, dl, _, us = _random_inputs(900 + V, look, Kmax, V, 0.5, T)
+    rng = wl.Rng(901 + V, "cpu")
+    tl = tl.masked_fill(rng.uniform(20, tuple(tl.shape)) < share, float("-inf"))
+    dl = dl.masked_fill(rng.uniform(21, tuple(dl.shape)) < share, float("-inf"))
+    tl[:, 7] = 0.5                                   # every row keeps a token
+    dl[:, :, 11] = 0.25
+    toks = wl.pick_tokens(rng, dl, T, 3)
+    excluded = 0
+    r0 = 0
+    for b, K in enumerate(look):
+        excluded += sum(1 for i in range(K) if tl[r0 + i, toks[b, i]] == float("-inf"))
+        r0 += K + 1
+    assert excluded >= 3
+    na, ot = run_sampler_gpu(tl, dl.contiguous(), toks, us, look, T, Kmax)
+    chk = check_sampler_against_oracle(tl, dl, toks, us, look, T, Kmax, na, ot)
+    assert chk.exact_accept >= B - 1 and chk.exact_token >= B - 2
+    r0 = 0
+    for b, K in enumerate(look):                     # no emitted token has probability zero under the target
+        a = int(na[b])
+        assert torch.isfinite(tl[r0 + a, int(ot[b, a])])
+        r0 += K + 1
+
+
+@pytest.mark.parametrize("V,k", [(128256, 40), (50257, 5), (4099, 1)])
+def test_top_k_filtered_rows(V, k):
+    """Target and draft rows after top-k filtering (everything but each row's k largest logits is -inf):
+    most statistics chunks of a row hold no finite value at all, the two sides keep overlapping but
+    different sets, and with k = 1 both distributions are single tokens."""
+    from helpers import check_sampler_against_oracle, run_sampler_gpu
+    Kmax, T, B = 4, 0.9, 10
+    look = [Kmax, 0] + [1 + b % Kmax for b in range(B - 2)]
+    tl, dl, _, us = _random_inputs(950 + V, look, Kmax, V, 0.3, T)
+
+    def top_k(x):
+        kth = x.topk(k, dim=-1).values[..., -1:]
+        return x.masked_fill(x < kth, float("-inf"))
+    tl, dl = top_k(tl), top_k(dl).contiguous()
+    toks = wl.pick_tokens(wl.Rng(951 + V, "cpu"), dl, T, 3)
+    na, ot = run_sampler_gpu(tl, dl, toks, us, look, T, Kmax)
+    chk = check_sampler_against_oracle(tl, dl, toks, us, look, T, Kmax, na, ot)
+    assert chk.exact_accept >= B - 1 and chk.exact_token >= B - 2
+    r0 = 0
+    for b, K in enumerate(look):
+        a = int(na[b])
+        assert torch.isfinite(tl[r0 + a, int(ot[b, a])])
+        r0 += K + 1
+    if k > 1:
+        assert (na < torch.tensor(look)).any() and (na > 0).any()
+
+
 def test_many_random_shapes_linear_and_tree():
     """150 seeded draws of (vocabulary, lookahead, temperature, batch, draft noise): the linear rule and
     the tree rule, every sequence against the oracle (decisions bit-exact outside the margins, tokens

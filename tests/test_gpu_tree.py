@@ -88,6 +88,33 @@ def test_tree_sampler_against_oracle(V, Kmax, T):
     assert len(set(na.tolist())) >= 3, "walks of different lengths should occur"
 
 
+@pytest.mark.parametrize("V,k", [(50257, 20), (1000, 2)])
+def test_tree_sampler_on_top_k_filtered_rows(V, k):
+    """Rows after top-k filtering (all but the k largest logits of a row are -inf, on both sides): whole
+    statistics chunks without a finite value, siblings that repeat a token, children the target excludes."""
+    Kmax, T, B = 8, 1.0, 9
+    n_nodes, parent, toks, tl, dl, us = make_tree_inputs(77 + V, B, Kmax, V, T, 0.3)
+
+    def top_k(x):
+        kth = x.topk(k, dim=-1).values[..., -1:]
+        return x.masked_fill(x < kth, float("-inf"))
+    tl, dl = top_k(tl), top_k(dl)
+    rng = wl.Rng(78 + V, "cpu")
+    for b, n in enumerate(n_nodes):                  # children drawn from the filtered draft row of their parent
+        if n:
+            rows = torch.stack([dl[b, parent[b, i] + 1] for i in range(n)])
+            toks[b, :n] = wl.pick_tokens(rng, rows[None], T, 300 + b)[0]
+    na, ot, pt = run_tree_sampler(n_nodes, parent, toks, tl, dl, us, T, Kmax)
+    chk = check_trees(n_nodes, parent, toks, tl, dl, us, T, Kmax, na, ot, pt)
+    assert chk.exact_walk >= B - 1
+    r0 = 0
+    for b, n in enumerate(n_nodes):                  # the final token has positive probability at the last kept node
+        a = int(na[b])
+        last = int(pt[b, a - 1]) + 1 if a else 0
+        assert torch.isfinite(tl[r0 + last, int(ot[b, a])])
+        r0 += n + 1
+
+
 def test_chain_tree_equals_the_linear_step():
     from helpers import run_sampler_gpu
     B, K, V, T = 10, 6, 2000, 0.9
