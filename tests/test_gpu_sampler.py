@@ -233,6 +233,35 @@ def test_top_k_filtered_rows(V, k):
         assert (na < torch.tensor(look)).any() and (na > 0).any()
 
 
+def test_extreme_temperatures_and_logit_scales():
+    """60 seeded draws with temperatures from 0.05 to 20 and logit spreads from 0.1 to 30 (softmaxes from
+    almost uniform to a single token carrying all the mass), vocabularies up to 151936: decisions against the
+    oracle as everywhere else, linear and tree rule."""
+    import random
+    import test_gpu_tree as TT
+    from helpers import check_sampler_against_oracle, run_sampler_gpu
+    exact = inside = 0
+    for seed in range(60):
+        r = random.Random(seed)
+        V = r.choice([97, 301, 1000, 4099, 16384, 16385, 32000, 50257, 128256, 151936])
+        Kmax = r.choice([1, 2, 5, 8, 15])
+        T = r.choice([0.05, 0.1, 0.3, 1.0, 3.0, 10.0, 20.0])
+        B = r.choice([1, 2, 7, 20])
+        sigma = r.choice([0.01, 0.3, 2.0])
+        scale = r.choice([0.1, 2.0, 10.0, 30.0])
+        look = [r.randrange(0, Kmax + 1) for _ in range(B)]
+        look[0] = Kmax
+        tl, dl, toks, us = _random_inputs(5000 + seed, look, Kmax, V, sigma, T, scale=scale)
+        na, ot = run_sampler_gpu(tl, dl, toks, us, look, T, Kmax)
+        chk = check_sampler_against_oracle(tl, dl, toks, us, look, T, Kmax, na, ot)
+        exact += chk.exact_accept + chk.exact_token
+        inside += chk.margin_accept + chk.margin_token
+        if V <= 50257:
+            inp = TT.make_tree_inputs(7000 + seed, B, Kmax, V, T, sigma)
+            TT.check_trees(*inp, T, Kmax, *TT.run_tree_sampler(*inp, T, Kmax))
+    assert inside <= 0.05 * (exact + inside)
+
+
 def test_many_random_shapes_linear_and_tree():
     """150 seeded draws of (vocabulary, lookahead, temperature, batch, draft noise): the linear rule and
     the tree rule, every sequence against the oracle (decisions bit-exact outside the margins, tokens
