@@ -66,7 +66,6 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
 {
     constexpr int STEPS = HD / 32;     // 32-dim steps of the score product
     constexpr int DT = HD / 16;        // 16-dim tiles of the output
-    constexpr int BLK_U4 = 8 * HD;     // uint4 per 32-position block (keys then values)
     const int lane = threadIdx.x & 63, c16 = lane & 15, gq = lane >> 4;
     const int item = CW > 0 ? blockIdx.x * max_chunks + (threadIdx.x >> 6) : blockIdx.x;   // ((b, hkv), chunk)
     const int chunk = CW > 0 ? (int)(threadIdx.x >> 6) : item % max_chunks;
@@ -122,6 +121,7 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
     } else {
         head = cache + cache_head_base(g, layer, t.seq_slot[b], hkc) / 8;
     }
+    const size_t blk_u4 = g.blk_stride / 8;   // from one block of this head to the next (contiguous cache)
 
     uint4 ka[2][STEPS], va[DT], kb[2][STEPS], vb[DT];
     // unconditional loads (a block index past the chunk re-reads the chunk's last block): with no
@@ -132,7 +132,7 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
         if constexpr (PAGED)
             p = head + (size_t)__builtin_amdgcn_readlane(my_page, bb - blk0) * (g.page_stride / 8) + lane;
         else
-            p = head + (size_t)bb * BLK_U4 + lane;
+            p = head + (size_t)bb * blk_u4 + lane;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll

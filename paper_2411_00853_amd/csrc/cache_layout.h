@@ -2,9 +2,14 @@
 //
 // fp32 caches are plain: [layer][slot][k|v][kv head][position][dim].
 //
-// bf16 caches are laid out for the attention kernel's matrix-instruction operands.  Per (layer,
-// slot, kv head) the positions are grouped in blocks of 32; a block holds a key part of 32*hd
-// elements followed by a value part of 32*hd elements:
+// bf16 caches are laid out for the attention kernel's matrix-instruction operands.  The positions
+// are grouped in blocks of 32, and a slot is stored as [layer][slot][block][kv head]: the wavefronts
+// that stream the heads of one sequence advance together, so at any moment they read one contiguous
+// stretch of memory (n_kv_heads * 64 * hd elements per block) and spread over all memory channels
+// whatever the slot capacity is.  (With [kv head][block] the distance between the streams is the
+// capacity of a head, and for some capacities -- 129 blocks of 128-dim heads, say -- the streams
+// fell on few channels: the attention launch took 14 % longer.)  One head's share of a block holds a
+// key part of 32*hd elements followed by a value part of 32*hd elements:
 //   key part:   [sub = 2 halves of 16 positions][dim group = hd/8][position in half = 16][8 dims]
 //               -> the A operand of S^T = K * Q^T for one half and one 32-dim step is a contiguous
 //                  1 KiB run: lane l reads 16 bytes at dim group 4*step + l/16, position l%16.
@@ -27,7 +32,7 @@ __host__ __device__ inline size_t cache_head_base(const CacheGeom& g, int layer,
 // Element offset of block blk of (layer, slot, head), either mode (bf16).
 __host__ __device__ inline size_t cache_block_base(const CacheGeom& g, int layer, int slot, int head, int blk)
 {
-    if (!g.table) return cache_head_base(g, layer, slot, head) + (size_t)blk * (64 * g.head_dim);
+    if (!g.table) return cache_head_base(g, layer, slot, head) + (size_t)blk * g.blk_stride;
     int page = g.table[(size_t)slot * g.blocks_per_slot + blk];
     if (page < 0) page = 0;   // never for a position the step may touch; keeps a stray access in bounds
     return (size_t)page * g.page_stride + ((size_t)layer * g.n_kv_heads + head) * (64 * g.head_dim);
@@ -63,21 +68,7 @@ __device__ inline void pool_trim(const PagePool& p, int slot, int new_len)
     }
 }
 
-// bf16 tiled order, offsets relative to cache_head_base
-__host__ __device__ inline size_t tiled_k_offset(int hd, int pos, int dim)
-{
-    const int blk = pos >> 5, t32 = pos & 31, sub = t32 >> 4, t16 = t32 & 15;
-    return (size_t)blk * (64 * hd) + ((size_t)(sub * (hd >> 3) + (dim >> 3)) * 16 + t16) * 8 + (dim & 7);
-}
-
-__host__ __device__ inline size_t tiled_v_offset(int hd, int pos, int dim)
-{
-    const int blk = pos >> 5, t32 = pos & 31, sub = t32 >> 4, t16 = t32 & 15;
-    const int g = t16 >> 2, e = (t16 & 3) + 4 * sub;
-    return (size_t)blk * (64 * hd) + 32 * hd + ((size_t)(dim >> 4) * 64 + g * 16 + (dim & 15)) * 8 + e;
-}
-
-// the same, inside one block (t32 = position & 31), relative to cache_block_base
+// bf16 tiled order inside one block (t32 = position & 31), relative to cache_block_base
 __host__ __device__ inline size_t tiled_k_within(int hd, int t32, int dim)
 {
     const int sub = t32 >> 4, t16 = t32 & 15;

@@ -161,15 +161,17 @@ struct RopeTable {
     const float* cos_sin;   // [max_kv_len][head_dim/2][2] cos, sin of pos * theta^(-2i/hd)
 };
 
-// bf16 cache tile order: per (layer, slot, kv head) a run of 32-key blocks; each block holds a key
-// part then a value part of 32*hd elements each (see attention.hip for the element order).
+// bf16 cache tile order: per (layer, slot) a run of 32-position blocks, each holding that block of
+// every kv head in turn; a head's block is a key part then a value part of 32*hd elements each (see
+// cache_layout.h for the element order).
 struct CacheGeom {
     int dtype;
     int n_layers, n_slots, n_kv_heads, head_dim;
     int t_pad;            // max_kv_len rounded up to 32
     size_t layer_stride;  // elements
     size_t slot_stride;
-    size_t head_stride;   // bf16: keys and values of one head (2*t_pad*hd); fp32: one plane (t_pad*hd)
+    size_t head_stride;   // bf16: one block of one head (64*hd); fp32: one plane (t_pad*hd)
+    size_t blk_stride;    // bf16: from a head's block to its next one (n_kv_heads*64*hd); fp32: unused
     // paged mode (bf16 only): the 32-position blocks of a slot live in pages of a shared pool,
     // [page][layer][kv head][block]; table[slot * blocks_per_slot + blk] names the page (-1: none)
     const int32_t* table; // NULL: contiguous mode

@@ -247,8 +247,9 @@ CacheGeom make_cache_geom(const spec_model_cfg& c)
     g.head_dim = c.head_dim;
     if (c.dtype == SPEC_DTYPE_BF16) {
         g.t_pad = (c.max_kv_len + 31) / 32 * 32;
-        g.head_stride = (size_t)2 * g.t_pad * c.head_dim;
-        g.slot_stride = (size_t)c.n_kv_heads * g.head_stride;
+        g.head_stride = (size_t)64 * c.head_dim;
+        g.blk_stride = (size_t)c.n_kv_heads * g.head_stride;
+        g.slot_stride = (size_t)(g.t_pad / 32) * g.blk_stride;
     } else {
         g.t_pad = c.max_kv_len;
         g.head_stride = (size_t)g.t_pad * c.head_dim;
