@@ -9,16 +9,17 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecverify.so")
-SOURCES = ["spec_verify.hip", "forward.hip", "sampler.hip", "gemm.hip", "attention.hip", "elementwise.hip",
-           "probe.hip", "decode.hip", "lookahead.hip"]
+SOURCES = ["attention.hip", "attention_reuse.hip", "spec_verify.hip", "forward.hip", "sampler.hip", "gemm.hip",
+           "elementwise.hip", "probe.hip", "decode.hip", "lookahead.hip"]
 # packed-fp32 instructions are disabled for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-# Per-source additions.  attention.hip: matrix instructions take their accumulators in ordinary vector
+# Per-source additions.  The attention kernels: matrix instructions take their accumulators in ordinary vector
 # registers; left to its default the compiler parks them in the accumulation registers and copies all
 # 32 of them out and back around every block's products (the rare rescaling is vector arithmetic).
 # The GEMM kernels keep the default: several of their variants measured slower with this option.
-SOURCE_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+SOURCE_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+                "attention_reuse.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 OBJ_DIR = os.path.join(HERE, "_build")
 
 
