@@ -245,7 +245,11 @@ __global__ void __launch_bounds__(TPB) stats_kernel(StepTables t, LookaheadPack 
         for (int i = 0; i < PER / 4; ++i) {
             int idx = i * TPB + threadIdx.x;
             float4 x = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-            if (idx * 4 < lim) x = p4[idx];   // lim is a multiple of 4 when VEC4
+            if (idx * 4 < lim) {   // lim is a multiple of 4 when VEC4
+                typedef float f32x4 __attribute__((ext_vector_type(4)));
+                const f32x4 y = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p4 + idx));
+                x = make_float4(y.x, y.y, y.z, y.w);
+            }
             v[4 * i + 0] = x.x; v[4 * i + 1] = x.y; v[4 * i + 2] = x.z; v[4 * i + 3] = x.w;
         }
         if (copy_out) {   // whole 16-byte stores (the launcher checked the alignment of the copy as well)
