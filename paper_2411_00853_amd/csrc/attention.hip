@@ -301,6 +301,10 @@ static AttnLaunchPlan plan_launch(const CacheGeom& g, bool paged, int n_q_heads,
         lp.p.chunk_keys = ((max_kv_len + few - 1) / few + 31) / 32 * 32;
         lp.p.max_chunks = (max_kv_len + lp.p.chunk_keys - 1) / lp.p.chunk_keys;
     }
+    // Two blocks: measured over 0..128 positions, 7B-shape paged step 5.04 -> 4.95 ms, decoding round 6.69 -> 6.62 ms,
+    // contiguous 7B-shape, tree and long-context steps 0.2-0.7 % shorter, nothing longer (32 and 96 positions were
+    // slower than none: the main loop takes two blocks per trip).
+    lp.p.lag_keys = 64;
     return lp;
 }
 

@@ -64,7 +64,7 @@ __device__ __forceinline__ uint4 kv_load(const uint4* p)
 template <int HD, int RT, bool PAGED, bool FUSED, int CW, bool STREAM>
 __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
     attn_chunk_kernel(StepTables t, LookaheadPack ks, CacheGeom g, int n_q_heads, int kv_share, int layer,
-                      const uint4* cache, const float* __restrict__ q, int max_chunks, int r_cap, float scale_log2e,
+                      const uint4* cache, const float* __restrict__ q, int max_chunks, int lag_keys, int r_cap, float scale_log2e,
                       float* __restrict__ part_o, float* __restrict__ part_ml, QkvSrc src, uint16_t* cache_w, XOut xo)
 {
     constexpr int STEPS = HD / 32;     // 32-dim steps of the score product
@@ -95,7 +95,15 @@ __global__ void __launch_bounds__(CW > 0 ? 64 * CW : 64)
     }
     const int n = t.seq_n[b];
     const int total = n + K + 1;
-    const int ck = seq_chunk_keys(total, max_chunks);
+    // Equal chunks, except that the chunks before the last are lag_keys longer when the last one stays
+    // long enough: its wavefront first puts the window's keys and values together (FUSED), and with a
+    // shorter run to stream afterwards it ends with the others instead of after them.
+    int ck = seq_chunk_keys(total, max_chunks);
+    if (lag_keys > 0) {
+        const int n_used = (total + ck - 1) / ck;
+        if (n_used >= 2 && total - (n_used - 1) * (ck + lag_keys) >= 2 * lag_keys + 64 && (!PAGED || ck + lag_keys <= 2048))
+            ck += lag_keys;
+    }
     const int key0 = chunk * ck;
     const bool active = chunk < max_chunks && key0 < total;
     if constexpr (CW == 0) {
@@ -493,9 +501,10 @@ static int launch_chunks(int rt, int cw, dim3 grid, dim3 wg_grid, hipStream_t s,
                          const AttnPlan& p, int r_cap, float sl2, float* part_o, float* part_ml, const QkvSrc& src,
                          void* cache_w, const XOut& xo)
 {
+    const int lag_keys = src.partial ? p.lag_keys : 0;   // only the fused prologue delays a wavefront
 #define SPECV_ATTN_CW(RT, PG, FU, CW_)                                                                         \
     hipLaunchKernelGGL((attn_chunk_kernel<HD, RT, PG, FU, CW_, STREAM>), CW_ > 0 ? wg_grid : grid, dim3(CW_ > 0 ? 64 * CW_ : 64), \
-                       0, s, t, ks, g, n_q_heads, kv_share, layer, (const uint4*)cache, q, p.max_chunks, r_cap, sl2, part_o, \
+                       0, s, t, ks, g, n_q_heads, kv_share, layer, (const uint4*)cache, q, p.max_chunks, lag_keys, r_cap, sl2, part_o, \
                        part_ml, src, (uint16_t*)cache_w, xo)
 #define SPECV_ATTN_GO(RT, PG, FU)                                                                              \
     do {                                                                                                         \

@@ -271,6 +271,7 @@ struct QkvSrc {
 struct AttnPlan {
     int chunk_keys;   // most keys a wavefront work item can get (multiple of 32): a sequence at max_kv_len
     int max_chunks;   // chunks per (sequence, kv head) at max_kv_len
+    int lag_keys;     // positions by which the chunks before a sequence's last one are longer (multiple of 32)
 };
 AttnPlan plan_attention(int max_kv_len, int batch, int n_kv_heads, int cu_count, bool paged = false);
 void set_attn_items_per_cu(int n);
