@@ -285,7 +285,8 @@ int spec_kv_rollback(spec_handle* h, const int32_t* seq_slot, const int32_t* new
                      void* stream);
 
 /* Copy positions [pos0, pos0+n_pos) of one slot between the cache and a plain device tensor
- * dtype[n_layers][2 (k,v)][n_kv_heads][n_pos][head_dim].  Does not change kv_len. */
+ * dtype[n_layers][2 (k,v)][n_kv_heads][n_pos][head_dim].  Does not change kv_len.  n_pos = 0 does
+ * nothing (the tensor pointer may then be NULL). */
 int spec_kv_import(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, const void* src, void* stream);
 int spec_kv_export(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, void* dst, void* stream);
 

@@ -494,7 +494,8 @@ extern "C" int spec_kv_rollback(spec_handle* h, const int32_t* seq_slot, const i
 static int kv_copy_common(spec_handle* h, int32_t slot, int32_t pos0, int32_t n_pos, void* plain, bool to_cache,
                           void* stream)
 {
-    if (!h || !plain) return fail(SPEC_ERR_INVALID_ARG, "NULL handle or tensor");
+    if (!h) return fail(SPEC_ERR_INVALID_ARG, "NULL handle");
+    if (!plain && n_pos != 0) return fail(SPEC_ERR_INVALID_ARG, "NULL tensor");   // (an empty tensor has no address)
     if (!h->has_model) return fail(SPEC_ERR_INVALID_ARG, "sampler-only handle has no KV cache");
     if (slot < 0 || slot >= h->cfg.max_batch) return fail(SPEC_ERR_INVALID_ARG, "slot outside 0..%d", h->cfg.max_batch - 1);
     if (pos0 < 0 || n_pos < 0 || pos0 + n_pos > h->cfg.max_kv_len)

@@ -331,6 +331,10 @@ def test_step_rollback_step_reproduces_bits_and_ignores_stale_slots():
     rig.sv.spec_kv_import(rig.h, 0, n0, junk)
     c = rig.step([0], [3], [2], toks[:1], dl[:1], us[:1], 1.0)
     assert torch.isfinite(c[0]).all()
+    # copying no positions is not an error (an empty tensor has no address)
+    empty = torch.empty((shape.n_layers, 2, shape.n_kv_heads, 0, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+    rig.sv.spec_kv_import(rig.h, 1, 5, empty)
+    rig.sv.spec_kv_export(rig.h, 1, 0, empty)
     # rolling back above the current length is refused on the device and reported
     rig.sv.spec_kv_rollback(rig.h, [1], [90])
     with pytest.raises(rig.sv.SpecError) as e:
