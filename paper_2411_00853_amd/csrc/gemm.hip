@@ -454,7 +454,7 @@ template <int MT, int NT, int KC, int RS = 1>
 int launch_variant(const GemmPlan& p, const void* xf, const void* w, int M, int K, int n_tiles, float* partial,
                    hipStream_t s)
 {
-    if constexpr (RS == 2) {
+    if constexpr (RS == 2 || (MT <= 4 && NT == 2)) {
         if (p.cg == 3) return launch_groups<MT, NT, KC, RS, 3>(p, xf, w, M, K, n_tiles, partial, s);
     }
     return launch_groups<MT, NT, KC, RS, 4>(p, xf, w, M, K, n_tiles, partial, s);
@@ -548,11 +548,21 @@ GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
            && ranges_with_work(2 * s) * 8 >= 2 * s * 7)
         s *= 2;
     p.n_split = s;
+    // Few rows, two column tiles per wavefront: three column groups per workgroup where four leave more than a
+    // fifth of the compute units without a workgroup and three fill them (7B-shape QKV: 192 workgroups of four
+    // wavefronts -> 256 of three).  A read stream of that size (100 MB) runs 10 % faster from 256 workgroups than
+    // from 192, and since the weights are fetched with streaming loads the GEMM follows: QKV 25.5 -> 22.5 us per
+    // launch, 7B-shape step 4.915 -> 4.853 ms, 1B-shape 0.897 -> 0.884, decoding round 6.67 -> 6.58 ms (before the
+    // streaming loads the same change gained nothing).  With four tiles per wavefront or five to seven row tiles
+    // it is mixed (72 rows -1 %, 88-96 rows +1.3..1.6 % per step) and is not made.
+    if (p.mt <= 4 && p.nt == 2) {
+        const int wg3 = (n_tiles + 3 * p.nt - 1) / (3 * p.nt) * s;
+        if (wg_x * s * 5 < cu_count * 4 && wg3 <= cu_count) p.cg = 3;
+    }
     // Many rows (the eight-wavefront variants): the matrix instructions set the pace, so compute units
     // without a workgroup are lost time; three column groups per workgroup instead of four when that
     // brings the launch from under four fifths of the compute units to at most all of them
-    // (157 rows: QKV 192 -> 256 workgroups, gate/up 172 -> 230; GEMM time of that step -6 %).  With
-    // few rows, where HBM sets the pace, the same change gained nothing and is not made.
+    // (157 rows: QKV 192 -> 256 workgroups, gate/up 172 -> 230; GEMM time of that step -6 %).
     if (p.mt >= 8 && p.rs == 2) {
         const int wg3 = (n_tiles + 3 * p.nt - 1) / (3 * p.nt) * s;
         if (wg_x * s * 5 < cu_count * 4 && wg3 <= cu_count) {

@@ -118,7 +118,8 @@ def test_plans_of_the_named_configurations():
     assert p.rows == 48 and p.n_passes == 1
     assert list(p.gemm_row_tiles) == [3] * 5
     # (the launch rounds these up to whole rounds of the 8 XCDs: 250 runs as a grid of 256)
-    assert list(p.gemm_workgroups) == [192, 256, 172, 256, 250]
+    # (the QKV projection as 256 workgroups of three wavefronts: four per workgroup would leave 64 compute units idle)
+    assert list(p.gemm_workgroups) == [256, 256, 172, 256, 250] and list(p.gemm_col_groups) == [3, 4, 4, 4, 4]
     assert (p.attn_kv_share, p.attn_small, p.attn_chunks, p.attn_wavefronts, p.attn_fused) == (1, 0, 2, 2, 1)
     assert p.gate_up_swiglu_inside == 1
     w = wl.workload_1b()
