@@ -41,7 +41,7 @@ def _check_invariants(shape, cfg, look, p, paged):
     for i in range(sv.PLAN_PROJECTIONS):
         mt, nt, s, kbs = p.gemm_row_tiles[i], p.gemm_col_tiles[i], p.gemm_k_ranges[i], p.gemm_k_blocks_per_range[i]
         assert mt * 16 >= p.pass_rows[0] and mt in (1, 2, 3, 4, 5, 6, 8, 10, 12, 14, 16, 18, 20, 22)
-        assert nt in (1, 2, 3, 4) and p.gemm_row_parts[i] in (1, 2) and p.gemm_col_groups[i] in (3, 4)
+        assert nt in (1, 2, 3, 4) and p.gemm_row_parts[i] in (1, 2) and p.gemm_col_groups[i] in (2, 3, 4)
         assert (p.gemm_row_parts[i] == 2) == (mt >= 8)
         assert s in (1, 2, 4, 8, 16) and kbs % 4 == 0 and s * kbs >= n_in[i] // 32
         with_work = -(-(n_in[i] // 32) // kbs)
@@ -119,7 +119,8 @@ def test_plans_of_the_named_configurations():
     assert list(p.gemm_row_tiles) == [3] * 5
     # (the launch rounds these up to whole rounds of the 8 XCDs: 250 runs as a grid of 256)
     # (the QKV projection as 256 workgroups of three wavefronts: four per workgroup would leave 64 compute units idle)
-    assert list(p.gemm_workgroups) == [256, 256, 172, 256, 250] and list(p.gemm_col_groups) == [3, 4, 4, 4, 4]
+    assert list(p.gemm_workgroups) == [256, 256, 172, 256, 250] and list(p.gemm_col_groups) == [3, 2, 4, 2, 4]
+    assert list(p.gemm_k_ranges) == [2, 4, 2, 4, 2]     # (two column groups: the narrow projections need half the K ranges)
     assert (p.attn_kv_share, p.attn_small, p.attn_chunks, p.attn_wavefronts, p.attn_fused) == (1, 0, 2, 2, 1)
     assert p.gate_up_swiglu_inside == 1
     w = wl.workload_1b()
