@@ -530,15 +530,7 @@ GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
     // projections and their consumers -0.3 ms of 6.6 at 157 rows.
     if (p.mt >= 5 && p.mt <= 12 && n_tiles < kWideMinTiles) p.nt = 2;
     p.cg = 4;
-    // Few rows and few columns (up to four row tiles, under 340 column tiles: the 4096-column projections, a small
-    // model's QKV): two column groups per workgroup.  Twice the column blocks fill the chip with half the K ranges,
-    // i.e. half the partial sums for the launch to write and for its consumer to add up, and two wavefronts per
-    // compute unit stream as fast as four (stand-alone read of 33 and 90 MB: 4.7 and 5.8 TB/s either way).  1B-shape
-    // step 0.884 -> 0.850 ms (its attention adds up four QKV ranges instead of eight), batch 8 1.242 -> 1.205,
-    // decoding round -0.3 %, 7B-shape step unchanged (down projection +1.7 us, its consumers and the rest -1.7).
-    if (p.mt <= 4 && p.nt == 2 && n_tiles < kWideMinTiles) p.cg = 2;
     p.rs = p.mt >= 8 ? 2 : 1;
-    const int wg_x = (n_tiles + p.cg * p.nt - 1) / (p.cg * p.nt);
     const int kb_total = K / 32;
     // K ranges: a power of two, just enough of them that the launch has about `target` workgroups.
     // Measured on MI355X: every launch pays a few microseconds of ramp-up and tail whatever its
@@ -553,10 +545,27 @@ GemmPlan plan_gemm(int M, int N, int K, int cu_count, bool split_x)
         const int per = ((kb_total + n - 1) / n + WPACK_KG - 1) / WPACK_KG * WPACK_KG;
         return (kb_total + per - 1) / per;
     };
-    int s = 1;
-    while (s < 16 && wg_x * s < target && (kb_total + 2 * s - 1) / (2 * s) >= 2 * kc
-           && ranges_with_work(2 * s) * 8 >= 2 * s * 7)
-        s *= 2;
+    auto ranges_for = [&](int blocks_x) {
+        int n = 1;
+        while (n < 16 && blocks_x * n < target && (kb_total + 2 * n - 1) / (2 * n) >= 2 * kc
+               && ranges_with_work(2 * n) * 8 >= 2 * n * 7)
+            n *= 2;
+        return n;
+    };
+    // Few rows and few columns (up to four row tiles, under 340 column tiles: the 4096-column projections, a small
+    // model's QKV): two column groups per workgroup.  Twice the column blocks fill the chip with half the K ranges,
+    // i.e. half the partial sums for the launch to write and for its consumer to add up, and two wavefronts per
+    // compute unit stream as fast as four (stand-alone read of 33 and 90 MB: 4.7 and 5.8 TB/s either way).  1B-shape
+    // step 0.884 -> 0.850 ms (its attention adds up four QKV ranges instead of eight), batch 8 1.242 -> 1.205,
+    // decoding round -0.3 %.  Only while a workgroup's K range stays within 2048: a workgroup stages all rows of
+    // X over its range, and at 2752 (the 7B-shape down projection in four ranges) the launch was 1.7 us slower,
+    // as much as its consumers gained; at 2048 (K = 8192) and below it costs the launch nothing.
+    if (p.mt <= 4 && p.nt == 2 && n_tiles < kWideMinTiles) {
+        const int n2 = ranges_for((n_tiles + 2 * p.nt - 1) / (2 * p.nt));
+        if ((kb_total + n2 - 1) / n2 * 32 <= 2048) p.cg = 2;
+    }
+    const int wg_x = (n_tiles + p.cg * p.nt - 1) / (p.cg * p.nt);
+    const int s = ranges_for(wg_x);
     p.n_split = s;
     // Few rows, two column tiles per wavefront: three column groups per workgroup where four leave more than a
     // fifth of the compute units without a workgroup and three fill them (7B-shape QKV: 192 workgroups of four

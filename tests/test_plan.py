@@ -119,8 +119,9 @@ def test_plans_of_the_named_configurations():
     assert list(p.gemm_row_tiles) == [3] * 5
     # (the launch rounds these up to whole rounds of the 8 XCDs: 250 runs as a grid of 256)
     # (the QKV projection as 256 workgroups of three wavefronts: four per workgroup would leave 64 compute units idle)
-    assert list(p.gemm_workgroups) == [256, 256, 172, 256, 250] and list(p.gemm_col_groups) == [3, 2, 4, 2, 4]
-    assert list(p.gemm_k_ranges) == [2, 4, 2, 4, 2]     # (two column groups: the narrow projections need half the K ranges)
+    assert list(p.gemm_workgroups) == [256, 256, 172, 256, 250] and list(p.gemm_col_groups) == [3, 2, 4, 4, 4]
+    # (two column groups where a workgroup's K range stays within 2048: the output projection in 4 ranges, not the down projection)
+    assert list(p.gemm_k_ranges) == [2, 4, 2, 8, 2]
     assert (p.attn_kv_share, p.attn_small, p.attn_chunks, p.attn_wavefronts, p.attn_fused) == (1, 0, 2, 2, 1)
     assert p.gate_up_swiglu_inside == 1
     w = wl.workload_1b()
